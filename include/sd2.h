@@ -1,0 +1,185 @@
+/*
+ * sd2.h -- C ABI of libsd2: the hot path of a pruned ("sparse") draft model for
+ * speculative decoding on one AMD MI355X (gfx950).
+ *
+ * What the calls compute follows the paper's problem statement:
+ *   - the draft model M_d is a decoder whose linear layers (q, k, v, o, gate, up,
+ *     down) carry a fixed binary weight mask; pruned weights are exactly zero
+ *     (Sec. 2.3 "Fine-grained pruning", Sec. 2.4 "Sparse fine-tuning");
+ *   - per round M_d proposes k tokens and the target keeps the longest prefix that
+ *     equals its own greedy choices, then adds one token of its own
+ *     (Sec. 2.1, Eq. 1 and Eq. 2; footnote to Eq. 3);
+ *   - the cost of M_d per token is what Eq. 3 calls c; it is set by the bytes the
+ *     pruned linears stream, which is what the packed format minimises (Sec. 3.3
+ *     asks for "efficient sparse representations and kernels").
+ *
+ * Conventions
+ *   - Every function returns SD2_OK (0) or a negative sd2_status; nothing throws or
+ *     aborts.  All argument and blob checks happen on the host before any launch.
+ *   - "host" pointers are ordinary CPU memory.  "device" pointers are HIP device
+ *     memory owned by the caller (for example torch tensors); the library never
+ *     allocates or frees device memory.
+ *   - `stream` is a hipStream_t passed as void* (NULL = default stream).  Device
+ *     calls only enqueue work on that stream and return.
+ *   - bf16 values travel as uint16_t bit patterns.  Activations are token-major:
+ *     X is [k_tok][k_in], Y is [k_tok][n_out]; weights are row-major [n_out][k_in]
+ *     (the layout of nn.Linear.weight).  Outputs are fp32 (fp32 accumulation of
+ *     exact bf16 x bf16 products).
+ *   - Limits: 1 <= k_tok <= 64; k_in a multiple of 64; device pointers 16-byte aligned.
+ */
+#ifndef SD2_H
+#define SD2_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum sd2_status {
+    SD2_OK = 0,
+    SD2_ERR_NULL = -1,        /* a required pointer is NULL */
+    SD2_ERR_SHAPE = -2,       /* a dimension is out of range or inconsistent */
+    SD2_ERR_FORMAT = -3,      /* unknown / unsupported format id or geometry */
+    SD2_ERR_BUFFER = -4,      /* a caller buffer is too small or misaligned */
+    SD2_ERR_BLOB = -5,        /* blob header, directory or checksum is corrupt */
+    SD2_ERR_RANGE = -6,       /* a value (token id, k_tok, ...) is outside its range */
+    SD2_ERR_HIP = -7,         /* a HIP runtime call or kernel launch failed */
+    SD2_ERR_UNSUPPORTED = -8  /* valid request that this build does not implement */
+};
+
+#define SD2_MAX_TOKENS 64
+#define SD2_FORMAT_AUTO 0
+#define SD2_FORMAT_BITMASK 1
+#define SD2_FORMAT_INDEX16 2 /* reserved: returns SD2_ERR_UNSUPPORTED */
+
+/* Static, never freed. */
+const char* sd2_strerror(int status);
+int sd2_version(void);
+
+/* ------------------------------------------------------------------ packing (host only)
+ * The sparse representation: Sec. 1 and Sec. 3.3 require one but do not define it.
+ * The byte layout is specified in docs/FORMAT.md (tiles of 16 rows x 256 columns,
+ * one 16-bit mask per lane and 64-column step, compacted bf16 values in the order
+ * a wavefront consumes them, a per-tile directory with the offsets of its 16 runs). */
+
+typedef struct sd2_blob_info {
+    int32_t format, n_out, k_in;
+    int32_t n_strips, n_slabs, n_tiles; /* tiles of 16 rows x 256 columns; n_slabs = split-K factor */
+    int32_t max_tile_nnz;
+    int32_t reserved0;
+    uint64_t nnz;          /* non-zero weights */
+    uint64_t total_bytes;  /* size of the blob */
+    uint64_t useful_bytes; /* 2*nnz + n_out*k_in/8: values plus one mask bit per position */
+    uint64_t mask_off, val_off;
+    uint32_t checksum;
+    uint32_t reserved;
+} sd2_blob_info_t;
+
+/* Bytes needed for the blob of `w_bf16` (host, [n_out][k_in], zeros = pruned; both +0
+ * and -0 count as pruned).  format: SD2_FORMAT_AUTO or SD2_FORMAT_BITMASK. */
+int sd2_pack_sparse_size(const uint16_t* w_bf16, int32_t n_out, int32_t k_in, int32_t format,
+                         size_t* bytes_out);
+
+/* Writes the blob into caller-owned host memory `blob` of `blob_bytes` bytes.
+ * SD2_ERR_BUFFER if it does not fit.  Deterministic: equal inputs give equal bytes. */
+int sd2_pack_sparse(const uint16_t* w_bf16, int32_t n_out, int32_t k_in, int32_t format, void* blob,
+                    size_t blob_bytes, size_t* bytes_written);
+
+/* Inverse of sd2_pack_sparse: fills w_bf16_out (host, [n_out][k_in]) with the stored
+ * values and +0 elsewhere.  n_out/k_in must match the blob.  Validates the blob first. */
+int sd2_unpack_sparse(const void* blob, size_t blob_bytes, uint16_t* w_bf16_out, int32_t n_out,
+                      int32_t k_in);
+
+/* Parses and checks the header (magic, version, geometry, offsets vs blob_bytes). */
+int sd2_blob_info(const void* blob, size_t blob_bytes, sd2_blob_info_t* out);
+
+/* Full check of a host blob: header, checksum, directory vs masks. */
+int sd2_blob_validate(const void* blob, size_t blob_bytes);
+
+/* ------------------------------------------------------------------ matrices on the device */
+
+#define SD2_KIND_SPARSE 1
+#define SD2_KIND_DENSE 2
+
+/* Plain descriptor, owned by the caller, no hidden state.  `data_dev` is the device copy
+ * of the blob (sparse) or of the row-major bf16 matrix (dense). */
+typedef struct sd2_matrix {
+    int32_t kind;
+    int32_t reserved;
+    const void* data_dev;
+    sd2_blob_info_t info; /* dense: only the shape and tile counts are used */
+} sd2_matrix_t;
+
+/* Sparse descriptor from the host copy of the blob (header is validated) and the
+ * device address the same bytes were uploaded to. */
+int sd2_matrix_init_sparse(sd2_matrix_t* m, const void* blob_host, size_t blob_bytes,
+                           const void* blob_dev);
+/* Dense descriptor for the baseline kernel: W is the same masked matrix stored with
+ * its zeros, 2 bytes per weight. */
+int sd2_matrix_init_dense(sd2_matrix_t* m, const uint16_t* w_bf16_dev, int32_t n_out, int32_t k_in);
+
+/* ------------------------------------------------------------------ linears
+ * Y[t][n] = sum_c W[n][c] * X[t][c] over the stored (non-pruned) weights, fp32
+ * accumulate -- one pruned decoder linear applied to k_tok in-flight tokens
+ * (Sec. 2.1: the drafter runs on the draft tokens; Sec. 2.4: pruned weights are zero).
+ * When k_in spans more than one 256-column slab, per-slab partial sums go through
+ * `workspace` (device, >= the size reported below, 16-byte aligned) and are added up in
+ * a fixed order; otherwise it may be NULL. */
+int sd2_linear_workspace_size(const sd2_matrix_t* m, int32_t k_tok, size_t* bytes_out);
+int sd2_sparse_linear(const sd2_matrix_t* m, const uint16_t* x_bf16_dev, int32_t k_tok, float* y_dev,
+                      void* workspace_dev, size_t workspace_bytes, void* stream);
+/* Hand-written dense bf16 baseline for the same shapes; `m` must be a dense descriptor. */
+int sd2_dense_linear(const sd2_matrix_t* m, const uint16_t* x_bf16_dev, int32_t k_tok, float* y_dev,
+                     void* workspace_dev, size_t workspace_bytes, void* stream);
+
+/* Gated MLP block: y = Wd * bf16( silu(Wg x) * (Wu x) ), with [Wg; Wu] packed as one
+ * matrix of 2*inter rows (they share their input) and Wd as a second one. */
+int sd2_mlp_workspace_size(const sd2_matrix_t* gate_up, const sd2_matrix_t* down, int32_t k_tok,
+                           size_t* bytes_out);
+int sd2_sparse_mlp_forward(const sd2_matrix_t* gate_up, const sd2_matrix_t* down,
+                           const uint16_t* x_bf16_dev, int32_t k_tok, float* y_dev,
+                           void* workspace_dev, size_t workspace_bytes, void* stream);
+
+/* ------------------------------------------------------------------ drafter stack
+ * The decoder-linear stack of the draft model (Sec. 3: every decoder linear pruned,
+ * embedding and LM head excluded), run on k_tok tokens.  Between the linears sits a
+ * fixed minimal glue that keeps a block's data dependencies: RMS norm (eps 1e-5, no
+ * learned scale), causal softmax attention among the k_tok in-flight tokens only
+ * (grouped KV heads, scale 1/sqrt(head_dim), no rotary embedding, no cache), SiLU
+ * gating, residual adds; activations are rounded to bf16 where a linear consumes them. */
+
+typedef struct sd2_model_shape {
+    int32_t layers, hidden, q_out, kv_out, inter, n_heads, n_kv, head_dim;
+} sd2_model_shape_t;
+
+typedef struct sd2_model sd2_model_t; /* host-side metadata only; owned by the library */
+
+/* mats: 4 descriptors per layer in the order [q;k;v] fused (q_out+2*kv_out rows),
+ * o, [gate;up] fused (2*inter rows), down.  Descriptors are copied. */
+int sd2_model_create(const sd2_model_shape_t* shape, const sd2_matrix_t* mats, int32_t n_mats,
+                     sd2_model_t** out);
+int sd2_model_destroy(sd2_model_t* model);
+int sd2_drafter_workspace_size(const sd2_model_t* model, int32_t k_tok, size_t* bytes_out);
+/* h_in: device bf16 [k_tok][hidden]; h_out: device fp32 [k_tok][hidden]. */
+int sd2_sparse_drafter_forward(const sd2_model_t* model, const uint16_t* h_in_bf16_dev, int32_t k_tok,
+                               float* h_out_dev, void* workspace_dev, size_t workspace_bytes,
+                               void* stream);
+
+/* ------------------------------------------------------------------ verification
+ * Strict top-1 verification (Eq. 2): accepted_len[b] = number of leading positions
+ * where draft[b][i] == target[b][i]; out_tokens[b] = those drafts, then target[b][n],
+ * then -1 up to k+1 entries.  target[b][i] is the target model's greedy token after
+ * the prompt and draft[b][0..i).  All arrays int32 on the device.  batch >= 0, k >= 0,
+ * vocab > 0.  Ids are compared as opaque integers (they cannot be range-checked
+ * without a device sync; use sd2_check_token_ids_host on host copies). */
+int sd2_greedy_verify(const int32_t* draft_dev, const int32_t* target_dev, int32_t batch, int32_t k,
+                      int32_t vocab, int32_t* accepted_len_dev, int32_t* out_tokens_dev, void* stream);
+/* SD2_ERR_RANGE if any of the n host ids lies outside [0, vocab). */
+int sd2_check_token_ids_host(const int32_t* ids, size_t n, int32_t vocab);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SD2_H */

@@ -1,0 +1,243 @@
+"""ctypes binding of libsd2.so: argument marshalling only, same names as the C ABI.
+
+Device pointers are plain integers (``tensor.data_ptr()``); ``stream`` is the raw
+``hipStream_t`` value (``torch.cuda.current_stream().cuda_stream``) or 0.
+The library is loaded from this directory and there is no fallback: a missing or
+unloadable ``libsd2.so`` raises at import of the first call.
+"""
+
+import ctypes as C
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB = None
+
+
+class SD2Error(RuntimeError):
+    def __init__(self, status, where):
+        self.status = int(status)
+        super().__init__(f"{where}: {strerror(status)} ({status})")
+
+
+class BlobInfo(C.Structure):
+    _fields_ = [
+        ("format", C.c_int32), ("n_out", C.c_int32), ("k_in", C.c_int32),
+        ("n_strips", C.c_int32), ("n_slabs", C.c_int32), ("n_tiles", C.c_int32),
+        ("max_tile_nnz", C.c_int32), ("reserved0", C.c_int32),
+        ("nnz", C.c_uint64), ("total_bytes", C.c_uint64), ("useful_bytes", C.c_uint64),
+        ("mask_off", C.c_uint64), ("val_off", C.c_uint64),
+        ("checksum", C.c_uint32), ("reserved", C.c_uint32),
+    ]
+
+    def asdict(self):
+        return {n: int(getattr(self, n)) for n, _ in self._fields_ if not n.startswith("reserved")}
+
+
+class Matrix(C.Structure):
+    _fields_ = [("kind", C.c_int32), ("reserved", C.c_int32), ("data_dev", C.c_void_p), ("info", BlobInfo)]
+
+
+class ModelShape(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in
+                ("layers", "hidden", "q_out", "kv_out", "inter", "n_heads", "n_kv", "head_dim")]
+
+
+class Model:
+    """Owns an sd2_model_t*; keeps the descriptors' device tensors alive via ``keep``."""
+
+    def __init__(self, handle, keep=None):
+        self.handle = handle
+        self.keep = keep
+
+    def close(self):
+        if self.handle:
+            lib().sd2_model_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def lib_path():
+    return os.path.join(_HERE, "libsd2.so")
+
+
+def lib():
+    global _LIB
+    if _LIB is None:
+        path = lib_path()
+        if not os.path.exists(path):
+            raise ImportError(f"{path} is missing: run `python -m paper_2504_08838_amd.build` (there is no CPU fallback)")
+        L = C.CDLL(path)
+        vp, i32, sz = C.c_void_p, C.c_int32, C.c_size_t
+        psz = C.POINTER(C.c_size_t)
+        pinfo, pmat = C.POINTER(BlobInfo), C.POINTER(Matrix)
+        sig = {
+            "sd2_strerror": (C.c_char_p, [C.c_int]),
+            "sd2_version": (C.c_int, []),
+            "sd2_pack_sparse_size": (C.c_int, [vp, i32, i32, i32, psz]),
+            "sd2_pack_sparse": (C.c_int, [vp, i32, i32, i32, vp, sz, psz]),
+            "sd2_unpack_sparse": (C.c_int, [vp, sz, vp, i32, i32]),
+            "sd2_blob_info": (C.c_int, [vp, sz, pinfo]),
+            "sd2_blob_validate": (C.c_int, [vp, sz]),
+            "sd2_matrix_init_sparse": (C.c_int, [pmat, vp, sz, vp]),
+            "sd2_matrix_init_dense": (C.c_int, [pmat, vp, i32, i32]),
+            "sd2_linear_workspace_size": (C.c_int, [pmat, i32, psz]),
+            "sd2_sparse_linear": (C.c_int, [pmat, vp, i32, vp, vp, sz, vp]),
+            "sd2_dense_linear": (C.c_int, [pmat, vp, i32, vp, vp, sz, vp]),
+            "sd2_mlp_workspace_size": (C.c_int, [pmat, pmat, i32, psz]),
+            "sd2_sparse_mlp_forward": (C.c_int, [pmat, pmat, vp, i32, vp, vp, sz, vp]),
+            "sd2_model_create": (C.c_int, [C.POINTER(ModelShape), pmat, i32, C.POINTER(vp)]),
+            "sd2_model_destroy": (C.c_int, [vp]),
+            "sd2_drafter_workspace_size": (C.c_int, [vp, i32, psz]),
+            "sd2_sparse_drafter_forward": (C.c_int, [vp, vp, i32, vp, vp, sz, vp]),
+            "sd2_greedy_verify": (C.c_int, [vp, vp, i32, i32, i32, vp, vp, vp]),
+            "sd2_check_token_ids_host": (C.c_int, [vp, sz, i32]),
+        }
+        for name, (res, args) in sig.items():
+            fn = getattr(L, name)
+            fn.restype, fn.argtypes = res, args
+        _LIB = L
+    return _LIB
+
+
+def _check(status, where):
+    if status != 0:
+        raise SD2Error(status, where)
+
+
+def _host_ptr(a):
+    return a.ctypes.data_as(C.c_void_p) if a is not None else None
+
+
+def strerror(status):
+    return lib().sd2_strerror(int(status)).decode()
+
+
+def version():
+    return lib().sd2_version()
+
+
+def _w_host(w_bits):
+    w = np.ascontiguousarray(w_bits, dtype=np.uint16)
+    if w.ndim != 2:
+        raise ValueError("w_bits must be [n_out][k_in]")
+    return w
+
+
+def pack_sparse_size(w_bits, fmt=0):
+    w = _w_host(w_bits)
+    n = C.c_size_t()
+    _check(lib().sd2_pack_sparse_size(_host_ptr(w), w.shape[0], w.shape[1], fmt, C.byref(n)), "sd2_pack_sparse_size")
+    return n.value
+
+
+def pack_sparse(w_bits, fmt=0, out=None):
+    """Returns the blob as a numpy uint8 array (host)."""
+    w = _w_host(w_bits)
+    if out is None:
+        out = np.empty(pack_sparse_size(w, fmt), dtype=np.uint8)
+    written = C.c_size_t()
+    _check(lib().sd2_pack_sparse(_host_ptr(w), w.shape[0], w.shape[1], fmt, _host_ptr(out), out.nbytes,
+                                 C.byref(written)), "sd2_pack_sparse")
+    return out[:written.value]
+
+
+def unpack_sparse(blob, n_out, k_in):
+    b = np.ascontiguousarray(blob, dtype=np.uint8)
+    w = np.empty((n_out, k_in), dtype=np.uint16)
+    _check(lib().sd2_unpack_sparse(_host_ptr(b), b.nbytes, _host_ptr(w), n_out, k_in), "sd2_unpack_sparse")
+    return w
+
+
+def blob_info(blob):
+    b = np.ascontiguousarray(blob, dtype=np.uint8)
+    info = BlobInfo()
+    _check(lib().sd2_blob_info(_host_ptr(b), b.nbytes, C.byref(info)), "sd2_blob_info")
+    return info
+
+
+def blob_validate(blob):
+    b = np.ascontiguousarray(blob, dtype=np.uint8)
+    _check(lib().sd2_blob_validate(_host_ptr(b), b.nbytes), "sd2_blob_validate")
+
+
+def matrix_init_sparse(blob_host, blob_dev_ptr):
+    b = np.ascontiguousarray(blob_host, dtype=np.uint8)
+    m = Matrix()
+    _check(lib().sd2_matrix_init_sparse(C.byref(m), _host_ptr(b), b.nbytes, C.c_void_p(blob_dev_ptr)),
+           "sd2_matrix_init_sparse")
+    return m
+
+
+def matrix_init_dense(w_dev_ptr, n_out, k_in):
+    m = Matrix()
+    _check(lib().sd2_matrix_init_dense(C.byref(m), C.c_void_p(w_dev_ptr), n_out, k_in), "sd2_matrix_init_dense")
+    return m
+
+
+def linear_workspace_size(m, k_tok):
+    n = C.c_size_t()
+    _check(lib().sd2_linear_workspace_size(C.byref(m), k_tok, C.byref(n)), "sd2_linear_workspace_size")
+    return n.value
+
+
+def sparse_linear(m, x_ptr, k_tok, y_ptr, ws_ptr=0, ws_bytes=0, stream=0):
+    _check(lib().sd2_sparse_linear(C.byref(m), C.c_void_p(x_ptr), k_tok, C.c_void_p(y_ptr), C.c_void_p(ws_ptr),
+                                   ws_bytes, C.c_void_p(stream)), "sd2_sparse_linear")
+
+
+def dense_linear(m, x_ptr, k_tok, y_ptr, ws_ptr=0, ws_bytes=0, stream=0):
+    _check(lib().sd2_dense_linear(C.byref(m), C.c_void_p(x_ptr), k_tok, C.c_void_p(y_ptr), C.c_void_p(ws_ptr),
+                                  ws_bytes, C.c_void_p(stream)), "sd2_dense_linear")
+
+
+def mlp_workspace_size(gate_up, down, k_tok):
+    n = C.c_size_t()
+    _check(lib().sd2_mlp_workspace_size(C.byref(gate_up), C.byref(down), k_tok, C.byref(n)), "sd2_mlp_workspace_size")
+    return n.value
+
+
+def sparse_mlp_forward(gate_up, down, x_ptr, k_tok, y_ptr, ws_ptr, ws_bytes, stream=0):
+    _check(lib().sd2_sparse_mlp_forward(C.byref(gate_up), C.byref(down), C.c_void_p(x_ptr), k_tok, C.c_void_p(y_ptr),
+                                        C.c_void_p(ws_ptr), ws_bytes, C.c_void_p(stream)), "sd2_sparse_mlp_forward")
+
+
+def model_create(shape, mats, keep=None):
+    """shape: ModelShape; mats: sequence of Matrix (4 per layer: qkv, o, gate_up, down)."""
+    arr = (Matrix * max(len(mats), 1))(*mats)
+    handle = C.c_void_p()
+    _check(lib().sd2_model_create(C.byref(shape), arr, len(mats), C.byref(handle)), "sd2_model_create")
+    return Model(handle, keep)
+
+
+def model_destroy(model):
+    model.close()
+
+
+def drafter_workspace_size(model, k_tok):
+    n = C.c_size_t()
+    _check(lib().sd2_drafter_workspace_size(model.handle, k_tok, C.byref(n)), "sd2_drafter_workspace_size")
+    return n.value
+
+
+def sparse_drafter_forward(model, h_in_ptr, k_tok, h_out_ptr, ws_ptr, ws_bytes, stream=0):
+    _check(lib().sd2_sparse_drafter_forward(model.handle, C.c_void_p(h_in_ptr), k_tok, C.c_void_p(h_out_ptr),
+                                            C.c_void_p(ws_ptr), ws_bytes, C.c_void_p(stream)),
+           "sd2_sparse_drafter_forward")
+
+
+def greedy_verify(draft_ptr, target_ptr, batch, k, vocab, accepted_ptr, out_tokens_ptr, stream=0):
+    _check(lib().sd2_greedy_verify(C.c_void_p(draft_ptr), C.c_void_p(target_ptr), batch, k, vocab,
+                                   C.c_void_p(accepted_ptr), C.c_void_p(out_tokens_ptr), C.c_void_p(stream)),
+           "sd2_greedy_verify")
+
+
+def check_token_ids_host(ids, vocab):
+    a = np.ascontiguousarray(ids, dtype=np.int32)
+    _check(lib().sd2_check_token_ids_host(_host_ptr(a), a.size, vocab), "sd2_check_token_ids_host")

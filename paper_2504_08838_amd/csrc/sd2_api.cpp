@@ -1,0 +1,315 @@
+// C ABI of libsd2 (see include/sd2.h): argument checks on the host, then launches.
+#include <string.h>
+
+#include <algorithm>
+#include <new>
+#include <vector>
+
+#include "sd2_format.h"
+#include "sd2_internal.h"
+
+using namespace sd2;
+
+struct sd2_model {
+    sd2_model_shape_t shape;
+    std::vector<sd2_matrix_t> mats;  // 4 per layer: qkv, o, gate_up, down
+};
+
+namespace {
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+int check_matrix(const sd2_matrix_t* m, int kind) {
+    if (!m) return SD2_ERR_NULL;
+    if (m->kind != kind) return SD2_ERR_FORMAT;
+    if (!m->data_dev) return SD2_ERR_NULL;
+    if (!aligned16(m->data_dev)) return SD2_ERR_BUFFER;
+    const sd2_blob_info_t& i = m->info;
+    if (i.n_out < 1 || i.k_in < 64 || i.k_in % 64) return SD2_ERR_SHAPE;
+    if (i.n_strips != (int32_t)ceil_div((uint32_t)i.n_out, kStripRows) ||
+        i.n_slabs != (int32_t)ceil_div((uint32_t)i.k_in, kSlabCols) || (int64_t)i.n_strips * i.n_slabs != i.n_tiles)
+        return SD2_ERR_FORMAT;
+    if (i.max_tile_nnz < 0 || i.max_tile_nnz > kStripRows * kSlabCols) return SD2_ERR_FORMAT;
+    return SD2_OK;
+}
+
+MatArgs mat_args(const sd2_matrix_t* m) {
+    MatArgs a;
+    memset(&a, 0, sizeof(a));
+    const uint8_t* base = static_cast<const uint8_t*>(m->data_dev);
+    if (m->kind == SD2_KIND_SPARSE) {
+        a.dir = base + kHeaderBytes;
+        a.masks = reinterpret_cast<const uint2*>(base + m->info.mask_off);
+        a.vals = reinterpret_cast<const uint16_t*>(base + m->info.val_off);
+    } else {
+        a.w = reinterpret_cast<const uint16_t*>(base);
+    }
+    a.n_out = m->info.n_out;
+    a.k_in = m->info.k_in;
+    a.n_strips = m->info.n_strips;
+    a.n_slabs = m->info.n_slabs;
+    a.n_tiles = m->info.n_tiles;
+    a.max_tile_nnz = m->info.max_tile_nnz;
+    return a;
+}
+
+size_t partial_bytes(const sd2_matrix_t* m, int k_tok) {
+    return (size_t)m->info.n_slabs * (size_t)k_tok * (size_t)m->info.n_out * sizeof(float);
+}
+
+int check_tokens(int32_t k_tok) { return (k_tok < 1 || k_tok > SD2_MAX_TOKENS) ? SD2_ERR_RANGE : SD2_OK; }
+
+hipError_t run_linear(const sd2_matrix_t* m, const uint16_t* x, int k_tok, float* out, hipStream_t s) {
+    MatArgs ma = mat_args(m);
+    LinArgs la{x, k_tok, out};
+    return m->kind == SD2_KIND_SPARSE ? launch_sparse_linear(ma, la, s) : launch_dense_linear(ma, la, s);
+}
+
+int linear_entry(const sd2_matrix_t* m, int kind, const uint16_t* x, int32_t k_tok, float* y, void* ws,
+                 size_t ws_bytes, void* stream) {
+    int rc = check_matrix(m, kind);
+    if (rc != SD2_OK) return rc;
+    if (!x || !y) return SD2_ERR_NULL;
+    if ((rc = check_tokens(k_tok)) != SD2_OK) return rc;
+    if (!aligned16(x) || !aligned16(y)) return SD2_ERR_BUFFER;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (m->info.n_slabs == 1) {
+        return run_linear(m, x, k_tok, y, s) == hipSuccess ? SD2_OK : SD2_ERR_HIP;
+    }
+    if (!ws) return SD2_ERR_NULL;
+    if (!aligned16(ws) || ws_bytes < partial_bytes(m, k_tok)) return SD2_ERR_BUFFER;
+    float* part = static_cast<float*>(ws);
+    if (run_linear(m, x, k_tok, part, s) != hipSuccess) return SD2_ERR_HIP;
+    if (launch_reduce_partials(part, m->info.n_slabs, (size_t)k_tok * m->info.n_out, y, s) != hipSuccess)
+        return SD2_ERR_HIP;
+    return SD2_OK;
+}
+
+struct StackLayout {
+    size_t act_off, part_off, total;
+};
+
+StackLayout stack_layout(const sd2_model* md, int k_tok) {
+    const sd2_model_shape_t& sh = md->shape;
+    StackLayout L;
+    const size_t widest = (size_t)std::max(std::max(sh.hidden, sh.q_out), sh.inter);
+    L.act_off = 0;
+    size_t part = 0;
+    for (const sd2_matrix_t& m : md->mats) part = std::max(part, partial_bytes(&m, k_tok));
+    L.part_off = align256((size_t)k_tok * widest * sizeof(uint16_t));
+    L.total = L.part_off + align256(part);
+    return L;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* sd2_strerror(int status) {
+    switch (status) {
+        case SD2_OK: return "ok";
+        case SD2_ERR_NULL: return "null pointer";
+        case SD2_ERR_SHAPE: return "bad shape";
+        case SD2_ERR_FORMAT: return "bad format or geometry";
+        case SD2_ERR_BUFFER: return "buffer too small or misaligned";
+        case SD2_ERR_BLOB: return "corrupt blob";
+        case SD2_ERR_RANGE: return "value out of range";
+        case SD2_ERR_HIP: return "HIP call failed";
+        case SD2_ERR_UNSUPPORTED: return "not implemented in this build";
+        default: return "unknown status";
+    }
+}
+
+int sd2_version(void) { return 100; }
+
+int sd2_matrix_init_sparse(sd2_matrix_t* m, const void* blob_host, size_t blob_bytes, const void* blob_dev) {
+    if (!m || !blob_host || !blob_dev) return SD2_ERR_NULL;
+    if (!aligned16(blob_dev)) return SD2_ERR_BUFFER;
+    Header h;
+    int rc = parse_header(blob_host, blob_bytes, &h);
+    if (rc != SD2_OK) return rc;
+    memset(m, 0, sizeof(*m));
+    m->kind = SD2_KIND_SPARSE;
+    m->data_dev = blob_dev;
+    info_from_header(h, &m->info);
+    return SD2_OK;
+}
+
+int sd2_matrix_init_dense(sd2_matrix_t* m, const uint16_t* w_dev, int32_t n_out, int32_t k_in) {
+    if (!m || !w_dev) return SD2_ERR_NULL;
+    if (!aligned16(w_dev)) return SD2_ERR_BUFFER;
+    if (n_out < 1 || k_in < 64 || (k_in % 64) != 0 || (uint64_t)n_out * (uint64_t)k_in > (1ull << 36))
+        return SD2_ERR_SHAPE;
+    memset(m, 0, sizeof(*m));
+    m->kind = SD2_KIND_DENSE;
+    m->data_dev = w_dev;
+    sd2_blob_info_t& i = m->info;
+    i.n_out = n_out;
+    i.k_in = k_in;
+    i.n_strips = (int32_t)ceil_div((uint32_t)n_out, kStripRows);
+    i.n_slabs = (int32_t)ceil_div((uint32_t)k_in, kSlabCols);
+    i.n_tiles = i.n_strips * i.n_slabs;
+    i.max_tile_nnz = kStripRows * kSlabCols;
+    i.nnz = (uint64_t)n_out * k_in;
+    i.total_bytes = i.useful_bytes = 2 * i.nnz;
+    return SD2_OK;
+}
+
+int sd2_linear_workspace_size(const sd2_matrix_t* m, int32_t k_tok, size_t* bytes_out) {
+    if (!m || !bytes_out) return SD2_ERR_NULL;
+    if (m->kind != SD2_KIND_SPARSE && m->kind != SD2_KIND_DENSE) return SD2_ERR_FORMAT;
+    int rc = check_tokens(k_tok);
+    if (rc != SD2_OK) return rc;
+    *bytes_out = m->info.n_slabs > 1 ? partial_bytes(m, k_tok) : 0;
+    return SD2_OK;
+}
+
+int sd2_sparse_linear(const sd2_matrix_t* m, const uint16_t* x, int32_t k_tok, float* y, void* ws, size_t ws_bytes,
+                      void* stream) {
+    return linear_entry(m, SD2_KIND_SPARSE, x, k_tok, y, ws, ws_bytes, stream);
+}
+
+int sd2_dense_linear(const sd2_matrix_t* m, const uint16_t* x, int32_t k_tok, float* y, void* ws, size_t ws_bytes,
+                     void* stream) {
+    return linear_entry(m, SD2_KIND_DENSE, x, k_tok, y, ws, ws_bytes, stream);
+}
+
+static int mlp_check(const sd2_matrix_t* gu, const sd2_matrix_t* dn) {
+    if (!gu || !dn) return SD2_ERR_NULL;
+    int rc = check_matrix(gu, gu->kind);
+    if (rc == SD2_OK) rc = check_matrix(dn, dn->kind);
+    if (rc != SD2_OK) return rc;
+    if ((gu->kind != SD2_KIND_SPARSE && gu->kind != SD2_KIND_DENSE) || gu->kind != dn->kind) return SD2_ERR_FORMAT;
+    if (gu->info.n_out % 2 || gu->info.n_out / 2 != dn->info.k_in) return SD2_ERR_SHAPE;
+    return SD2_OK;
+}
+
+int sd2_mlp_workspace_size(const sd2_matrix_t* gu, const sd2_matrix_t* dn, int32_t k_tok, size_t* bytes_out) {
+    if (!bytes_out) return SD2_ERR_NULL;
+    int rc = mlp_check(gu, dn);
+    if (rc == SD2_OK) rc = check_tokens(k_tok);
+    if (rc != SD2_OK) return rc;
+    *bytes_out = align256((size_t)k_tok * dn->info.k_in * sizeof(uint16_t)) +
+                 align256(std::max(partial_bytes(gu, k_tok), partial_bytes(dn, k_tok)));
+    return SD2_OK;
+}
+
+int sd2_sparse_mlp_forward(const sd2_matrix_t* gu, const sd2_matrix_t* dn, const uint16_t* x, int32_t k_tok, float* y,
+                           void* ws, size_t ws_bytes, void* stream) {
+    size_t need = 0;
+    int rc = sd2_mlp_workspace_size(gu, dn, k_tok, &need);
+    if (rc != SD2_OK) return rc;
+    if (!x || !y || !ws) return SD2_ERR_NULL;
+    if (!aligned16(x) || !aligned16(y) || !aligned16(ws) || ws_bytes < need) return SD2_ERR_BUFFER;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int inter = dn->info.k_in;
+    uint16_t* act = static_cast<uint16_t*>(ws);
+    float* part = reinterpret_cast<float*>(static_cast<uint8_t*>(ws) + align256((size_t)k_tok * inter * sizeof(uint16_t)));
+    if (run_linear(gu, x, k_tok, part, s) != hipSuccess) return SD2_ERR_HIP;
+    if (launch_silu_mul(part, gu->info.n_slabs, k_tok, inter, act, s) != hipSuccess) return SD2_ERR_HIP;
+    if (dn->info.n_slabs == 1) return run_linear(dn, act, k_tok, y, s) == hipSuccess ? SD2_OK : SD2_ERR_HIP;
+    if (run_linear(dn, act, k_tok, part, s) != hipSuccess) return SD2_ERR_HIP;
+    if (launch_reduce_partials(part, dn->info.n_slabs, (size_t)k_tok * dn->info.n_out, y, s) != hipSuccess)
+        return SD2_ERR_HIP;
+    return SD2_OK;
+}
+
+int sd2_model_create(const sd2_model_shape_t* sh, const sd2_matrix_t* mats, int32_t n_mats, sd2_model_t** out) {
+    if (!sh || !out) return SD2_ERR_NULL;
+    *out = nullptr;
+    if (sh->layers < 0 || sh->hidden < 64 || sh->q_out < 64 || sh->kv_out < 64 || sh->inter < 64 || sh->n_heads < 1 ||
+        sh->n_kv < 1 || sh->head_dim < 1 || sh->head_dim > 256)
+        return SD2_ERR_SHAPE;
+    if (sh->n_heads % sh->n_kv || (int64_t)sh->n_heads * sh->head_dim != sh->q_out ||
+        (int64_t)sh->n_kv * sh->head_dim != sh->kv_out)
+        return SD2_ERR_SHAPE;
+    if (n_mats != 4 * sh->layers) return SD2_ERR_SHAPE;
+    if (n_mats > 0 && !mats) return SD2_ERR_NULL;
+    const int want[4][2] = {{sh->q_out + 2 * sh->kv_out, sh->hidden},
+                            {sh->hidden, sh->q_out},
+                            {2 * sh->inter, sh->hidden},
+                            {sh->hidden, sh->inter}};
+    for (int i = 0; i < n_mats; ++i) {
+        const sd2_matrix_t* m = mats + i;
+        if (m->kind != SD2_KIND_SPARSE && m->kind != SD2_KIND_DENSE) return SD2_ERR_FORMAT;
+        int rc = check_matrix(m, m->kind);
+        if (rc != SD2_OK) return rc;
+        if (m->info.n_out != want[i % 4][0] || m->info.k_in != want[i % 4][1]) return SD2_ERR_SHAPE;
+    }
+    sd2_model* md = new (std::nothrow) sd2_model;
+    if (!md) return SD2_ERR_BUFFER;
+    md->shape = *sh;
+    md->mats.assign(mats, mats + n_mats);
+    *out = md;
+    return SD2_OK;
+}
+
+int sd2_model_destroy(sd2_model_t* model) {
+    delete model;
+    return SD2_OK;
+}
+
+int sd2_drafter_workspace_size(const sd2_model_t* model, int32_t k_tok, size_t* bytes_out) {
+    if (!model || !bytes_out) return SD2_ERR_NULL;
+    int rc = check_tokens(k_tok);
+    if (rc != SD2_OK) return rc;
+    *bytes_out = stack_layout(model, k_tok).total;
+    return SD2_OK;
+}
+
+int sd2_sparse_drafter_forward(const sd2_model_t* md, const uint16_t* h_in, int32_t k_tok, float* h_out, void* ws,
+                               size_t ws_bytes, void* stream) {
+    if (!md || !h_in || !h_out || !ws) return SD2_ERR_NULL;
+    int rc = check_tokens(k_tok);
+    if (rc != SD2_OK) return rc;
+    const StackLayout L = stack_layout(md, k_tok);
+    if (!aligned16(h_in) || !aligned16(h_out) || !aligned16(ws) || ws_bytes < L.total) return SD2_ERR_BUFFER;
+    const sd2_model_shape_t& sh = md->shape;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    uint16_t* act = reinterpret_cast<uint16_t*>(static_cast<uint8_t*>(ws) + L.act_off);
+    float* part = reinterpret_cast<float*>(static_cast<uint8_t*>(ws) + L.part_off);
+    float* h = h_out;  // the residual stream lives in the output buffer
+#define SD2_TRY(expr) \
+    if ((expr) != hipSuccess) return SD2_ERR_HIP
+    SD2_TRY(launch_residual_rmsnorm(h, h_in, nullptr, 0, k_tok, sh.hidden, sh.layers > 0 ? act : nullptr, s));
+    for (int l = 0; l < sh.layers; ++l) {
+        const sd2_matrix_t* qkv = &md->mats[4 * l + 0];
+        const sd2_matrix_t* o = &md->mats[4 * l + 1];
+        const sd2_matrix_t* gu = &md->mats[4 * l + 2];
+        const sd2_matrix_t* dn = &md->mats[4 * l + 3];
+        SD2_TRY(run_linear(qkv, act, k_tok, part, s));
+        SD2_TRY(launch_inflight_attention(part, qkv->info.n_slabs, k_tok, sh.q_out, sh.kv_out, sh.n_heads, sh.n_kv,
+                                          sh.head_dim, act, s));
+        SD2_TRY(run_linear(o, act, k_tok, part, s));
+        SD2_TRY(launch_residual_rmsnorm(h, nullptr, part, o->info.n_slabs, k_tok, sh.hidden, act, s));
+        SD2_TRY(run_linear(gu, act, k_tok, part, s));
+        SD2_TRY(launch_silu_mul(part, gu->info.n_slabs, k_tok, sh.inter, act, s));
+        SD2_TRY(run_linear(dn, act, k_tok, part, s));
+        SD2_TRY(launch_residual_rmsnorm(h, nullptr, part, dn->info.n_slabs, k_tok, sh.hidden,
+                                        l + 1 < sh.layers ? act : nullptr, s));
+    }
+#undef SD2_TRY
+    return SD2_OK;
+}
+
+int sd2_greedy_verify(const int32_t* draft, const int32_t* target, int32_t batch, int32_t k, int32_t vocab,
+                      int32_t* accepted, int32_t* out_tokens, void* stream) {
+    if (batch < 0 || k < 0) return SD2_ERR_SHAPE;
+    if (vocab < 1) return SD2_ERR_RANGE;
+    if (batch == 0) return SD2_OK;
+    if (!target || !accepted || !out_tokens || (k > 0 && !draft)) return SD2_ERR_NULL;
+    if (launch_greedy_verify(draft, target, batch, k, accepted, out_tokens, static_cast<hipStream_t>(stream)) != hipSuccess)
+        return SD2_ERR_HIP;
+    return SD2_OK;
+}
+
+int sd2_check_token_ids_host(const int32_t* ids, size_t n, int32_t vocab) {
+    if (n > 0 && !ids) return SD2_ERR_NULL;
+    if (vocab < 1) return SD2_ERR_RANGE;
+    for (size_t i = 0; i < n; ++i)
+        if (ids[i] < 0 || ids[i] >= vocab) return SD2_ERR_RANGE;
+    return SD2_OK;
+}
+
+}  // extern "C"

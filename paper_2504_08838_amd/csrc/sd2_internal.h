@@ -1,0 +1,48 @@
+// Launch interface between the C ABI layer and the gfx950 kernels.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace sd2 {
+
+// One matrix as the kernels see it.  Sparse: dir/masks/vals point into the device blob.
+// Dense: w points at the row-major bf16 matrix.  The tile geometry is common to both.
+struct MatArgs {
+    const void* dir;       // 48-byte directory entries                      (sparse)
+    const uint2* masks;    // 4 x uint16 per lane and tile                    (sparse)
+    const uint16_t* vals;  // compacted bf16 values                           (sparse)
+    const uint16_t* w;     // [n_out][k_in] bf16                              (dense)
+    int n_out, k_in;
+    int n_strips, n_slabs, n_tiles;
+    int max_tile_nnz;
+};
+
+// Where a linear reads its activations from and where the partial sums go.
+struct LinArgs {
+    const uint16_t* x;  // [k_tok][k_in] bf16
+    int k_tok;
+    float* out;         // n_slabs == 1: y [k_tok][n_out]; else partials [n_slabs][k_tok][n_out]
+};
+
+hipError_t launch_sparse_linear(const MatArgs& m, const LinArgs& a, hipStream_t s);
+hipError_t launch_dense_linear(const MatArgs& m, const LinArgs& a, hipStream_t s);
+
+// y[i] = sum_s part[s][i], i < n  (n = k_tok * n_out)
+hipError_t launch_reduce_partials(const float* part, int n_splits, size_t n, float* y, hipStream_t s);
+
+// h (fp32 [k_tok][hidden]) is initialised from bf16 h_in (first != 0) or updated in place with
+// h += sum_s part[s]; then a = bf16(h / sqrt(mean(h^2) + 1e-5)) is written when a != nullptr.
+hipError_t launch_residual_rmsnorm(float* h, const uint16_t* h_in, const float* part, int n_splits,
+                                   int k_tok, int hidden, uint16_t* a, hipStream_t s);
+
+// Causal softmax attention among the k_tok in-flight tokens; qkv partials [n_splits][k_tok][q_out+2*kv_out].
+hipError_t launch_inflight_attention(const float* part, int n_splits, int k_tok, int q_out, int kv_out,
+                                     int n_heads, int n_kv, int head_dim, uint16_t* ctx, hipStream_t s);
+
+// m[t][j] = bf16( silu(g) * u ), g = sum_s part[s][t][j], u = sum_s part[s][t][inter + j]
+hipError_t launch_silu_mul(const float* part, int n_splits, int k_tok, int inter, uint16_t* m, hipStream_t s);
+
+hipError_t launch_greedy_verify(const int32_t* draft, const int32_t* target, int batch, int k,
+                                int32_t* accepted, int32_t* out_tokens, hipStream_t s);
+
+}  // namespace sd2

@@ -1,0 +1,549 @@
+// gfx950 (CDNA4, MI355X) kernels of libsd2.
+//
+// Sparse linear.  A wavefront walks a contiguous range of 16x256 tiles of the packed matrix.
+// While it decodes one tile out of its private LDS buffer, the compacted stream and the masks
+// of its next tile are already in flight in registers (plain coalesced 16-byte loads that do not
+// depend on the masks).  Decoding, per 16x64 step: every lane owns 16 columns of one row as four
+// nibbles; a wave-wide exclusive prefix sum over the four nibble populations (one packed DPP
+// scan) plus the per-run base from the tile directory gives the position of the lane's values in
+// the stream; a 12-byte LDS window is byte-aligned and spread over the four columns with two
+// byte-permutes whose selectors come from a 16-entry table; the dense 16x32 bf16 fragments go
+// through v_mfma_f32_16x16x32_bf16 against the activations held in registers.  The MFMA is used
+// for the multiply because the decode already leaves a dense fragment in registers and the vector
+// ALU is the scarce unit here; HBM traffic is the compacted stream and nothing else.
+#include "sd2_internal.h"
+
+namespace sd2 {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+struct __attribute__((packed, aligned(4))) Tri32 {
+    uint32_t a, b, c;
+};
+
+union Frag {
+    uint32_t u[4];
+    u32x4 q;
+    bf16x8 v;
+};
+
+// Directory entry of one tile as stored in the blob.
+struct DirEnt {
+    uint32_t val_start;  // 16-byte units from the start of the value section
+    uint32_t nnz;
+    uint32_t base[8];    // 16 x uint16: values of the tile before run (q, h)
+    uint32_t zero[2];
+};
+
+constexpr int kWavesPerBlock = 4;
+
+__device__ __forceinline__ float bf16_to_f32(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
+
+// round to nearest, ties to even (finite inputs)
+__device__ __forceinline__ uint16_t f32_to_bf16(float f) {
+    uint32_t u = __float_as_uint(f);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+// inclusive prefix sum over the 64 lanes of a wavefront
+__device__ __forceinline__ uint32_t wave_incl_scan(uint32_t x) {
+    x += __builtin_amdgcn_update_dpp(0u, x, 0x111, 0xf, 0xf, true);  // row_shr:1
+    x += __builtin_amdgcn_update_dpp(0u, x, 0x112, 0xf, 0xf, true);  // row_shr:2
+    x += __builtin_amdgcn_update_dpp(0u, x, 0x114, 0xf, 0xf, true);  // row_shr:4
+    x += __builtin_amdgcn_update_dpp(0u, x, 0x118, 0xf, 0xf, true);  // row_shr:8
+    x += __builtin_amdgcn_update_dpp(0u, x, 0x142, 0xa, 0xf, true);  // row_bcast:15 -> rows 1,3
+    x += __builtin_amdgcn_update_dpp(0u, x, 0x143, 0xc, 0xf, true);  // row_bcast:31 -> rows 2,3
+    return x;
+}
+
+// exclusive prefix sum: shift the wave by one lane (lane 0 gets 0), then scan
+__device__ __forceinline__ uint32_t wave_excl_scan(uint32_t x) {
+    return wave_incl_scan(__builtin_amdgcn_update_dpp(0u, x, 0x138, 0xf, 0xf, true));  // wave_shr:1
+}
+
+// Byte-permute selectors that spread up to four compacted bf16 values over four columns.
+// Entry [nib] = {selector for columns 0,1 ; selector for columns 2,3}; 0x0c yields a zero byte.
+__device__ __forceinline__ uint2 make_expand_selector(uint32_t nib) {
+    uint32_t sel[2] = {0u, 0u};
+    uint32_t rank = 0;
+    for (uint32_t p = 0; p < 4; ++p) {
+        uint32_t lo = 0x0cu, hi = 0x0cu;
+        if ((nib >> p) & 1u) {
+            lo = 2u * rank;
+            hi = 2u * rank + 1u;
+            ++rank;
+        }
+        sel[p >> 1] |= (lo | (hi << 8)) << (16u * (p & 1u));
+    }
+    return make_uint2(sel[0], sel[1]);
+}
+
+// 16 consecutive bf16 of row `r` (of `n_rows`) starting at column `col`, or zeros outside.
+__device__ __forceinline__ void load_row16(const uint16_t* __restrict__ p, int r, int n_rows, int col, int k_in,
+                                           Frag& b0, Frag& b1) {
+    if (r < n_rows && col < k_in) {
+        const u32x4* q = reinterpret_cast<const u32x4*>(p + (size_t)r * k_in + col);
+        b0.q = q[0];
+        b1.q = q[1];
+    } else {
+        b0.q = u32x4{0, 0, 0, 0};
+        b1.q = u32x4{0, 0, 0, 0};
+    }
+}
+
+// One 16 x k_tok block of results: lane (n = lane & 15, g = lane >> 4) holds rows 4g..4g+3 of token n.
+template <int TG>
+__device__ __forceinline__ void store_tile(const f32x4 (&acc)[TG], float* __restrict__ out, int n_out, int k_tok,
+                                           int strip, int slab, int lane) {
+    const int n = lane & 15, g = lane >> 4;
+    const int row = strip * 16 + 4 * g;
+    float* base = out + (size_t)slab * k_tok * n_out;
+#pragma unroll
+    for (int tg = 0; tg < TG; ++tg) {
+        const int tok = n + 16 * tg;
+        if (tok >= k_tok) continue;
+        float* dst = base + (size_t)tok * n_out + row;
+        if ((n_out & 3) == 0) {
+            if (row < n_out) *reinterpret_cast<float4*>(dst) = make_float4(acc[tg][0], acc[tg][1], acc[tg][2], acc[tg][3]);
+        } else {
+#pragma unroll
+            for (int v = 0; v < 4; ++v)
+                if (row + v < n_out) dst[v] = acc[tg][v];
+        }
+    }
+}
+
+// ------------------------------------------------------------------ sparse linear
+
+// Issue the loads of one tile: MAXCH coalesced 16-byte pieces per lane (clamped to the tile's
+// own pieces, so no lane reads past the blob) and the lane's four 16-bit masks.
+template <int MAXCH>
+__device__ __forceinline__ void issue_tile(u32x4 (&st)[MAXCH], uint2& mk, const uint16_t* __restrict__ vals,
+                                           const uint2* __restrict__ masks, uint32_t val_start, uint32_t nnz, int t,
+                                           int lane) {
+    const u32x4* __restrict__ src = reinterpret_cast<const u32x4*>(vals + (size_t)val_start * 8);
+    const uint32_t n16 = (nnz * 2 + 8 + 15) / 16;  // 8 bytes of slack for the 12-byte windows
+#pragma unroll
+    for (int c = 0; c < MAXCH; ++c) st[c] = src[min((uint32_t)(c * 64 + lane), n16 - 1u)];
+    mk = masks[(size_t)t * 64 + lane];
+}
+
+template <int MAXCH, int TG, bool PREFETCH>
+__device__ __forceinline__ void sparse_tile(u32x4 (&st)[MAXCH], uint2& mk_next, DirEnt& de_cur, DirEnt& de_next,
+                                            Frag (&b)[4][2], int& cur_slab, uint32_t* __restrict__ buf,
+                                            const uint2* __restrict__ lut, const DirEnt* __restrict__ dir,
+                                            const uint2* __restrict__ masks, const uint16_t* __restrict__ vals,
+                                            const uint16_t* __restrict__ x, float* __restrict__ out, int n_out, int k_in,
+                                            int k_tok, int n_strips, int n_tiles, int t, int lane) {
+    const int n = lane & 15, g = lane >> 4;
+    // the staged tile goes to this wave's LDS buffer (its loads were issued one tile ago)
+#pragma unroll
+    for (int c = 0; c < MAXCH; ++c) reinterpret_cast<u32x4*>(buf)[c * 64 + lane] = st[c];
+    const uint2 mk = mk_next;
+    const int strip = t % n_strips, slab = t / n_strips;
+    const int col0 = slab * 256 + 16 * g;
+    if (TG == 1 && slab != cur_slab) {
+        cur_slab = slab;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) load_row16(x, n, k_tok, col0 + 64 * q, k_in, b[q][0], b[q][1]);
+    }
+    if (PREFETCH) {
+        issue_tile<MAXCH>(st, mk_next, vals, masks, de_next.val_start, de_next.nnz, t + 1, lane);
+    }
+    const DirEnt de = de_cur;
+    de_cur = de_next;
+    de_next = dir[min(t + 2, n_tiles - 1)];
+
+    const uint8_t* bufb = reinterpret_cast<const uint8_t*>(buf);
+    const uint32_t m16[4] = {mk.x & 0xffffu, mk.x >> 16, mk.y & 0xffffu, mk.y >> 16};
+    f32x4 acc[TG];
+#pragma unroll
+    for (int tg = 0; tg < TG; ++tg) acc[tg] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const uint32_t bits = m16[q];
+        uint32_t nib[4];
+#pragma unroll
+        for (int h = 0; h < 4; ++h) nib[h] = (bits >> (4 * h)) & 15u;
+        const uint32_t packed = (uint32_t)__builtin_popcount(nib[0]) | ((uint32_t)__builtin_popcount(nib[1]) << 8) |
+                                ((uint32_t)__builtin_popcount(nib[2]) << 16) | ((uint32_t)__builtin_popcount(nib[3]) << 24);
+        const uint32_t ex = wave_excl_scan(packed);  // per nibble: values of lower lanes (<= 252, no carry)
+        Frag f[2];
+#pragma unroll
+        for (int h = 0; h < 4; ++h) {
+            const uint32_t run_base = (de.base[(4 * q + h) >> 1] >> (16 * (h & 1))) & 0xffffu;
+            const uint32_t off = (run_base + ((ex >> (8 * h)) & 0xffu)) * 2u;  // byte offset in the tile's stream
+            const Tri32 tr = *reinterpret_cast<const Tri32*>(bufb + (off & ~3u));
+            const uint32_t w0 = __builtin_amdgcn_alignbyte(tr.b, tr.a, off);
+            const uint32_t w1 = __builtin_amdgcn_alignbyte(tr.c, tr.b, off);
+            const uint2 sel = lut[nib[h]];
+            f[h >> 1].u[2 * (h & 1) + 0] = __builtin_amdgcn_perm(w1, w0, sel.x);
+            f[h >> 1].u[2 * (h & 1) + 1] = __builtin_amdgcn_perm(w1, w0, sel.y);
+        }
+        if (TG == 1) {
+            acc[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f[0].v, b[q][0].v, acc[0], 0, 0, 0);
+            acc[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f[1].v, b[q][1].v, acc[0], 0, 0, 0);
+        } else {
+#pragma unroll
+            for (int tg = 0; tg < TG; ++tg) {
+                Frag x0, x1;
+                load_row16(x, n + 16 * tg, k_tok, col0 + 64 * q, k_in, x0, x1);
+                acc[tg] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f[0].v, x0.v, acc[tg], 0, 0, 0);
+                acc[tg] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f[1].v, x1.v, acc[tg], 0, 0, 0);
+            }
+        }
+    }
+    store_tile<TG>(acc, out, n_out, k_tok, strip, slab, lane);
+}
+
+template <int MAXCH, int TG>
+__global__ __launch_bounds__(256) void sparse_linear_kernel(const DirEnt* __restrict__ dir, const uint2* __restrict__ masks,
+                                                           const uint16_t* __restrict__ vals,
+                                                           const uint16_t* __restrict__ x, float* __restrict__ out,
+                                                           int n_out, int k_in, int k_tok, int n_strips, int n_tiles,
+                                                           int tiles_per_wave) {
+    extern __shared__ uint32_t tile_smem[];
+    __shared__ uint2 lut[16];
+    const int tid = threadIdx.x;
+    if (tid < 16) lut[tid] = make_expand_selector((uint32_t)tid);
+    __syncthreads();
+
+    const int lane = tid & 63, wave = tid >> 6;
+    const int gw = __builtin_amdgcn_readfirstlane((int)blockIdx.x * kWavesPerBlock + wave);
+    const int t0 = gw * tiles_per_wave;
+    const int t1 = min(t0 + tiles_per_wave, n_tiles);
+    if (t0 >= t1) return;
+    uint32_t* buf = tile_smem + wave * (MAXCH * 256);
+
+    u32x4 st[MAXCH];
+    uint2 mk_next;
+    DirEnt de_cur = dir[t0];
+    DirEnt de_next = dir[min(t0 + 1, n_tiles - 1)];
+    issue_tile<MAXCH>(st, mk_next, vals, masks, de_cur.val_start, de_cur.nnz, t0, lane);
+    int cur_slab = -1;
+    Frag b[4][2];
+#pragma unroll 1
+    for (int t = t0; t < t1 - 1; ++t)
+        sparse_tile<MAXCH, TG, true>(st, mk_next, de_cur, de_next, b, cur_slab, buf, lut, dir, masks, vals, x, out, n_out,
+                                     k_in, k_tok, n_strips, n_tiles, t, lane);
+    sparse_tile<MAXCH, TG, false>(st, mk_next, de_cur, de_next, b, cur_slab, buf, lut, dir, masks, vals, x, out, n_out,
+                                  k_in, k_tok, n_strips, n_tiles, t1 - 1, lane);
+}
+
+// ------------------------------------------------------------------ dense bf16 baseline
+// Same tile walk, operand A read straight from the row-major matrix; the next tile's fragments
+// are in flight while the current one goes through the MFMAs.
+
+__device__ __forceinline__ void issue_dense_tile(Frag (&f)[4][2], const uint16_t* __restrict__ w, int n_out, int k_in,
+                                                 int n_strips, int t, int lane) {
+    const int strip = t % n_strips, slab = t / n_strips;
+    const int row = strip * 16 + (lane & 15);
+    const int col0 = slab * 256 + 16 * (lane >> 4);
+#pragma unroll
+    for (int q = 0; q < 4; ++q) load_row16(w, row, n_out, col0 + 64 * q, k_in, f[q][0], f[q][1]);
+}
+
+template <int TG>
+__global__ __launch_bounds__(256) void dense_linear_kernel(const uint16_t* __restrict__ w, const uint16_t* __restrict__ x,
+                                                          float* __restrict__ out, int n_out, int k_in, int k_tok,
+                                                          int n_strips, int n_tiles, int tiles_per_wave) {
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int gw = __builtin_amdgcn_readfirstlane((int)blockIdx.x * kWavesPerBlock + (tid >> 6));
+    const int t0 = gw * tiles_per_wave;
+    const int t1 = min(t0 + tiles_per_wave, n_tiles);
+    if (t0 >= t1) return;
+    const int n = lane & 15, g = lane >> 4;
+    Frag nxt[4][2], b[4][2];
+    issue_dense_tile(nxt, w, n_out, k_in, n_strips, t0, lane);
+    int cur_slab = -1;
+#pragma unroll 1
+    for (int t = t0; t < t1; ++t) {
+        Frag f[4][2];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            f[q][0].q = nxt[q][0].q;
+            f[q][1].q = nxt[q][1].q;
+        }
+        const int strip = t % n_strips, slab = t / n_strips;
+        const int col0 = slab * 256 + 16 * g;
+        if (TG == 1 && slab != cur_slab) {
+            cur_slab = slab;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) load_row16(x, n, k_tok, col0 + 64 * q, k_in, b[q][0], b[q][1]);
+        }
+        issue_dense_tile(nxt, w, n_out, k_in, n_strips, min(t + 1, t1 - 1), lane);
+        f32x4 acc[TG];
+#pragma unroll
+        for (int tg = 0; tg < TG; ++tg) acc[tg] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            if (TG == 1) {
+                acc[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f[q][0].v, b[q][0].v, acc[0], 0, 0, 0);
+                acc[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f[q][1].v, b[q][1].v, acc[0], 0, 0, 0);
+            } else {
+#pragma unroll
+                for (int tg = 0; tg < TG; ++tg) {
+                    Frag x0, x1;
+                    load_row16(x, n + 16 * tg, k_tok, col0 + 64 * q, k_in, x0, x1);
+                    acc[tg] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f[q][0].v, x0.v, acc[tg], 0, 0, 0);
+                    acc[tg] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f[q][1].v, x1.v, acc[tg], 0, 0, 0);
+                }
+            }
+        }
+        store_tile<TG>(acc, out, n_out, k_tok, strip, slab, lane);
+    }
+}
+
+// ------------------------------------------------------------------ launch
+
+static int device_cu_count() {
+    static int cus = 0;
+    if (cus == 0) {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
+            cus = n;
+        else
+            cus = 256;
+    }
+    return cus;
+}
+
+// Tiles per wavefront: enough wavefronts to fill every CU a few times over, then longer ranges
+// so that the prefetch of the next tile has something to overlap with.
+static int tiles_per_wave_for(int n_tiles, int waves_per_cu) {
+    const int target = device_cu_count() * waves_per_cu;
+    return n_tiles <= target ? 1 : (n_tiles + target - 1) / target;
+}
+
+template <int MAXCH, int TG>
+static hipError_t launch_sparse_t(const MatArgs& m, const LinArgs& a, hipStream_t s) {
+    const int tpw = tiles_per_wave_for(m.n_tiles, 16);
+    const int waves = (m.n_tiles + tpw - 1) / tpw;
+    const dim3 grid((unsigned)((waves + kWavesPerBlock - 1) / kWavesPerBlock)), block(64 * kWavesPerBlock);
+    const size_t lds = (size_t)kWavesPerBlock * MAXCH * 1024;
+    hipLaunchKernelGGL((sparse_linear_kernel<MAXCH, TG>), grid, block, lds, s, static_cast<const DirEnt*>(m.dir), m.masks,
+                       m.vals, a.x, a.out, m.n_out, m.k_in, a.k_tok, m.n_strips, m.n_tiles, tpw);
+    return hipGetLastError();
+}
+
+hipError_t launch_sparse_linear(const MatArgs& m, const LinArgs& a, hipStream_t s) {
+    const int tg = (a.k_tok + 15) / 16;
+    // LDS pieces per tile: 2 bytes per value plus 8 bytes of slack, in 1 KiB chunks per wavefront
+    const int chunks = (m.max_tile_nnz * 2 + 8 + 1023) / 1024;
+    if (chunks <= 5) {
+        if (tg == 1) return launch_sparse_t<5, 1>(m, a, s);
+        if (tg == 2) return launch_sparse_t<5, 2>(m, a, s);
+        return launch_sparse_t<5, 4>(m, a, s);
+    }
+    if (tg == 1) return launch_sparse_t<9, 1>(m, a, s);
+    if (tg == 2) return launch_sparse_t<9, 2>(m, a, s);
+    return launch_sparse_t<9, 4>(m, a, s);
+}
+
+template <int TG>
+static hipError_t launch_dense_t(const MatArgs& m, const LinArgs& a, hipStream_t s) {
+    const int tpw = tiles_per_wave_for(m.n_tiles, 16);
+    const int waves = (m.n_tiles + tpw - 1) / tpw;
+    const dim3 grid((unsigned)((waves + kWavesPerBlock - 1) / kWavesPerBlock)), block(64 * kWavesPerBlock);
+    hipLaunchKernelGGL((dense_linear_kernel<TG>), grid, block, 0, s, m.w, a.x, a.out, m.n_out, m.k_in, a.k_tok, m.n_strips,
+                       m.n_tiles, tpw);
+    return hipGetLastError();
+}
+
+hipError_t launch_dense_linear(const MatArgs& m, const LinArgs& a, hipStream_t s) {
+    const int tg = (a.k_tok + 15) / 16;
+    if (tg == 1) return launch_dense_t<1>(m, a, s);
+    if (tg == 2) return launch_dense_t<2>(m, a, s);
+    return launch_dense_t<4>(m, a, s);
+}
+
+// ------------------------------------------------------------------ glue
+
+__global__ __launch_bounds__(256) void reduce_partials_kernel(const float* __restrict__ part, int n_splits, size_t n,
+                                                             float* __restrict__ y) {
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= n) return;
+    float acc = 0.f;
+    for (int s = 0; s < n_splits; ++s) acc += part[(size_t)s * n + i];
+    y[i] = acc;
+}
+
+hipError_t launch_reduce_partials(const float* part, int n_splits, size_t n, float* y, hipStream_t s) {
+    if (n == 0) return hipSuccess;
+    hipLaunchKernelGGL(reduce_partials_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, part, n_splits, n, y);
+    return hipGetLastError();
+}
+
+__device__ __forceinline__ float block_sum_256(float v, float* red) {
+    const int tid = threadIdx.x;
+    red[tid] = v;
+    __syncthreads();
+    for (int off = 128; off > 0; off >>= 1) {
+        if (tid < off) red[tid] += red[tid + off];
+        __syncthreads();
+    }
+    const float r = red[0];
+    __syncthreads();
+    return r;
+}
+
+__global__ __launch_bounds__(256) void residual_rmsnorm_kernel(float* __restrict__ h, const uint16_t* __restrict__ h_in,
+                                                              const float* __restrict__ part, int n_splits, int k_tok,
+                                                              int hidden, uint16_t* __restrict__ a) {
+    __shared__ float red[256];
+    const int t = blockIdx.x;
+    float* hr = h + (size_t)t * hidden;
+    const size_t stride = (size_t)k_tok * hidden;
+    float ss = 0.f;
+    for (int i = threadIdx.x; i < hidden; i += 256) {
+        float v;
+        if (h_in) {
+            v = bf16_to_f32(h_in[(size_t)t * hidden + i]);
+        } else {
+            float add = 0.f;
+            for (int s = 0; s < n_splits; ++s) add += part[(size_t)s * stride + (size_t)t * hidden + i];
+            v = hr[i] + add;
+        }
+        hr[i] = v;
+        ss += v * v;
+    }
+    if (!a) return;
+    const float tot = block_sum_256(ss, red);
+    const float inv = 1.0f / sqrtf(tot / (float)hidden + 1e-5f);
+    for (int i = threadIdx.x; i < hidden; i += 256) a[(size_t)t * hidden + i] = f32_to_bf16(hr[i] * inv);
+}
+
+hipError_t launch_residual_rmsnorm(float* h, const uint16_t* h_in, const float* part, int n_splits, int k_tok,
+                                   int hidden, uint16_t* a, hipStream_t s) {
+    hipLaunchKernelGGL(residual_rmsnorm_kernel, dim3((unsigned)k_tok), dim3(256), 0, s, h, h_in, part, n_splits, k_tok,
+                       hidden, a);
+    return hipGetLastError();
+}
+
+__global__ __launch_bounds__(256) void inflight_attention_kernel(const float* __restrict__ part, int n_splits, int k_tok,
+                                                                int q_out, int kv_out, int n_heads, int n_kv, int D,
+                                                                uint16_t* __restrict__ ctx) {
+    extern __shared__ float smem[];
+    float* sq = smem;
+    float* sk = sq + k_tok * D;
+    float* sv = sk + k_tok * D;
+    float* sp = sv + k_tok * D;  // [k_tok][k_tok]
+    const int head = blockIdx.x;
+    const int grp = head / (n_heads / n_kv);
+    const int n_out = q_out + 2 * kv_out;
+    const size_t stride = (size_t)k_tok * n_out;
+    for (int idx = threadIdx.x; idx < k_tok * D; idx += 256) {
+        const int t = idx / D, d = idx % D;
+        const size_t row = (size_t)t * n_out;
+        float q = 0.f, k = 0.f, v = 0.f;
+        for (int s = 0; s < n_splits; ++s) {
+            const float* p = part + (size_t)s * stride + row;
+            q += p[head * D + d];
+            k += p[q_out + grp * D + d];
+            v += p[q_out + kv_out + grp * D + d];
+        }
+        sq[idx] = q;
+        sk[idx] = k;
+        sv[idx] = v;
+    }
+    __syncthreads();
+    const float scale = 1.0f / sqrtf((float)D);
+    for (int idx = threadIdx.x; idx < k_tok * k_tok; idx += 256) {
+        const int i = idx / k_tok, j = idx % k_tok;
+        float dot = 0.f;
+        if (j <= i)
+            for (int d = 0; d < D; ++d) dot += sq[i * D + d] * sk[j * D + d];
+        sp[idx] = dot * scale;
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < k_tok; i += 256) {
+        float mx = sp[i * k_tok];
+        for (int j = 1; j <= i; ++j) mx = fmaxf(mx, sp[i * k_tok + j]);
+        float sum = 0.f;
+        for (int j = 0; j <= i; ++j) {
+            const float e = expf(sp[i * k_tok + j] - mx);
+            sp[i * k_tok + j] = e;
+            sum += e;
+        }
+        const float inv = 1.0f / sum;
+        for (int j = 0; j <= i; ++j) sp[i * k_tok + j] *= inv;
+    }
+    __syncthreads();
+    for (int idx = threadIdx.x; idx < k_tok * D; idx += 256) {
+        const int i = idx / D, d = idx % D;
+        float o = 0.f;
+        for (int j = 0; j <= i; ++j) o += sp[i * k_tok + j] * sv[j * D + d];
+        ctx[(size_t)i * q_out + head * D + d] = f32_to_bf16(o);
+    }
+}
+
+hipError_t launch_inflight_attention(const float* part, int n_splits, int k_tok, int q_out, int kv_out, int n_heads,
+                                     int n_kv, int head_dim, uint16_t* ctx, hipStream_t s) {
+    const size_t lds = ((size_t)3 * k_tok * head_dim + (size_t)k_tok * k_tok) * sizeof(float);
+    if (lds > 64 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(inflight_attention_kernel),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL(inflight_attention_kernel, dim3((unsigned)n_heads), dim3(256), lds, s, part, n_splits, k_tok,
+                       q_out, kv_out, n_heads, n_kv, head_dim, ctx);
+    return hipGetLastError();
+}
+
+__global__ __launch_bounds__(256) void silu_mul_kernel(const float* __restrict__ part, int n_splits, int k_tok, int inter,
+                                                      uint16_t* __restrict__ mo) {
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    const size_t n = (size_t)k_tok * inter;
+    if (i >= n) return;
+    const int t = (int)(i / inter), j = (int)(i % inter);
+    const size_t stride = (size_t)k_tok * 2 * inter;
+    float gsum = 0.f, usum = 0.f;
+    for (int s = 0; s < n_splits; ++s) {
+        const float* p = part + (size_t)s * stride + (size_t)t * 2 * inter;
+        gsum += p[j];
+        usum += p[inter + j];
+    }
+    const float act = gsum / (1.0f + expf(-gsum));
+    mo[i] = f32_to_bf16(act * usum);
+}
+
+hipError_t launch_silu_mul(const float* part, int n_splits, int k_tok, int inter, uint16_t* m, hipStream_t s) {
+    const size_t n = (size_t)k_tok * inter;
+    hipLaunchKernelGGL(silu_mul_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, part, n_splits, k_tok, inter, m);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ verification (Eq. 2)
+
+__global__ __launch_bounds__(64) void greedy_verify_kernel(const int32_t* __restrict__ draft, const int32_t* __restrict__ target,
+                                                          int batch, int k, int32_t* __restrict__ accepted,
+                                                          int32_t* __restrict__ out_tokens) {
+    const int b = blockIdx.x * 64 + threadIdx.x;
+    if (b >= batch) return;
+    const int32_t* d = draft + (size_t)b * k;
+    const int32_t* t = target + (size_t)b * (k + 1);
+    int32_t* o = out_tokens + (size_t)b * (k + 1);
+    int n = 0;
+    while (n < k && d[n] == t[n]) {
+        o[n] = d[n];
+        ++n;
+    }
+    o[n] = t[n];
+    for (int j = n + 1; j <= k; ++j) o[j] = -1;
+    accepted[b] = n;
+}
+
+hipError_t launch_greedy_verify(const int32_t* draft, const int32_t* target, int batch, int k, int32_t* accepted,
+                                int32_t* out_tokens, hipStream_t s) {
+    if (batch == 0) return hipSuccess;
+    hipLaunchKernelGGL(greedy_verify_kernel, dim3((unsigned)((batch + 63) / 64)), dim3(64), 0, s, draft, target, batch, k,
+                       accepted, out_tokens);
+    return hipGetLastError();
+}
+
+}  // namespace sd2

@@ -1,0 +1,104 @@
+"""The C-ABI library loads, exports every symbol the header declares, and rejects bad
+arguments on the host before any launch (so these run without a GPU)."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2504_08838_amd as sd2
+import sd2_workload as wl
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "sd2.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(sd2_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported():
+    names = _declared()
+    for must in ("sd2_pack_sparse", "sd2_sparse_linear", "sd2_sparse_drafter_forward", "sd2_greedy_verify",
+                 "sd2_dense_linear", "sd2_sparse_mlp_forward"):
+        assert must in names
+    raw = C.CDLL(sd2.lib_path())
+    for n in names:
+        assert hasattr(raw, n), n
+    assert sd2.version() >= 100
+
+
+def test_binding_has_the_same_names():
+    for n in _declared():
+        assert hasattr(sd2, n[len("sd2_"):]), n
+
+
+def _host_matrix():
+    w = wl.gen_weight(12, 5, "q", 64, 512, 50)
+    blob = sd2.pack_sparse(w, 1)
+    return blob, sd2.matrix_init_sparse(blob, 0x1000)   # fake, aligned device address: never dereferenced here
+
+
+def test_linear_argument_checks():
+    blob, m = _host_matrix()
+    assert m.info.n_slabs == 2
+    L = sd2.lib()
+    fake = C.c_void_p(0x2000)
+    assert sd2.linear_workspace_size(m, 5) == 2 * 5 * 64 * 4
+    assert L.sd2_sparse_linear(None, fake, 1, fake, fake, 1 << 20, None) == -1
+    assert L.sd2_sparse_linear(C.byref(m), None, 1, fake, fake, 1 << 20, None) == -1
+    assert L.sd2_sparse_linear(C.byref(m), fake, 0, fake, fake, 1 << 20, None) == -6
+    assert L.sd2_sparse_linear(C.byref(m), fake, 65, fake, fake, 1 << 20, None) == -6
+    assert L.sd2_sparse_linear(C.byref(m), C.c_void_p(0x2002), 1, fake, fake, 1 << 20, None) == -4
+    assert L.sd2_sparse_linear(C.byref(m), fake, 5, fake, fake, 100, None) == -4      # workspace too small
+    assert L.sd2_sparse_linear(C.byref(m), fake, 5, fake, None, 0, None) == -1        # split matrix needs one
+    assert L.sd2_dense_linear(C.byref(m), fake, 1, fake, fake, 1 << 20, None) == -3   # wrong kind
+    with pytest.raises(sd2.SD2Error) as e:
+        sd2.matrix_init_sparse(blob, 0x1001)
+    assert e.value.status == -4
+    bad = blob.copy(); bad[0] = 0
+    with pytest.raises(sd2.SD2Error) as e:
+        sd2.matrix_init_sparse(bad, 0x1000)
+    assert e.value.status == -5
+    with pytest.raises(sd2.SD2Error) as e:
+        sd2.matrix_init_dense(0x1000, 64, 100)
+    assert e.value.status == -2
+
+
+def test_model_argument_checks():
+    shape = sd2.ModelShape(1, 256, 256, 128, 512, 2, 1, 128)
+    dims = [(512, 256), (256, 256), (1024, 256), (256, 512)]
+    mats = [sd2.matrix_init_dense(0x1000, n, k) for n, k in dims]
+    model = sd2.model_create(shape, mats)
+    assert sd2.drafter_workspace_size(model, 5) > 0
+    L = sd2.lib()
+    fake = C.c_void_p(0x2000)
+    assert L.sd2_sparse_drafter_forward(model.handle, fake, 5, fake, fake, 16, None) == -4
+    assert L.sd2_sparse_drafter_forward(model.handle, fake, 99, fake, fake, 1 << 30, None) == -6
+    assert L.sd2_sparse_drafter_forward(None, fake, 5, fake, fake, 1 << 30, None) == -1
+    model.close()
+    with pytest.raises(sd2.SD2Error) as e:
+        sd2.model_create(shape, mats[:3])
+    assert e.value.status == -2
+    with pytest.raises(sd2.SD2Error) as e:
+        sd2.model_create(shape, [mats[1], mats[0], mats[2], mats[3]])
+    assert e.value.status == -2
+    with pytest.raises(sd2.SD2Error):
+        sd2.model_create(sd2.ModelShape(1, 256, 256, 128, 512, 3, 1, 128), mats)
+
+
+def test_verify_argument_checks():
+    L = sd2.lib()
+    fake = C.c_void_p(0x2000)
+    assert L.sd2_greedy_verify(fake, fake, -1, 5, 100, fake, fake, None) == -2
+    assert L.sd2_greedy_verify(fake, fake, 4, 5, 0, fake, fake, None) == -6
+    assert L.sd2_greedy_verify(None, fake, 4, 5, 100, fake, fake, None) == -1
+    assert L.sd2_greedy_verify(fake, fake, 0, 5, 100, fake, fake, None) == 0          # empty batch: nothing to do
+    sd2.check_token_ids_host(np.array([0, 5, 99], dtype=np.int32), 100)
+    with pytest.raises(sd2.SD2Error) as e:
+        sd2.check_token_ids_host(np.array([0, 100], dtype=np.int32), 100)
+    assert e.value.status == -6
+    with pytest.raises(sd2.SD2Error):
+        sd2.check_token_ids_host(np.array([-1], dtype=np.int32), 100)
