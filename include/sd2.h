@@ -130,6 +130,11 @@ int sd2_matrix_init_dense(sd2_matrix_t* m, const uint16_t* w_bf16_dev, int32_t n
 int sd2_linear_workspace_size(const sd2_matrix_t* m, int32_t k_tok, size_t* bytes_out);
 int sd2_sparse_linear(const sd2_matrix_t* m, const uint16_t* x_bf16_dev, int32_t k_tok, float* y_dev,
                       void* workspace_dev, size_t workspace_bytes, void* stream);
+/* The same product without the final add: writes the n_slabs per-slab partial results
+ * [n_slabs][k_tok][n_out] (fp32) to `partials_dev` (>= n_slabs*k_tok*n_out*4 bytes).  This is
+ * what the stack's glue kernels consume; with n_slabs == 1 it equals sd2_sparse_linear. */
+int sd2_sparse_linear_partials(const sd2_matrix_t* m, const uint16_t* x_bf16_dev, int32_t k_tok,
+                               float* partials_dev, size_t partials_bytes, void* stream);
 /* Hand-written dense bf16 baseline for the same shapes; `m` must be a dense descriptor. */
 int sd2_dense_linear(const sd2_matrix_t* m, const uint16_t* x_bf16_dev, int32_t k_tok, float* y_dev,
                      void* workspace_dev, size_t workspace_bytes, void* stream);
@@ -166,6 +171,18 @@ int sd2_drafter_workspace_size(const sd2_model_t* model, int32_t k_tok, size_t* 
 int sd2_sparse_drafter_forward(const sd2_model_t* model, const uint16_t* h_in_bf16_dev, int32_t k_tok,
                                float* h_out_dev, void* workspace_dev, size_t workspace_bytes,
                                void* stream);
+
+/* Debug variant for step-by-step checking: the same forward, which also records, per linear
+ * (4 per layer, in execution order), the fp32 values its input glue read -- the residual
+ * stream for the normed inputs, the q|k|v results for attention, the gate|up results for the
+ * gated product -- and the bf16 activations it handed to the linear.  trace_dev layout:
+ * n_lin x [k_tok][kmax] uint16, then (256-byte aligned) n_lin x [k_tok][smax] float, with
+ * kmax = max(hidden, q_out, inter) and smax = max(hidden, q_out + 2 kv_out, 2 inter). */
+int sd2_drafter_trace_size(const sd2_model_t* model, int32_t k_tok, size_t* bytes_out);
+int sd2_sparse_drafter_forward_trace(const sd2_model_t* model, const uint16_t* h_in_bf16_dev,
+                                     int32_t k_tok, float* h_out_dev, void* workspace_dev,
+                                     size_t workspace_bytes, void* trace_dev, size_t trace_bytes,
+                                     void* stream);
 
 /* ------------------------------------------------------------------ verification
  * Strict top-1 verification (Eq. 2): accepted_len[b] = number of leading positions

@@ -24,6 +24,7 @@ from .binding import (  # noqa: F401
     matrix_init_dense,
     linear_workspace_size,
     sparse_linear,
+    sparse_linear_partials,
     dense_linear,
     mlp_workspace_size,
     sparse_mlp_forward,
@@ -31,6 +32,8 @@ from .binding import (  # noqa: F401
     model_destroy,
     drafter_workspace_size,
     sparse_drafter_forward,
+    drafter_trace_size,
+    sparse_drafter_forward_trace,
     greedy_verify,
     check_token_ids_host,
 )

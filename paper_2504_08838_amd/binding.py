@@ -89,6 +89,7 @@ def lib():
             "sd2_matrix_init_dense": (C.c_int, [pmat, vp, i32, i32]),
             "sd2_linear_workspace_size": (C.c_int, [pmat, i32, psz]),
             "sd2_sparse_linear": (C.c_int, [pmat, vp, i32, vp, vp, sz, vp]),
+            "sd2_sparse_linear_partials": (C.c_int, [pmat, vp, i32, vp, sz, vp]),
             "sd2_dense_linear": (C.c_int, [pmat, vp, i32, vp, vp, sz, vp]),
             "sd2_mlp_workspace_size": (C.c_int, [pmat, pmat, i32, psz]),
             "sd2_sparse_mlp_forward": (C.c_int, [pmat, pmat, vp, i32, vp, vp, sz, vp]),
@@ -96,6 +97,8 @@ def lib():
             "sd2_model_destroy": (C.c_int, [vp]),
             "sd2_drafter_workspace_size": (C.c_int, [vp, i32, psz]),
             "sd2_sparse_drafter_forward": (C.c_int, [vp, vp, i32, vp, vp, sz, vp]),
+            "sd2_drafter_trace_size": (C.c_int, [vp, i32, psz]),
+            "sd2_sparse_drafter_forward_trace": (C.c_int, [vp, vp, i32, vp, vp, sz, vp, sz, vp]),
             "sd2_greedy_verify": (C.c_int, [vp, vp, i32, i32, i32, vp, vp, vp]),
             "sd2_check_token_ids_host": (C.c_int, [vp, sz, i32]),
         }
@@ -192,6 +195,11 @@ def sparse_linear(m, x_ptr, k_tok, y_ptr, ws_ptr=0, ws_bytes=0, stream=0):
                                    ws_bytes, C.c_void_p(stream)), "sd2_sparse_linear")
 
 
+def sparse_linear_partials(m, x_ptr, k_tok, part_ptr, part_bytes, stream=0):
+    _check(lib().sd2_sparse_linear_partials(C.byref(m), C.c_void_p(x_ptr), k_tok, C.c_void_p(part_ptr), part_bytes,
+                                            C.c_void_p(stream)), "sd2_sparse_linear_partials")
+
+
 def dense_linear(m, x_ptr, k_tok, y_ptr, ws_ptr=0, ws_bytes=0, stream=0):
     _check(lib().sd2_dense_linear(C.byref(m), C.c_void_p(x_ptr), k_tok, C.c_void_p(y_ptr), C.c_void_p(ws_ptr),
                                   ws_bytes, C.c_void_p(stream)), "sd2_dense_linear")
@@ -230,6 +238,18 @@ def sparse_drafter_forward(model, h_in_ptr, k_tok, h_out_ptr, ws_ptr, ws_bytes, 
     _check(lib().sd2_sparse_drafter_forward(model.handle, C.c_void_p(h_in_ptr), k_tok, C.c_void_p(h_out_ptr),
                                             C.c_void_p(ws_ptr), ws_bytes, C.c_void_p(stream)),
            "sd2_sparse_drafter_forward")
+
+
+def drafter_trace_size(model, k_tok):
+    n = C.c_size_t()
+    _check(lib().sd2_drafter_trace_size(model.handle, k_tok, C.byref(n)), "sd2_drafter_trace_size")
+    return n.value
+
+
+def sparse_drafter_forward_trace(model, h_in_ptr, k_tok, h_out_ptr, ws_ptr, ws_bytes, trace_ptr, trace_bytes, stream=0):
+    _check(lib().sd2_sparse_drafter_forward_trace(model.handle, C.c_void_p(h_in_ptr), k_tok, C.c_void_p(h_out_ptr),
+                                                  C.c_void_p(ws_ptr), ws_bytes, C.c_void_p(trace_ptr), trace_bytes,
+                                                  C.c_void_p(stream)), "sd2_sparse_drafter_forward_trace")
 
 
 def greedy_verify(draft_ptr, target_ptr, batch, k, vocab, accepted_ptr, out_tokens_ptr, stream=0):

@@ -1,4 +1,5 @@
 // C ABI of libsd2 (see include/sd2.h): argument checks on the host, then launches.
+#include <stdlib.h>
 #include <string.h>
 
 #include <algorithm>
@@ -102,6 +103,40 @@ StackLayout stack_layout(const sd2_model* md, int k_tok) {
     return L;
 }
 
+MegaGeo mega_geo(const sd2_matrix_t& m) {
+    MegaGeo g;
+    memset(&g, 0, sizeof(g));
+    g.n_out = m.info.n_out;
+    g.k_in = m.info.k_in;
+    g.n_strips = m.info.n_strips;
+    g.n_slabs = m.info.n_slabs;
+    g.n_tiles = m.info.n_tiles;
+    g.mask_off = m.info.mask_off;
+    g.val_off = m.info.val_off;
+    return g;
+}
+
+// The single-launch persistent kernel serves the decode regime (k_tok <= 8) of an all-sparse model
+// whose layers share one geometry; everything else runs as one launch per linear and glue step.
+// SD2_FORWARD=multi forces the latter (used by tests to cover both).
+bool use_mega_path(const sd2_model* md, int k_tok) {
+    const char* force = getenv("SD2_FORWARD");
+    if (force && strcmp(force, "multi") == 0) return false;
+    const sd2_model_shape_t& sh = md->shape;
+    if (sh.layers < 1) return false;
+    int max_nnz = 0;
+    for (size_t i = 0; i < md->mats.size(); ++i) {
+        const sd2_matrix_t& m = md->mats[i];
+        const sd2_matrix_t& ref = md->mats[i % 4];
+        if (m.kind != SD2_KIND_SPARSE) return false;
+        if (m.info.mask_off != ref.info.mask_off || m.info.val_off != ref.info.val_off) return false;
+        max_nnz = std::max(max_nnz, m.info.max_tile_nnz);
+    }
+    MegaGeo geo[4];
+    for (int kd = 0; kd < 4; ++kd) geo[kd] = mega_geo(md->mats[kd]);
+    return mega_supported(geo, sh.layers, sh.head_dim, k_tok, max_nnz);
+}
+
 }  // namespace
 
 extern "C" {
@@ -168,6 +203,16 @@ int sd2_linear_workspace_size(const sd2_matrix_t* m, int32_t k_tok, size_t* byte
 int sd2_sparse_linear(const sd2_matrix_t* m, const uint16_t* x, int32_t k_tok, float* y, void* ws, size_t ws_bytes,
                       void* stream) {
     return linear_entry(m, SD2_KIND_SPARSE, x, k_tok, y, ws, ws_bytes, stream);
+}
+
+int sd2_sparse_linear_partials(const sd2_matrix_t* m, const uint16_t* x, int32_t k_tok, float* part, size_t part_bytes,
+                               void* stream) {
+    int rc = check_matrix(m, SD2_KIND_SPARSE);
+    if (rc != SD2_OK) return rc;
+    if (!x || !part) return SD2_ERR_NULL;
+    if ((rc = check_tokens(k_tok)) != SD2_OK) return rc;
+    if (!aligned16(x) || !aligned16(part) || part_bytes < partial_bytes(m, k_tok)) return SD2_ERR_BUFFER;
+    return run_linear(m, x, k_tok, part, static_cast<hipStream_t>(stream)) == hipSuccess ? SD2_OK : SD2_ERR_HIP;
 }
 
 int sd2_dense_linear(const sd2_matrix_t* m, const uint16_t* x, int32_t k_tok, float* y, void* ws, size_t ws_bytes,
@@ -254,43 +299,143 @@ int sd2_drafter_workspace_size(const sd2_model_t* model, int32_t k_tok, size_t* 
     if (!model || !bytes_out) return SD2_ERR_NULL;
     int rc = check_tokens(k_tok);
     if (rc != SD2_OK) return rc;
-    *bytes_out = stack_layout(model, k_tok).total;
+    const sd2_model_shape_t& sh = model->shape;
+    const size_t mega = mega_layout(sh.layers, sh.hidden, sh.q_out, sh.kv_out, sh.inter, k_tok).total;
+    *bytes_out = std::max(stack_layout(model, k_tok).total, mega);
     return SD2_OK;
 }
 
-int sd2_sparse_drafter_forward(const sd2_model_t* md, const uint16_t* h_in, int32_t k_tok, float* h_out, void* ws,
-                               size_t ws_bytes, void* stream) {
+struct TraceLayout {
+    int kmax, smax;
+    size_t x_off, src_off, total;
+};
+
+static TraceLayout trace_layout(const sd2_model* md, int k_tok) {
+    const sd2_model_shape_t& sh = md->shape;
+    TraceLayout T;
+    T.kmax = std::max(std::max(sh.hidden, sh.q_out), sh.inter);
+    T.smax = std::max(std::max(sh.hidden, sh.q_out + 2 * sh.kv_out), 2 * sh.inter);
+    const size_t n_lin = (size_t)4 * sh.layers;
+    T.x_off = 0;
+    T.src_off = align256(n_lin * k_tok * T.kmax * sizeof(uint16_t));
+    T.total = T.src_off + align256(n_lin * k_tok * T.smax * sizeof(float));
+    return T;
+}
+
+static int forward_impl(const sd2_model_t* md, const uint16_t* h_in, int32_t k_tok, float* h_out, void* ws,
+                        size_t ws_bytes, void* trace, void* stream) {
     if (!md || !h_in || !h_out || !ws) return SD2_ERR_NULL;
     int rc = check_tokens(k_tok);
     if (rc != SD2_OK) return rc;
     const StackLayout L = stack_layout(md, k_tok);
-    if (!aligned16(h_in) || !aligned16(h_out) || !aligned16(ws) || ws_bytes < L.total) return SD2_ERR_BUFFER;
     const sd2_model_shape_t& sh = md->shape;
+    const MegaLayout ML = mega_layout(sh.layers, sh.hidden, sh.q_out, sh.kv_out, sh.inter, k_tok);
+    if (!aligned16(h_in) || !aligned16(h_out) || !aligned16(ws) || ws_bytes < std::max(L.total, ML.total))
+        return SD2_ERR_BUFFER;
     hipStream_t s = static_cast<hipStream_t>(stream);
+    if (use_mega_path(md, k_tok)) {
+        MegaArgs ma;
+        memset(&ma, 0, sizeof(ma));
+        for (int kd = 0; kd < 4; ++kd) ma.geo[kd] = mega_geo(md->mats[kd]);
+        ma.layers = sh.layers;
+        ma.hidden = sh.hidden;
+        ma.q_out = sh.q_out;
+        ma.kv_out = sh.kv_out;
+        ma.inter = sh.inter;
+        ma.n_heads = sh.n_heads;
+        ma.n_kv = sh.n_kv;
+        ma.head_dim = sh.head_dim;
+        ma.k_tok = k_tok;
+        ma.spin_limit = 1 << 22;
+        uint8_t* base = static_cast<uint8_t*>(ws);
+        ma.h = h_out;
+        ma.bar = reinterpret_cast<unsigned*>(base + ML.bar_off);
+        ma.err = reinterpret_cast<unsigned*>(base + ML.err_off);
+        ma.sumsq = reinterpret_cast<float*>(base + ML.sumsq_off);
+        ma.strip_cnt = reinterpret_cast<unsigned*>(base + ML.cnt_off);
+        ma.yqkv = reinterpret_cast<float*>(base + ML.yqkv_off);
+        ma.ygu = reinterpret_cast<float*>(base + ML.ygu_off);
+        for (size_t i = 0; i < md->mats.size(); ++i) ma.blob[i] = static_cast<const unsigned char*>(md->mats[i].data_dev);
+        if (trace) {
+            const TraceLayout T = trace_layout(md, k_tok);
+            ma.trace_x = reinterpret_cast<uint16_t*>(static_cast<uint8_t*>(trace) + T.x_off);
+            ma.trace_src = reinterpret_cast<float*>(static_cast<uint8_t*>(trace) + T.src_off);
+            ma.trace_kmax = T.kmax;
+            ma.trace_smax = T.smax;
+        }
+        return launch_mega_forward(ma, h_in, base, ML.total, s) == hipSuccess ? SD2_OK : SD2_ERR_HIP;
+    }
     uint16_t* act = reinterpret_cast<uint16_t*>(static_cast<uint8_t*>(ws) + L.act_off);
     float* part = reinterpret_cast<float*>(static_cast<uint8_t*>(ws) + L.part_off);
     float* h = h_out;  // the residual stream lives in the output buffer
 #define SD2_TRY(expr) \
     if ((expr) != hipSuccess) return SD2_ERR_HIP
+    const TraceLayout T = trace_layout(md, k_tok);
+    // records what linear `lin` consumed: `width` fp32 source values per token (copied, or summed from partials)
+    // and the `k_in` bf16 activations now sitting in `act`
+    auto record = [&](int lin, const float* src_copy, const float* src_part, int n_splits, int width, int k_in) -> hipError_t {
+        if (!trace) return hipSuccess;
+        uint16_t* tx = reinterpret_cast<uint16_t*>(static_cast<uint8_t*>(trace) + T.x_off) + (size_t)lin * k_tok * T.kmax;
+        float* ts = reinterpret_cast<float*>(static_cast<uint8_t*>(trace) + T.src_off) + (size_t)lin * k_tok * T.smax;
+        hipError_t e = hipMemcpy2DAsync(tx, (size_t)T.kmax * 2, act, (size_t)k_in * 2, (size_t)k_in * 2, k_tok,
+                                        hipMemcpyDeviceToDevice, s);
+        if (e != hipSuccess) return e;
+        if (src_copy)
+            return hipMemcpy2DAsync(ts, (size_t)T.smax * 4, src_copy, (size_t)width * 4, (size_t)width * 4, k_tok,
+                                    hipMemcpyDeviceToDevice, s);
+        for (int t = 0; t < k_tok; ++t) {
+            // partials are [split][token][width]: reduce one token row at a time into the padded trace row
+            e = launch_reduce_partials_strided(src_part + (size_t)t * width, n_splits, (size_t)k_tok * width, (size_t)width,
+                                               ts + (size_t)t * T.smax, s);
+            if (e != hipSuccess) return e;
+        }
+        return hipSuccess;
+    };
     SD2_TRY(launch_residual_rmsnorm(h, h_in, nullptr, 0, k_tok, sh.hidden, sh.layers > 0 ? act : nullptr, s));
     for (int l = 0; l < sh.layers; ++l) {
         const sd2_matrix_t* qkv = &md->mats[4 * l + 0];
         const sd2_matrix_t* o = &md->mats[4 * l + 1];
         const sd2_matrix_t* gu = &md->mats[4 * l + 2];
         const sd2_matrix_t* dn = &md->mats[4 * l + 3];
+        SD2_TRY(record(4 * l + 0, h, nullptr, 0, sh.hidden, sh.hidden));
         SD2_TRY(run_linear(qkv, act, k_tok, part, s));
         SD2_TRY(launch_inflight_attention(part, qkv->info.n_slabs, k_tok, sh.q_out, sh.kv_out, sh.n_heads, sh.n_kv,
                                           sh.head_dim, act, s));
+        SD2_TRY(record(4 * l + 1, nullptr, part, qkv->info.n_slabs, sh.q_out + 2 * sh.kv_out, sh.q_out));
         SD2_TRY(run_linear(o, act, k_tok, part, s));
         SD2_TRY(launch_residual_rmsnorm(h, nullptr, part, o->info.n_slabs, k_tok, sh.hidden, act, s));
+        SD2_TRY(record(4 * l + 2, h, nullptr, 0, sh.hidden, sh.hidden));
         SD2_TRY(run_linear(gu, act, k_tok, part, s));
         SD2_TRY(launch_silu_mul(part, gu->info.n_slabs, k_tok, sh.inter, act, s));
+        SD2_TRY(record(4 * l + 3, nullptr, part, gu->info.n_slabs, 2 * sh.inter, sh.inter));
         SD2_TRY(run_linear(dn, act, k_tok, part, s));
         SD2_TRY(launch_residual_rmsnorm(h, nullptr, part, dn->info.n_slabs, k_tok, sh.hidden,
                                         l + 1 < sh.layers ? act : nullptr, s));
     }
 #undef SD2_TRY
     return SD2_OK;
+}
+
+int sd2_sparse_drafter_forward(const sd2_model_t* md, const uint16_t* h_in, int32_t k_tok, float* h_out, void* ws,
+                               size_t ws_bytes, void* stream) {
+    return forward_impl(md, h_in, k_tok, h_out, ws, ws_bytes, nullptr, stream);
+}
+
+int sd2_drafter_trace_size(const sd2_model_t* model, int32_t k_tok, size_t* bytes_out) {
+    if (!model || !bytes_out) return SD2_ERR_NULL;
+    int rc = check_tokens(k_tok);
+    if (rc != SD2_OK) return rc;
+    *bytes_out = std::max(trace_layout(model, k_tok).total, (size_t)256);
+    return SD2_OK;
+}
+
+int sd2_sparse_drafter_forward_trace(const sd2_model_t* md, const uint16_t* h_in, int32_t k_tok, float* h_out, void* ws,
+                                     size_t ws_bytes, void* trace, size_t trace_bytes, void* stream) {
+    if (!md || !trace) return SD2_ERR_NULL;
+    int rc = check_tokens(k_tok);
+    if (rc != SD2_OK) return rc;
+    if (!aligned16(trace) || trace_bytes < trace_layout(md, k_tok).total) return SD2_ERR_BUFFER;
+    return forward_impl(md, h_in, k_tok, h_out, ws, ws_bytes, trace, stream);
 }
 
 int sd2_greedy_verify(const int32_t* draft, const int32_t* target, int32_t batch, int32_t k, int32_t vocab,

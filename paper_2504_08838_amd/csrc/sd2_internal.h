@@ -30,6 +30,10 @@ hipError_t launch_dense_linear(const MatArgs& m, const LinArgs& a, hipStream_t s
 // y[i] = sum_s part[s][i], i < n  (n = k_tok * n_out)
 hipError_t launch_reduce_partials(const float* part, int n_splits, size_t n, float* y, hipStream_t s);
 
+// y[i] = sum_s part[s * split_stride + i], i < n
+hipError_t launch_reduce_partials_strided(const float* part, int n_splits, size_t split_stride, size_t n, float* y,
+                                          hipStream_t s);
+
 // h (fp32 [k_tok][hidden]) is initialised from bf16 h_in (first != 0) or updated in place with
 // h += sum_s part[s]; then a = bf16(h / sqrt(mean(h^2) + 1e-5)) is written when a != nullptr.
 hipError_t launch_residual_rmsnorm(float* h, const uint16_t* h_in, const float* part, int n_splits,
@@ -44,5 +48,43 @@ hipError_t launch_silu_mul(const float* part, int n_splits, int k_tok, int inter
 
 hipError_t launch_greedy_verify(const int32_t* draft, const int32_t* target, int batch, int k,
                                 int32_t* accepted, int32_t* out_tokens, hipStream_t s);
+
+}  // namespace sd2
+
+namespace sd2 {
+
+// ---- whole-forward persistent kernel ("mega" path): one cooperative launch per forward.
+constexpr int kMegaMaxLayers = 64;
+constexpr int kMegaMaxTok = 8;
+
+struct MegaGeo {
+    int n_out, k_in, n_strips, n_slabs, n_tiles, pad;
+    unsigned long long mask_off, val_off;  // byte offsets inside a blob (equal for all layers of a kind)
+};
+
+struct MegaArgs {
+    MegaGeo geo[4];  // qkv, o, gate_up, down
+    int layers, hidden, q_out, kv_out, inter, n_heads, n_kv, head_dim, k_tok, spin_limit;
+    float* h;             // [k_tok][hidden] residual stream = output
+    float* yqkv;          // [2][k_tok][q_out + 2 kv_out] accumulators (layer parity)
+    float* ygu;           // [2][k_tok][2 inter]
+    float* sumsq;         // [2 layers + 1][16] sums of squares of h per token
+    unsigned* strip_cnt;  // [2 layers][n_strips(hidden)] arrivals per 16-row strip of h
+    unsigned* bar;        // grid barrier state (see mega kernel)
+    unsigned* err;        // set to 1 if a bounded wait ran out
+    uint16_t* trace_x;    // optional [phase][k_tok][trace_kmax] bf16: the activations each linear consumed
+    float* trace_src;     // optional [phase][k_tok][trace_smax] fp32: the values its input glue read
+    int trace_kmax, trace_smax;
+    const unsigned char* blob[4 * kMegaMaxLayers];
+};
+
+struct MegaLayout {
+    size_t bar_off, err_off, sumsq_off, cnt_off, yqkv_off, ygu_off, total;  // everything in [0, total) starts as zero
+};
+
+MegaLayout mega_layout(int layers, int hidden, int q_out, int kv_out, int inter, int k_tok);
+// true when the persistent kernel can run this model on the current device
+bool mega_supported(const MegaGeo (&geo)[4], int layers, int head_dim, int k_tok, int max_tile_nnz);
+hipError_t launch_mega_forward(const MegaArgs& a, const uint16_t* h_in, void* zero_base, size_t zero_bytes, hipStream_t s);
 
 }  // namespace sd2

@@ -75,3 +75,26 @@ def run_forward(model, h_in_bits, hidden) -> np.ndarray:
     sd2.sparse_drafter_forward(model, h_in.data_ptr(), k_tok, h_out.data_ptr(), ws.data_ptr(), ws_bytes, stream_ptr())
     torch.cuda.synchronize()
     return h_out.cpu().numpy()
+
+
+def run_forward_trace(model, h_in_bits, shape):
+    """-> (h_out, x [n_lin][k][kmax] bf16 bits, src [n_lin][k][smax] fp32) from the step-recording forward."""
+    k_tok = h_in_bits.shape[0]
+    n_lin = 4 * shape.layers
+    kmax = max(shape.hidden, shape.q_out, shape.inter)
+    smax = max(shape.hidden, shape.q_out + 2 * shape.kv_out, 2 * shape.inter)
+    h_in = dev(h_in_bits)
+    h_out = torch.full((k_tok, shape.hidden), float("nan"), dtype=torch.float32, device="cuda")
+    ws_bytes = sd2.drafter_workspace_size(model, k_tok)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+    tb = sd2.drafter_trace_size(model, k_tok)
+    trace = torch.zeros(tb, dtype=torch.uint8, device="cuda")
+    sd2.sparse_drafter_forward_trace(model, h_in.data_ptr(), k_tok, h_out.data_ptr(), ws.data_ptr(), ws_bytes,
+                                     trace.data_ptr(), tb, stream_ptr())
+    torch.cuda.synchronize()
+    raw = trace.cpu().numpy()
+    x_bytes = n_lin * k_tok * kmax * 2
+    src_off = (x_bytes + 255) // 256 * 256
+    x = raw[:x_bytes].view(np.uint16).reshape(n_lin, k_tok, kmax)
+    src = raw[src_off:src_off + n_lin * k_tok * smax * 4].view(np.float32).reshape(n_lin, k_tok, smax)
+    return h_out.cpu().numpy(), x, src
