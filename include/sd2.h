@@ -177,7 +177,8 @@ int sd2_sparse_drafter_forward(const sd2_model_t* model, const uint16_t* h_in_bf
  * stream for the normed inputs, the q|k|v results for attention, the gate|up results for the
  * gated product -- and the bf16 activations it handed to the linear.  trace_dev layout:
  * n_lin x [k_tok][kmax] uint16, then (256-byte aligned) n_lin x [k_tok][smax] float, with
- * kmax = max(hidden, q_out, inter) and smax = max(hidden, q_out + 2 kv_out, 2 inter). */
+ * kmax = max(hidden, q_out, inter) and smax = max(hidden, q_out + 2 kv_out, 2 inter); after that
+ * (256-byte aligned, up to the size reported) per-workgroup timestamps of the single-launch kernel. */
 int sd2_drafter_trace_size(const sd2_model_t* model, int32_t k_tok, size_t* bytes_out);
 int sd2_sparse_drafter_forward_trace(const sd2_model_t* model, const uint16_t* h_in_bf16_dev,
                                      int32_t k_tok, float* h_out_dev, void* workspace_dev,

@@ -119,7 +119,7 @@ MegaGeo mega_geo(const sd2_matrix_t& m) {
 // The single-launch persistent kernel serves the decode regime (k_tok <= 8) of an all-sparse model
 // whose layers share one geometry; everything else runs as one launch per linear and glue step.
 // SD2_FORWARD=multi forces the latter (used by tests to cover both).
-bool use_mega_path(const sd2_model* md, int k_tok) {
+bool plan_mega_path(const sd2_model* md, int k_tok, MegaGeo (&geo)[4]) {
     const char* force = getenv("SD2_FORWARD");
     if (force && strcmp(force, "multi") == 0) return false;
     const sd2_model_shape_t& sh = md->shape;
@@ -132,9 +132,8 @@ bool use_mega_path(const sd2_model* md, int k_tok) {
         if (m.info.mask_off != ref.info.mask_off || m.info.val_off != ref.info.val_off) return false;
         max_nnz = std::max(max_nnz, m.info.max_tile_nnz);
     }
-    MegaGeo geo[4];
     for (int kd = 0; kd < 4; ++kd) geo[kd] = mega_geo(md->mats[kd]);
-    return mega_supported(geo, sh.layers, sh.head_dim, k_tok, max_nnz);
+    return mega_plan(geo, sh.layers, sh.hidden, sh.head_dim, k_tok, max_nnz);
 }
 
 }  // namespace
@@ -307,7 +306,7 @@ int sd2_drafter_workspace_size(const sd2_model_t* model, int32_t k_tok, size_t* 
 
 struct TraceLayout {
     int kmax, smax;
-    size_t x_off, src_off, total;
+    size_t x_off, src_off, time_off, total;
 };
 
 static TraceLayout trace_layout(const sd2_model* md, int k_tok) {
@@ -318,7 +317,9 @@ static TraceLayout trace_layout(const sd2_model* md, int k_tok) {
     const size_t n_lin = (size_t)4 * sh.layers;
     T.x_off = 0;
     T.src_off = align256(n_lin * k_tok * T.kmax * sizeof(uint16_t));
-    T.total = T.src_off + align256(n_lin * k_tok * T.smax * sizeof(float));
+    T.time_off = T.src_off + align256(n_lin * k_tok * T.smax * sizeof(float));
+    // per workgroup and linear four timestamps (only the single-launch kernel fills them)
+    T.total = T.time_off + align256((size_t)std::max(mega_grid_size(), 1) * n_lin * 4 * sizeof(unsigned long long));
     return T;
 }
 
@@ -333,10 +334,9 @@ static int forward_impl(const sd2_model_t* md, const uint16_t* h_in, int32_t k_t
     if (!aligned16(h_in) || !aligned16(h_out) || !aligned16(ws) || ws_bytes < std::max(L.total, ML.total))
         return SD2_ERR_BUFFER;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    if (use_mega_path(md, k_tok)) {
-        MegaArgs ma;
-        memset(&ma, 0, sizeof(ma));
-        for (int kd = 0; kd < 4; ++kd) ma.geo[kd] = mega_geo(md->mats[kd]);
+    MegaArgs ma;
+    memset(&ma, 0, sizeof(ma));
+    if (plan_mega_path(md, k_tok, ma.geo)) {
         ma.layers = sh.layers;
         ma.hidden = sh.hidden;
         ma.q_out = sh.q_out;
@@ -351,8 +351,6 @@ static int forward_impl(const sd2_model_t* md, const uint16_t* h_in, int32_t k_t
         ma.h = h_out;
         ma.bar = reinterpret_cast<unsigned*>(base + ML.bar_off);
         ma.err = reinterpret_cast<unsigned*>(base + ML.err_off);
-        ma.sumsq = reinterpret_cast<float*>(base + ML.sumsq_off);
-        ma.strip_cnt = reinterpret_cast<unsigned*>(base + ML.cnt_off);
         ma.yqkv = reinterpret_cast<float*>(base + ML.yqkv_off);
         ma.ygu = reinterpret_cast<float*>(base + ML.ygu_off);
         for (size_t i = 0; i < md->mats.size(); ++i) ma.blob[i] = static_cast<const unsigned char*>(md->mats[i].data_dev);
@@ -362,6 +360,10 @@ static int forward_impl(const sd2_model_t* md, const uint16_t* h_in, int32_t k_t
             ma.trace_src = reinterpret_cast<float*>(static_cast<uint8_t*>(trace) + T.src_off);
             ma.trace_kmax = T.kmax;
             ma.trace_smax = T.smax;
+            ma.trace_time = reinterpret_cast<unsigned long long*>(static_cast<uint8_t*>(trace) + T.time_off);
+            // SD2_MEGA_TIMING=1: keep only the per-workgroup timestamps (profiling the production kernel)
+            const char* tonly = getenv("SD2_MEGA_TIMING");
+            if (tonly && tonly[0] == '1') ma.trace_x = nullptr;
         }
         return launch_mega_forward(ma, h_in, base, ML.total, s) == hipSuccess ? SD2_OK : SD2_ERR_HIP;
     }

@@ -56,9 +56,13 @@ namespace sd2 {
 // ---- whole-forward persistent kernel ("mega" path): one cooperative launch per forward.
 constexpr int kMegaMaxLayers = 64;
 constexpr int kMegaMaxTok = 8;
+constexpr int kMegaMaxHidden = 3072;
 
+// One kind of matrix (qkv, o, gate_up, down).  Workgroup c < n_sblk * n_bblk owns the block of
+// s_blk strips x b_blk slabs with strip block c % n_sblk and slab block c / n_sblk.
 struct MegaGeo {
-    int n_out, k_in, n_strips, n_slabs, n_tiles, pad;
+    int n_out, k_in, n_strips, n_slabs, n_tiles;
+    int s_blk, b_blk, n_sblk, n_bblk, pad;
     unsigned long long mask_off, val_off;  // byte offsets inside a blob (equal for all layers of a kind)
 };
 
@@ -68,23 +72,24 @@ struct MegaArgs {
     float* h;             // [k_tok][hidden] residual stream = output
     float* yqkv;          // [2][k_tok][q_out + 2 kv_out] accumulators (layer parity)
     float* ygu;           // [2][k_tok][2 inter]
-    float* sumsq;         // [2 layers + 1][16] sums of squares of h per token
-    unsigned* strip_cnt;  // [2 layers][n_strips(hidden)] arrivals per 16-row strip of h
     unsigned* bar;        // grid barrier state (see mega kernel)
     unsigned* err;        // set to 1 if a bounded wait ran out
     uint16_t* trace_x;    // optional [phase][k_tok][trace_kmax] bf16: the activations each linear consumed
     float* trace_src;     // optional [phase][k_tok][trace_smax] fp32: the values its input glue read
     int trace_kmax, trace_smax;
+    unsigned long long* trace_time;  // optional [workgroup][phase][4] 100 MHz timestamps: start, barrier, prologue, tiles
     const unsigned char* blob[4 * kMegaMaxLayers];
 };
 
 struct MegaLayout {
-    size_t bar_off, err_off, sumsq_off, cnt_off, yqkv_off, ygu_off, total;  // everything in [0, total) starts as zero
+    size_t bar_off, err_off, yqkv_off, ygu_off, total;  // everything in [0, total) starts as zero
 };
 
 MegaLayout mega_layout(int layers, int hidden, int q_out, int kv_out, int inter, int k_tok);
-// true when the persistent kernel can run this model on the current device
-bool mega_supported(const MegaGeo (&geo)[4], int layers, int head_dim, int k_tok, int max_tile_nnz);
+// workgroups of the persistent kernel on the current device (0 when it cannot run here)
+int mega_grid_size();
+// Chooses the workgroup tiling of each matrix kind; false when the persistent kernel cannot run this model here.
+bool mega_plan(MegaGeo (&geo)[4], int layers, int hidden, int head_dim, int k_tok, int max_tile_nnz);
 hipError_t launch_mega_forward(const MegaArgs& a, const uint16_t* h_in, void* zero_base, size_t zero_bytes, hipStream_t s);
 
 }  // namespace sd2
