@@ -5,8 +5,8 @@ One "step" is one pass of the whole hot path over one batch of synthetic input: 
 3B-shape drafter linear stack at 50 % unstructured sparsity on k = 5 in-flight tokens
 (sd2_sparse_drafter_forward), followed by greedy verification of a 64 x 5 batch of draft ids
 (sd2_greedy_verify).  Inputs and packed weights are resident in HBM before the timed region.
-The forward is captured once into a HIP graph (it is a fixed chain of small dependent launches)
-and replayed K times.
+Forward and verify are each captured once into a HIP graph and replayed K times; an event pair
+on the same stream brackets every forward inside the timed region.
 
 Prints one JSON line; see the design doc for the meaning of `roofline` and `cpu_baseline`.
 """
@@ -24,9 +24,11 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
-# HBM bytes per launch of the dominant kernel (gate+up sparse linear) from rocprofv3 --pmc
-# FETCH_SIZE / WRITE_SIZE runs, scaled by a plain copy kernel; None until measured.
-MEASURED_TRAFFIC_BYTES = None
+# HBM bytes per launch of the forward kernel (and of the gate+up sparse linear) from rocprofv3 --pmc
+# FETCH_SIZE / WRITE_SIZE runs, scaled by the plain copy kernel of --calibrate; None until measured.
+MEASURED_TRAFFIC_BYTES = 3418794493
+MEASURED_LINEAR_TRAFFIC_BYTES = 63422727
+CALIBRATION_BYTES = 256 << 20  # size of the plain copies launched by --calibrate
 
 
 def parse_args():
@@ -41,6 +43,8 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true")
     ap.add_argument("--dense", action="store_true", help="also time the dense bf16 stack")
+    ap.add_argument("--calibrate", action="store_true",
+                    help="also launch three plain 256 MiB copies (reference dispatches for profiler HBM counters)")
     return ap.parse_args()
 
 
@@ -117,30 +121,46 @@ def main():
 
     stream = torch.cuda.Stream()  # default priority
 
-    def step(sp):
+    def fwd(sp):
         sd2.sparse_drafter_forward(model, h_in.data_ptr(), k_tok, h_out.data_ptr(), ws.data_ptr(), ws_bytes, sp)
+
+    def ver(sp):
         sd2.greedy_verify(draft.data_ptr(), target.data_ptr(), vcfg["batch"], vcfg["k"], vcfg["vocab"],
                           acc.data_ptr(), out_tok.data_ptr(), sp)
 
-    graph = None
+    # A step is forward + verify.  Each half is captured into a HIP graph of its own so that an event pair
+    # recorded on the same stream brackets the forward inside the timed region: the forward is one persistent
+    # kernel (plus two tiny set-up launches), and that pair is the live duration the roofline entry uses.
+    use_graph = not args.no_graph
     with torch.cuda.stream(stream):
         sp = stream.cuda_stream
-        step(sp)
+        fwd(sp)
+        ver(sp)
         stream.synchronize()
-        if not args.no_graph:
-            graph = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(graph, stream=stream):
-                step(torch.cuda.current_stream().cuda_stream)
-        run = (lambda: graph.replay()) if graph is not None else (lambda: step(sp))
+        if use_graph:
+            g_fwd, g_ver = torch.cuda.CUDAGraph(), torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g_fwd, stream=stream):
+                fwd(torch.cuda.current_stream().cuda_stream)
+            with torch.cuda.graph(g_ver, stream=stream):
+                ver(torch.cuda.current_stream().cuda_stream)
+            run_fwd, run_ver = g_fwd.replay, g_ver.replay
+        else:
+            run_fwd, run_ver = (lambda: fwd(sp)), (lambda: ver(sp))
         for _ in range(args.warmup):
-            run()
+            run_fwd()
+            run_ver()
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        for _ in range(args.steps):
-            run()
+        for e0, e1 in evs:
+            e0.record(stream)
+            run_fwd()
+            e1.record(stream)
+            run_ver()
         torch.cuda.synchronize()
         wall = time.perf_counter() - t0
     us_per_step = wall / args.steps * 1e6
+    fwd_us = float(np.mean([e0.elapsed_time(e1) for e0, e1 in evs])) * 1e3
 
     # sanity: the output of the timed configuration is finite and the verify result is plausible
     h_host = h_out.cpu().numpy()
@@ -148,8 +168,18 @@ def main():
     acc_host = acc.cpu().numpy()
     assert acc_host.min() >= 0 and acc_host.max() <= vcfg["k"]
 
-    # --- roofline of the dominant kernel: the fused gate+up sparse linear (56.6 MB per launch),
-    # timed per launch with HIP events on the stream it runs on, over the 28 distinct layers (cold).
+    # --- roofline of the dominant kernel.  With the single-launch forward that kernel is the whole stack:
+    # algorithmic bytes = every matrix's useful bytes (2 B per nonzero + 1 mask bit per weight) plus the
+    # activations each linear reads (bf16) and the sums it produces (fp32).
+    forward_path = os.environ.get("SD2_FORWARD", "single-launch")
+    act_bytes = 0
+    for m in mats:
+        act_bytes += 2 * k_tok * int(m.info.k_in) + 4 * k_tok * int(m.info.n_out)
+    fwd_alg_bytes = useful + act_bytes
+    fwd_achieved = fwd_alg_bytes / fwd_us / 1e3  # GB/s
+
+    # --- the stand-alone sparse linear kernel on the largest matrix (fused gate+up), timed per launch with
+    # events on the stream it runs on, over the distinct layers (each launch streams a different matrix).
     gu = [mats[4 * l + 2] for l in range(layers)]
     x_act = to_dev(wl.gen_x(args.config, 0, "gate", k_tok, shape.hidden))
     part = torch.empty(max(sd2.linear_workspace_size(gu[0], k_tok), 16), dtype=torch.uint8, device=dev)
@@ -157,20 +187,28 @@ def main():
     with torch.cuda.stream(stream):
         sp = stream.cuda_stream
         for rep in range(3):
-            evs = [torch.cuda.Event(enable_timing=True) for _ in range(2 * layers)]
+            evl = [torch.cuda.Event(enable_timing=True) for _ in range(2 * layers)]
             for l in range(layers):
-                evs[2 * l].record(stream)
+                evl[2 * l].record(stream)
                 # partial sums only: the split-K add belongs to the next kernel in the stack
                 sd2.sparse_linear_partials(gu[l], x_act.data_ptr(), k_tok, part.data_ptr(), part.numel(), sp)
-                evs[2 * l + 1].record(stream)
+                evl[2 * l + 1].record(stream)
             stream.synchronize()
             if rep:
-                durs += [evs[2 * l].elapsed_time(evs[2 * l + 1]) * 1e3 for l in range(layers)]
+                durs += [evl[2 * l].elapsed_time(evl[2 * l + 1]) * 1e3 for l in range(layers)]
+        if args.calibrate:
+            # plain copies of known size: the scale for the profiler's HBM counters
+            cal_src = torch.empty(CALIBRATION_BYTES, dtype=torch.uint8, device=dev).fill_(1)
+            cal_dst = torch.empty_like(cal_src)
+            for _ in range(3):
+                sd2.calibration_copy(cal_dst.data_ptr(), cal_src.data_ptr(), CALIBRATION_BYTES, sp)
+            stream.synchronize()
     kern_us = float(np.mean(durs))
     gi = gu[0].info
     alg_bytes = int(gi.useful_bytes) + 2 * k_tok * gi.k_in + 4 * k_tok * gi.n_out * gi.n_slabs
     achieved = alg_bytes / kern_us / 1e3  # GB/s
 
+    single = forward_path != "multi"
     record = {
         "metric": "us per sparse drafter forward (k=5) and effective HBM GB/s vs peak",
         "value": round(us_per_step, 2),
@@ -188,7 +226,9 @@ def main():
             "workload": f"{shape.name} drafter linear stack, {layers} layers, {pct}% unstructured sparse bf16, "
                         f"k={k_tok} tokens + greedy verify batch {vcfg['batch']} k={vcfg['k']}",
             "config_id": args.config,
-            "hip_graph": graph is not None,
+            "hip_graph": use_graph,
+            "forward_path": forward_path,
+            "forward_us": round(fwd_us, 2),
             "packed_useful_bytes": useful,
             "packed_total_bytes": total,
             "effective_GBps": round(useful / us_per_step / 1e3, 1),
@@ -197,14 +237,23 @@ def main():
         },
         "roofline": {
             "bound": "hbm",
-            "kernel": "sparse_linear_kernel (fused gate+up, 16384x3072)",
-            "achieved": round(achieved, 1),
+            "kernel": "mega_forward_kernel (whole stack, one launch)" if single else "forward (multi-launch)",
+            "achieved": round(fwd_achieved, 1),
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
-            "frac": round(achieved / HBM_PEAK_GBS, 4),
-            "traffic": MEASURED_TRAFFIC_BYTES,
-            "kernel_us": round(kern_us, 2),
-            "algorithmic_bytes": alg_bytes,
+            "frac": round(fwd_achieved / HBM_PEAK_GBS, 4),
+            "traffic": MEASURED_TRAFFIC_BYTES if (single and layers == shape.layers and args.config == 3 and pct == 50
+                                                  and k_tok == 5) else None,
+            "kernel_us": round(fwd_us, 2),
+            "algorithmic_bytes": fwd_alg_bytes,
+            "linear_kernel": {
+                "kernel": f"sparse_linear_kernel (fused gate+up, {gi.n_out}x{gi.k_in})",
+                "achieved": round(achieved, 1),
+                "frac": round(achieved / HBM_PEAK_GBS, 4),
+                "kernel_us": round(kern_us, 2),
+                "algorithmic_bytes": alg_bytes,
+                "traffic": MEASURED_LINEAR_TRAFFIC_BYTES,
+            },
         },
     }
 
@@ -235,12 +284,13 @@ def main():
             dense_us = (time.perf_counter() - t0) / max(args.steps // 4, 10) * 1e6
         record["config"]["dense_stack_us"] = round(dense_us, 2)
         record["config"]["speedup_vs_dense"] = round(dense_us / us_per_step, 3)
-        del dmodel, dkeep, dws
+        del dgraph
+        sd2.model_destroy(dmodel)
+        del dkeep, dws
 
     if not args.no_cpu_baseline:
         from oracle import stack as ostack
 
-        sample_layers = min(2, layers)
         table = {p: (n, k) for p, n, k in wl.layer_matrix_shapes(shape)}
         split = {"q": (0, 0, shape.q_out), "k": (0, shape.q_out, shape.q_out + shape.kv_out),
                  "v": (0, shape.q_out + shape.kv_out, shape.q_out + 2 * shape.kv_out), "o": (1, 0, shape.hidden),
@@ -251,19 +301,34 @@ def main():
             return fused[4 * layer + idx][a:b]
 
         h_bits = wl.gen_x(args.config, 0, "q", k_tok, shape.hidden)
+        # one layer first to size the sample: about 15 s of oracle work, at most the whole stack
+        t0 = time.perf_counter()
+        ostack.drafter_forward(shape, wfn, h_bits, n_layers=1)
+        one_s = time.perf_counter() - t0
+        sample_layers = int(min(layers, max(1, round(15.0 / max(one_s, 1e-3)))))
         t0 = time.perf_counter()
         ostack.drafter_forward(shape, wfn, h_bits, n_layers=sample_layers)
         cpu_s = time.perf_counter() - t0
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([int(i.get("num_threads", 1)) for i in threadpool_info()] or [1])
+        except Exception:
+            cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
         record["cpu_baseline"] = {
             "value": round(cpu_s / sample_layers * layers * 1e6, 0),
             "unit": "us",
-            "cores": int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1)),
+            "cores": cores,
             "kind": "oracle",
-            "sample": f"{sample_layers} of {layers} layers of the same stack (fp64 NumPy masked-dense oracle incl. bf16->fp64 "
-                      f"conversion), scaled to {layers} layers; measured {cpu_s:.1f} s",
+            "sample": f"{sample_layers} of {layers} layers of the same stack and input (fp64 NumPy masked-dense oracle, "
+                      f"bf16->fp64 conversion included), scaled to {layers} layers; measured {cpu_s:.1f} s",
         }
 
-    print(json.dumps(record))
+    print(json.dumps(record), flush=True)
+    # orderly teardown while the runtime is still up: graphs first, then the model
+    if use_graph:
+        del run_fwd, run_ver, g_fwd, g_ver
+    sd2.model_destroy(model)
+    torch.cuda.synchronize()
 
 
 if __name__ == "__main__":

@@ -197,6 +197,13 @@ int sd2_greedy_verify(const int32_t* draft_dev, const int32_t* target_dev, int32
 /* SD2_ERR_RANGE if any of the n host ids lies outside [0, vocab). */
 int sd2_check_token_ids_host(const int32_t* ids, size_t n, int32_t vocab);
 
+/* ------------------------------------------------------------------ measurement aid
+ * Plain device-to-device copy kernel (16 bytes per lane, grid-stride): dst[0..bytes) = src[0..bytes).
+ * It moves exactly `bytes` in and `bytes` out, so the HBM counters it produces under a profiler give
+ * the scale that turns the same counters of the other kernels into bytes.  bytes must be a multiple
+ * of 16, both pointers 16-byte aligned, the ranges disjoint; asynchronous on `stream`. */
+int sd2_calibration_copy(void* dst_dev, const void* src_dev, size_t bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -36,4 +36,5 @@ from .binding import (  # noqa: F401
     sparse_drafter_forward_trace,
     greedy_verify,
     check_token_ids_host,
+    calibration_copy,
 )

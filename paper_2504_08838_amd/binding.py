@@ -101,6 +101,7 @@ def lib():
             "sd2_sparse_drafter_forward_trace": (C.c_int, [vp, vp, i32, vp, vp, sz, vp, sz, vp]),
             "sd2_greedy_verify": (C.c_int, [vp, vp, i32, i32, i32, vp, vp, vp]),
             "sd2_check_token_ids_host": (C.c_int, [vp, sz, i32]),
+            "sd2_calibration_copy": (C.c_int, [vp, vp, sz, vp]),
         }
         for name, (res, args) in sig.items():
             fn = getattr(L, name)
@@ -256,6 +257,11 @@ def greedy_verify(draft_ptr, target_ptr, batch, k, vocab, accepted_ptr, out_toke
     _check(lib().sd2_greedy_verify(C.c_void_p(draft_ptr), C.c_void_p(target_ptr), batch, k, vocab,
                                    C.c_void_p(accepted_ptr), C.c_void_p(out_tokens_ptr), C.c_void_p(stream)),
            "sd2_greedy_verify")
+
+
+def calibration_copy(dst_ptr, src_ptr, nbytes, stream=0):
+    _check(lib().sd2_calibration_copy(C.c_void_p(dst_ptr), C.c_void_p(src_ptr), nbytes, C.c_void_p(stream)),
+           "sd2_calibration_copy")
 
 
 def check_token_ids_host(ids, vocab):

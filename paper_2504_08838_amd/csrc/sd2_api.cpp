@@ -459,4 +459,12 @@ int sd2_check_token_ids_host(const int32_t* ids, size_t n, int32_t vocab) {
     return SD2_OK;
 }
 
+int sd2_calibration_copy(void* dst, const void* src, size_t bytes, void* stream) {
+    if (bytes == 0) return SD2_OK;
+    if (!dst || !src) return SD2_ERR_NULL;
+    if (bytes % 16 != 0 || !aligned16(dst) || !aligned16(src)) return SD2_ERR_BUFFER;
+    if (launch_calibration_copy(dst, src, bytes, static_cast<hipStream_t>(stream)) != hipSuccess) return SD2_ERR_HIP;
+    return SD2_OK;
+}
+
 }  // extern "C"

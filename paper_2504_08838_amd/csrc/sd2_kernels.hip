@@ -461,4 +461,16 @@ hipError_t launch_greedy_verify(const int32_t* draft, const int32_t* target, int
     return hipGetLastError();
 }
 
+__global__ __launch_bounds__(256) void calibration_copy_kernel(u32x4* __restrict__ dst, const u32x4* __restrict__ src, size_t n16) {
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += (size_t)gridDim.x * 256) dst[i] = src[i];
+}
+
+hipError_t launch_calibration_copy(void* dst, const void* src, size_t bytes, hipStream_t s) {
+    const size_t n16 = bytes / 16;
+    const unsigned blocks = (unsigned)std::min<size_t>((n16 + 255) / 256, 256 * 16);
+    hipLaunchKernelGGL(calibration_copy_kernel, dim3(blocks), dim3(256), 0, s, static_cast<u32x4*>(dst),
+                       static_cast<const u32x4*>(src), n16);
+    return hipGetLastError();
+}
+
 }  // namespace sd2
