@@ -319,7 +319,7 @@ static TraceLayout trace_layout(const sd2_model* md, int k_tok) {
     T.src_off = align256(n_lin * k_tok * T.kmax * sizeof(uint16_t));
     T.time_off = T.src_off + align256(n_lin * k_tok * T.smax * sizeof(float));
     // per workgroup and linear four timestamps (only the single-launch kernel fills them)
-    T.total = T.time_off + align256((size_t)std::max(mega_grid_size(), 1) * n_lin * 4 * sizeof(unsigned long long));
+    T.total = T.time_off + align256((size_t)std::max(mega_grid_size(), 1) * n_lin * 8 * sizeof(unsigned long long));
     return T;
 }
 
@@ -354,6 +354,7 @@ static int forward_impl(const sd2_model_t* md, const uint16_t* h_in, int32_t k_t
         ma.yqkv = reinterpret_cast<float*>(base + ML.yqkv_off);
         ma.ygu = reinterpret_cast<float*>(base + ML.ygu_off);
         for (size_t i = 0; i < md->mats.size(); ++i) ma.blob[i] = static_cast<const unsigned char*>(md->mats[i].data_dev);
+        bool probe = false;
         if (trace) {
             const TraceLayout T = trace_layout(md, k_tok);
             ma.trace_x = reinterpret_cast<uint16_t*>(static_cast<uint8_t*>(trace) + T.x_off);
@@ -361,11 +362,13 @@ static int forward_impl(const sd2_model_t* md, const uint16_t* h_in, int32_t k_t
             ma.trace_kmax = T.kmax;
             ma.trace_smax = T.smax;
             ma.trace_time = reinterpret_cast<unsigned long long*>(static_cast<uint8_t*>(trace) + T.time_off);
-            // SD2_MEGA_TIMING=1: keep only the per-workgroup timestamps (profiling the production kernel)
+            // SD2_MEGA_TIMING=1: keep only the per-workgroup timestamps (profiling the production kernel);
+            // =2: the same plus wavefront 0's split into waiting for streams and decoding
             const char* tonly = getenv("SD2_MEGA_TIMING");
-            if (tonly && tonly[0] == '1') ma.trace_x = nullptr;
+            if (tonly && (tonly[0] == '1' || tonly[0] == '2')) ma.trace_x = nullptr;
+            probe = tonly && tonly[0] == '2';
         }
-        return launch_mega_forward(ma, h_in, base, ML.total, s) == hipSuccess ? SD2_OK : SD2_ERR_HIP;
+        return launch_mega_forward(ma, h_in, base, ML.total, probe, s) == hipSuccess ? SD2_OK : SD2_ERR_HIP;
     }
     uint16_t* act = reinterpret_cast<uint16_t*>(static_cast<uint8_t*>(ws) + L.act_off);
     float* part = reinterpret_cast<float*>(static_cast<uint8_t*>(ws) + L.part_off);

@@ -31,12 +31,16 @@ constexpr int kWavesPerBlock = 4;
 
 __device__ __forceinline__ float bf16_to_f32(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
 
-// round to nearest, ties to even (finite inputs)
-__device__ __forceinline__ uint16_t f32_to_bf16(float f) {
-    uint32_t u = __float_as_uint(f);
-    u += 0x7FFFu + ((u >> 16) & 1u);
-    return (uint16_t)(u >> 16);
+// fp32 -> bf16, round to nearest, ties to even: the gfx950 packed conversion instruction
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+    const f32x2 v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
 }
+
+__device__ __forceinline__ uint16_t f32_to_bf16(float f) { return (uint16_t)(pack_bf16(f, 0.f) & 0xffffu); }
 
 // inclusive prefix sum over the 64 lanes of a wavefront
 __device__ __forceinline__ uint32_t wave_incl_scan(uint32_t x) {
@@ -95,6 +99,85 @@ __device__ __forceinline__ void issue_tile(u32x4 (&st)[MAXCH], uint2& mk, const 
 #pragma unroll
     for (int c = 0; c < MAXCH; ++c) st[c] = src[min((uint32_t)(c * 64 + lane), n16 - 1u)];
     mk = masks[(size_t)t * 64 + lane];
+}
+
+// Expands the tile staged in this wavefront's LDS buffer into its eight MFMA A operands and hands
+// them, one 64-column super-step at a time, to use(q, f0, f1).
+//
+// Lane l owns row l % 16 and, in super-step q, columns 64q + 16(l / 16) + 0..15 as four nibbles of
+// its 16-bit mask.  The values of run (q, h) = nibble h of every lane, in lane order, start at
+// base[4q + h] (16-bit halves of the eight directory words); a lane's own values follow those of the
+// lower lanes, whose count is an exclusive wave prefix sum of the nibble popcounts (four 8-bit fields
+// scanned in one dword).  A 12-byte LDS window at the 4-byte-aligned address below the lane's first
+// value, two byte-aligns and two byte-permutes with a selector looked up by the nibble put its (at most
+// four) values into their columns and zeros elsewhere.  (A single 8-byte read at the 2-byte-aligned
+// address is legal on gfx950 but measured far slower.)  The stream carries eight bytes of slack, so the
+// window never leaves the buffer.
+//
+// The four scans run first and the sixteen LDS reads of two super-steps are issued back to back
+// before the first is consumed, so that a wavefront pays the LDS latency twice per tile, not per nibble.
+template <typename F>
+__device__ __forceinline__ void expand_tile(const uint8_t* __restrict__ bufb, const uint2* __restrict__ lut,
+                                            const uint32_t (&base)[8], uint2 mk, F&& use) {
+    const uint32_t m16[4] = {mk.x & 0xffffu, mk.x >> 16, mk.y & 0xffffu, mk.y >> 16};
+    uint32_t ex[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const uint32_t bits = m16[q];
+        const uint32_t packed = (uint32_t)__builtin_popcount(bits & 0xfu) | ((uint32_t)__builtin_popcount(bits & 0xf0u) << 8) |
+                                ((uint32_t)__builtin_popcount(bits & 0xf00u) << 16) |
+                                ((uint32_t)__builtin_popcount(bits & 0xf000u) << 24);
+        ex[q] = wave_excl_scan(packed);  // per nibble: values of lower lanes (<= 252, no carry)
+    }
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+        Tri32 tr[8];
+        uint2 sel[8];
+        uint32_t off[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int q = 2 * half + (i >> 2), h = i & 3;
+            const uint32_t run_base = (base[(4 * q + h) >> 1] >> (16 * (h & 1))) & 0xffffu;
+            off[i] = (run_base + ((ex[q] >> (8 * h)) & 0xffu)) * 2u;  // byte offset in the tile's stream
+            tr[i] = *reinterpret_cast<const Tri32*>(bufb + (off[i] & ~3u));
+            sel[i] = lut[(m16[q] >> (4 * h)) & 15u];
+        }
+        Frag f[2][2];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int h = i & 3;
+            const uint32_t w0 = __builtin_amdgcn_alignbyte(tr[i].b, tr[i].a, off[i]);
+            const uint32_t w1 = __builtin_amdgcn_alignbyte(tr[i].c, tr[i].b, off[i]);
+            f[i >> 2][h >> 1].u[2 * (h & 1) + 0] = __builtin_amdgcn_perm(w1, w0, sel[i].x);
+            f[i >> 2][h >> 1].u[2 * (h & 1) + 1] = __builtin_amdgcn_perm(w1, w0, sel[i].y);
+        }
+        use(2 * half, f[0][0], f[0][1]);
+        use(2 * half + 1, f[1][0], f[1][1]);
+    }
+}
+
+// The same request with the value stream written straight into LDS (no staging registers): piece c of the
+// tile lands at lds_buf + c * 1024 bytes, 16 bytes per lane in lane order.  lds_buf is wave-uniform.  The
+// data is in LDS once the wavefront's vector-memory counter has drained (s_waitcnt vmcnt(0)).
+template <int MAXCH>
+__device__ __forceinline__ void issue_tile_lds(uint32_t* lds_buf, uint2& mk, const uint16_t* __restrict__ vals,
+                                               const uint2* __restrict__ tile_masks, uint32_t val_start, uint32_t nnz,
+                                               int lane) {
+    const u32x4* __restrict__ src = reinterpret_cast<const u32x4*>(vals + (size_t)val_start * 8);
+    const uint32_t n16 = (nnz * 2 + 8 + 15) / 16;
+#pragma unroll
+    for (int c = 0; c < MAXCH; ++c)
+        __builtin_amdgcn_global_load_lds(
+            (const __attribute__((address_space(1))) void*)(src + min((uint32_t)(c * 64 + lane), n16 - 1u)),
+            (__attribute__((address_space(3))) void*)(lds_buf + c * 256), 16, 0, 0);
+    mk = tile_masks[lane];
+}
+
+// Waits until every vector-memory operation of this wavefront has completed (loads returned, direct-to-LDS
+// data written) without touching the other counters, and keeps the compiler from moving LDS reads above it.
+__device__ __forceinline__ void wait_vector_memory() {
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0), expcnt and lgkmcnt unconstrained
+    asm volatile("" ::: "memory");
 }
 
 }  // namespace sd2

@@ -80,7 +80,8 @@ struct MegaArgs {
     uint16_t* trace_x;    // optional [phase][k_tok][trace_kmax] bf16: the activations each linear consumed
     float* trace_src;     // optional [phase][k_tok][trace_smax] fp32: the values its input glue read
     int trace_kmax, trace_smax;
-    unsigned long long* trace_time;  // optional [workgroup][phase][4] 100 MHz timestamps: start, barrier, prologue, tiles
+    unsigned long long* trace_time;  // optional [workgroup][phase][8] 100 MHz clock: start, barrier, prologue, tiles (timestamps);
+                                     // wavefront 0's ticks spent waiting for streams, ticks decoding, tiles; spare
     const unsigned char* blob[4 * kMegaMaxLayers];
 };
 
@@ -93,6 +94,8 @@ MegaLayout mega_layout(int layers, int hidden, int q_out, int kv_out, int inter,
 int mega_grid_size();
 // Chooses the workgroup tiling of each matrix kind; false when the persistent kernel cannot run this model here.
 bool mega_plan(MegaGeo (&geo)[4], int layers, int hidden, int head_dim, int k_tok, int max_tile_nnz);
-hipError_t launch_mega_forward(const MegaArgs& a, const uint16_t* h_in, void* zero_base, size_t zero_bytes, hipStream_t s);
+// probe: timestamps only, plus wavefront 0's wait/decode split (needs a.trace_time, a.trace_x == nullptr)
+hipError_t launch_mega_forward(const MegaArgs& a, const uint16_t* h_in, void* zero_base, size_t zero_bytes, bool probe,
+                               hipStream_t s);
 
 }  // namespace sd2

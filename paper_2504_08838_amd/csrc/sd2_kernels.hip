@@ -66,45 +66,23 @@ __device__ __forceinline__ void sparse_tile(u32x4 (&st)[MAXCH], uint2& mk_next, 
     de_cur = de_next;
     de_next = dir[min(t + 2, n_tiles - 1)];
 
-    const uint8_t* bufb = reinterpret_cast<const uint8_t*>(buf);
-    const uint32_t m16[4] = {mk.x & 0xffffu, mk.x >> 16, mk.y & 0xffffu, mk.y >> 16};
     f32x4 acc[TG];
 #pragma unroll
     for (int tg = 0; tg < TG; ++tg) acc[tg] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-        const uint32_t bits = m16[q];
-        uint32_t nib[4];
-#pragma unroll
-        for (int h = 0; h < 4; ++h) nib[h] = (bits >> (4 * h)) & 15u;
-        const uint32_t packed = (uint32_t)__builtin_popcount(nib[0]) | ((uint32_t)__builtin_popcount(nib[1]) << 8) |
-                                ((uint32_t)__builtin_popcount(nib[2]) << 16) | ((uint32_t)__builtin_popcount(nib[3]) << 24);
-        const uint32_t ex = wave_excl_scan(packed);  // per nibble: values of lower lanes (<= 252, no carry)
-        Frag f[2];
-#pragma unroll
-        for (int h = 0; h < 4; ++h) {
-            const uint32_t run_base = (de.base[(4 * q + h) >> 1] >> (16 * (h & 1))) & 0xffffu;
-            const uint32_t off = (run_base + ((ex >> (8 * h)) & 0xffu)) * 2u;  // byte offset in the tile's stream
-            const Tri32 tr = *reinterpret_cast<const Tri32*>(bufb + (off & ~3u));
-            const uint32_t w0 = __builtin_amdgcn_alignbyte(tr.b, tr.a, off);
-            const uint32_t w1 = __builtin_amdgcn_alignbyte(tr.c, tr.b, off);
-            const uint2 sel = lut[nib[h]];
-            f[h >> 1].u[2 * (h & 1) + 0] = __builtin_amdgcn_perm(w1, w0, sel.x);
-            f[h >> 1].u[2 * (h & 1) + 1] = __builtin_amdgcn_perm(w1, w0, sel.y);
-        }
+    expand_tile(reinterpret_cast<const uint8_t*>(buf), lut, de.base, mk, [&](int q, const Frag& f0, const Frag& f1) {
         if (TG == 1) {
-            acc[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f[0].v, b[q][0].v, acc[0], 0, 0, 0);
-            acc[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f[1].v, b[q][1].v, acc[0], 0, 0, 0);
+            acc[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f0.v, b[q][0].v, acc[0], 0, 0, 0);
+            acc[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f1.v, b[q][1].v, acc[0], 0, 0, 0);
         } else {
 #pragma unroll
             for (int tg = 0; tg < TG; ++tg) {
                 Frag x0, x1;
                 load_row16(x, n + 16 * tg, k_tok, col0 + 64 * q, k_in, x0, x1);
-                acc[tg] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f[0].v, x0.v, acc[tg], 0, 0, 0);
-                acc[tg] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f[1].v, x1.v, acc[tg], 0, 0, 0);
+                acc[tg] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f0.v, x0.v, acc[tg], 0, 0, 0);
+                acc[tg] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f1.v, x1.v, acc[tg], 0, 0, 0);
             }
         }
-    }
+    });
     store_tile<TG>(acc, out, n_out, k_tok, strip, slab, lane);
 }
 

@@ -22,20 +22,19 @@ constexpr int kMegaWaves = 12;
 constexpr int kMegaThreads = 64 * kMegaWaves;
 constexpr int kMegaCh = 5;                          // 1 KiB pieces of a staged tile
 constexpr int kTileDw = kMegaCh * 256;              // dwords per wavefront tile buffer
-constexpr int kMaxB = 8;                            // slabs per workgroup block (activation columns kept in LDS)
+constexpr int kMaxB = 6;                            // slabs per workgroup block (activation columns kept in LDS)
 constexpr int kMaxBAtt = 3;                         // ... for the linear that follows attention
 constexpr int kMaxS = 16;                           // strips per workgroup block (LDS accumulators)
 constexpr int kXldsDw = kMaxB * kMegaMaxTok * 256 / 2;  // bf16 [slab][token][256]
 constexpr int kRedDw = kMaxS * kMegaMaxTok * 16;        // fp32 [strip][token][row]
 constexpr int kMiscDw = 512;                            // attention probabilities, per-token scalars
 constexpr int kAttHeads = 6;                            // heads (and kv heads) one workgroup may need
-constexpr int kScrDw = 3 * kMegaMaxTok * kAttHeads * 128;  // prologue scratch; the tile buffers live in the same area
-constexpr int kAreaDw = kScrDw > kMegaWaves * kTileDw ? kScrDw : kMegaWaves * kTileDw;
-constexpr size_t kMegaLds = (size_t)(kAreaDw + kXldsDw + kRedDw + kMiscDw) * 4;
+constexpr int kAreaDw = 2 * kMegaWaves * kTileDw;       // two tile buffers per wavefront: one being expanded, one being filled
+constexpr size_t kMegaLds = (size_t)(kAreaDw + kXldsDw + kRedDw + kMiscDw + 4 * 12) * 4;
 constexpr int kBarWords = 32 + 8 * 32 + 8 * 32;     // top counter, 8 group counters, 8 group flags
-static_assert(kMaxB * kMegaMaxTok * 256 <= kAreaDw, "column stash must fit the scratch area");
 static_assert(kAttHeads * 128 == kMegaThreads, "one thread per (head slot, dimension)");
-static_assert(4 * kMegaThreads >= kMegaMaxHidden && 3 * kMegaThreads >= kMaxB * 256, "prologue chunking");
+static_assert(4 * kMegaThreads >= kMegaMaxHidden && 2 * kMegaThreads >= kMaxB * 256, "columns per thread in the prologues");
+static_assert(kMaxBAtt * 256 <= kAttHeads * 128, "attention block fits the head slots");
 
 #define SD2_AGENT __HIP_MEMORY_SCOPE_AGENT
 
@@ -61,88 +60,101 @@ __device__ __forceinline__ float wave_sum(float v) {
 // gives scalar loads, where indexing the by-value parameter would make the compiler copy it to scratch.
 typedef const __attribute__((address_space(4))) MegaArgs* KArgs;
 
+// One tile of this wavefront's walk, all fields wave-uniform.
 struct TileRef {
-    int p;   // phase = 4 * layer + kind; == n_phases when there is no tile
-    int ss;  // strip inside the workgroup's block
-    int sl;  // slab inside the workgroup's block
-    int t;   // tile index inside the matrix
+    int p;                       // phase = 4 * layer + kind; == n_phases when there is no tile
+    int ss, sl;                  // strip and slab inside the workgroup's block
+    const unsigned char* dir;    // the tile's directory entry
+    const unsigned char* masks;  // the tile's 64 x 8 mask bytes
+    const unsigned char* vals;   // value section of the tile's blob
 };
 
-// Where this workgroup's block of each matrix kind starts (computed once).
-struct KindPlan {
+// Per-kind plan in LDS, written once by threads 0..3: where this workgroup's block starts and the
+// blob offsets common to all layers of the kind.
+constexpr int kPlanDw = 12;  // s_blk b_blk strip0 slab0 | n_strips n_slabs active - | mask_off(2) val_off(2)
+
+struct PhasePlan {
     int s_blk, b_blk, strip0, slab0, n_strips, n_slabs, active;
+    const unsigned char* blob;
+    unsigned long long mask_off, val_off;
 };
 
-// The plan of one kind is rebuilt from the kernarg segment whenever it is needed (scalar loads and a
-// scalar division): keeping the four plans in a local aggregate chosen at run time would put them in
-// scratch memory and turn every tile index into a per-lane value.
-__device__ __forceinline__ KindPlan pick_plan(KArgs ka, int kind, int cu) {
-    KindPlan k;
-    const int n_sblk = ka->geo[kind].n_sblk, n_bblk = ka->geo[kind].n_bblk;
-    k.s_blk = ka->geo[kind].s_blk;
-    k.b_blk = ka->geo[kind].b_blk;
-    const int q = cu / n_sblk;
-    k.strip0 = (cu - q * n_sblk) * k.s_blk;
-    k.slab0 = q * k.b_blk;
-    k.n_strips = ka->geo[kind].n_strips;
-    k.n_slabs = ka->geo[kind].n_slabs;
-    k.active = cu < n_sblk * n_bblk;
-    return k;
+__device__ __forceinline__ int uni(uint32_t v) { return __builtin_amdgcn_readfirstlane((int)v); }
+
+__device__ __forceinline__ void load_phase(PhasePlan& pp, KArgs ka, const uint32_t* plans, int p, int n_phases) {
+    pp.active = 0;
+    if (p >= n_phases) return;
+    const u32x4* e = reinterpret_cast<const u32x4*>(plans + (p & 3) * kPlanDw);
+    const u32x4 a = e[0], b = e[1], c = e[2];  // same address in every lane: one broadcast read each
+    pp.blob = ka->blob[p];
+    pp.s_blk = uni(a[0]);
+    pp.b_blk = uni(a[1]);
+    pp.strip0 = uni(a[2]);
+    pp.slab0 = uni(a[3]);
+    pp.n_strips = uni(b[0]);
+    pp.n_slabs = uni(b[1]);
+    pp.active = uni(b[2]);
+    pp.mask_off = (unsigned long long)(uint32_t)uni(c[0]) | ((unsigned long long)(uint32_t)uni(c[1]) << 32);
+    pp.val_off = (unsigned long long)(uint32_t)uni(c[2]) | ((unsigned long long)(uint32_t)uni(c[3]) << 32);
 }
 
-// First tile of this wavefront at or after local position (ss, sl) of phase p; tiles of a block are numbered
-// strip-first and dealt to the 16 wavefronts round-robin, so a wavefront advances by 16 strips at a time.
-__device__ __forceinline__ TileRef find_tile(KArgs ka, int cu, int p, int ss, int sl, int n_phases, int wave) {
-    for (; p < n_phases; ++p) {
-        const KindPlan k = pick_plan(ka, p & 3, cu);
-        if (k.active) {
-            for (;;) {
-                while (ss >= k.s_blk) {
-                    ss -= k.s_blk;
-                    ++sl;
-                }
-                if (sl >= k.b_blk) break;
-                const int strip = k.strip0 + ss, slab = k.slab0 + sl;
-                if (strip < k.n_strips && slab < k.n_slabs) return TileRef{p, ss, sl, slab * k.n_strips + strip};
-                ss += kMegaWaves;
+// Walks this wavefront's tiles in execution order: within a phase the tiles of the workgroup's block are
+// numbered strip-first and dealt to the wavefronts round-robin; phases follow each other.  The plan of the
+// phase it stands in is kept in scalar registers, so a step inside a phase is a handful of scalar operations.
+struct TileIter {
+    int p, ss, sl;
+    PhasePlan pp;
+};
+
+__device__ __forceinline__ TileRef iter_next(TileIter& it, KArgs ka, const uint32_t* plans, int n_phases, int wave) {
+    for (;;) {
+        if (it.p >= n_phases) return TileRef{n_phases, 0, 0, nullptr, nullptr, nullptr};
+        if (it.pp.active) {
+            while (it.ss >= it.pp.s_blk) {  // s_blk >= 1
+                it.ss -= it.pp.s_blk;
+                ++it.sl;
+            }
+            if (it.sl < it.pp.b_blk) {
+                const int strip = it.pp.strip0 + it.ss, slab = it.pp.slab0 + it.sl;
+                const bool ok = strip < it.pp.n_strips && slab < it.pp.n_slabs;
+                const size_t t = (size_t)slab * it.pp.n_strips + strip;
+                const TileRef r{it.p, it.ss, it.sl, it.pp.blob + 128 + t * 48, it.pp.blob + it.pp.mask_off + t * 512,
+                                it.pp.blob + it.pp.val_off};
+                it.ss += kMegaWaves;
+                if (ok) return r;
+                continue;
             }
         }
-        ss = wave;
-        sl = 0;
+        ++it.p;
+        load_phase(it.pp, ka, plans, it.p, n_phases);
+        it.ss = wave;
+        it.sl = 0;
     }
-    return TileRef{n_phases, 0, 0, 0};
 }
 
-__device__ __forceinline__ TileRef next_tile(KArgs ka, int cu, TileRef r, int n_phases, int wave) {
-    if (r.p >= n_phases) return r;
-    return find_tile(ka, cu, r.p, r.ss + kMegaWaves, r.sl, n_phases, wave);
-}
-
-// The 12 dwords of a directory entry, one per lane (lanes 0..11); converted to scalars a tile later.
-__device__ __forceinline__ uint32_t load_dir_raw(KArgs ka, TileRef r, int n_phases, int lane) {
+// The 12 dwords of a tile's directory entry, one per lane (lanes 0..11); read back with readlane when needed.
+__device__ __forceinline__ uint32_t load_dir_raw(const TileRef& r, int n_phases, int lane) {
     if (r.p >= n_phases) return 0u;
-    const uint32_t* d = reinterpret_cast<const uint32_t*>(ka->blob[r.p] + 128) + (size_t)r.t * 12;
-    return d[lane < 12 ? lane : 11];
+    return reinterpret_cast<const uint32_t*>(r.dir)[lane < 12 ? lane : 11];
 }
 
-__device__ __forceinline__ DirEnt dir_from_raw(uint32_t raw) {
-    DirEnt e;
-    e.val_start = (uint32_t)__builtin_amdgcn_readlane((int)raw, 0);
-    e.nnz = (uint32_t)__builtin_amdgcn_readlane((int)raw, 1);
-#pragma unroll
-    for (int i = 0; i < 8; ++i) e.base[i] = (uint32_t)__builtin_amdgcn_readlane((int)raw, 2 + i);
-    e.zero[0] = e.zero[1] = 0;
-    return e;
-}
+__device__ __forceinline__ uint32_t raw_word(uint32_t raw, int i) { return (uint32_t)__builtin_amdgcn_readlane((int)raw, i); }
 
 // Grid barrier: 8 groups of workgroups (by id mod 8) count arrivals, the last of each group
 // arrives at the top counter, the very last releases the 8 group flags.  Counters only grow;
 // `gen` is the number of barriers passed.  Waits are bounded: on overrun *err is set and the
 // kernel keeps going (results are then invalid, but every wave still terminates).
-__device__ __forceinline__ void grid_barrier(unsigned* bar, unsigned* err, unsigned ncu, unsigned& gen, int spin_limit) {
-    __builtin_amdgcn_s_waitcnt(0);  // this wave's stores and atomics have been acknowledged
+//
+// The barrier comes in two halves so that a wavefront can expand its next weight tile (which needs no
+// activations) between announcing its arrival and waiting for the release.
+//
+// Arrive: every wavefront has its stores and atomics acknowledged; thread 0 then counts the workgroup in.
+// Returns true (in thread 0) when this workgroup was the last one and has released everybody.
+__device__ __forceinline__ bool barrier_arrive(unsigned* bar, unsigned ncu, unsigned& gen) {
+    __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
     gen += 1;
+    bool released = false;
     if (threadIdx.x == 0) {
         unsigned* top = bar;
         unsigned* gcount = bar + 32;
@@ -150,33 +162,39 @@ __device__ __forceinline__ void grid_barrier(unsigned* bar, unsigned* err, unsig
         const unsigned grp = blockIdx.x & 7u;
         const unsigned ngrp = ncu < 8u ? ncu : 8u;
         const unsigned gsize = (ncu - grp + 7u) / 8u;
-        bool wait = true;
         const unsigned prev = __hip_atomic_fetch_add(&gcount[grp * 32], 1u, __ATOMIC_RELAXED, SD2_AGENT);
         if (prev + 1 == gen * gsize) {
             const unsigned p2 = __hip_atomic_fetch_add(top, 1u, __ATOMIC_RELAXED, SD2_AGENT);
             if (p2 + 1 == gen * ngrp) {
-                wait = false;
+                released = true;
                 for (unsigned g = 0; g < ngrp; ++g) __hip_atomic_store(&gflag[g * 32], gen, __ATOMIC_RELAXED, SD2_AGENT);
             }
         }
-        if (wait) {
-            int spins = 0;
-            while (__hip_atomic_load(&gflag[grp * 32], __ATOMIC_RELAXED, SD2_AGENT) < gen) {
-                __builtin_amdgcn_s_sleep(2);
-                if (++spins > spin_limit) {
-                    __hip_atomic_store(err, 1u, __ATOMIC_RELAXED, SD2_AGENT);
-                    break;
-                }
+    }
+    return released;
+}
+
+// Wait: thread 0 polls its group's flag (bounded), one wavefront drops this CU's (and its XCD's) cached
+// copies so that the ordinary cached loads of the prologue see what the other XCDs wrote through to
+// memory with their atomics, and the workgroup goes on together.
+__device__ __forceinline__ void barrier_wait(unsigned* bar, unsigned* err, unsigned gen, bool released, int spin_limit) {
+    if (threadIdx.x == 0 && !released) {
+        unsigned* gflag = bar + 32 + 8 * 32;
+        const unsigned grp = blockIdx.x & 7u;
+        int spins = 0;
+        while (__hip_atomic_load(&gflag[grp * 32], __ATOMIC_RELAXED, SD2_AGENT) < gen) {
+            __builtin_amdgcn_s_sleep(2);
+            if (++spins > spin_limit) {
+                __hip_atomic_store(err, 1u, __ATOMIC_RELAXED, SD2_AGENT);
+                break;
             }
         }
     }
-    // One wavefront drops this CU's (and its XCD's) cached copies, so that the ordinary cached loads
-    // of the prologue see what the other XCDs wrote through to memory with their atomics.
     if (threadIdx.x < 64) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
     __syncthreads();
 }
 
-template <bool TRACE>
+template <bool TRACE, bool PROBE>
 __global__ __launch_bounds__(kMegaThreads) void mega_forward_kernel(const MegaArgs a) {
     extern __shared__ uint32_t mega_lds[];
     __shared__ uint2 lut[16];
@@ -189,31 +207,53 @@ __global__ __launch_bounds__(kMegaThreads) void mega_forward_kernel(const MegaAr
     const int k_tok = a.k_tok;
     KArgs ka = (KArgs)__builtin_amdgcn_kernarg_segment_ptr();
 
-    uint32_t* buf = mega_lds + wave * kTileDw;                  // this wave's tile buffer
-    float* scr = reinterpret_cast<float*>(mega_lds);            // prologue scratch (aliases all tile buffers)
+    uint32_t* bufs = mega_lds + wave * (2 * kTileDw);           // this wave's two tile buffers
+    int cb = 0;                                                 // the one the current tile's stream is in (or on its way to)
     uint16_t* xlds = reinterpret_cast<uint16_t*>(mega_lds + kAreaDw);
     float* red = reinterpret_cast<float*>(mega_lds + kAreaDw + kXldsDw);
-    float* misc = red + kRedDw;                                 // [0,384) probabilities, [384,400) per-token scalars
+    float* misc = red + kRedDw;                                 // [0,384) attention scores / probabilities, 6 heads x 8 x 8
+    float* sums = misc + 384;                                   // [0,8) sums of squares, [8,16) their inverse roots
     if (tid < 16) lut[tid] = make_expand_selector((uint32_t)tid);
-    for (int i = tid; i < kRedDw; i += kMegaThreads) red[i] = 0.f;
+    for (int i = tid; i < kRedDw + kMiscDw; i += kMegaThreads) red[i] = 0.f;  // accumulators, scores, sums
+    for (int i = tid; i < kXldsDw; i += kMegaThreads) (mega_lds + kAreaDw)[i] = 0u;  // rows of unused token slots stay zero
 
-    // this wave's first three tiles; the first one's stream is requested right away
-    TileRef cur = find_tile(ka, cu, 0, wave, 0, n_phases, wave);
-    TileRef nxt = next_tile(ka, cu, cur, n_phases, wave);
-    TileRef nn = next_tile(ka, cu, nxt, n_phases, wave);
-    DirEnt de_cur = dir_from_raw(load_dir_raw(ka, cur, n_phases, lane));
-    DirEnt de_nxt = dir_from_raw(load_dir_raw(ka, nxt, n_phases, lane));
-    uint32_t de_raw = load_dir_raw(ka, nn, n_phases, lane);
-    u32x4 st[kMegaCh];
-    uint2 mk_next = make_uint2(0, 0);
-#pragma unroll
-    for (int c = 0; c < kMegaCh; ++c) st[c] = u32x4{0, 0, 0, 0};
-    if (cur.p < n_phases) {
-        const unsigned char* bl = ka->blob[cur.p];
-        issue_tile<kMegaCh>(st, mk_next, reinterpret_cast<const uint16_t*>(bl + ka->geo[cur.p & 3].val_off),
-                            reinterpret_cast<const uint2*>(bl + ka->geo[cur.p & 3].mask_off), de_cur.val_start, de_cur.nnz,
-                            cur.t, lane);
+    // per-kind plans -> LDS
+    uint32_t* plans = reinterpret_cast<uint32_t*>(misc + kMiscDw);
+    if (tid < 4) {
+        const int n_sblk = ka->geo[tid].n_sblk, n_bblk = ka->geo[tid].n_bblk;
+        const int s_blk = max(ka->geo[tid].s_blk, 1), b_blk = ka->geo[tid].b_blk;
+        const int qb = cu / n_sblk;
+        uint32_t* e = plans + tid * kPlanDw;
+        e[0] = (uint32_t)s_blk;
+        e[1] = (uint32_t)b_blk;
+        e[2] = (uint32_t)((cu - qb * n_sblk) * s_blk);
+        e[3] = (uint32_t)(qb * b_blk);
+        e[4] = (uint32_t)ka->geo[tid].n_strips;
+        e[5] = (uint32_t)ka->geo[tid].n_slabs;
+        e[6] = cu < n_sblk * n_bblk ? 1u : 0u;
+        e[7] = 0u;
+        e[8] = (uint32_t)ka->geo[tid].mask_off;
+        e[9] = (uint32_t)(ka->geo[tid].mask_off >> 32);
+        e[10] = (uint32_t)ka->geo[tid].val_off;
+        e[11] = (uint32_t)(ka->geo[tid].val_off >> 32);
     }
+    __syncthreads();
+    // this wave's first three tiles; the first one's stream is requested right away
+    TileIter it;
+    it.p = 0;
+    it.ss = wave;
+    it.sl = 0;
+    load_phase(it.pp, ka, plans, 0, n_phases);
+    TileRef cur = iter_next(it, ka, plans, n_phases, wave);
+    TileRef nxt = iter_next(it, ka, plans, n_phases, wave);
+    TileRef nn = iter_next(it, ka, plans, n_phases, wave);
+    uint32_t raw_cur = load_dir_raw(cur, n_phases, lane);
+    uint32_t raw_nxt = load_dir_raw(nxt, n_phases, lane);
+    uint32_t raw_nn = load_dir_raw(nn, n_phases, lane);
+    uint2 mk_next = make_uint2(0, 0);
+    if (cur.p < n_phases)
+        issue_tile_lds<kMegaCh>(bufs, mk_next, reinterpret_cast<const uint16_t*>(cur.vals),
+                                reinterpret_cast<const uint2*>(cur.masks), raw_word(raw_cur, 0), raw_word(raw_cur, 1), lane);
     unsigned gen = 0;
 
     for (int p = 0; p < n_phases; ++p) {
@@ -225,188 +265,189 @@ __global__ __launch_bounds__(kMegaThreads) void mega_forward_kernel(const MegaAr
         ge.n_slabs = ka->geo[kind].n_slabs;
         ge.s_blk = ka->geo[kind].s_blk;
         ge.b_blk = ka->geo[kind].b_blk;
-        unsigned long long* tt = a.trace_time ? a.trace_time + ((size_t)cu * n_phases + p) * 4 : nullptr;
+        unsigned long long* tt = a.trace_time ? a.trace_time + ((size_t)cu * n_phases + p) * 8 : nullptr;
         if (tt && tid == 0) tt[0] = __builtin_amdgcn_s_memrealtime();
-        if (p > 0) grid_barrier(a.bar, a.err, (unsigned)ncu, gen, a.spin_limit);
+        bool released = false;
+        if (p > 0) released = barrier_arrive(a.bar, (unsigned)ncu, gen);
+
+        // Stages this wave's current tile in its LDS buffer, requests the stream of the one after it and the
+        // directory entry of the third, and moves the walk on; returns what the expansion of the staged tile needs.
+        auto stage_tile = [&](uint2& mk, uint32_t (&base)[8]) -> const uint8_t* {
+            wait_vector_memory();  // the current tile's stream is in LDS, its masks in registers
+            mk = mk_next;
+            const uint8_t* bufb = reinterpret_cast<const uint8_t*>(bufs + cb * kTileDw);
+            cb ^= 1;
+            if (nxt.p < n_phases)
+                issue_tile_lds<kMegaCh>(bufs + cb * kTileDw, mk_next, reinterpret_cast<const uint16_t*>(nxt.vals),
+                                        reinterpret_cast<const uint2*>(nxt.masks), raw_word(raw_nxt, 0), raw_word(raw_nxt, 1), lane);
+            const TileRef n3 = iter_next(it, ka, plans, n_phases, wave);
+            const uint32_t raw_n3 = load_dir_raw(n3, n_phases, lane);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) base[i] = raw_word(raw_cur, 2 + i);
+            cur = nxt;
+            nxt = nn;
+            nn = n3;
+            raw_cur = raw_nxt;
+            raw_nxt = raw_nn;
+            raw_nn = raw_n3;
+            return bufb;
+        };
+
+        // While the barrier settles, this wave's first tile of the phase is expanded into its eight MFMA operands:
+        // weights do not depend on activations.
+        Frag fpre[4][2];
+        const bool have_pre = cur.p == p;
+        const int pre_ss = cur.ss, pre_sl = cur.sl;
+        if (have_pre) {
+            uint2 mk;
+            uint32_t base[8];
+            const uint8_t* bufb = stage_tile(mk, base);
+            expand_tile(bufb, lut, base, mk, [&](int q, const Frag& f0, const Frag& f1) {
+                fpre[q][0].q = f0.q;
+                fpre[q][1].q = f1.q;
+            });
+        } else {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) fpre[q][0].q = fpre[q][1].q = u32x4{0, 0, 0, 0};  // defined in every path
+        }
+        if (PROBE && tt && tid == 0) tt[4] = __builtin_amdgcn_s_memrealtime();
+        if (p > 0) barrier_wait(a.bar, a.err, gen, released, a.spin_limit);
         if (tt && tid == 0) tt[1] = __builtin_amdgcn_s_memrealtime();
 
         // ---------------- prologue: the activation columns of this workgroup's slabs, as bf16 in LDS
-        const KindPlan kpl = pick_plan(ka, kind, cu);
-        const bool active = kpl.active;
-        const int col_lo = kpl.slab0 * 256;                                       // first column of the block
+        const uint32_t* kpl = plans + kind * kPlanDw;
+        const bool active = uni(kpl[6]) != 0;
+        const int strip_lo = uni(kpl[2]);
+        const int col_lo = uni(kpl[3]) * 256;                                     // first column of the block
         const int n_col = active ? max(0, min(ge.b_blk * 256, ge.k_in - col_lo)) : 0;  // columns that exist
         const int nqkv = a.q_out + 2 * a.kv_out;
         float* yq = a.yqkv + (size_t)(layer & 1) * k_tok * nqkv;
         float* yg = a.ygu + (size_t)(layer & 1) * k_tok * 2 * a.inter;
         const size_t tr_x = ((size_t)p * k_tok) * a.trace_kmax, tr_s = ((size_t)p * k_tok) * a.trace_smax;
 
+        // columns past the end of a ragged last slab must read as zero
+        if (n_col < ge.b_blk * 256)
+            for (int idx = tid; idx < ge.b_blk * kMegaMaxTok * 256; idx += kMegaThreads)
+                if ((idx >> 11) * 256 + (idx & 255) >= n_col) xlds[idx] = 0;
+
         if (kind == 0 || kind == 2) {
-            // (1) the whole residual: squares for the norm, and a stash of the columns this block needs;
-            // four tokens x four column chunks of loads are in flight at a time
-            if (tid < 16) misc[384 + tid] = 0.f;
-            __syncthreads();
-            for (int t0 = 0; t0 < k_tok; t0 += 4) {
-                float hv[4][4];
+            // Thread i owns columns 4i..4i+3 of every token: all loads of the residual are in flight at once,
+            // the squares meet in LDS, and each thread then normalises and rounds the columns it holds.
+            const int c4 = 4 * tid;
+            f32x4 hv[kMegaMaxTok];
 #pragma unroll
-                for (int tt = 0; tt < 4; ++tt)
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const int col = tid + e * kMegaThreads;
-                        hv[tt][e] = (t0 + tt < k_tok && col < a.hidden) ? aload(a.h + (size_t)(t0 + tt) * a.hidden + col) : 0.f;
-                    }
-#pragma unroll
-                for (int tt = 0; tt < 4; ++tt) {
-                    const int t = t0 + tt;
-                    if (t < k_tok) {
-                        float ss = 0.f;
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) {
-                            ss += hv[tt][e] * hv[tt][e];
-                            const int c = tid + e * kMegaThreads - col_lo;
-                            if (c >= 0 && c < n_col) {
-                                scr[t * (kMaxB * 256) + c] = hv[tt][e];
-                                if (TRACE) a.trace_src[tr_s + (size_t)t * a.trace_smax + col_lo + c] = hv[tt][e];
-                            }
-                        }
-                        ss = wave_sum(ss);
-                        if (lane == 0) atomicAdd(&misc[384 + t], ss);
-                    }
-                }
+            for (int t = 0; t < kMegaMaxTok; ++t)
+                hv[t] = (t < k_tok && c4 < a.hidden) ? *reinterpret_cast<const f32x4*>(a.h + (size_t)t * a.hidden + c4)
+                                                     : f32x4{0.f, 0.f, 0.f, 0.f};
+            if (PROBE) {
+                    __builtin_amdgcn_s_waitcnt(0);
+                    if (tt && tid == 0) tt[5] = __builtin_amdgcn_s_memrealtime();
             }
-            __syncthreads();
-            if (tid < k_tok) misc[400 + tid] = 1.0f / sqrtf(misc[384 + tid] / (float)a.hidden + 1e-5f);
-            __syncthreads();
-            // (2) normalise and round
-            for (int idx = tid; idx < ge.b_blk * kMegaMaxTok * 256; idx += kMegaThreads) {
-                const int c = idx & 255, t = (idx >> 8) & (kMegaMaxTok - 1), sl = idx >> 11;
-                const int cc = sl * 256 + c;
-                uint16_t v = 0;
-                if (t < k_tok && cc < n_col) {
-                    v = f32_to_bf16(scr[t * (kMaxB * 256) + cc] * misc[400 + t]);
-                    if (TRACE) a.trace_x[tr_x + (size_t)t * a.trace_kmax + col_lo + cc] = v;
+#pragma unroll
+            for (int t = 0; t < kMegaMaxTok; ++t)
+                if (t < k_tok) {
+                    const float ss = wave_sum(hv[t][0] * hv[t][0] + hv[t][1] * hv[t][1] + hv[t][2] * hv[t][2] + hv[t][3] * hv[t][3]);
+                    if (lane == 0) atomicAdd(&sums[t], ss);
                 }
-                xlds[idx] = v;
-            }
             // recycle an accumulator that is idle now: it will be added into two layers from here
-            float* z = kind == 2 ? yq : a.ygu + (size_t)((layer + 1) & 1) * k_tok * 2 * a.inter;
-            const int zn = kind == 2 ? k_tok * nqkv : k_tok * 2 * a.inter;
-            if (kind == 2 || layer > 0) {
-                const int z0 = (int)((long long)zn * cu / ncu), z1 = (int)((long long)zn * (cu + 1) / ncu);
-                for (int i = z0 + tid; i < z1; i += kMegaThreads) astore(z + i, 0.f);
+            {
+                float* z = kind == 2 ? yq : a.ygu + (size_t)((layer + 1) & 1) * k_tok * 2 * a.inter;
+                const int zn = kind == 2 ? k_tok * nqkv : k_tok * 2 * a.inter;
+                if (kind == 2 || layer > 0) {
+                    const int z0 = (int)((long long)zn * cu / ncu), z1 = (int)((long long)zn * (cu + 1) / ncu);
+                    for (int i = z0 + tid; i < z1; i += kMegaThreads) astore(z + i, 0.f);
+                }
+            }
+            __syncthreads();
+            if (tid < k_tok) sums[8 + tid] = 1.0f / sqrtf(sums[tid] / (float)a.hidden + 1e-5f);
+            __syncthreads();
+            const int c = c4 - col_lo;
+            if (c >= 0 && c < n_col) {
+#pragma unroll
+                for (int t = 0; t < kMegaMaxTok; ++t)
+                    if (t < k_tok) {
+                        const float inv = sums[8 + t];
+                        const uint32_t lo = pack_bf16(hv[t][0] * inv, hv[t][1] * inv);
+                        const uint32_t hi = pack_bf16(hv[t][2] * inv, hv[t][3] * inv);
+                        *reinterpret_cast<uint2*>(xlds + ((c >> 8) * kMegaMaxTok + t) * 256 + (c & 255)) = make_uint2(lo, hi);
+                        if (TRACE) {
+                            *reinterpret_cast<f32x4*>(a.trace_src + tr_s + (size_t)t * a.trace_smax + c4) = hv[t];
+                            *reinterpret_cast<uint2*>(a.trace_x + tr_x + (size_t)t * a.trace_kmax + c4) = make_uint2(lo, hi);
+                        }
+                    }
             }
         } else if (kind == 3) {
-            // rows of unused token slots are zero; then four tokens x three column chunks per round of loads
-            for (int idx = tid; idx < ge.b_blk * kMegaMaxTok * 256; idx += kMegaThreads)
-                if (((idx >> 8) & (kMegaMaxTok - 1)) >= k_tok) xlds[idx] = 0;
-            for (int t0 = 0; t0 < k_tok; t0 += 4) {
-                float gv[4][3], uv[4][3];
+            // thread i owns columns 2i, 2i+1 of the block; gate and up of every token are in flight at once
+            const int c = 2 * tid;
+            if (c < n_col) {
+                f32x2 gv[kMegaMaxTok], uv[kMegaMaxTok];
 #pragma unroll
-                for (int tt = 0; tt < 4; ++tt)
-#pragma unroll
-                    for (int e = 0; e < 3; ++e) {
-                        const int cc = tid + e * kMegaThreads;
-                        const bool ok = t0 + tt < k_tok && cc < n_col;
-                        const float* row = yg + (size_t)(t0 + tt) * 2 * a.inter + col_lo + cc;
-                        gv[tt][e] = ok ? aload(row) : 0.f;
-                        uv[tt][e] = ok ? aload(row + a.inter) : 0.f;
+                for (int t = 0; t < kMegaMaxTok; ++t) {
+                    gv[t] = uv[t] = f32x2{0.f, 0.f};  // defined in every path: nothing is carried from the phase before
+                    if (t < k_tok) {
+                        const float* row = yg + (size_t)t * 2 * a.inter + col_lo + c;
+                        gv[t] = *reinterpret_cast<const f32x2*>(row);
+                        uv[t] = *reinterpret_cast<const f32x2*>(row + a.inter);
                     }
+                }
 #pragma unroll
-                for (int tt = 0; tt < 4; ++tt)
-#pragma unroll
-                    for (int e = 0; e < 3; ++e) {
-                        const int t = t0 + tt, cc = tid + e * kMegaThreads;
-                        if (t < k_tok && cc < ge.b_blk * 256) {
-                            uint16_t v = 0;
-                            if (cc < n_col) {
-                                v = f32_to_bf16(gv[tt][e] / (1.0f + expf(-gv[tt][e])) * uv[tt][e]);
-                                if (TRACE) {
-                                    a.trace_x[tr_x + (size_t)t * a.trace_kmax + col_lo + cc] = v;
-                                    a.trace_src[tr_s + (size_t)t * a.trace_smax + col_lo + cc] = gv[tt][e];
-                                    a.trace_src[tr_s + (size_t)t * a.trace_smax + a.inter + col_lo + cc] = uv[tt][e];
-                                }
-                            }
-                            xlds[((cc >> 8) * kMegaMaxTok + t) * 256 + (cc & 255)] = v;
+                for (int t = 0; t < kMegaMaxTok; ++t)
+                    if (t < k_tok) {
+                        // hardware exp2 and reciprocal: about 1e-6 relative, far inside the bf16 rounding that follows
+                        const uint32_t pk = pack_bf16(gv[t][0] * __builtin_amdgcn_rcpf(1.0f + __expf(-gv[t][0])) * uv[t][0],
+                                                      gv[t][1] * __builtin_amdgcn_rcpf(1.0f + __expf(-gv[t][1])) * uv[t][1]);
+                        *reinterpret_cast<uint32_t*>(xlds + ((c >> 8) * kMegaMaxTok + t) * 256 + (c & 255)) = pk;
+                        if (TRACE) {
+                            float* ts = a.trace_src + tr_s + (size_t)t * a.trace_smax + col_lo + c;
+                            *reinterpret_cast<f32x2*>(ts) = gv[t];
+                            *reinterpret_cast<f32x2*>(ts + a.inter) = uv[t];
+                            *reinterpret_cast<uint32_t*>(a.trace_x + tr_x + (size_t)t * a.trace_kmax + col_lo + c) = pk;
                         }
                     }
             }
-        } else {  // kind == 1: causal attention among the in-flight tokens for the heads of these slabs
+        } else {
+            // kind == 1: causal attention among the in-flight tokens.  Thread (head slot hh, dimension d) keeps q of
+            // its head and k, v of that head's kv group for every token in registers; a score is summed over the
+            // 128 dimensions = two wavefronts (cross-lane adds, then one LDS add per wavefront).
             const int D = 128;
-            for (int idx = tid; idx < ge.b_blk * kMegaMaxTok * 256; idx += kMegaThreads) xlds[idx] = 0;
-            float* sq = scr;
-            float* sk = sq + kMegaMaxTok * kAttHeads * 128;
-            float* sv = sk + kMegaMaxTok * kAttHeads * 128;
-            float* sp = misc;  // [head][i][j], 8 x 8 per head
-            int h_lo = 0, nh = 0, g_lo = 0, ng = 0;
+            const int hh = wave >> 1, d = (wave & 1) * 64 + lane;  // head slot is wave-uniform: scalar addressing
             const int rep = a.n_heads / a.n_kv;
-            if (n_col > 0) {
-                h_lo = col_lo / D;
-                nh = (col_lo + n_col - 1) / D - h_lo + 1;
-                g_lo = h_lo / rep;
-                ng = (h_lo + nh - 1) / rep - g_lo + 1;
-            }
-            {
-                // thread (head slot hh = tid / 128, dimension d): q of the block's heads, k and v of their kv heads,
-                // four tokens per round of loads
-                const int hh = tid >> 7, d = tid & 127;
-                for (int t0 = 0; t0 < k_tok; t0 += 4) {
-                    float qv[4], kv[4], vv[4];
+            const int head = col_lo / D + hh;                 // blocks start on head boundaries (256 | col_lo)
+            const int kvh = head / rep;
+            const bool live = hh * D < n_col;
+            float qv[kMegaMaxTok], kv[kMegaMaxTok], vv[kMegaMaxTok];
 #pragma unroll
-                    for (int tt = 0; tt < 4; ++tt) {
-                        const int t = t0 + tt;
-                        const bool okq = t < k_tok && hh < nh, okk = t < k_tok && hh < ng;
-                        const float* rq = yq + (size_t)t * nqkv + (h_lo + hh) * D + d;
-                        const float* rk = yq + (size_t)t * nqkv + a.q_out + (g_lo + hh) * D + d;
-                        qv[tt] = okq ? aload(rq) : 0.f;
-                        kv[tt] = okk ? aload(rk) : 0.f;
-                        vv[tt] = okk ? aload(rk + a.kv_out) : 0.f;
-                    }
-#pragma unroll
-                    for (int tt = 0; tt < 4; ++tt) {
-                        const int t = t0 + tt;
-                        if (t < k_tok && hh < kAttHeads) {
-                            const int el = (t * kAttHeads + hh) * 128 + d;
-                            sq[el] = qv[tt];
-                            sk[el] = kv[tt];
-                            sv[el] = vv[tt];
-                            if (TRACE) {
-                                float* ts = a.trace_src + tr_s + (size_t)t * a.trace_smax;
-                                if (hh < nh) ts[(h_lo + hh) * D + d] = qv[tt];
-                                if (hh < ng) {
-                                    ts[a.q_out + (g_lo + hh) * D + d] = kv[tt];
-                                    ts[a.q_out + a.kv_out + (g_lo + hh) * D + d] = vv[tt];
-                                }
-                            }
-                        }
-                    }
+            for (int t = 0; t < kMegaMaxTok; ++t) {
+                qv[t] = kv[t] = vv[t] = 0.f;
+                if (live && t < k_tok) {
+                    const float* row = yq + (size_t)t * nqkv;
+                    qv[t] = row[head * D + d];
+                    kv[t] = row[a.q_out + kvh * D + d];
+                    vv[t] = row[a.q_out + a.kv_out + kvh * D + d];
                 }
             }
-            __syncthreads();
-            // scores: one wavefront per (head, i, j <= i), two dimensions per lane
-            const float scale = 1.0f / sqrtf((float)D);
-            {
-                int item = 0;
-                for (int hh = 0; hh < nh; ++hh) {
-                    const int gg = (h_lo + hh) / rep - g_lo;
-                    for (int i = 0; i < k_tok; ++i)
-                        for (int j = 0; j <= i; ++j, ++item) {
-                            if (item % kMegaWaves != wave) continue;
-                            const float* qa = sq + (i * kAttHeads + hh) * 128;
-                            const float* kb = sk + (j * kAttHeads + gg) * 128;
-                            const float dot = wave_sum(qa[lane] * kb[lane] + qa[lane + 64] * kb[lane + 64]);
-                            if (lane == 0) sp[(hh * 8 + i) * 8 + j] = dot * scale;
+            float* sp = misc + hh * 64;  // this head's [i][j] scores, 8 x 8
+            if (live) {
+#pragma unroll
+                for (int i = 0; i < kMegaMaxTok; ++i)
+#pragma unroll
+                    for (int j = 0; j <= i; ++j)
+                        if (i < k_tok) {
+                            const float part = wave_sum(qv[i] * kv[j]);
+                            if (lane == 0) atomicAdd(&sp[i * 8 + j], part);
                         }
-                }
             }
             __syncthreads();
             if (tid < kAttHeads * 8) {
-                const int i = tid & 7, hh = tid >> 3;
-                if (hh < nh && i < k_tok) {
-                    float* row = sp + (hh * 8 + i) * 8;
-                    float mx = row[0];
-                    for (int j = 1; j <= i; ++j) mx = fmaxf(mx, row[j]);
+                const int i = tid & 7, h2 = tid >> 3;
+                if (h2 * D < n_col && i < k_tok) {
+                    float* row = misc + h2 * 64 + i * 8;
+                    const float scale = 1.0f / sqrtf((float)D);
+                    float mx = row[0] * scale;
+                    for (int j = 1; j <= i; ++j) mx = fmaxf(mx, row[j] * scale);
                     float sum = 0.f;
                     for (int j = 0; j <= i; ++j) {
-                        const float e = expf(row[j] - mx);
+                        const float e = expf(row[j] * scale - mx);
                         row[j] = e;
                         sum += e;
                     }
@@ -415,20 +456,25 @@ __global__ __launch_bounds__(kMegaThreads) void mega_forward_kernel(const MegaAr
                 }
             }
             __syncthreads();
-            {
-                const int hh = tid >> 7, d = tid & 127;
-                const int cc = (h_lo + hh) * D + d - col_lo;
-                if (hh < nh && cc >= 0 && cc < n_col) {
-                    const int gg = (h_lo + hh) / rep - g_lo;
-                    for (int t = 0; t < k_tok; ++t) {
-                        const float* row = sp + (hh * 8 + t) * 8;
+            if (live) {
+                const int cc = hh * D + d;
+#pragma unroll
+                for (int t = 0; t < kMegaMaxTok; ++t)
+                    if (t < k_tok) {
                         float o = 0.f;
-                        for (int j = 0; j <= t; ++j) o += row[j] * sv[(j * kAttHeads + gg) * 128 + d];
+#pragma unroll
+                        for (int j = 0; j <= t; ++j) o += sp[t * 8 + j] * vv[j];
                         const uint16_t cv = f32_to_bf16(o);
                         xlds[((cc >> 8) * kMegaMaxTok + t) * 256 + (cc & 255)] = cv;
-                        if (TRACE) a.trace_x[tr_x + (size_t)t * a.trace_kmax + col_lo + cc] = cv;
+                        if (TRACE) {
+                            a.trace_x[tr_x + (size_t)t * a.trace_kmax + col_lo + cc] = cv;
+                            float* ts = a.trace_src + tr_s + (size_t)t * a.trace_smax;
+                            ts[head * D + d] = qv[t];
+                            // heads of one kv group all record the same k and v
+                            ts[a.q_out + kvh * D + d] = kv[t];
+                            ts[a.q_out + a.kv_out + kvh * D + d] = vv[t];
+                        }
                     }
-                }
             }
         }
         __syncthreads();
@@ -439,15 +485,11 @@ __global__ __launch_bounds__(kMegaThreads) void mega_forward_kernel(const MegaAr
         Frag b[4][2];
 #pragma unroll
         for (int q = 0; q < 4; ++q) b[q][0].q = b[q][1].q = u32x4{0, 0, 0, 0};
-        while (cur.p == p) {
-#pragma unroll
-            for (int c = 0; c < kMegaCh; ++c) reinterpret_cast<u32x4*>(buf)[c * 64 + lane] = st[c];
-            const uint2 mk = mk_next;
-            const int sl_strip = cur.ss, sl_slab = cur.sl;
-            if (sl_slab != cur_slab) {
-                cur_slab = sl_slab;
+        auto load_b = [&](int sl) {  // the slab's activation columns as MFMA B operands: lane (n, g) = token n, columns 16g..
+            if (sl != cur_slab) {
+                cur_slab = sl;
                 if (n < kMegaMaxTok) {
-                    const u32x4* xr = reinterpret_cast<const u32x4*>(xlds + (sl_slab * kMegaMaxTok + n) * 256 + 16 * g);
+                    const u32x4* xr = reinterpret_cast<const u32x4*>(xlds + (sl * kMegaMaxTok + n) * 256 + 16 * g);
 #pragma unroll
                     for (int q = 0; q < 4; ++q) {
                         b[q][0].q = xr[8 * q];
@@ -455,59 +497,42 @@ __global__ __launch_bounds__(kMegaThreads) void mega_forward_kernel(const MegaAr
                     }
                 }
             }
-            const DirEnt de = de_cur;
-            de_cur = de_nxt;
-            de_nxt = dir_from_raw(de_raw);
-            if (nxt.p < n_phases) {
-                const unsigned char* bl = ka->blob[nxt.p];
-                issue_tile<kMegaCh>(st, mk_next, reinterpret_cast<const uint16_t*>(bl + ka->geo[nxt.p & 3].val_off),
-                                    reinterpret_cast<const uint2*>(bl + ka->geo[nxt.p & 3].mask_off), de_cur.val_start,
-                                    de_cur.nnz, nxt.t, lane);
-            }
-            const TileRef n3 = next_tile(ka, cu, nn, n_phases, wave);
-            de_raw = load_dir_raw(ka, n3, n_phases, lane);
-
-            const uint8_t* bufb = reinterpret_cast<const uint8_t*>(buf);
-            const uint32_t m16[4] = {mk.x & 0xffffu, mk.x >> 16, mk.y & 0xffffu, mk.y >> 16};
-            f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const uint32_t bits = m16[q];
-                uint32_t nib[4];
-#pragma unroll
-                for (int h = 0; h < 4; ++h) nib[h] = (bits >> (4 * h)) & 15u;
-                const uint32_t packed = (uint32_t)__builtin_popcount(nib[0]) | ((uint32_t)__builtin_popcount(nib[1]) << 8) |
-                                        ((uint32_t)__builtin_popcount(nib[2]) << 16) |
-                                        ((uint32_t)__builtin_popcount(nib[3]) << 24);
-                const uint32_t ex = wave_excl_scan(packed);
-                Frag f[2];
-#pragma unroll
-                for (int h = 0; h < 4; ++h) {
-                    const uint32_t run_base = (de.base[(4 * q + h) >> 1] >> (16 * (h & 1))) & 0xffffu;
-                    const uint32_t off = (run_base + ((ex >> (8 * h)) & 0xffu)) * 2u;
-                    const Tri32 tr = *reinterpret_cast<const Tri32*>(bufb + (off & ~3u));
-                    const uint32_t w0 = __builtin_amdgcn_alignbyte(tr.b, tr.a, off);
-                    const uint32_t w1 = __builtin_amdgcn_alignbyte(tr.c, tr.b, off);
-                    const uint2 sel = lut[nib[h]];
-                    f[h >> 1].u[2 * (h & 1) + 0] = __builtin_amdgcn_perm(w1, w0, sel.x);
-                    f[h >> 1].u[2 * (h & 1) + 1] = __builtin_amdgcn_perm(w1, w0, sel.y);
-                }
-                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f[0].v, b[q][0].v, acc, 0, 0, 0);
-                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f[1].v, b[q][1].v, acc, 0, 0, 0);
-            }
-            // ---- add to this strip's accumulator in LDS: lane (n, g) owns rows 4g..4g+3 of token n
+        };
+        auto add_strip = [&](int ss, const f32x4& acc) {  // lane (n, g) owns rows 4g..4g+3 of token n
             if (n < kMegaMaxTok) {
-                float* r = red + (sl_strip * kMegaMaxTok + n) * 16 + 4 * g;
+                float* r = red + (ss * kMegaMaxTok + n) * 16 + 4 * g;
 #pragma unroll
                 for (int v = 0; v < 4; ++v) atomicAdd(r + v, acc[v]);
             }
-            cur = nxt;
-            nxt = nn;
-            nn = n3;
+        };
+        if (have_pre) {
+            load_b(pre_sl);
+            f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fpre[q][0].v, b[q][0].v, acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fpre[q][1].v, b[q][1].v, acc, 0, 0, 0);
+            }
+            add_strip(pre_ss, acc);
+        }
+        while (cur.p == p) {
+            const int ss = cur.ss, sl = cur.sl;
+            uint2 mk;
+            uint32_t base[8];
+            const uint8_t* bufb = stage_tile(mk, base);
+            load_b(sl);
+            f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
+            expand_tile(bufb, lut, base, mk, [&](int q, const Frag& f0, const Frag& f1) {
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f0.v, b[q][0].v, acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f1.v, b[q][1].v, acc, 0, 0, 0);
+            });
+            add_strip(ss, acc);
         }
         __syncthreads();
         if (tt && tid == 0) tt[3] = __builtin_amdgcn_s_memrealtime();
 
+        // the LDS sums the next prologue adds into start from zero
+        if (tid < 400) misc[tid] = 0.f;
         // ---------------- the block's results leave the CU: split-K across the slab blocks by float atomics
         if (active) {
             float* ybase = kind == 0 ? yq : (kind == 2 ? yg : a.h);
@@ -515,7 +540,7 @@ __global__ __launch_bounds__(kMegaThreads) void mega_forward_kernel(const MegaAr
                 const int r = idx & 15, t = (idx >> 4) & (kMegaMaxTok - 1), sl = idx >> 7;
                 const float v = red[idx];
                 red[idx] = 0.f;
-                const int strip = kpl.strip0 + sl, row = strip * 16 + r;
+                const int strip = strip_lo + sl, row = strip * 16 + r;
                 if (t < k_tok && strip < ge.n_strips && row < ge.n_out) aadd(ybase + (size_t)t * ge.n_out + row, v);
             }
         }
@@ -560,13 +585,15 @@ static int mega_grid() {
         if (hipGetDevice(&dev) == hipSuccess &&
             hipDeviceGetAttribute(&coop, hipDeviceAttributeCooperativeLaunch, dev) == hipSuccess && coop &&
             hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0 &&
-            hipFuncSetAttribute(reinterpret_cast<const void*>(mega_forward_kernel<false>),
+            hipFuncSetAttribute(reinterpret_cast<const void*>(mega_forward_kernel<false, false>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMegaLds) == hipSuccess &&
-            hipFuncSetAttribute(reinterpret_cast<const void*>(mega_forward_kernel<true>),
+            hipFuncSetAttribute(reinterpret_cast<const void*>(mega_forward_kernel<true, false>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMegaLds) == hipSuccess &&
+            hipFuncSetAttribute(reinterpret_cast<const void*>(mega_forward_kernel<false, true>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMegaLds) == hipSuccess) {
             int per_cu = 0, per_cu_t = 0;
-            if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, mega_forward_kernel<false>, kMegaThreads, kMegaLds) == hipSuccess &&
-                hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu_t, mega_forward_kernel<true>, kMegaThreads, kMegaLds) == hipSuccess &&
+            if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, mega_forward_kernel<false, false>, kMegaThreads, kMegaLds) == hipSuccess &&
+                hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu_t, mega_forward_kernel<true, false>, kMegaThreads, kMegaLds) == hipSuccess &&
                 per_cu >= 1 && per_cu_t >= 1)
                 cus = n;
         }
@@ -608,7 +635,8 @@ bool mega_plan(MegaGeo (&geo)[4], int layers, int hidden, int head_dim, int k_to
     return true;
 }
 
-hipError_t launch_mega_forward(const MegaArgs& a, const uint16_t* h_in, void* zero_base, size_t zero_bytes, hipStream_t s) {
+hipError_t launch_mega_forward(const MegaArgs& a, const uint16_t* h_in, void* zero_base, size_t zero_bytes, bool probe,
+                               hipStream_t s) {
     const int ncu = mega_grid();
     if (ncu < 1) return hipErrorNotSupported;
     hipLaunchKernelGGL(mega_zero_kernel, dim3(256), dim3(256), 0, s, static_cast<uint32_t*>(zero_base), zero_bytes / 4);
@@ -618,8 +646,9 @@ hipError_t launch_mega_forward(const MegaArgs& a, const uint16_t* h_in, void* ze
     if (e != hipSuccess) return e;
     MegaArgs args = a;
     void* params[] = {&args};
-    const void* fn = a.trace_x ? reinterpret_cast<const void*>(mega_forward_kernel<true>)
-                               : reinterpret_cast<const void*>(mega_forward_kernel<false>);
+    const void* fn = a.trace_x ? reinterpret_cast<const void*>(mega_forward_kernel<true, false>)
+                    : probe ? reinterpret_cast<const void*>(mega_forward_kernel<false, true>)
+                            : reinterpret_cast<const void*>(mega_forward_kernel<false, false>);
     return hipLaunchCooperativeKernel(fn, dim3((unsigned)ncu), dim3(kMegaThreads), params, kMegaLds, s);
 }
 

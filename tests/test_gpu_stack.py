@@ -77,14 +77,15 @@ def test_qwen_shape_one_layer_sparsity_70(forward_path):
     assert ol.rel_l2(out, ref) <= E2E_TOL
 
 
-def _check_rounded(gpu_bits, exact, what):
+def _check_rounded(gpu_bits, exact, what, abs_slack=0.0):
     """The GPU's bf16 activation must be a correct rounding of the oracle's fp64 value, up to the fp32
-    evaluation error of the glue: |gpu - exact| <= half a bf16 step (+ 1e-5 relative)."""
+    evaluation error of the glue: |gpu - exact| <= half a bf16 step + 2e-5 relative (+ abs_slack where the
+    value is a sum of terms that may cancel: fp32 summation error scales with the terms, not with the sum)."""
     from oracle.bf16 import bits_to_f64
     g = bits_to_f64(gpu_bits)
     mag = np.maximum(np.abs(g), np.abs(exact))
     step = 2.0 ** (np.floor(np.log2(np.maximum(mag, 2.0 ** -126))) - 7)
-    bad = np.abs(g - exact) > 0.5 * step + 2e-5 * mag + 1e-30
+    bad = np.abs(g - exact) > 0.5 * step + 2e-5 * mag + abs_slack + 1e-30
     assert not bad.any(), (what, int(bad.sum()), float(np.abs(g - exact)[bad].max()))
     flips = f64_to_bits(exact) != gpu_bits
     assert flips.mean() < 0.02, (what, float(flips.mean()))
@@ -109,7 +110,9 @@ def _verify_steps(shape, get, h_in, h_out, x, src):
         qkv = src[4 * l + 1][:, :Q + 2 * KV].astype(np.float64)
         assert ol.rel_l2(qkv, ol.sparse_linear(wqkv, x[4 * l + 0][:, :H])) <= TOL, (l, "qkv")
         ctx = os_.inflight_attention(qkv[:, :Q], qkv[:, Q:Q + KV], qkv[:, Q + KV:], shape.n_heads, shape.n_kv, shape.head_dim)
-        _check_rounded(x[4 * l + 1][:, :Q], ctx, (l, "attention"))
+        # ctx = sum_j p_j v_j with p summing to one: the fp32 error is a few ulps of max|v|, also where ctx ~ 0
+        v_max = float(np.abs(qkv[:, Q + KV:]).max())
+        _check_rounded(x[4 * l + 1][:, :Q], ctx, (l, "attention"), abs_slack=16 * 2.0 ** -24 * v_max)
         h1 = src[4 * l + 2][:, :H].astype(np.float64)
         assert ol.rel_l2(h1 - h0, ol.sparse_linear(get(l, "o"), x[4 * l + 1][:, :Q])) <= TOL, (l, "o")
         _check_rounded(x[4 * l + 2][:, :H], os_.rmsnorm(h1), (l, "norm2"))
