@@ -25,12 +25,16 @@ constexpr int kTileDw = kMegaCh * 256;              // dwords per wavefront tile
 constexpr int kMaxB = 6;                            // slabs per workgroup block (activation columns kept in LDS)
 constexpr int kMaxBAtt = 3;                         // ... for the linear that follows attention
 constexpr int kMaxS = 16;                           // strips per workgroup block (LDS accumulators)
-constexpr int kXldsDw = kMaxB * kMegaMaxTok * 256 / 2;  // bf16 [slab][token][256]
+// A token's 256 activation columns of a slab take a row of 264 bf16: with 528-byte rows the eight tokens that read
+// the same 16 columns for the MFMA B operand (one 16-byte read per lane) fall into eight different bank groups.
+constexpr int kXRow = 264;
+constexpr int kXldsDw = kMaxB * kMegaMaxTok * kXRow / 2;  // bf16 [slab][token][kXRow]
 constexpr int kRedDw = kMaxS * kMegaMaxTok * 16;        // fp32 [strip][token][row]
+constexpr int kPlanDw = 12;                             // per-kind plan: s_eff b_eff strip0 slab0 | n_strips 1/s_eff active - | mask_off(2) val_off(2)
 constexpr int kMiscDw = 512;                            // attention probabilities, per-token scalars
 constexpr int kAttHeads = 6;                            // heads (and kv heads) one workgroup may need
 constexpr int kAreaDw = 2 * kMegaWaves * kTileDw;       // two tile buffers per wavefront: one being expanded, one being filled
-constexpr size_t kMegaLds = (size_t)(kAreaDw + kXldsDw + kRedDw + kMiscDw + 4 * 12) * 4;
+constexpr size_t kMegaLds = (size_t)(kAreaDw + kXldsDw + kRedDw + kMiscDw + 4 * kPlanDw) * 4;
 constexpr int kBarWords = 32 + 8 * 32 + 8 * 32;     // top counter, 8 group counters, 8 group flags
 static_assert(kAttHeads * 128 == kMegaThreads, "one thread per (head slot, dimension)");
 static_assert(4 * kMegaThreads >= kMegaMaxHidden && 2 * kMegaThreads >= kMaxB * 256, "columns per thread in the prologues");
@@ -60,85 +64,76 @@ __device__ __forceinline__ float wave_sum(float v) {
 // gives scalar loads, where indexing the by-value parameter would make the compiler copy it to scratch.
 typedef const __attribute__((address_space(4))) MegaArgs* KArgs;
 
-// One tile of this wavefront's walk, all fields wave-uniform.
-struct TileRef {
-    int p;                       // phase = 4 * layer + kind; == n_phases when there is no tile
-    int ss, sl;                  // strip and slab inside the workgroup's block
-    const unsigned char* dir;    // the tile's directory entry
-    const unsigned char* masks;  // the tile's 64 x 8 mask bytes
-    const unsigned char* vals;   // value section of the tile's blob
-};
-
-// Per-kind plan in LDS, written once by threads 0..3: where this workgroup's block starts and the
-// blob offsets common to all layers of the kind.
-constexpr int kPlanDw = 12;  // s_blk b_blk strip0 slab0 | n_strips n_slabs active - | mask_off(2) val_off(2)
-
-struct PhasePlan {
-    int s_blk, b_blk, strip0, slab0, n_strips, n_slabs, active;
-    const unsigned char* blob;
-    unsigned long long mask_off, val_off;
-};
+// Per-kind plan in LDS, written once by threads 0..3: the part of the matrix this workgroup owns (clipped to
+// the matrix, so every position of the s_eff x b_eff block is a real tile) and the blob offsets common to all
+// layers of the kind.
+constexpr int kMaxTilesPerWave = 8;  // per phase: ceil(kMaxS * kMaxB / waves)
+static_assert(kMaxS * kMaxB <= kMaxTilesPerWave * kMegaWaves, "a wavefront describes at most eight tiles per phase");
 
 __device__ __forceinline__ int uni(uint32_t v) { return __builtin_amdgcn_readfirstlane((int)v); }
 
-__device__ __forceinline__ void load_phase(PhasePlan& pp, KArgs ka, const uint32_t* plans, int p, int n_phases) {
-    pp.active = 0;
-    if (p >= n_phases) return;
-    const u32x4* e = reinterpret_cast<const u32x4*>(plans + (p & 3) * kPlanDw);
-    const u32x4 a = e[0], b = e[1], c = e[2];  // same address in every lane: one broadcast read each
-    pp.blob = ka->blob[p];
-    pp.s_blk = uni(a[0]);
-    pp.b_blk = uni(a[1]);
-    pp.strip0 = uni(a[2]);
-    pp.slab0 = uni(a[3]);
-    pp.n_strips = uni(b[0]);
-    pp.n_slabs = uni(b[1]);
-    pp.active = uni(b[2]);
-    pp.mask_off = (unsigned long long)(uint32_t)uni(c[0]) | ((unsigned long long)(uint32_t)uni(c[1]) << 32);
-    pp.val_off = (unsigned long long)(uint32_t)uni(c[2]) | ((unsigned long long)(uint32_t)uni(c[3]) << 32);
-}
-
-// Walks this wavefront's tiles in execution order: within a phase the tiles of the workgroup's block are
-// numbered strip-first and dealt to the wavefronts round-robin; phases follow each other.  The plan of the
-// phase it stands in is kept in scalar registers, so a step inside a phase is a handful of scalar operations.
-struct TileIter {
-    int p, ss, sl;
-    PhasePlan pp;
+// This wavefront's tiles of one phase, described in lanes: the block's tiles are numbered strip-first and
+// dealt to the wavefronts round-robin, tile j of the wavefront is block position wave + 12 j.  Lane L holds
+// what belongs to tile L / 8: its index in the matrix, its place in the block, and (lanes 8j + d) the dwords of
+// its directory entry.  One pass of vector arithmetic and two loads per phase replace per-tile index juggling;
+// a tile's numbers are then picked with v_readlane at lane 8j.
+struct PhaseTiles {
+    uint32_t t;    // tile index in the matrix
+    uint32_t key;  // strip in block | slab in block << 8
+    uint32_t ra;   // lane 8j + d: directory dword d       (val_start, nnz, run bases 0..11)
+    uint32_t rb;   // lane 8j + d: directory dword 8 + d   (run bases 12..15 in d = 0, 1)
+    int n;         // number of tiles (wave-uniform)
+    const unsigned char* masks;  // mask section of the phase's blob
+    const unsigned char* vals;   // value section
 };
 
-__device__ __forceinline__ TileRef iter_next(TileIter& it, KArgs ka, const uint32_t* plans, int n_phases, int wave) {
-    for (;;) {
-        if (it.p >= n_phases) return TileRef{n_phases, 0, 0, nullptr, nullptr, nullptr};
-        if (it.pp.active) {
-            while (it.ss >= it.pp.s_blk) {  // s_blk >= 1
-                it.ss -= it.pp.s_blk;
-                ++it.sl;
-            }
-            if (it.sl < it.pp.b_blk) {
-                const int strip = it.pp.strip0 + it.ss, slab = it.pp.slab0 + it.sl;
-                const bool ok = strip < it.pp.n_strips && slab < it.pp.n_slabs;
-                const size_t t = (size_t)slab * it.pp.n_strips + strip;
-                const TileRef r{it.p, it.ss, it.sl, it.pp.blob + 128 + t * 48, it.pp.blob + it.pp.mask_off + t * 512,
-                                it.pp.blob + it.pp.val_off};
-                it.ss += kMegaWaves;
-                if (ok) return r;
-                continue;
-            }
-        }
-        ++it.p;
-        load_phase(it.pp, ka, plans, it.p, n_phases);
-        it.ss = wave;
-        it.sl = 0;
+__device__ __forceinline__ void plan_phase(PhaseTiles& pt, KArgs ka, const uint32_t* plans, int p, int n_phases, int wave,
+                                           int lane) {
+    pt.t = pt.key = pt.ra = pt.rb = 0u;
+    pt.n = 0;
+    pt.masks = pt.vals = nullptr;
+    if (p >= n_phases) return;
+    const u32x4* e = reinterpret_cast<const u32x4*>(plans + (p & 3) * kPlanDw);
+    const u32x4 a = e[0], b = e[1], c = e[2];  // same address in every lane: broadcast reads, values stay in VGPRs
+    const int s_eff = (int)a[0], b_eff = (int)a[1];
+    const int i = wave + kMegaWaves * (lane >> 3);  // block position of tile lane / 8
+    const bool valid = i < s_eff * b_eff;
+    const int sl = (int)(((float)i + 0.5f) * __uint_as_float(b[1]));  // i / s_eff, exact for these small integers
+    const int ss = i - sl * s_eff;
+    const uint32_t t = (a[3] + (uint32_t)sl) * b[0] + a[2] + (uint32_t)ss;
+    const unsigned char* blob = ka->blob[p];
+    pt.masks = blob + ((unsigned long long)(uint32_t)uni(c[0]) | ((unsigned long long)(uint32_t)uni(c[1]) << 32));
+    pt.vals = blob + ((unsigned long long)(uint32_t)uni(c[2]) | ((unsigned long long)(uint32_t)uni(c[3]) << 32));
+    pt.n = __builtin_popcountll(__ballot(valid && (lane & 7) == 0));
+    if (valid) {
+        const uint32_t* d = reinterpret_cast<const uint32_t*>(blob + 128) + (size_t)t * 12;
+        pt.t = t;
+        pt.key = (uint32_t)ss | ((uint32_t)sl << 8);
+        pt.ra = d[lane & 7];
+        pt.rb = d[8 + (lane & 3)];
     }
 }
 
-// The 12 dwords of a tile's directory entry, one per lane (lanes 0..11); read back with readlane when needed.
-__device__ __forceinline__ uint32_t load_dir_raw(const TileRef& r, int n_phases, int lane) {
-    if (r.p >= n_phases) return 0u;
-    return reinterpret_cast<const uint32_t*>(r.dir)[lane < 12 ? lane : 11];
+__device__ __forceinline__ uint32_t lane_word(uint32_t v, int l) { return (uint32_t)__builtin_amdgcn_readlane((int)v, l); }
+
+// Requests the value stream (straight into LDS) and the masks of tile j of a phase.
+__device__ __forceinline__ void issue_phase_tile(const PhaseTiles& pt, int j, uint32_t* lds_buf, uint2& mk, int lane) {
+    const uint32_t val_start = lane_word(pt.ra, 8 * j), nnz = lane_word(pt.ra, 8 * j + 1), t = lane_word(pt.t, 8 * j);
+    issue_tile_lds<kMegaCh>(lds_buf, mk, reinterpret_cast<const uint16_t*>(pt.vals),
+                            reinterpret_cast<const uint2*>(pt.masks + (size_t)t * 512), val_start, nnz, lane);
 }
 
-__device__ __forceinline__ uint32_t raw_word(uint32_t raw, int i) { return (uint32_t)__builtin_amdgcn_readlane((int)raw, i); }
+// The sixteen run bases of tile j as the eight directory words that hold them.
+__device__ __forceinline__ void tile_bases(const PhaseTiles& pt, int j, int lane, uint32_t (&base)[8]) {
+    // bring the tile's lanes down to lanes 0..7 (one cross-lane move each), then pick with constant lane numbers
+    const int src = ((lane + 8 * j) & 63) * 4;
+    const uint32_t ra = (uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)pt.ra);
+    const uint32_t rb = (uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)pt.rb);
+#pragma unroll
+    for (int i = 0; i < 6; ++i) base[i] = lane_word(ra, 2 + i);
+    base[6] = lane_word(rb, 0);
+    base[7] = lane_word(rb, 1);
+}
 
 // Grid barrier: 8 groups of workgroups (by id mod 8) count arrivals, the last of each group
 // arrives at the top counter, the very last releases the 8 group flags.  Counters only grow;
@@ -221,16 +216,20 @@ __global__ __launch_bounds__(kMegaThreads) void mega_forward_kernel(const MegaAr
     uint32_t* plans = reinterpret_cast<uint32_t*>(misc + kMiscDw);
     if (tid < 4) {
         const int n_sblk = ka->geo[tid].n_sblk, n_bblk = ka->geo[tid].n_bblk;
-        const int s_blk = max(ka->geo[tid].s_blk, 1), b_blk = ka->geo[tid].b_blk;
+        const int s_blk = ka->geo[tid].s_blk, b_blk = ka->geo[tid].b_blk;
         const int qb = cu / n_sblk;
+        const int strip0 = (cu - qb * n_sblk) * s_blk, slab0 = qb * b_blk;
+        const bool act = cu < n_sblk * n_bblk;
+        const int s_eff = act ? max(0, min(s_blk, ka->geo[tid].n_strips - strip0)) : 0;
+        const int b_eff = act ? max(0, min(b_blk, ka->geo[tid].n_slabs - slab0)) : 0;
         uint32_t* e = plans + tid * kPlanDw;
-        e[0] = (uint32_t)s_blk;
-        e[1] = (uint32_t)b_blk;
-        e[2] = (uint32_t)((cu - qb * n_sblk) * s_blk);
-        e[3] = (uint32_t)(qb * b_blk);
+        e[0] = (uint32_t)s_eff;
+        e[1] = (uint32_t)(s_eff > 0 ? b_eff : 0);
+        e[2] = (uint32_t)strip0;
+        e[3] = (uint32_t)slab0;
         e[4] = (uint32_t)ka->geo[tid].n_strips;
-        e[5] = (uint32_t)ka->geo[tid].n_slabs;
-        e[6] = cu < n_sblk * n_bblk ? 1u : 0u;
+        e[5] = __float_as_uint(1.0f / (float)max(s_eff, 1));
+        e[6] = act ? 1u : 0u;
         e[7] = 0u;
         e[8] = (uint32_t)ka->geo[tid].mask_off;
         e[9] = (uint32_t)(ka->geo[tid].mask_off >> 32);
@@ -238,22 +237,11 @@ __global__ __launch_bounds__(kMegaThreads) void mega_forward_kernel(const MegaAr
         e[11] = (uint32_t)(ka->geo[tid].val_off >> 32);
     }
     __syncthreads();
-    // this wave's first three tiles; the first one's stream is requested right away
-    TileIter it;
-    it.p = 0;
-    it.ss = wave;
-    it.sl = 0;
-    load_phase(it.pp, ka, plans, 0, n_phases);
-    TileRef cur = iter_next(it, ka, plans, n_phases, wave);
-    TileRef nxt = iter_next(it, ka, plans, n_phases, wave);
-    TileRef nn = iter_next(it, ka, plans, n_phases, wave);
-    uint32_t raw_cur = load_dir_raw(cur, n_phases, lane);
-    uint32_t raw_nxt = load_dir_raw(nxt, n_phases, lane);
-    uint32_t raw_nn = load_dir_raw(nn, n_phases, lane);
+    // this wave's tiles of the first phase; the first one's stream is requested right away
+    PhaseTiles ct, nt;
+    plan_phase(ct, ka, plans, 0, n_phases, wave, lane);
     uint2 mk_next = make_uint2(0, 0);
-    if (cur.p < n_phases)
-        issue_tile_lds<kMegaCh>(bufs, mk_next, reinterpret_cast<const uint16_t*>(cur.vals),
-                                reinterpret_cast<const uint2*>(cur.masks), raw_word(raw_cur, 0), raw_word(raw_cur, 1), lane);
+    if (ct.n > 0) issue_phase_tile(ct, 0, bufs, mk_next, lane);
     unsigned gen = 0;
 
     for (int p = 0; p < n_phases; ++p) {
@@ -267,41 +255,37 @@ __global__ __launch_bounds__(kMegaThreads) void mega_forward_kernel(const MegaAr
         ge.b_blk = ka->geo[kind].b_blk;
         unsigned long long* tt = a.trace_time ? a.trace_time + ((size_t)cu * n_phases + p) * 8 : nullptr;
         if (tt && tid == 0) tt[0] = __builtin_amdgcn_s_memrealtime();
+        // next phase's tiles: planned now so that the directory loads have the whole phase to arrive
+        plan_phase(nt, ka, plans, p + 1, n_phases, wave, lane);
         bool released = false;
         if (p > 0) released = barrier_arrive(a.bar, (unsigned)ncu, gen);
 
-        // Stages this wave's current tile in its LDS buffer, requests the stream of the one after it and the
-        // directory entry of the third, and moves the walk on; returns what the expansion of the staged tile needs.
-        auto stage_tile = [&](uint2& mk, uint32_t (&base)[8]) -> const uint8_t* {
-            wait_vector_memory();  // the current tile's stream is in LDS, its masks in registers
+        // Waits for tile j's stream, requests the stream of the tile after it (the next one of this phase, else the
+        // first one of the next phase: weights do not depend on activations) and returns what the expansion needs.
+        auto stage_tile = [&](int j, uint2& mk, uint32_t (&base)[8], int& ss, int& sl) -> const uint8_t* {
+            wait_vector_memory();  // the tile's stream is in LDS, its masks in registers
             mk = mk_next;
             const uint8_t* bufb = reinterpret_cast<const uint8_t*>(bufs + cb * kTileDw);
             cb ^= 1;
-            if (nxt.p < n_phases)
-                issue_tile_lds<kMegaCh>(bufs + cb * kTileDw, mk_next, reinterpret_cast<const uint16_t*>(nxt.vals),
-                                        reinterpret_cast<const uint2*>(nxt.masks), raw_word(raw_nxt, 0), raw_word(raw_nxt, 1), lane);
-            const TileRef n3 = iter_next(it, ka, plans, n_phases, wave);
-            const uint32_t raw_n3 = load_dir_raw(n3, n_phases, lane);
-#pragma unroll
-            for (int i = 0; i < 8; ++i) base[i] = raw_word(raw_cur, 2 + i);
-            cur = nxt;
-            nxt = nn;
-            nn = n3;
-            raw_cur = raw_nxt;
-            raw_nxt = raw_nn;
-            raw_nn = raw_n3;
+            if (j + 1 < ct.n)
+                issue_phase_tile(ct, j + 1, bufs + cb * kTileDw, mk_next, lane);
+            else if (nt.n > 0)
+                issue_phase_tile(nt, 0, bufs + cb * kTileDw, mk_next, lane);
+            tile_bases(ct, j, lane, base);
+            const uint32_t key = lane_word(ct.key, 8 * j);
+            ss = (int)(key & 255u);
+            sl = (int)(key >> 8);
             return bufb;
         };
 
-        // While the barrier settles, this wave's first tile of the phase is expanded into its eight MFMA operands:
-        // weights do not depend on activations.
+        // While the barrier settles, this wave's first tile of the phase is expanded into its eight MFMA operands.
         Frag fpre[4][2];
-        const bool have_pre = cur.p == p;
-        const int pre_ss = cur.ss, pre_sl = cur.sl;
+        const bool have_pre = ct.n > 0;
+        int pre_ss = 0, pre_sl = 0;
         if (have_pre) {
             uint2 mk;
             uint32_t base[8];
-            const uint8_t* bufb = stage_tile(mk, base);
+            const uint8_t* bufb = stage_tile(0, mk, base, pre_ss, pre_sl);
             expand_tile(bufb, lut, base, mk, [&](int q, const Frag& f0, const Frag& f1) {
                 fpre[q][0].q = f0.q;
                 fpre[q][1].q = f1.q;
@@ -328,7 +312,7 @@ __global__ __launch_bounds__(kMegaThreads) void mega_forward_kernel(const MegaAr
         // columns past the end of a ragged last slab must read as zero
         if (n_col < ge.b_blk * 256)
             for (int idx = tid; idx < ge.b_blk * kMegaMaxTok * 256; idx += kMegaThreads)
-                if ((idx >> 11) * 256 + (idx & 255) >= n_col) xlds[idx] = 0;
+                if ((idx >> 11) * 256 + (idx & 255) >= n_col) xlds[(idx >> 8) * kXRow + (idx & 255)] = 0;
 
         if (kind == 0 || kind == 2) {
             // Thread i owns columns 4i..4i+3 of every token: all loads of the residual are in flight at once,
@@ -369,7 +353,7 @@ __global__ __launch_bounds__(kMegaThreads) void mega_forward_kernel(const MegaAr
                         const float inv = sums[8 + t];
                         const uint32_t lo = pack_bf16(hv[t][0] * inv, hv[t][1] * inv);
                         const uint32_t hi = pack_bf16(hv[t][2] * inv, hv[t][3] * inv);
-                        *reinterpret_cast<uint2*>(xlds + ((c >> 8) * kMegaMaxTok + t) * 256 + (c & 255)) = make_uint2(lo, hi);
+                        *reinterpret_cast<uint2*>(xlds + ((c >> 8) * kMegaMaxTok + t) * kXRow + (c & 255)) = make_uint2(lo, hi);
                         if (TRACE) {
                             *reinterpret_cast<f32x4*>(a.trace_src + tr_s + (size_t)t * a.trace_smax + c4) = hv[t];
                             *reinterpret_cast<uint2*>(a.trace_x + tr_x + (size_t)t * a.trace_kmax + c4) = make_uint2(lo, hi);
@@ -396,7 +380,7 @@ __global__ __launch_bounds__(kMegaThreads) void mega_forward_kernel(const MegaAr
                         // hardware exp2 and reciprocal: about 1e-6 relative, far inside the bf16 rounding that follows
                         const uint32_t pk = pack_bf16(gv[t][0] * __builtin_amdgcn_rcpf(1.0f + __expf(-gv[t][0])) * uv[t][0],
                                                       gv[t][1] * __builtin_amdgcn_rcpf(1.0f + __expf(-gv[t][1])) * uv[t][1]);
-                        *reinterpret_cast<uint32_t*>(xlds + ((c >> 8) * kMegaMaxTok + t) * 256 + (c & 255)) = pk;
+                        *reinterpret_cast<uint32_t*>(xlds + ((c >> 8) * kMegaMaxTok + t) * kXRow + (c & 255)) = pk;
                         if (TRACE) {
                             float* ts = a.trace_src + tr_s + (size_t)t * a.trace_smax + col_lo + c;
                             *reinterpret_cast<f32x2*>(ts) = gv[t];
@@ -465,7 +449,7 @@ __global__ __launch_bounds__(kMegaThreads) void mega_forward_kernel(const MegaAr
 #pragma unroll
                         for (int j = 0; j <= t; ++j) o += sp[t * 8 + j] * vv[j];
                         const uint16_t cv = f32_to_bf16(o);
-                        xlds[((cc >> 8) * kMegaMaxTok + t) * 256 + (cc & 255)] = cv;
+                        xlds[((cc >> 8) * kMegaMaxTok + t) * kXRow + (cc & 255)] = cv;
                         if (TRACE) {
                             a.trace_x[tr_x + (size_t)t * a.trace_kmax + col_lo + cc] = cv;
                             float* ts = a.trace_src + tr_s + (size_t)t * a.trace_smax;
@@ -489,7 +473,7 @@ __global__ __launch_bounds__(kMegaThreads) void mega_forward_kernel(const MegaAr
             if (sl != cur_slab) {
                 cur_slab = sl;
                 if (n < kMegaMaxTok) {
-                    const u32x4* xr = reinterpret_cast<const u32x4*>(xlds + (sl * kMegaMaxTok + n) * 256 + 16 * g);
+                    const u32x4* xr = reinterpret_cast<const u32x4*>(xlds + (sl * kMegaMaxTok + n) * kXRow + 16 * g);
 #pragma unroll
                     for (int q = 0; q < 4; ++q) {
                         b[q][0].q = xr[8 * q];
@@ -498,7 +482,7 @@ __global__ __launch_bounds__(kMegaThreads) void mega_forward_kernel(const MegaAr
                 }
             }
         };
-        auto add_strip = [&](int ss, const f32x4& acc) {  // lane (n, g) owns rows 4g..4g+3 of token n
+        auto add_strip = [&](int ss, const f32x4 acc) {  // lane (n, g) owns rows 4g..4g+3 of token n
             if (n < kMegaMaxTok) {
                 float* r = red + (ss * kMegaMaxTok + n) * 16 + 4 * g;
 #pragma unroll
@@ -507,27 +491,31 @@ __global__ __launch_bounds__(kMegaThreads) void mega_forward_kernel(const MegaAr
         };
         if (have_pre) {
             load_b(pre_sl);
-            f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
+            // two accumulators: consecutive MFMAs do not wait for each other's result
+            f32x4 acc0 = f32x4{0.f, 0.f, 0.f, 0.f}, acc1 = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fpre[q][0].v, b[q][0].v, acc, 0, 0, 0);
-                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fpre[q][1].v, b[q][1].v, acc, 0, 0, 0);
+                acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fpre[q][0].v, b[q][0].v, acc0, 0, 0, 0);
+                acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fpre[q][1].v, b[q][1].v, acc1, 0, 0, 0);
             }
-            add_strip(pre_ss, acc);
+            add_strip(pre_ss, acc0 + acc1);
         }
-        while (cur.p == p) {
-            const int ss = cur.ss, sl = cur.sl;
+        for (int j = 1; j < ct.n; ++j) {
+            int ss, sl;
             uint2 mk;
             uint32_t base[8];
-            const uint8_t* bufb = stage_tile(mk, base);
+            const uint8_t* bufb = stage_tile(j, mk, base, ss, sl);
             load_b(sl);
-            f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
+            f32x4 acc0 = f32x4{0.f, 0.f, 0.f, 0.f}, acc1 = f32x4{0.f, 0.f, 0.f, 0.f};
             expand_tile(bufb, lut, base, mk, [&](int q, const Frag& f0, const Frag& f1) {
-                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f0.v, b[q][0].v, acc, 0, 0, 0);
-                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f1.v, b[q][1].v, acc, 0, 0, 0);
+                acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f0.v, b[q][0].v, acc0, 0, 0, 0);
+                acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f1.v, b[q][1].v, acc1, 0, 0, 0);
             });
-            add_strip(ss, acc);
+            add_strip(ss, acc0 + acc1);
         }
+        // a wavefront without tiles in this phase starts the stream of its first tile of the next one here
+        if (ct.n == 0 && nt.n > 0) issue_phase_tile(nt, 0, bufs + cb * kTileDw, mk_next, lane);
+        ct = nt;
         __syncthreads();
         if (tt && tid == 0) tt[3] = __builtin_amdgcn_s_memrealtime();
 
