@@ -284,6 +284,36 @@ def main():
             dense_us = (time.perf_counter() - t0) / max(args.steps // 4, 10) * 1e6
         record["config"]["dense_stack_us"] = round(dense_us, 2)
         record["config"]["speedup_vs_dense"] = round(dense_us / us_per_step, 3)
+
+        # The same comparison without any glue: every linear of the stack as an independent call on its own
+        # seeded input (sd2_sparse_linear against sd2_dense_linear, same masked weights), event-timed per call.
+        def linears_us(matrices, fn):
+            tot = 0.0
+            with torch.cuda.stream(stream):
+                spp = stream.cuda_stream
+                for kind in range(4):
+                    ms_k = [matrices[4 * l + kind] for l in range(layers)]
+                    info = ms_k[0].info
+                    xk = to_dev(wl.gen_x(args.config, 0, ("q", "o", "gate", "down")[kind], k_tok, int(info.k_in)))
+                    yk = torch.empty((k_tok, int(info.n_out)), dtype=torch.float32, device=dev)
+                    wsb = max(sd2.linear_workspace_size(ms_k[0], k_tok), 16)
+                    wsk = torch.empty(wsb, dtype=torch.uint8, device=dev)
+                    best = None
+                    for rep in range(3):
+                        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                        e0.record(stream)
+                        for m in ms_k:
+                            fn(m, xk.data_ptr(), k_tok, yk.data_ptr(), wsk.data_ptr(), wsb, spp)
+                        e1.record(stream)
+                        stream.synchronize()
+                        t = e0.elapsed_time(e1) * 1e3
+                        best = t if best is None or (rep and t < best) else best
+                    tot += best
+            return tot
+
+        sp_lin, de_lin = linears_us(mats, sd2.sparse_linear), linears_us(dmats, sd2.dense_linear)
+        record["config"]["linears_only_us"] = {"sparse": round(sp_lin, 1), "dense": round(de_lin, 1),
+                                               "speedup": round(de_lin / sp_lin, 3)}
         del dgraph
         sd2.model_destroy(dmodel)
         del dkeep, dws

@@ -88,7 +88,7 @@ int linear_entry(const sd2_matrix_t* m, int kind, const uint16_t* x, int32_t k_t
 }
 
 struct StackLayout {
-    size_t act_off, part_off, total;
+    size_t act_off, part_off, ssq_off, total;
 };
 
 StackLayout stack_layout(const sd2_model* md, int k_tok) {
@@ -99,7 +99,8 @@ StackLayout stack_layout(const sd2_model* md, int k_tok) {
     size_t part = 0;
     for (const sd2_matrix_t& m : md->mats) part = std::max(part, partial_bytes(&m, k_tok));
     L.part_off = align256((size_t)k_tok * widest * sizeof(uint16_t));
-    L.total = L.part_off + align256(part);
+    L.ssq_off = L.part_off + align256(part);
+    L.total = L.ssq_off + align256((size_t)k_tok * ((sh.hidden + 255) / 256) * sizeof(float));
     return L;
 }
 
@@ -372,6 +373,7 @@ static int forward_impl(const sd2_model_t* md, const uint16_t* h_in, int32_t k_t
     }
     uint16_t* act = reinterpret_cast<uint16_t*>(static_cast<uint8_t*>(ws) + L.act_off);
     float* part = reinterpret_cast<float*>(static_cast<uint8_t*>(ws) + L.part_off);
+    float* ssq = reinterpret_cast<float*>(static_cast<uint8_t*>(ws) + L.ssq_off);
     float* h = h_out;  // the residual stream lives in the output buffer
 #define SD2_TRY(expr) \
     if ((expr) != hipSuccess) return SD2_ERR_HIP
@@ -396,7 +398,7 @@ static int forward_impl(const sd2_model_t* md, const uint16_t* h_in, int32_t k_t
         }
         return hipSuccess;
     };
-    SD2_TRY(launch_residual_rmsnorm(h, h_in, nullptr, 0, k_tok, sh.hidden, sh.layers > 0 ? act : nullptr, s));
+    SD2_TRY(launch_residual_rmsnorm(h, h_in, nullptr, 0, k_tok, sh.hidden, sh.layers > 0 ? act : nullptr, ssq, s));
     for (int l = 0; l < sh.layers; ++l) {
         const sd2_matrix_t* qkv = &md->mats[4 * l + 0];
         const sd2_matrix_t* o = &md->mats[4 * l + 1];
@@ -408,14 +410,14 @@ static int forward_impl(const sd2_model_t* md, const uint16_t* h_in, int32_t k_t
                                           sh.head_dim, act, s));
         SD2_TRY(record(4 * l + 1, nullptr, part, qkv->info.n_slabs, sh.q_out + 2 * sh.kv_out, sh.q_out));
         SD2_TRY(run_linear(o, act, k_tok, part, s));
-        SD2_TRY(launch_residual_rmsnorm(h, nullptr, part, o->info.n_slabs, k_tok, sh.hidden, act, s));
+        SD2_TRY(launch_residual_rmsnorm(h, nullptr, part, o->info.n_slabs, k_tok, sh.hidden, act, ssq, s));
         SD2_TRY(record(4 * l + 2, h, nullptr, 0, sh.hidden, sh.hidden));
         SD2_TRY(run_linear(gu, act, k_tok, part, s));
         SD2_TRY(launch_silu_mul(part, gu->info.n_slabs, k_tok, sh.inter, act, s));
         SD2_TRY(record(4 * l + 3, nullptr, part, gu->info.n_slabs, 2 * sh.inter, sh.inter));
         SD2_TRY(run_linear(dn, act, k_tok, part, s));
         SD2_TRY(launch_residual_rmsnorm(h, nullptr, part, dn->info.n_slabs, k_tok, sh.hidden,
-                                        l + 1 < sh.layers ? act : nullptr, s));
+                                        l + 1 < sh.layers ? act : nullptr, ssq, s));
     }
 #undef SD2_TRY
     return SD2_OK;

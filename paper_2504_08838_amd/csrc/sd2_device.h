@@ -114,11 +114,12 @@ __device__ __forceinline__ void issue_tile(u32x4 (&st)[MAXCH], uint2& mk, const 
 // address is legal on gfx950 but measured far slower.)  The stream carries eight bytes of slack, so the
 // window never leaves the buffer.
 //
-// The four scans run first and the sixteen LDS reads of two super-steps are issued back to back
-// before the first is consumed, so that a wavefront pays the LDS latency twice per tile, not per nibble.
-template <typename F>
+// The four scans run first and the LDS reads of STEPS super-steps are issued back to back before the
+// first is consumed, so that a wavefront pays the LDS latency 4 / STEPS times per tile, not per nibble.
+template <int STEPS = 2, typename F>
 __device__ __forceinline__ void expand_tile(const uint8_t* __restrict__ bufb, const uint2* __restrict__ lut,
                                             const uint32_t (&base)[8], uint2 mk, F&& use) {
+    static_assert(STEPS == 1 || STEPS == 2 || STEPS == 4, "super-steps whose LDS reads are batched");
     const uint32_t m16[4] = {mk.x & 0xffffu, mk.x >> 16, mk.y & 0xffffu, mk.y >> 16};
     uint32_t ex[4];
 #pragma unroll
@@ -130,29 +131,29 @@ __device__ __forceinline__ void expand_tile(const uint8_t* __restrict__ bufb, co
         ex[q] = wave_excl_scan(packed);  // per nibble: values of lower lanes (<= 252, no carry)
     }
 #pragma unroll
-    for (int half = 0; half < 2; ++half) {
-        Tri32 tr[8];
-        uint2 sel[8];
-        uint32_t off[8];
+    for (int part = 0; part < 4 / STEPS; ++part) {
+        Tri32 tr[4 * STEPS];
+        uint2 sel[4 * STEPS];
+        uint32_t off[4 * STEPS];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const int q = 2 * half + (i >> 2), h = i & 3;
+        for (int i = 0; i < 4 * STEPS; ++i) {
+            const int q = STEPS * part + (i >> 2), h = i & 3;
             const uint32_t run_base = (base[(4 * q + h) >> 1] >> (16 * (h & 1))) & 0xffffu;
             off[i] = (run_base + ((ex[q] >> (8 * h)) & 0xffu)) * 2u;  // byte offset in the tile's stream
             tr[i] = *reinterpret_cast<const Tri32*>(bufb + (off[i] & ~3u));
             sel[i] = lut[(m16[q] >> (4 * h)) & 15u];
         }
-        Frag f[2][2];
+        Frag f[STEPS][2];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
+        for (int i = 0; i < 4 * STEPS; ++i) {
             const int h = i & 3;
             const uint32_t w0 = __builtin_amdgcn_alignbyte(tr[i].b, tr[i].a, off[i]);
             const uint32_t w1 = __builtin_amdgcn_alignbyte(tr[i].c, tr[i].b, off[i]);
             f[i >> 2][h >> 1].u[2 * (h & 1) + 0] = __builtin_amdgcn_perm(w1, w0, sel[i].x);
             f[i >> 2][h >> 1].u[2 * (h & 1) + 1] = __builtin_amdgcn_perm(w1, w0, sel[i].y);
         }
-        use(2 * half, f[0][0], f[0][1]);
-        use(2 * half + 1, f[1][0], f[1][1]);
+#pragma unroll
+        for (int j = 0; j < STEPS; ++j) use(STEPS * part + j, f[j][0], f[j][1]);
     }
 }
 

@@ -34,10 +34,11 @@ hipError_t launch_reduce_partials(const float* part, int n_splits, size_t n, flo
 hipError_t launch_reduce_partials_strided(const float* part, int n_splits, size_t split_stride, size_t n, float* y,
                                           hipStream_t s);
 
-// h (fp32 [k_tok][hidden]) is initialised from bf16 h_in (first != 0) or updated in place with
+// h (fp32 [k_tok][hidden]) is initialised from bf16 h_in (when given) or updated in place with
 // h += sum_s part[s]; then a = bf16(h / sqrt(mean(h^2) + 1e-5)) is written when a != nullptr.
+// ssq: scratch of k_tok * ceil(hidden / 256) floats (per-block sums of squares).
 hipError_t launch_residual_rmsnorm(float* h, const uint16_t* h_in, const float* part, int n_splits,
-                                   int k_tok, int hidden, uint16_t* a, hipStream_t s);
+                                   int k_tok, int hidden, uint16_t* a, float* ssq, hipStream_t s);
 
 // Causal softmax attention among the k_tok in-flight tokens; qkv partials [n_splits][k_tok][q_out+2*kv_out].
 hipError_t launch_inflight_attention(const float* part, int n_splits, int k_tok, int q_out, int kv_out,

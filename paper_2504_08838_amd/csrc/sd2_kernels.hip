@@ -14,6 +14,10 @@
 #include "sd2_device.h"
 #include "sd2_internal.h"
 
+#ifndef SD2_LINEAR_STEPS
+#define SD2_LINEAR_STEPS 1  // super-steps per batch of LDS reads in the stand-alone kernel (16 waves per CU hide the rest)
+#endif
+
 namespace sd2 {
 
 // One 16 x k_tok block of results: lane (n = lane & 15, g = lane >> 4) holds rows 4g..4g+3 of token n.
@@ -69,7 +73,7 @@ __device__ __forceinline__ void sparse_tile(u32x4 (&st)[MAXCH], uint2& mk_next, 
     f32x4 acc[TG];
 #pragma unroll
     for (int tg = 0; tg < TG; ++tg) acc[tg] = f32x4{0.f, 0.f, 0.f, 0.f};
-    expand_tile(reinterpret_cast<const uint8_t*>(buf), lut, de.base, mk, [&](int q, const Frag& f0, const Frag& f1) {
+    expand_tile<SD2_LINEAR_STEPS>(reinterpret_cast<const uint8_t*>(buf), lut, de.base, mk, [&](int q, const Frag& f0, const Frag& f1) {
         if (TG == 1) {
             acc[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f0.v, b[q][0].v, acc[0], 0, 0, 0);
             acc[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f1.v, b[q][1].v, acc[0], 0, 0, 0);
@@ -285,36 +289,52 @@ __device__ __forceinline__ float block_sum_256(float v, float* red) {
     return r;
 }
 
-__global__ __launch_bounds__(256) void residual_rmsnorm_kernel(float* __restrict__ h, const uint16_t* __restrict__ h_in,
-                                                              const float* __restrict__ part, int n_splits, int k_tok,
-                                                              int hidden, uint16_t* __restrict__ a) {
-    __shared__ float red[256];
-    const int t = blockIdx.x;
-    float* hr = h + (size_t)t * hidden;
-    const size_t stride = (size_t)k_tok * hidden;
-    float ss = 0.f;
-    for (int i = threadIdx.x; i < hidden; i += 256) {
-        float v;
-        if (h_in) {
-            v = bf16_to_f32(h_in[(size_t)t * hidden + i]);
-        } else {
-            float add = 0.f;
-            for (int s = 0; s < n_splits; ++s) add += part[(size_t)s * stride + (size_t)t * hidden + i];
-            v = hr[i] + add;
-        }
-        hr[i] = v;
-        ss += v * v;
+// Sum of n_splits partial results, four independent chains so that the loads overlap.
+__device__ __forceinline__ float sum_splits(const float* __restrict__ p, int n_splits, size_t stride) {
+    float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+    int s = 0;
+    for (; s + 4 <= n_splits; s += 4) {
+        a0 += p[(size_t)s * stride];
+        a1 += p[(size_t)(s + 1) * stride];
+        a2 += p[(size_t)(s + 2) * stride];
+        a3 += p[(size_t)(s + 3) * stride];
     }
-    if (!a) return;
-    const float tot = block_sum_256(ss, red);
+    for (; s < n_splits; ++s) a0 += p[(size_t)s * stride];
+    return (a0 + a1) + (a2 + a3);
+}
+
+// Step 1 of the residual update: block (c, t) owns 256 columns of token t.  h is initialised from bf16 h_in or
+// updated with the sum of the partials; the block's sum of squares goes to ssq[t][c].
+__global__ __launch_bounds__(256) void residual_update_kernel(float* __restrict__ h, const uint16_t* __restrict__ h_in,
+                                                             const float* __restrict__ part, int n_splits, int k_tok,
+                                                             int hidden, float* __restrict__ ssq) {
+    __shared__ float red[256];
+    const int t = blockIdx.y, i = blockIdx.x * 256 + threadIdx.x;
+    float v = 0.f;
+    if (i < hidden) {
+        const size_t at = (size_t)t * hidden + i;
+        v = h_in ? bf16_to_f32(h_in[at]) : h[at] + sum_splits(part + at, n_splits, (size_t)k_tok * hidden);
+        h[at] = v;
+    }
+    const float tot = block_sum_256(v * v, red);
+    if (threadIdx.x == 0) ssq[(size_t)t * gridDim.x + blockIdx.x] = tot;
+}
+
+// Step 2: a = bf16(h / sqrt(mean(h^2) + 1e-5)), the mean taken from the per-block sums of step 1.
+__global__ __launch_bounds__(256) void rmsnorm_apply_kernel(const float* __restrict__ h, const float* __restrict__ ssq,
+                                                           int hidden, uint16_t* __restrict__ a) {
+    const int t = blockIdx.y, i = blockIdx.x * 256 + threadIdx.x;
+    float tot = 0.f;
+    for (unsigned c = 0; c < gridDim.x; ++c) tot += ssq[(size_t)t * gridDim.x + c];  // same order in every thread
     const float inv = 1.0f / sqrtf(tot / (float)hidden + 1e-5f);
-    for (int i = threadIdx.x; i < hidden; i += 256) a[(size_t)t * hidden + i] = f32_to_bf16(hr[i] * inv);
+    if (i < hidden) a[(size_t)t * hidden + i] = f32_to_bf16(h[(size_t)t * hidden + i] * inv);
 }
 
 hipError_t launch_residual_rmsnorm(float* h, const uint16_t* h_in, const float* part, int n_splits, int k_tok,
-                                   int hidden, uint16_t* a, hipStream_t s) {
-    hipLaunchKernelGGL(residual_rmsnorm_kernel, dim3((unsigned)k_tok), dim3(256), 0, s, h, h_in, part, n_splits, k_tok,
-                       hidden, a);
+                                   int hidden, uint16_t* a, float* ssq, hipStream_t s) {
+    const dim3 grid((unsigned)((hidden + 255) / 256), (unsigned)k_tok);
+    hipLaunchKernelGGL(residual_update_kernel, grid, dim3(256), 0, s, h, h_in, part, n_splits, k_tok, hidden, ssq);
+    if (a) hipLaunchKernelGGL(rmsnorm_apply_kernel, grid, dim3(256), 0, s, h, ssq, hidden, a);
     return hipGetLastError();
 }
 
@@ -332,26 +352,24 @@ __global__ __launch_bounds__(256) void inflight_attention_kernel(const float* __
     const size_t stride = (size_t)k_tok * n_out;
     for (int idx = threadIdx.x; idx < k_tok * D; idx += 256) {
         const int t = idx / D, d = idx % D;
-        const size_t row = (size_t)t * n_out;
-        float q = 0.f, k = 0.f, v = 0.f;
-        for (int s = 0; s < n_splits; ++s) {
-            const float* p = part + (size_t)s * stride + row;
-            q += p[head * D + d];
-            k += p[q_out + grp * D + d];
-            v += p[q_out + kv_out + grp * D + d];
-        }
-        sq[idx] = q;
-        sk[idx] = k;
-        sv[idx] = v;
+        const float* p = part + (size_t)t * n_out;
+        sq[idx] = sum_splits(p + head * D + d, n_splits, stride);
+        sk[idx] = sum_splits(p + q_out + grp * D + d, n_splits, stride);
+        sv[idx] = sum_splits(p + q_out + kv_out + grp * D + d, n_splits, stride);
     }
     __syncthreads();
+    // scores: eight threads per (i, j) pair, each over an eighth of the head dimension
     const float scale = 1.0f / sqrtf((float)D);
-    for (int idx = threadIdx.x; idx < k_tok * k_tok; idx += 256) {
-        const int i = idx / k_tok, j = idx % k_tok;
+    const int r = threadIdx.x & 7, seg = D / 8;
+    for (int pair = threadIdx.x >> 3; pair < k_tok * k_tok; pair += 32) {
+        const int i = pair / k_tok, j = pair % k_tok;
         float dot = 0.f;
         if (j <= i)
-            for (int d = 0; d < D; ++d) dot += sq[i * D + d] * sk[j * D + d];
-        sp[idx] = dot * scale;
+            for (int d = r * seg; d < (r + 1) * seg; ++d) dot += sq[i * D + d] * sk[j * D + d];
+        dot += __shfl_xor(dot, 1);
+        dot += __shfl_xor(dot, 2);
+        dot += __shfl_xor(dot, 4);
+        if (r == 0) sp[pair] = dot * scale;
     }
     __syncthreads();
     for (int i = threadIdx.x; i < k_tok; i += 256) {

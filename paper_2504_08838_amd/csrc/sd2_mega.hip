@@ -16,6 +16,10 @@
 #include "sd2_device.h"
 #include "sd2_internal.h"
 
+#ifndef SD2_MEGA_STEPS
+#define SD2_MEGA_STEPS 2  // super-steps per batch of LDS reads in the tile expansion
+#endif
+
 namespace sd2 {
 
 constexpr int kMegaWaves = 12;
@@ -286,7 +290,7 @@ __global__ __launch_bounds__(kMegaThreads) void mega_forward_kernel(const MegaAr
             uint2 mk;
             uint32_t base[8];
             const uint8_t* bufb = stage_tile(0, mk, base, pre_ss, pre_sl);
-            expand_tile(bufb, lut, base, mk, [&](int q, const Frag& f0, const Frag& f1) {
+            expand_tile<SD2_MEGA_STEPS>(bufb, lut, base, mk, [&](int q, const Frag& f0, const Frag& f1) {
                 fpre[q][0].q = f0.q;
                 fpre[q][1].q = f1.q;
             });
@@ -507,7 +511,7 @@ __global__ __launch_bounds__(kMegaThreads) void mega_forward_kernel(const MegaAr
             const uint8_t* bufb = stage_tile(j, mk, base, ss, sl);
             load_b(sl);
             f32x4 acc0 = f32x4{0.f, 0.f, 0.f, 0.f}, acc1 = f32x4{0.f, 0.f, 0.f, 0.f};
-            expand_tile(bufb, lut, base, mk, [&](int q, const Frag& f0, const Frag& f1) {
+            expand_tile<SD2_MEGA_STEPS>(bufb, lut, base, mk, [&](int q, const Frag& f0, const Frag& f1) {
                 acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f0.v, b[q][0].v, acc0, 0, 0, 0);
                 acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f1.v, b[q][1].v, acc1, 0, 0, 0);
             });
