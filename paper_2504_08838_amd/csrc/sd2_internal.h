@@ -66,7 +66,9 @@ constexpr int kMegaMaxHidden = 3072;
 // s_blk strips x b_blk slabs with strip block c % n_sblk and slab block c / n_sblk.
 struct MegaGeo {
     int n_out, k_in, n_strips, n_slabs, n_tiles;
-    int s_blk, b_blk, n_sblk, n_bblk, pad;
+    int s_blk, b_blk, n_sblk, n_bblk;
+    int n_grp, grp_slabs;  // a strip's b_blk slabs are cut into n_grp groups of grp_slabs; one wavefront sums a group in registers
+    int pad;
     unsigned long long mask_off, val_off;  // byte offsets inside a blob (equal for all layers of a kind)
 };
 

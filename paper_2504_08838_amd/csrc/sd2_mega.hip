@@ -33,8 +33,9 @@ constexpr int kMaxS = 16;                           // strips per workgroup bloc
 // the same 16 columns for the MFMA B operand (one 16-byte read per lane) fall into eight different bank groups.
 constexpr int kXRow = 264;
 constexpr int kXldsDw = kMaxB * kMegaMaxTok * kXRow / 2;  // bf16 [slab][token][kXRow]
-constexpr int kRedDw = kMaxS * kMegaMaxTok * 16;        // fp32 [strip][token][row]
-constexpr int kPlanDw = 12;                             // per-kind plan: s_eff b_eff strip0 slab0 | n_strips 1/s_eff active - | mask_off(2) val_off(2)
+constexpr int kMaxUnits = 24;                           // (strip, slab group) units of a block: one result slot each
+constexpr int kRedDw = kMaxUnits * kMegaMaxTok * 16;    // fp32 [strip][group][token][row]
+constexpr int kPlanDw = 16;                             // per-kind plan: s_eff b_eff strip0 slab0 | n_strips 1/grp_slabs active tiles/wave | mask_off(2) val_off(2) | grp_slabs n_grp 1/n_grp -
 constexpr int kMiscDw = 512;                            // attention probabilities, per-token scalars
 constexpr int kAttHeads = 6;                            // heads (and kv heads) one workgroup may need
 constexpr int kAreaDw = 2 * kMegaWaves * kTileDw;       // two tile buffers per wavefront: one being expanded, one being filled
@@ -72,24 +73,30 @@ typedef const __attribute__((address_space(4))) MegaArgs* KArgs;
 // the matrix, so every position of the s_eff x b_eff block is a real tile) and the blob offsets common to all
 // layers of the kind.
 constexpr int kMaxTilesPerWave = 8;  // per phase: ceil(kMaxS * kMaxB / waves)
-static_assert(kMaxS * kMaxB <= kMaxTilesPerWave * kMegaWaves, "a wavefront describes at most eight tiles per phase");
+
 
 __device__ __forceinline__ int uni(uint32_t v) { return __builtin_amdgcn_readfirstlane((int)v); }
 
-// This wavefront's tiles of one phase, described in lanes: the block's tiles are numbered strip-first and
-// dealt to the wavefronts round-robin, tile j of the wavefront is block position wave + 12 j.  Lane L holds
-// what belongs to tile L / 8: its index in the matrix, its place in the block, and (lanes 8j + d) the dwords of
-// its directory entry.  One pass of vector arithmetic and two loads per phase replace per-tile index juggling;
-// a tile's numbers are then picked with v_readlane at lane 8j.
+// This wavefront's tiles of one phase, described in lanes.  A block's work is cut into units: the slabs of a
+// strip form n_grp groups of grp_slabs consecutive slabs, unit u = strip * n_grp + group.  Units are dealt to the
+// wavefronts in runs (unit order), and a wavefront walks the tiles of a unit one after the other, so that the sums
+// of a unit stay in the MFMA accumulator and reach LDS once, with a plain store into the unit's own slot.
+// Tile j of the wavefront is position i = wave * per_wave + j of that walk.  Lane L holds what belongs to tile
+// L / 8: its index in the matrix, a key (place in the block and flags), and (lanes 8j + d) the dwords of its
+// directory entry.  One pass of vector arithmetic and two loads per phase replace per-tile index juggling; a
+// tile's numbers are then picked with v_readlane at lane 8j.  A position whose slab lies past the matrix (ragged
+// last block) is an empty tile: nothing is loaded for it and its masks are zero.
 struct PhaseTiles {
     uint32_t t;    // tile index in the matrix
-    uint32_t key;  // strip in block | slab in block << 8
+    uint32_t key;  // strip in block | slab in block << 8 | unit << 16 | first of unit << 24 | last << 25 | empty << 26
     uint32_t ra;   // lane 8j + d: directory dword d       (val_start, nnz, run bases 0..11)
     uint32_t rb;   // lane 8j + d: directory dword 8 + d   (run bases 12..15 in d = 0, 1)
     int n;         // number of tiles (wave-uniform)
     const unsigned char* masks;  // mask section of the phase's blob
     const unsigned char* vals;   // value section
 };
+
+constexpr uint32_t kKeyFirst = 1u << 24, kKeyLast = 1u << 25, kKeyEmpty = 1u << 26;
 
 __device__ __forceinline__ void plan_phase(PhaseTiles& pt, KArgs ka, const uint32_t* plans, int p, int n_phases, int wave,
                                            int lane) {
@@ -98,23 +105,33 @@ __device__ __forceinline__ void plan_phase(PhaseTiles& pt, KArgs ka, const uint3
     pt.masks = pt.vals = nullptr;
     if (p >= n_phases) return;
     const u32x4* e = reinterpret_cast<const u32x4*>(plans + (p & 3) * kPlanDw);
-    const u32x4 a = e[0], b = e[1], c = e[2];  // same address in every lane: broadcast reads, values stay in VGPRs
-    const int s_eff = (int)a[0], b_eff = (int)a[1];
-    const int i = wave + kMegaWaves * (lane >> 3);  // block position of tile lane / 8
-    const bool valid = i < s_eff * b_eff;
-    const int sl = (int)(((float)i + 0.5f) * __uint_as_float(b[1]));  // i / s_eff, exact for these small integers
-    const int ss = i - sl * s_eff;
+    const u32x4 a = e[0], b = e[1], c = e[2], d4 = e[3];  // same address in every lane: broadcast reads, values stay in VGPRs
+    const int s_eff = (int)a[0], b_eff = (int)a[1], per_wave = (int)b[3];
+    const int grp_slabs = (int)d4[0], n_grp = (int)d4[1];
+    const int j = lane >> 3;
+    const int i = wave * per_wave + j;
+    // exact for these small integers: i / grp_slabs, u / n_grp
+    const int u = (int)(((float)i + 0.5f) * __uint_as_float(b[1]));
+    const int r = i - u * grp_slabs;
+    const int ss = (int)(((float)u + 0.5f) * __uint_as_float(d4[2]));
+    const int grp = u - ss * n_grp;
+    const int sl = grp * grp_slabs + r;
+    const bool exists = j < per_wave && ss < s_eff;
+    const bool empty = sl >= b_eff;
     const uint32_t t = (a[3] + (uint32_t)sl) * b[0] + a[2] + (uint32_t)ss;
     const unsigned char* blob = ka->blob[p];
     pt.masks = blob + ((unsigned long long)(uint32_t)uni(c[0]) | ((unsigned long long)(uint32_t)uni(c[1]) << 32));
     pt.vals = blob + ((unsigned long long)(uint32_t)uni(c[2]) | ((unsigned long long)(uint32_t)uni(c[3]) << 32));
-    pt.n = __builtin_popcountll(__ballot(valid && (lane & 7) == 0));
-    if (valid) {
-        const uint32_t* d = reinterpret_cast<const uint32_t*>(blob + 128) + (size_t)t * 12;
-        pt.t = t;
-        pt.key = (uint32_t)ss | ((uint32_t)sl << 8);
-        pt.ra = d[lane & 7];
-        pt.rb = d[8 + (lane & 3)];
+    pt.n = __builtin_popcountll(__ballot(exists && (lane & 7) == 0));
+    if (exists) {
+        pt.key = (uint32_t)ss | ((uint32_t)sl << 8) | ((uint32_t)u << 16) | (r == 0 ? kKeyFirst : 0u) |
+                 (r == grp_slabs - 1 ? kKeyLast : 0u) | (empty ? kKeyEmpty : 0u);
+        if (!empty) {
+            const uint32_t* d = reinterpret_cast<const uint32_t*>(blob + 128) + (size_t)t * 12;
+            pt.t = t;
+            pt.ra = d[lane & 7];
+            pt.rb = d[8 + (lane & 3)];
+        }
     }
 }
 
@@ -122,6 +139,10 @@ __device__ __forceinline__ uint32_t lane_word(uint32_t v, int l) { return (uint3
 
 // Requests the value stream (straight into LDS) and the masks of tile j of a phase.
 __device__ __forceinline__ void issue_phase_tile(const PhaseTiles& pt, int j, uint32_t* lds_buf, uint2& mk, int lane) {
+    if (lane_word(pt.key, 8 * j) & kKeyEmpty) {  // nothing stored for it: all-zero masks expand to zeros
+        mk = make_uint2(0u, 0u);
+        return;
+    }
     const uint32_t val_start = lane_word(pt.ra, 8 * j), nnz = lane_word(pt.ra, 8 * j + 1), t = lane_word(pt.t, 8 * j);
     issue_tile_lds<kMegaCh>(lds_buf, mk, reinterpret_cast<const uint16_t*>(pt.vals),
                             reinterpret_cast<const uint2*>(pt.masks + (size_t)t * 512), val_start, nnz, lane);
@@ -226,19 +247,25 @@ __global__ __launch_bounds__(kMegaThreads) void mega_forward_kernel(const MegaAr
         const bool act = cu < n_sblk * n_bblk;
         const int s_eff = act ? max(0, min(s_blk, ka->geo[tid].n_strips - strip0)) : 0;
         const int b_eff = act ? max(0, min(b_blk, ka->geo[tid].n_slabs - slab0)) : 0;
+        const int n_grp = max(ka->geo[tid].n_grp, 1), grp_slabs = max(ka->geo[tid].grp_slabs, 1);
+        const int units_per_wave = (s_blk * n_grp + kMegaWaves - 1) / kMegaWaves;
         uint32_t* e = plans + tid * kPlanDw;
-        e[0] = (uint32_t)s_eff;
-        e[1] = (uint32_t)(s_eff > 0 ? b_eff : 0);
+        e[0] = (uint32_t)(b_eff > 0 ? s_eff : 0);
+        e[1] = (uint32_t)b_eff;
         e[2] = (uint32_t)strip0;
         e[3] = (uint32_t)slab0;
         e[4] = (uint32_t)ka->geo[tid].n_strips;
-        e[5] = __float_as_uint(1.0f / (float)max(s_eff, 1));
+        e[5] = __float_as_uint(1.0f / (float)grp_slabs);
         e[6] = act ? 1u : 0u;
-        e[7] = 0u;
+        e[7] = (uint32_t)(units_per_wave * grp_slabs);  // tiles per wavefront
         e[8] = (uint32_t)ka->geo[tid].mask_off;
         e[9] = (uint32_t)(ka->geo[tid].mask_off >> 32);
         e[10] = (uint32_t)ka->geo[tid].val_off;
         e[11] = (uint32_t)(ka->geo[tid].val_off >> 32);
+        e[12] = (uint32_t)grp_slabs;
+        e[13] = (uint32_t)n_grp;
+        e[14] = __float_as_uint(1.0f / (float)n_grp);
+        e[15] = 0u;
     }
     __syncthreads();
     // this wave's tiles of the first phase; the first one's stream is requested right away
@@ -257,6 +284,7 @@ __global__ __launch_bounds__(kMegaThreads) void mega_forward_kernel(const MegaAr
         ge.n_slabs = ka->geo[kind].n_slabs;
         ge.s_blk = ka->geo[kind].s_blk;
         ge.b_blk = ka->geo[kind].b_blk;
+        const int n_grp = max(ka->geo[kind].n_grp, 1);
         unsigned long long* tt = a.trace_time ? a.trace_time + ((size_t)cu * n_phases + p) * 8 : nullptr;
         if (tt && tid == 0) tt[0] = __builtin_amdgcn_s_memrealtime();
         // next phase's tiles: planned now so that the directory loads have the whole phase to arrive
@@ -266,7 +294,7 @@ __global__ __launch_bounds__(kMegaThreads) void mega_forward_kernel(const MegaAr
 
         // Waits for tile j's stream, requests the stream of the tile after it (the next one of this phase, else the
         // first one of the next phase: weights do not depend on activations) and returns what the expansion needs.
-        auto stage_tile = [&](int j, uint2& mk, uint32_t (&base)[8], int& ss, int& sl) -> const uint8_t* {
+        auto stage_tile = [&](int j, uint2& mk, uint32_t (&base)[8], uint32_t& key) -> const uint8_t* {
             wait_vector_memory();  // the tile's stream is in LDS, its masks in registers
             mk = mk_next;
             const uint8_t* bufb = reinterpret_cast<const uint8_t*>(bufs + cb * kTileDw);
@@ -276,20 +304,18 @@ __global__ __launch_bounds__(kMegaThreads) void mega_forward_kernel(const MegaAr
             else if (nt.n > 0)
                 issue_phase_tile(nt, 0, bufs + cb * kTileDw, mk_next, lane);
             tile_bases(ct, j, lane, base);
-            const uint32_t key = lane_word(ct.key, 8 * j);
-            ss = (int)(key & 255u);
-            sl = (int)(key >> 8);
+            key = lane_word(ct.key, 8 * j);
             return bufb;
         };
 
         // While the barrier settles, this wave's first tile of the phase is expanded into its eight MFMA operands.
         Frag fpre[4][2];
         const bool have_pre = ct.n > 0;
-        int pre_ss = 0, pre_sl = 0;
+        uint32_t pre_key = 0;
         if (have_pre) {
             uint2 mk;
             uint32_t base[8];
-            const uint8_t* bufb = stage_tile(0, mk, base, pre_ss, pre_sl);
+            const uint8_t* bufb = stage_tile(0, mk, base, pre_key);
             expand_tile<SD2_MEGA_STEPS>(bufb, lut, base, mk, [&](int q, const Frag& f0, const Frag& f1) {
                 fpre[q][0].q = f0.q;
                 fpre[q][1].q = f1.q;
@@ -486,40 +512,43 @@ __global__ __launch_bounds__(kMegaThreads) void mega_forward_kernel(const MegaAr
                 }
             }
         };
-        auto add_strip = [&](int ss, const f32x4 acc) {  // lane (n, g) owns rows 4g..4g+3 of token n
+        // The sums of a unit (a strip's group of slabs) stay in the accumulators from its first tile to its last;
+        // then lane (n, g) stores rows 4g..4g+3 of token n into the unit's own slot: no other wavefront writes there.
+        f32x4 acc0 = f32x4{0.f, 0.f, 0.f, 0.f}, acc1 = f32x4{0.f, 0.f, 0.f, 0.f};
+        auto unit_done = [&](uint32_t key) {
             if (n < kMegaMaxTok) {
-                float* r = red + (ss * kMegaMaxTok + n) * 16 + 4 * g;
-#pragma unroll
-                for (int v = 0; v < 4; ++v) atomicAdd(r + v, acc[v]);
+                const int unit = (int)((key >> 16) & 255u);
+                *reinterpret_cast<f32x4*>(red + (unit * kMegaMaxTok + n) * 16 + 4 * g) = acc0 + acc1;
             }
         };
         if (have_pre) {
-            load_b(pre_sl);
+            load_b((int)((pre_key >> 8) & 255u));
             // two accumulators: consecutive MFMAs do not wait for each other's result
-            f32x4 acc0 = f32x4{0.f, 0.f, 0.f, 0.f}, acc1 = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
                 acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fpre[q][0].v, b[q][0].v, acc0, 0, 0, 0);
                 acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fpre[q][1].v, b[q][1].v, acc1, 0, 0, 0);
             }
-            add_strip(pre_ss, acc0 + acc1);
+            if (pre_key & kKeyLast) unit_done(pre_key);
         }
+        if (PROBE && tt && tid == 0) tt[6] = __builtin_amdgcn_s_memrealtime();
         for (int j = 1; j < ct.n; ++j) {
-            int ss, sl;
+            uint32_t key;
             uint2 mk;
             uint32_t base[8];
-            const uint8_t* bufb = stage_tile(j, mk, base, ss, sl);
-            load_b(sl);
-            f32x4 acc0 = f32x4{0.f, 0.f, 0.f, 0.f}, acc1 = f32x4{0.f, 0.f, 0.f, 0.f};
+            const uint8_t* bufb = stage_tile(j, mk, base, key);
+            load_b((int)((key >> 8) & 255u));
+            if (key & kKeyFirst) acc0 = acc1 = f32x4{0.f, 0.f, 0.f, 0.f};
             expand_tile<SD2_MEGA_STEPS>(bufb, lut, base, mk, [&](int q, const Frag& f0, const Frag& f1) {
                 acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f0.v, b[q][0].v, acc0, 0, 0, 0);
                 acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f1.v, b[q][1].v, acc1, 0, 0, 0);
             });
-            add_strip(ss, acc0 + acc1);
+            if (key & kKeyLast) unit_done(key);
         }
         // a wavefront without tiles in this phase starts the stream of its first tile of the next one here
         if (ct.n == 0 && nt.n > 0) issue_phase_tile(nt, 0, bufs + cb * kTileDw, mk_next, lane);
         ct = nt;
+        if (PROBE && tt && tid == 0) tt[7] = __builtin_amdgcn_s_memrealtime();
         __syncthreads();
         if (tt && tid == 0) tt[3] = __builtin_amdgcn_s_memrealtime();
 
@@ -530,8 +559,12 @@ __global__ __launch_bounds__(kMegaThreads) void mega_forward_kernel(const MegaAr
             float* ybase = kind == 0 ? yq : (kind == 2 ? yg : a.h);
             for (int idx = tid; idx < ge.s_blk * kMegaMaxTok * 16; idx += kMegaThreads) {
                 const int r = idx & 15, t = (idx >> 4) & (kMegaMaxTok - 1), sl = idx >> 7;
-                const float v = red[idx];
-                red[idx] = 0.f;
+                float v = 0.f;
+                for (int gq = 0; gq < n_grp; ++gq) {  // the strip's slab groups, each summed by one wavefront
+                    float* slot = red + (((sl * n_grp + gq) * kMegaMaxTok + t) << 4) + r;
+                    v += *slot;
+                    *slot = 0.f;
+                }
                 const int strip = strip_lo + sl, row = strip * 16 + r;
                 if (t < k_tok && strip < ge.n_strips && row < ge.n_out) aadd(ybase + (size_t)t * ge.n_out + row, v);
             }
@@ -595,26 +628,38 @@ static int mega_grid() {
 
 int mega_grid_size() { return mega_grid(); }
 
-// Block of s strips x b slabs per workgroup: fewest tiles per workgroup, then the widest block
-// (fewer slab blocks mean fewer float atomics leaving the CU).
+// Block of s strips x b slabs per workgroup, the b slabs of a strip cut into groups of grp_slabs (a group is summed
+// in registers by one wavefront): fewest tiles for the busiest wavefront, then fewest tiles per workgroup, then the
+// widest block (fewer slab blocks mean fewer float atomics leaving the CU), then the fewest groups.
 static bool plan_kind(MegaGeo& g, int ncu, int max_b) {
-    long best_cost = -1;
+    long best_wave = -1, best_cost = -1;
     for (int b = 1; b <= max_b && b <= g.n_slabs; ++b) {
         const int n_bblk = (g.n_slabs + b - 1) / b;
         const int max_sblk = ncu / n_bblk;
         if (max_sblk < 1) continue;
         const int s = (g.n_strips + max_sblk - 1) / max_sblk;
         if (s > kMaxS) continue;
-        const long cost = (long)s * b;
-        if (best_cost < 0 || cost < best_cost || (cost == best_cost && b > g.b_blk)) {
-            best_cost = cost;
-            g.s_blk = s;
-            g.b_blk = b;
-            g.n_sblk = (g.n_strips + s - 1) / s;
-            g.n_bblk = n_bblk;
+        for (int grp_slabs = b; grp_slabs >= 1; --grp_slabs) {
+            const int n_grp = (b + grp_slabs - 1) / grp_slabs;
+            if (s * n_grp > kMaxUnits) continue;
+            const long wave_tiles = (long)((s * n_grp + kMegaWaves - 1) / kMegaWaves) * grp_slabs;
+            if (wave_tiles > kMaxTilesPerWave) continue;
+            const long cost = (long)s * b;
+            const bool better = best_wave < 0 || wave_tiles < best_wave || (wave_tiles == best_wave && cost < best_cost) ||
+                                (wave_tiles == best_wave && cost == best_cost && b > g.b_blk);
+            if (better) {
+                best_wave = wave_tiles;
+                best_cost = cost;
+                g.s_blk = s;
+                g.b_blk = b;
+                g.n_sblk = (g.n_strips + s - 1) / s;
+                g.n_bblk = n_bblk;
+                g.n_grp = n_grp;
+                g.grp_slabs = grp_slabs;
+            }
         }
     }
-    return best_cost > 0;
+    return best_wave > 0;
 }
 
 bool mega_plan(MegaGeo (&geo)[4], int layers, int hidden, int head_dim, int k_tok, int max_tile_nnz) {
