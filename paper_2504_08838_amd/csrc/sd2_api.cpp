@@ -349,11 +349,15 @@ static int forward_impl(const sd2_model_t* md, const uint16_t* h_in, int32_t k_t
         ma.k_tok = k_tok;
         ma.spin_limit = 1 << 22;
         uint8_t* base = static_cast<uint8_t*>(ws);
-        ma.h = h_out;
+        ma.h_out = h_out;
         ma.bar = reinterpret_cast<unsigned*>(base + ML.bar_off);
         ma.err = reinterpret_cast<unsigned*>(base + ML.err_off);
         ma.yqkv = reinterpret_cast<float*>(base + ML.yqkv_off);
         ma.ygu = reinterpret_cast<float*>(base + ML.ygu_off);
+        ma.hv = reinterpret_cast<float*>(base + ML.hv_off);
+        ma.h_stride = ML.h_stride;
+        ma.yqkv_stride = ML.yqkv_stride;
+        ma.ygu_stride = ML.ygu_stride;
         for (size_t i = 0; i < md->mats.size(); ++i) ma.blob[i] = static_cast<const unsigned char*>(md->mats[i].data_dev);
         bool probe = false;
         if (trace) {
@@ -369,7 +373,7 @@ static int forward_impl(const sd2_model_t* md, const uint16_t* h_in, int32_t k_t
             if (tonly && (tonly[0] == '1' || tonly[0] == '2')) ma.trace_x = nullptr;
             probe = tonly && tonly[0] == '2';
         }
-        return launch_mega_forward(ma, h_in, base, ML.total, probe, s) == hipSuccess ? SD2_OK : SD2_ERR_HIP;
+        return launch_mega_forward(ma, h_in, base, ML.hv_off, probe, s) == hipSuccess ? SD2_OK : SD2_ERR_HIP;
     }
     uint16_t* act = reinterpret_cast<uint16_t*>(static_cast<uint8_t*>(ws) + L.act_off);
     float* part = reinterpret_cast<float*>(static_cast<uint8_t*>(ws) + L.part_off);

@@ -75,9 +75,13 @@ struct MegaGeo {
 struct MegaArgs {
     MegaGeo geo[4];  // qkv, o, gate_up, down
     int layers, hidden, q_out, kv_out, inter, n_heads, n_kv, head_dim, k_tok, spin_limit;
-    float* h;             // [k_tok][hidden] residual stream = output
-    float* yqkv;          // [2][k_tok][q_out + 2 kv_out] accumulators (layer parity)
-    float* ygu;           // [2][k_tok][2 inter]
+    // Every activation buffer is written (by atomics that complete at memory) and afterwards read at addresses no
+    // CU has touched before in this launch: one copy per layer, so a barrier needs no cache invalidation.
+    float* hv;            // [2 layers][k_tok][hidden] residual versions 0 .. 2 layers - 1 (stride h_stride floats)
+    float* h_out;         // [k_tok][hidden] version 2 layers = the output
+    float* yqkv;          // [layers][k_tok][q_out + 2 kv_out] accumulators (stride yqkv_stride floats)
+    float* ygu;           // [layers][k_tok][2 inter] (stride ygu_stride floats)
+    unsigned long long h_stride, yqkv_stride, ygu_stride;
     unsigned* bar;        // grid barrier state (see mega kernel)
     unsigned* err;        // set to 1 if a bounded wait ran out
     uint16_t* trace_x;    // optional [phase][k_tok][trace_kmax] bf16: the activations each linear consumed
@@ -89,7 +93,8 @@ struct MegaArgs {
 };
 
 struct MegaLayout {
-    size_t bar_off, err_off, yqkv_off, ygu_off, total;  // everything in [0, total) starts as zero
+    size_t bar_off, err_off, yqkv_off, ygu_off, hv_off, total;  // [0, hv_off) starts as zero
+    size_t h_stride, yqkv_stride, ygu_stride;                    // in floats
 };
 
 MegaLayout mega_layout(int layers, int hidden, int q_out, int kv_out, int inter, int k_tok);

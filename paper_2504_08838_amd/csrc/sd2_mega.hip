@@ -36,7 +36,7 @@ constexpr int kXldsDw = kMaxB * kMegaMaxTok * kXRow / 2;  // bf16 [slab][token][
 constexpr int kMaxUnits = 24;                           // (strip, slab group) units of a block: one result slot each
 constexpr int kRedDw = kMaxUnits * kMegaMaxTok * 16;    // fp32 [strip][group][token][row]
 constexpr int kPlanDw = 16;                             // per-kind plan: s_eff b_eff strip0 slab0 | n_strips 1/grp_slabs active tiles/wave | mask_off(2) val_off(2) | grp_slabs n_grp 1/n_grp -
-constexpr int kMiscDw = 512;                            // attention probabilities, per-token scalars
+constexpr int kMiscDw = 544;                            // attention probabilities, per-token scalars
 constexpr int kAttHeads = 6;                            // heads (and kv heads) one workgroup may need
 constexpr int kAreaDw = 2 * kMegaWaves * kTileDw;       // two tile buffers per wavefront: one being expanded, one being filled
 constexpr size_t kMegaLds = (size_t)(kAreaDw + kXldsDw + kRedDw + kMiscDw + 4 * kPlanDw) * 4;
@@ -194,9 +194,7 @@ __device__ __forceinline__ bool barrier_arrive(unsigned* bar, unsigned ncu, unsi
     return released;
 }
 
-// Wait: thread 0 polls its group's flag (bounded), one wavefront drops this CU's (and its XCD's) cached
-// copies so that the ordinary cached loads of the prologue see what the other XCDs wrote through to
-// memory with their atomics, and the workgroup goes on together.
+// Wait: thread 0 polls its group's flag (bounded) and the workgroup goes on together.
 __device__ __forceinline__ void barrier_wait(unsigned* bar, unsigned* err, unsigned gen, bool released, int spin_limit) {
     if (threadIdx.x == 0 && !released) {
         unsigned* gflag = bar + 32 + 8 * 32;
@@ -210,7 +208,8 @@ __device__ __forceinline__ void barrier_wait(unsigned* bar, unsigned* err, unsig
             }
         }
     }
-    if (threadIdx.x < 64) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+    // No cache invalidation: what is read after a barrier lies at addresses no CU has read before in this launch.
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
     __syncthreads();
 }
 
@@ -231,8 +230,9 @@ __global__ __launch_bounds__(kMegaThreads) void mega_forward_kernel(const MegaAr
     int cb = 0;                                                 // the one the current tile's stream is in (or on its way to)
     uint16_t* xlds = reinterpret_cast<uint16_t*>(mega_lds + kAreaDw);
     float* red = reinterpret_cast<float*>(mega_lds + kAreaDw + kXldsDw);
-    float* misc = red + kRedDw;                                 // [0,384) attention scores / probabilities, 6 heads x 8 x 8
-    float* sums = misc + 384;                                   // [0,8) sums of squares, [8,16) their inverse roots
+    float* misc = red + kRedDw;                                 // [0,432) attention scores / probabilities
+    float* sums = misc + 432;                                   // [8,16) inverse root mean squares of the tokens
+    float* part_sums = misc + 448;                              // [wave][token] sums of squares of a wavefront's columns
     if (tid < 16) lut[tid] = make_expand_selector((uint32_t)tid);
     for (int i = tid; i < kRedDw + kMiscDw; i += kMegaThreads) red[i] = 0.f;  // accumulators, scores, sums
     for (int i = tid; i < kXldsDw; i += kMegaThreads) (mega_lds + kAreaDw)[i] = 0u;  // rows of unused token slots stay zero
@@ -335,8 +335,12 @@ __global__ __launch_bounds__(kMegaThreads) void mega_forward_kernel(const MegaAr
         const int col_lo = uni(kpl[3]) * 256;                                     // first column of the block
         const int n_col = active ? max(0, min(ge.b_blk * 256, ge.k_in - col_lo)) : 0;  // columns that exist
         const int nqkv = a.q_out + 2 * a.kv_out;
-        float* yq = a.yqkv + (size_t)(layer & 1) * k_tok * nqkv;
-        float* yg = a.ygu + (size_t)(layer & 1) * k_tok * 2 * a.inter;
+        float* yq = a.yqkv + (size_t)layer * a.yqkv_stride;
+        float* yg = a.ygu + (size_t)layer * a.ygu_stride;
+        // residual versions: 2 layer before the attention output is added, 2 layer + 1 after it, 2 layer + 2 after the MLP
+        const int hv_in = 2 * layer + (kind >= 2 ? 1 : 0);  // what this phase's norm reads / what its output is added to
+        const float* h_cur = a.hv + (size_t)hv_in * a.h_stride;
+        float* h_nxt = hv_in + 1 == 2 * a.layers ? a.h_out : a.hv + (size_t)(hv_in + 1) * a.h_stride;
         const size_t tr_x = ((size_t)p * k_tok) * a.trace_kmax, tr_s = ((size_t)p * k_tok) * a.trace_smax;
 
         // columns past the end of a ragged last slab must read as zero
@@ -351,7 +355,7 @@ __global__ __launch_bounds__(kMegaThreads) void mega_forward_kernel(const MegaAr
             f32x4 hv[kMegaMaxTok];
 #pragma unroll
             for (int t = 0; t < kMegaMaxTok; ++t)
-                hv[t] = (t < k_tok && c4 < a.hidden) ? *reinterpret_cast<const f32x4*>(a.h + (size_t)t * a.hidden + c4)
+                hv[t] = (t < k_tok && c4 < a.hidden) ? *reinterpret_cast<const f32x4*>(h_cur + (size_t)t * a.hidden + c4)
                                                      : f32x4{0.f, 0.f, 0.f, 0.f};
             if (PROBE) {
                     __builtin_amdgcn_s_waitcnt(0);
@@ -361,19 +365,26 @@ __global__ __launch_bounds__(kMegaThreads) void mega_forward_kernel(const MegaAr
             for (int t = 0; t < kMegaMaxTok; ++t)
                 if (t < k_tok) {
                     const float ss = wave_sum(hv[t][0] * hv[t][0] + hv[t][1] * hv[t][1] + hv[t][2] * hv[t][2] + hv[t][3] * hv[t][3]);
-                    if (lane == 0) atomicAdd(&sums[t], ss);
+                    if (lane == 0) part_sums[wave * kMegaMaxTok + t] = ss;  // plain store: LDS float atomics are slow
                 }
-            // recycle an accumulator that is idle now: it will be added into two layers from here
-            {
-                float* z = kind == 2 ? yq : a.ygu + (size_t)((layer + 1) & 1) * k_tok * 2 * a.inter;
-                const int zn = kind == 2 ? k_tok * nqkv : k_tok * 2 * a.inter;
-                if (kind == 2 || layer > 0) {
-                    const int z0 = (int)((long long)zn * cu / ncu), z1 = (int)((long long)zn * (cu + 1) / ncu);
-                    for (int i = z0 + tid; i < z1; i += kMegaThreads) astore(z + i, 0.f);
-                }
+            // the next version of the residual starts as a copy of this one (the linear after next adds into it); the
+            // workgroups share the copying, written through to memory
+            if ((tid % ncu) == cu && c4 < a.hidden) {
+#pragma unroll
+                for (int t = 0; t < kMegaMaxTok; ++t)
+                    if (t < k_tok) {
+                        float* dst = h_nxt + (size_t)t * a.hidden + c4;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) astore(dst + e, hv[t][e]);
+                    }
             }
             __syncthreads();
-            if (tid < k_tok) sums[8 + tid] = 1.0f / sqrtf(sums[tid] / (float)a.hidden + 1e-5f);
+            if (tid < k_tok) {
+                float tot = 0.f;
+#pragma unroll
+                for (int w = 0; w < kMegaWaves; ++w) tot += part_sums[w * kMegaMaxTok + tid];
+                sums[8 + tid] = 1.0f / sqrtf(tot / (float)a.hidden + 1e-5f);
+            }
             __syncthreads();
             const int c = c4 - col_lo;
             if (c >= 0 && c < n_col) {
@@ -440,7 +451,9 @@ __global__ __launch_bounds__(kMegaThreads) void mega_forward_kernel(const MegaAr
                     vv[t] = row[a.q_out + a.kv_out + kvh * D + d];
                 }
             }
-            float* sp = misc + hh * 64;  // this head's [i][j] scores, 8 x 8
+            // scores of a head: lower triangle [i][j <= i] at i (i + 1) / 2 + j, 36 entries; two shares, one per wavefront
+            float* sp = misc + hh * 36;
+            float* sp_hi = misc + 216 + hh * 36;
             if (live) {
 #pragma unroll
                 for (int i = 0; i < kMegaMaxTok; ++i)
@@ -448,20 +461,22 @@ __global__ __launch_bounds__(kMegaThreads) void mega_forward_kernel(const MegaAr
                     for (int j = 0; j <= i; ++j)
                         if (i < k_tok) {
                             const float part = wave_sum(qv[i] * kv[j]);
-                            if (lane == 0) atomicAdd(&sp[i * 8 + j], part);
+                            if (lane == 0) ((wave & 1) ? sp_hi : sp)[i * (i + 1) / 2 + j] = part;  // plain stores, summed below
                         }
             }
             __syncthreads();
             if (tid < kAttHeads * 8) {
                 const int i = tid & 7, h2 = tid >> 3;
                 if (h2 * D < n_col && i < k_tok) {
-                    float* row = misc + h2 * 64 + i * 8;
+                    float* row = misc + h2 * 36 + i * (i + 1) / 2;
+                    const float* row_hi = row + 216;
                     const float scale = 1.0f / sqrtf((float)D);
-                    float mx = row[0] * scale;
-                    for (int j = 1; j <= i; ++j) mx = fmaxf(mx, row[j] * scale);
+                    for (int j = 0; j <= i; ++j) row[j] = (row[j] + row_hi[j]) * scale;
+                    float mx = row[0];
+                    for (int j = 1; j <= i; ++j) mx = fmaxf(mx, row[j]);
                     float sum = 0.f;
                     for (int j = 0; j <= i; ++j) {
-                        const float e = expf(row[j] * scale - mx);
+                        const float e = expf(row[j] - mx);
                         row[j] = e;
                         sum += e;
                     }
@@ -477,7 +492,7 @@ __global__ __launch_bounds__(kMegaThreads) void mega_forward_kernel(const MegaAr
                     if (t < k_tok) {
                         float o = 0.f;
 #pragma unroll
-                        for (int j = 0; j <= t; ++j) o += sp[t * 8 + j] * vv[j];
+                        for (int j = 0; j <= t; ++j) o += sp[t * (t + 1) / 2 + j] * vv[j];
                         const uint16_t cv = f32_to_bf16(o);
                         xlds[((cc >> 8) * kMegaMaxTok + t) * kXRow + (cc & 255)] = cv;
                         if (TRACE) {
@@ -552,11 +567,9 @@ __global__ __launch_bounds__(kMegaThreads) void mega_forward_kernel(const MegaAr
         __syncthreads();
         if (tt && tid == 0) tt[3] = __builtin_amdgcn_s_memrealtime();
 
-        // the LDS sums the next prologue adds into start from zero
-        if (tid < 400) misc[tid] = 0.f;
         // ---------------- the block's results leave the CU: split-K across the slab blocks by float atomics
         if (active) {
-            float* ybase = kind == 0 ? yq : (kind == 2 ? yg : a.h);
+            float* ybase = kind == 0 ? yq : (kind == 2 ? yg : h_nxt);
             for (int idx = tid; idx < ge.s_blk * kMegaMaxTok * 16; idx += kMegaThreads) {
                 const int r = idx & 15, t = (idx >> 4) & (kMegaMaxTok - 1), sl = idx >> 7;
                 float v = 0.f;
@@ -574,30 +587,33 @@ __global__ __launch_bounds__(kMegaThreads) void mega_forward_kernel(const MegaAr
 
 // ---------------------------------------------------------------- set-up kernels and launch
 
-__global__ __launch_bounds__(256) void mega_zero_kernel(uint32_t* p, size_t n) {
-    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) p[i] = 0u;
-}
-
-__global__ __launch_bounds__(256) void mega_h_init_kernel(float* __restrict__ h, const uint16_t* __restrict__ h_in, size_t n) {
-    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
-    if (i < n) h[i] = bf16_to_f32(h_in[i]);
+// One set-up launch: the barrier words and accumulators start from zero, the residual from the bf16 input.
+__global__ __launch_bounds__(256) void mega_setup_kernel(uint32_t* __restrict__ zero, size_t n_zero, float* __restrict__ h,
+                                                        const uint16_t* __restrict__ h_in, size_t n_h) {
+    const size_t i0 = (size_t)blockIdx.x * 256 + threadIdx.x, step = (size_t)gridDim.x * 256;
+    for (size_t i = i0; i < n_zero; i += step) zero[i] = 0u;
+    for (size_t i = i0; i < n_h; i += step) h[i] = bf16_to_f32(h_in[i]);
 }
 
 static size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
 MegaLayout mega_layout(int layers, int hidden, int q_out, int kv_out, int inter, int k_tok) {
-    (void)layers;
-    (void)hidden;
     MegaLayout L;
+    const size_t nl = (size_t)(layers > 0 ? layers : 1);
+    L.h_stride = align256((size_t)k_tok * hidden * 4) / 4;
+    L.yqkv_stride = align256((size_t)k_tok * (q_out + 2 * kv_out) * 4) / 4;
+    L.ygu_stride = align256((size_t)k_tok * 2 * inter * 4) / 4;
     size_t off = 0;
     L.bar_off = off;
     off += align256((size_t)kBarWords * 4);
     L.err_off = off;
     off += 256;
     L.yqkv_off = off;
-    off += align256((size_t)2 * k_tok * (q_out + 2 * kv_out) * 4);
+    off += nl * L.yqkv_stride * 4;
     L.ygu_off = off;
-    off += align256((size_t)2 * k_tok * 2 * inter * 4);
+    off += nl * L.ygu_stride * 4;
+    L.hv_off = off;
+    off += 2 * nl * L.h_stride * 4;
     L.total = off;
     return L;
 }
@@ -676,9 +692,9 @@ hipError_t launch_mega_forward(const MegaArgs& a, const uint16_t* h_in, void* ze
                                hipStream_t s) {
     const int ncu = mega_grid();
     if (ncu < 1) return hipErrorNotSupported;
-    hipLaunchKernelGGL(mega_zero_kernel, dim3(256), dim3(256), 0, s, static_cast<uint32_t*>(zero_base), zero_bytes / 4);
     const size_t nh = (size_t)a.k_tok * a.hidden;
-    hipLaunchKernelGGL(mega_h_init_kernel, dim3((unsigned)((nh + 255) / 256)), dim3(256), 0, s, a.h, h_in, nh);
+    hipLaunchKernelGGL(mega_setup_kernel, dim3(512), dim3(256), 0, s, static_cast<uint32_t*>(zero_base), zero_bytes / 4, a.hv,
+                       h_in, nh);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     MegaArgs args = a;
