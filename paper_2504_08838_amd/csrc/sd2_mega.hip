@@ -40,7 +40,7 @@ constexpr int kMiscDw = 544;                            // attention probabiliti
 constexpr int kAttHeads = 6;                            // heads (and kv heads) one workgroup may need
 constexpr int kAreaDw = 2 * kMegaWaves * kTileDw;       // two tile buffers per wavefront: one being expanded, one being filled
 constexpr size_t kMegaLds = (size_t)(kAreaDw + kXldsDw + kRedDw + kMiscDw + 4 * kPlanDw) * 4;
-constexpr int kBarWords = 32 + 8 * 32 + 8 * 32;     // top counter, 8 group counters, 8 group flags
+constexpr int kBarWords = 8 * 32;                   // 8 group counters, one per 128-byte line
 static_assert(kAttHeads * 128 == kMegaThreads, "one thread per (head slot, dimension)");
 static_assert(4 * kMegaThreads >= kMegaMaxHidden && 2 * kMegaThreads >= kMaxB * 256, "columns per thread in the prologues");
 static_assert(kMaxBAtt * 256 <= kAttHeads * 128, "attention block fits the head slots");
@@ -160,50 +160,37 @@ __device__ __forceinline__ void tile_bases(const PhaseTiles& pt, int j, int lane
     base[7] = lane_word(rb, 1);
 }
 
-// Grid barrier: 8 groups of workgroups (by id mod 8) count arrivals, the last of each group
-// arrives at the top counter, the very last releases the 8 group flags.  Counters only grow;
-// `gen` is the number of barriers passed.  Waits are bounded: on overrun *err is set and the
-// kernel keeps going (results are then invalid, but every wave still terminates).
+// Grid barrier: the workgroups form 8 groups (by id mod 8), each with an arrival counter of its own in a separate
+// cache line.  Counters only grow; `gen` is the number of barriers passed, so after barrier number gen counter g
+// holds gen * (size of group g).  Arriving is one atomic add whose result nobody waits for; waiting is eight lanes
+// of one wavefront polling the eight counters side by side, so a barrier costs about one trip to memory and back
+// after the last arrival.  Waits are bounded: on overrun *err is set and the kernel keeps going (results are then
+// invalid, but every wave still terminates).
 //
 // The barrier comes in two halves so that a wavefront can expand its next weight tile (which needs no
 // activations) between announcing its arrival and waiting for the release.
 //
 // Arrive: every wavefront has its stores and atomics acknowledged; thread 0 then counts the workgroup in.
-// Returns true (in thread 0) when this workgroup was the last one and has released everybody.
-__device__ __forceinline__ bool barrier_arrive(unsigned* bar, unsigned ncu, unsigned& gen) {
+__device__ __forceinline__ void barrier_arrive(unsigned* bar, unsigned& gen) {
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
     gen += 1;
-    bool released = false;
-    if (threadIdx.x == 0) {
-        unsigned* top = bar;
-        unsigned* gcount = bar + 32;
-        unsigned* gflag = bar + 32 + 8 * 32;
-        const unsigned grp = blockIdx.x & 7u;
-        const unsigned ngrp = ncu < 8u ? ncu : 8u;
-        const unsigned gsize = (ncu - grp + 7u) / 8u;
-        const unsigned prev = __hip_atomic_fetch_add(&gcount[grp * 32], 1u, __ATOMIC_RELAXED, SD2_AGENT);
-        if (prev + 1 == gen * gsize) {
-            const unsigned p2 = __hip_atomic_fetch_add(top, 1u, __ATOMIC_RELAXED, SD2_AGENT);
-            if (p2 + 1 == gen * ngrp) {
-                released = true;
-                for (unsigned g = 0; g < ngrp; ++g) __hip_atomic_store(&gflag[g * 32], gen, __ATOMIC_RELAXED, SD2_AGENT);
-            }
-        }
-    }
-    return released;
+    if (threadIdx.x == 0) (void)__hip_atomic_fetch_add(&bar[(blockIdx.x & 7u) * 32], 1u, __ATOMIC_RELAXED, SD2_AGENT);
 }
 
-// Wait: thread 0 polls its group's flag (bounded) and the workgroup goes on together.
-__device__ __forceinline__ void barrier_wait(unsigned* bar, unsigned* err, unsigned gen, bool released, int spin_limit) {
-    if (threadIdx.x == 0 && !released) {
-        unsigned* gflag = bar + 32 + 8 * 32;
-        const unsigned grp = blockIdx.x & 7u;
+// Wait: lanes 0..7 of the first wavefront poll the group counters (bounded), then the workgroup goes on together.
+__device__ __forceinline__ void barrier_wait(unsigned* bar, unsigned* err, unsigned ncu, unsigned gen, int spin_limit) {
+    if (threadIdx.x < 64) {
+        const unsigned g = threadIdx.x;
+        const unsigned ngrp = ncu < 8u ? ncu : 8u;
+        const unsigned want = g < ngrp ? gen * ((ncu - g + 7u) / 8u) : 0u;
         int spins = 0;
-        while (__hip_atomic_load(&gflag[grp * 32], __ATOMIC_RELAXED, SD2_AGENT) < gen) {
-            __builtin_amdgcn_s_sleep(2);
+        for (;;) {
+            const unsigned have = g < ngrp ? __hip_atomic_load(&bar[g * 32], __ATOMIC_RELAXED, SD2_AGENT) : 0u;
+            if (__all(have >= want)) break;  // wave-uniform exit
+            __builtin_amdgcn_s_sleep(1);
             if (++spins > spin_limit) {
-                __hip_atomic_store(err, 1u, __ATOMIC_RELAXED, SD2_AGENT);
+                if (g == 0) __hip_atomic_store(err, 1u, __ATOMIC_RELAXED, SD2_AGENT);
                 break;
             }
         }
@@ -289,8 +276,7 @@ __global__ __launch_bounds__(kMegaThreads) void mega_forward_kernel(const MegaAr
         if (tt && tid == 0) tt[0] = __builtin_amdgcn_s_memrealtime();
         // next phase's tiles: planned now so that the directory loads have the whole phase to arrive
         plan_phase(nt, ka, plans, p + 1, n_phases, wave, lane);
-        bool released = false;
-        if (p > 0) released = barrier_arrive(a.bar, (unsigned)ncu, gen);
+        if (p > 0) barrier_arrive(a.bar, gen);
 
         // Waits for tile j's stream, requests the stream of the tile after it (the next one of this phase, else the
         // first one of the next phase: weights do not depend on activations) and returns what the expansion needs.
@@ -325,7 +311,7 @@ __global__ __launch_bounds__(kMegaThreads) void mega_forward_kernel(const MegaAr
             for (int q = 0; q < 4; ++q) fpre[q][0].q = fpre[q][1].q = u32x4{0, 0, 0, 0};  // defined in every path
         }
         if (PROBE && tt && tid == 0) tt[4] = __builtin_amdgcn_s_memrealtime();
-        if (p > 0) barrier_wait(a.bar, a.err, gen, released, a.spin_limit);
+        if (p > 0) barrier_wait(a.bar, a.err, (unsigned)ncu, gen, a.spin_limit);
         if (tt && tid == 0) tt[1] = __builtin_amdgcn_s_memrealtime();
 
         // ---------------- prologue: the activation columns of this workgroup's slabs, as bf16 in LDS
