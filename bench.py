@@ -26,8 +26,8 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 # HBM bytes per launch of the forward kernel (and of the gate+up sparse linear) from rocprofv3 --pmc
 # FETCH_SIZE / WRITE_SIZE runs, scaled by the plain copy kernel of --calibrate; None until measured.
-MEASURED_TRAFFIC_BYTES = 3418794493
-MEASURED_LINEAR_TRAFFIC_BYTES = 63422727
+MEASURED_TRAFFIC_BYTES = 3447977452
+MEASURED_LINEAR_TRAFFIC_BYTES = 63313736
 CALIBRATION_BYTES = 256 << 20  # size of the plain copies launched by --calibrate
 
 
