@@ -274,9 +274,9 @@ __global__ __launch_bounds__(kMegaThreads) void mega_forward_kernel(const MegaAr
         const int n_grp = max(ka->geo[kind].n_grp, 1);
         unsigned long long* tt = a.trace_time ? a.trace_time + ((size_t)cu * n_phases + p) * 8 : nullptr;
         if (tt && tid == 0) tt[0] = __builtin_amdgcn_s_memrealtime();
+        if (p > 0) barrier_arrive(a.bar, gen);
         // next phase's tiles: planned now so that the directory loads have the whole phase to arrive
         plan_phase(nt, ka, plans, p + 1, n_phases, wave, lane);
-        if (p > 0) barrier_arrive(a.bar, gen);
 
         // Waits for tile j's stream, requests the stream of the tile after it (the next one of this phase, else the
         // first one of the next phase: weights do not depend on activations) and returns what the expansion needs.
