@@ -145,6 +145,21 @@ def test_forward_step_by_step(which, forward_path):
     assert ol.rel_l2(plain, h_out) <= 5e-3
 
 
+@pytest.mark.parametrize("pct", [50, 60, 70])
+@pytest.mark.parametrize("k_tok", [1, 3, 5, 8])
+def test_cfg4_cells_link_by_link(pct, k_tok):
+    """The twelve cells of the 1.5B-shape configuration (sparsity x tokens in flight), one decoder layer each,
+    through the default (single-launch) forward, every link against the oracle."""
+    import gpu_util as gu
+    shape = SimpleNamespace(**{**wl.CONFIGS[4]["shape"].__dict__, "layers": 1})
+    get = _weights(shape, 4, pct)
+    h_in = wl.gen_x(4, 0, "q", k_tok, shape.hidden)
+    model = gu.build_model(shape, get)
+    h_out, x, src = gu.run_forward_trace(model, h_in, shape)
+    _verify_steps(shape, get, h_in, h_out, x, src)
+    assert ol.rel_l2(gu.run_forward(model, h_in, shape.hidden), os_.drafter_forward(shape, get, h_in)) <= E2E_TOL
+
+
 def test_zero_layers_returns_input():
     import gpu_util as gu
     z = SimpleNamespace(**{**SMALL.__dict__, "layers": 0})
