@@ -162,7 +162,8 @@ def main():
     us_per_step = wall / args.steps * 1e6
     fwd_us = float(np.mean([e0.elapsed_time(e1) for e0, e1 in evs])) * 1e3
 
-    # sanity: the output of the timed configuration is finite and the verify result is plausible
+    # sanity: no bounded wait ran out, the output of the timed configuration is finite, the verify result plausible
+    sd2.drafter_forward_status(model, k_tok, ws.data_ptr(), stream.cuda_stream)
     h_host = h_out.cpu().numpy()
     assert np.isfinite(h_host).all(), "non-finite drafter output"
     acc_host = acc.cpu().numpy()

@@ -46,7 +46,8 @@ enum sd2_status {
     SD2_ERR_BLOB = -5,        /* blob header, directory or checksum is corrupt */
     SD2_ERR_RANGE = -6,       /* a value (token id, k_tok, ...) is outside its range */
     SD2_ERR_HIP = -7,         /* a HIP runtime call or kernel launch failed */
-    SD2_ERR_UNSUPPORTED = -8  /* valid request that this build does not implement */
+    SD2_ERR_UNSUPPORTED = -8, /* valid request that this build does not implement */
+    SD2_ERR_TIMEOUT = -9      /* a bounded wait inside a kernel ran out; the results of that call are invalid */
 };
 
 #define SD2_MAX_TOKENS 64
@@ -171,6 +172,11 @@ int sd2_drafter_workspace_size(const sd2_model_t* model, int32_t k_tok, size_t* 
 int sd2_sparse_drafter_forward(const sd2_model_t* model, const uint16_t* h_in_bf16_dev, int32_t k_tok,
                                float* h_out_dev, void* workspace_dev, size_t workspace_bytes,
                                void* stream);
+/* The forward is asynchronous and its single-launch kernel synchronises the GPU's compute units with
+ * bounded waits (it needs all of them at once; a wait that runs out sets a flag in the workspace and the
+ * kernel still ends).  This call waits for `stream`, reads that flag of the last forward that used
+ * `workspace_dev` with this model and k_tok, and returns SD2_OK or SD2_ERR_TIMEOUT. */
+int sd2_drafter_forward_status(const sd2_model_t* model, int32_t k_tok, const void* workspace_dev, void* stream);
 
 /* Debug variant for step-by-step checking: the same forward, which also records, per linear
  * (4 per layer, in execution order), the fp32 values its input glue read -- the residual

@@ -34,6 +34,7 @@ from .binding import (  # noqa: F401
     sparse_drafter_forward,
     drafter_trace_size,
     sparse_drafter_forward_trace,
+    drafter_forward_status,
     greedy_verify,
     check_token_ids_host,
     calibration_copy,

@@ -101,6 +101,7 @@ def lib():
             "sd2_sparse_drafter_forward_trace": (C.c_int, [vp, vp, i32, vp, vp, sz, vp, sz, vp]),
             "sd2_greedy_verify": (C.c_int, [vp, vp, i32, i32, i32, vp, vp, vp]),
             "sd2_check_token_ids_host": (C.c_int, [vp, sz, i32]),
+            "sd2_drafter_forward_status": (C.c_int, [vp, i32, vp, vp]),
             "sd2_calibration_copy": (C.c_int, [vp, vp, sz, vp]),
         }
         for name, (res, args) in sig.items():
@@ -251,6 +252,11 @@ def sparse_drafter_forward_trace(model, h_in_ptr, k_tok, h_out_ptr, ws_ptr, ws_b
     _check(lib().sd2_sparse_drafter_forward_trace(model.handle, C.c_void_p(h_in_ptr), k_tok, C.c_void_p(h_out_ptr),
                                                   C.c_void_p(ws_ptr), ws_bytes, C.c_void_p(trace_ptr), trace_bytes,
                                                   C.c_void_p(stream)), "sd2_sparse_drafter_forward_trace")
+
+
+def drafter_forward_status(model, k_tok, ws_ptr, stream=0):
+    _check(lib().sd2_drafter_forward_status(model.handle, k_tok, C.c_void_p(ws_ptr), C.c_void_p(stream)),
+           "sd2_drafter_forward_status")
 
 
 def greedy_verify(draft_ptr, target_ptr, batch, k, vocab, accepted_ptr, out_tokens_ptr, stream=0):

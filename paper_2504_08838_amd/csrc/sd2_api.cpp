@@ -152,6 +152,7 @@ const char* sd2_strerror(int status) {
         case SD2_ERR_RANGE: return "value out of range";
         case SD2_ERR_HIP: return "HIP call failed";
         case SD2_ERR_UNSUPPORTED: return "not implemented in this build";
+        case SD2_ERR_TIMEOUT: return "a bounded wait inside a kernel ran out";
         default: return "unknown status";
     }
 }
@@ -347,7 +348,9 @@ static int forward_impl(const sd2_model_t* md, const uint16_t* h_in, int32_t k_t
         ma.n_kv = sh.n_kv;
         ma.head_dim = sh.head_dim;
         ma.k_tok = k_tok;
-        ma.spin_limit = 1 << 22;
+        // about a second of polling per barrier before the forward is given up (SD2_MEGA_SPIN_LIMIT overrides: tests)
+        ma.spin_limit = 1 << 20;
+        if (const char* sl = getenv("SD2_MEGA_SPIN_LIMIT")) ma.spin_limit = std::max(0, atoi(sl));
         uint8_t* base = static_cast<uint8_t*>(ws);
         ma.h_out = h_out;
         ma.bar = reinterpret_cast<unsigned*>(base + ML.bar_off);
@@ -430,6 +433,21 @@ static int forward_impl(const sd2_model_t* md, const uint16_t* h_in, int32_t k_t
 int sd2_sparse_drafter_forward(const sd2_model_t* md, const uint16_t* h_in, int32_t k_tok, float* h_out, void* ws,
                                size_t ws_bytes, void* stream) {
     return forward_impl(md, h_in, k_tok, h_out, ws, ws_bytes, nullptr, stream);
+}
+
+int sd2_drafter_forward_status(const sd2_model_t* md, int32_t k_tok, const void* ws, void* stream) {
+    if (!md || !ws) return SD2_ERR_NULL;
+    int rc = check_tokens(k_tok);
+    if (rc != SD2_OK) return rc;
+    if (hipStreamSynchronize(static_cast<hipStream_t>(stream)) != hipSuccess) return SD2_ERR_HIP;
+    MegaGeo geo[4];
+    if (!plan_mega_path(md, k_tok, geo)) return SD2_OK;  // the multi-launch path has no waits inside kernels
+    const sd2_model_shape_t& sh = md->shape;
+    const MegaLayout ML = mega_layout(sh.layers, sh.hidden, sh.q_out, sh.kv_out, sh.inter, k_tok);
+    unsigned flag = 0;
+    if (hipMemcpy(&flag, static_cast<const uint8_t*>(ws) + ML.err_off, sizeof(flag), hipMemcpyDeviceToHost) != hipSuccess)
+        return SD2_ERR_HIP;
+    return flag ? SD2_ERR_TIMEOUT : SD2_OK;
 }
 
 int sd2_drafter_trace_size(const sd2_model_t* model, int32_t k_tok, size_t* bytes_out) {

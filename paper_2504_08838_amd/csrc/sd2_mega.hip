@@ -179,7 +179,7 @@ __device__ __forceinline__ void barrier_arrive(unsigned* bar, unsigned& gen) {
 }
 
 // Wait: lanes 0..7 of the first wavefront poll the group counters (bounded), then the workgroup goes on together.
-__device__ __forceinline__ void barrier_wait(unsigned* bar, unsigned* err, unsigned ncu, unsigned gen, int spin_limit) {
+__device__ __forceinline__ void barrier_wait(unsigned* bar, unsigned* err, unsigned ncu, unsigned gen, int& spin_limit) {
     if (threadIdx.x < 64) {
         const unsigned g = threadIdx.x;
         const unsigned ngrp = ncu < 8u ? ncu : 8u;
@@ -191,6 +191,7 @@ __device__ __forceinline__ void barrier_wait(unsigned* bar, unsigned* err, unsig
             __builtin_amdgcn_s_sleep(1);
             if (++spins > spin_limit) {
                 if (g == 0) __hip_atomic_store(err, 1u, __ATOMIC_RELAXED, SD2_AGENT);
+                spin_limit = 0;  // the forward is lost: later barriers of this wavefront give up at once
                 break;
             }
         }
@@ -261,6 +262,7 @@ __global__ __launch_bounds__(kMegaThreads) void mega_forward_kernel(const MegaAr
     uint2 mk_next = make_uint2(0, 0);
     if (ct.n > 0) issue_phase_tile(ct, 0, bufs, mk_next, lane);
     unsigned gen = 0;
+    int spin_limit = a.spin_limit;
 
     for (int p = 0; p < n_phases; ++p) {
         const int layer = p >> 2, kind = p & 3;
@@ -311,7 +313,7 @@ __global__ __launch_bounds__(kMegaThreads) void mega_forward_kernel(const MegaAr
             for (int q = 0; q < 4; ++q) fpre[q][0].q = fpre[q][1].q = u32x4{0, 0, 0, 0};  // defined in every path
         }
         if (PROBE && tt && tid == 0) tt[4] = __builtin_amdgcn_s_memrealtime();
-        if (p > 0) barrier_wait(a.bar, a.err, (unsigned)ncu, gen, a.spin_limit);
+        if (p > 0) barrier_wait(a.bar, a.err, (unsigned)ncu, gen, spin_limit);
         if (tt && tid == 0) tt[1] = __builtin_amdgcn_s_memrealtime();
 
         // ---------------- prologue: the activation columns of this workgroup's slabs, as bf16 in LDS

@@ -73,7 +73,7 @@ def run_forward(model, h_in_bits, hidden) -> np.ndarray:
     ws_bytes = sd2.drafter_workspace_size(model, k_tok)
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
     sd2.sparse_drafter_forward(model, h_in.data_ptr(), k_tok, h_out.data_ptr(), ws.data_ptr(), ws_bytes, stream_ptr())
-    torch.cuda.synchronize()
+    sd2.drafter_forward_status(model, k_tok, ws.data_ptr(), stream_ptr())  # waits; raises if a bounded wait ran out
     return h_out.cpu().numpy()
 
 

@@ -160,6 +160,29 @@ def test_cfg4_cells_link_by_link(pct, k_tok):
     assert ol.rel_l2(gu.run_forward(model, h_in, shape.hidden), os_.drafter_forward(shape, get, h_in)) <= E2E_TOL
 
 
+def test_bounded_wait_reports_timeout(monkeypatch):
+    """Failure handling: with a spin limit of zero every grid barrier gives up at its first unsuccessful poll.  All
+    wavefronts still run to the end (nothing hangs), and the status call reports that the forward is invalid."""
+    import torch
+    import paper_2504_08838_amd as sd2
+    import gpu_util as gu
+    monkeypatch.delenv("SD2_FORWARD", raising=False)
+    get = _weights(SMALL, 14)
+    model = gu.build_model(SMALL, get)
+    h_in = gu.dev(wl.gen_x(14, 0, "q", 5, SMALL.hidden))
+    h_out = torch.zeros((5, SMALL.hidden), dtype=torch.float32, device="cuda")
+    ws_bytes = sd2.drafter_workspace_size(model, 5)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+    monkeypatch.setenv("SD2_MEGA_SPIN_LIMIT", "0")
+    sd2.sparse_drafter_forward(model, h_in.data_ptr(), 5, h_out.data_ptr(), ws.data_ptr(), ws_bytes, gu.stream_ptr())
+    with pytest.raises(sd2.SD2Error):
+        sd2.drafter_forward_status(model, 5, ws.data_ptr(), gu.stream_ptr())
+    monkeypatch.delenv("SD2_MEGA_SPIN_LIMIT")
+    sd2.sparse_drafter_forward(model, h_in.data_ptr(), 5, h_out.data_ptr(), ws.data_ptr(), ws_bytes, gu.stream_ptr())
+    sd2.drafter_forward_status(model, 5, ws.data_ptr(), gu.stream_ptr())   # the next call is fine again
+    assert ol.rel_l2(h_out.cpu().numpy(), os_.drafter_forward(SMALL, get, wl.gen_x(14, 0, "q", 5, SMALL.hidden))) <= E2E_TOL
+
+
 def test_zero_layers_returns_input():
     import gpu_util as gu
     z = SimpleNamespace(**{**SMALL.__dict__, "layers": 0})
