@@ -120,15 +120,22 @@ template <int STEPS = 2, typename F>
 __device__ __forceinline__ void expand_tile(const uint8_t* __restrict__ bufb, const uint2* __restrict__ lut,
                                             const uint32_t (&base)[8], uint2 mk, F&& use) {
     static_assert(STEPS == 1 || STEPS == 2 || STEPS == 4, "super-steps whose LDS reads are batched");
-    const uint32_t m16[4] = {mk.x & 0xffffu, mk.x >> 16, mk.y & 0xffffu, mk.y >> 16};
+    // Nibble popcounts of a 32-bit mask word (two super-steps) at once: the classic pairwise sums give eight
+    // 4-bit counts, two masks split them into bytes, and one byte permute per super-step lines up its four counts.
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) uint8_t*)bufb;  // LDS byte address
     uint32_t ex[4];
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-        const uint32_t bits = m16[q];
-        const uint32_t packed = (uint32_t)__builtin_popcount(bits & 0xfu) | ((uint32_t)__builtin_popcount(bits & 0xf0u) << 8) |
-                                ((uint32_t)__builtin_popcount(bits & 0xf00u) << 16) |
-                                ((uint32_t)__builtin_popcount(bits & 0xf000u) << 24);
-        ex[q] = wave_excl_scan(packed);  // per nibble: values of lower lanes (<= 252, no carry)
+    for (int w = 0; w < 2; ++w) {
+        const uint32_t m = w ? mk.y : mk.x;
+        uint32_t x = m - ((m >> 1) & 0x55555555u);
+        x = (x & 0x33333333u) + ((x >> 2) & 0x33333333u);      // nibble n holds popcount(nibble n of m), 0..4
+        const uint32_t even = x & 0x0f0f0f0fu;                 // bytes: counts of nibbles 0, 2, 4, 6
+        const uint32_t odd = (x >> 4) & 0x0f0f0f0fu;           // bytes: counts of nibbles 1, 3, 5, 7
+        // v_perm_b32(hi, lo, sel): selector byte 0..3 picks from lo, 4..7 from hi
+        const uint32_t lo_step = __builtin_amdgcn_perm(odd, even, 0x05010400u);  // [n0, n1, n2, n3]
+        const uint32_t hi_step = __builtin_amdgcn_perm(odd, even, 0x07030602u);  // [n4, n5, n6, n7]
+        ex[2 * w] = wave_excl_scan(lo_step);      // per nibble: values of lower lanes (<= 252, no carry)
+        ex[2 * w + 1] = wave_excl_scan(hi_step);
     }
 #pragma unroll
     for (int part = 0; part < 4 / STEPS; ++part) {
@@ -138,10 +145,17 @@ __device__ __forceinline__ void expand_tile(const uint8_t* __restrict__ bufb, co
 #pragma unroll
         for (int i = 0; i < 4 * STEPS; ++i) {
             const int q = STEPS * part + (i >> 2), h = i & 3;
+            const uint32_t m = (q >> 1) ? mk.y : mk.x;
             const uint32_t run_base = (base[(4 * q + h) >> 1] >> (16 * (h & 1))) & 0xffffu;
-            off[i] = (run_base + ((ex[q] >> (8 * h)) & 0xffu)) * 2u;  // byte offset in the tile's stream
-            tr[i] = *reinterpret_cast<const Tri32*>(bufb + (off[i] & ~3u));
-            sel[i] = lut[(m16[q] >> (4 * h)) & 15u];
+            // LDS address of the lane's first value: the run's start is scalar arithmetic, the lane adds its prefix
+            // (the buffer is 4-byte aligned, so the low address bits are the byte offset's)
+            off[i] = (lds_base + run_base * 2u) + __builtin_amdgcn_ubfe(ex[q], 8 * h, 8) * 2u;
+            const __attribute__((address_space(3))) uint32_t* win =
+                (const __attribute__((address_space(3))) uint32_t*)(uintptr_t)(off[i] & ~3u);
+            tr[i].a = win[0];
+            tr[i].b = win[1];
+            tr[i].c = win[2];
+            sel[i] = lut[__builtin_amdgcn_ubfe(m, 16 * (q & 1) + 4 * h, 4)];
         }
         Frag f[STEPS][2];
 #pragma unroll
