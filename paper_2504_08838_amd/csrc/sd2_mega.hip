@@ -263,6 +263,7 @@ __global__ __launch_bounds__(kMegaThreads) void mega_forward_kernel(const MegaAr
     if (ct.n > 0) issue_phase_tile(ct, 0, bufs, mk_next, lane);
     unsigned gen = 0;
     int spin_limit = a.spin_limit;
+    const bool copies_residual = (tid % ncu) == cu;  // this thread's columns of the residual are copied by this workgroup
 
     for (int p = 0; p < n_phases; ++p) {
         const int layer = p >> 2, kind = p & 3;
@@ -357,7 +358,7 @@ __global__ __launch_bounds__(kMegaThreads) void mega_forward_kernel(const MegaAr
                 }
             // the next version of the residual starts as a copy of this one (the linear after next adds into it); the
             // workgroups share the copying, written through to memory
-            if ((tid % ncu) == cu && c4 < a.hidden) {
+            if (copies_residual && c4 < a.hidden) {
 #pragma unroll
                 for (int t = 0; t < kMegaMaxTok; ++t)
                     if (t < k_tok) {
@@ -453,24 +454,23 @@ __global__ __launch_bounds__(kMegaThreads) void mega_forward_kernel(const MegaAr
                         }
             }
             __syncthreads();
-            if (tid < kAttHeads * 8) {
-                const int i = tid & 7, h2 = tid >> 3;
-                if (h2 * D < n_col && i < k_tok) {
-                    float* row = misc + h2 * 36 + i * (i + 1) / 2;
-                    const float* row_hi = row + 216;
-                    const float scale = 1.0f / sqrtf((float)D);
-                    for (int j = 0; j <= i; ++j) row[j] = (row[j] + row_hi[j]) * scale;
-                    float mx = row[0];
-                    for (int j = 1; j <= i; ++j) mx = fmaxf(mx, row[j]);
-                    float sum = 0.f;
-                    for (int j = 0; j <= i; ++j) {
-                        const float e = expf(row[j] - mx);
-                        row[j] = e;
-                        sum += e;
-                    }
-                    const float inv = 1.0f / sum;
-                    for (int j = 0; j <= i; ++j) row[j] *= inv;
-                }
+            // softmax: wavefront = head, lane = (row i, column j); a row's maximum and sum go round its eight lanes
+            if (wave < kAttHeads && wave * D < n_col) {
+                const int i = lane >> 3, j = lane & 7;
+                const bool on = i < k_tok && j <= i;
+                float* row = misc + wave * 36 + i * (i + 1) / 2;
+                const float scale = 1.0f / sqrtf((float)D);
+                const float sc = on ? (row[j] + row[216 + j]) * scale : -3.0e38f;
+                float mx = sc;
+                mx = fmaxf(mx, __shfl_xor(mx, 1));
+                mx = fmaxf(mx, __shfl_xor(mx, 2));
+                mx = fmaxf(mx, __shfl_xor(mx, 4));
+                const float e = on ? __expf(sc - mx) : 0.f;
+                float sum = e;
+                sum += __shfl_xor(sum, 1);
+                sum += __shfl_xor(sum, 2);
+                sum += __shfl_xor(sum, 4);
+                if (on) row[j] = e * __builtin_amdgcn_rcpf(sum);
             }
             __syncthreads();
             if (live) {
