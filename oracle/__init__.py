@@ -19,6 +19,7 @@ Pins (see tests, all runnable without a GPU):
               all-zero weights leave the residual stream untouched.
   verify   -- hand-worked examples of Eq. 2, all 2^k match patterns, closed-form mean.
   macs     -- reproduces the abstract's MAC reduction for the 3B drafter.
+  lm_head  -- identity weights return the normalised input; duplicated rows: lowest index wins; triple loop.
 Model quality (accepted length on real prompts, task accuracy) is parity unpinned
 and out of scope: it needs trained weights and evaluation suites.
 """
