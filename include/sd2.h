@@ -191,6 +191,26 @@ int sd2_sparse_drafter_forward_trace(const sd2_model_t* model, const uint16_t* h
                                      size_t workspace_bytes, void* trace_dev, size_t trace_bytes,
                                      void* stream);
 
+/* ------------------------------------------------------------------ LM head with greedy choice
+ * The drafter's next-token choice (Eq. 1 with greedy decoding, as in the footnote to Eq. 3): the
+ * largest logit of the LM head, the one linear of the drafter that stays dense (Sec. 2.3 prunes
+ * the decoder blocks; Sec. 3.2 counts the head's MACs in full).  For each of the k_tok rows of h:
+ *   a = bf16(h / sqrt(mean(h^2) + 1e-5))      final RMS norm, no learned scale
+ *   logit[v] = sum_c W[v][c] * a[c]            fp32 accumulation of exact bf16 products
+ *   token = the lowest v among the largest logits
+ * w_lm_bf16_dev: device, row-major [vocab][hidden] bf16 (the layout of nn.Linear.weight), read only.
+ * h_dev: device fp32 [k_tok][hidden] (what sd2_sparse_drafter_forward writes).  token_ids_dev: device
+ * int32 [k_tok].  max_logit_dev (fp32 [k_tok]) and logits_dev (fp32 [k_tok][vocab], every entry
+ * written) are optional: NULL skips them, and without logits_dev nothing of size vocab is written.
+ * hidden: a multiple of 128, at most 8192.  vocab >= 1 (need not be a multiple of 16).  k_tok > 16
+ * streams the matrix once per 16 tokens.  workspace_dev: >= the reported size, 16-byte aligned,
+ * contents irrelevant before and after.  A row whose logits are all NaN yields token 0.
+ * Asynchronous on `stream`; all checks happen on the host before the first launch. */
+int sd2_lm_head_workspace_size(int32_t vocab, int32_t hidden, int32_t k_tok, size_t* bytes_out);
+int sd2_lm_head_argmax(const uint16_t* w_lm_bf16_dev, int32_t vocab, int32_t hidden, const float* h_dev,
+                       int32_t k_tok, int32_t* token_ids_dev, float* max_logit_dev, float* logits_dev,
+                       void* workspace_dev, size_t workspace_bytes, void* stream);
+
 /* ------------------------------------------------------------------ verification
  * Strict top-1 verification (Eq. 2): accepted_len[b] = number of leading positions
  * where draft[b][i] == target[b][i]; out_tokens[b] = those drafts, then target[b][n],

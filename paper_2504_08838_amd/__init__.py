@@ -38,4 +38,6 @@ from .binding import (  # noqa: F401
     greedy_verify,
     check_token_ids_host,
     calibration_copy,
+    lm_head_argmax,
+    lm_head_workspace_size,
 )

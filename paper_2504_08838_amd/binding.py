@@ -103,6 +103,8 @@ def lib():
             "sd2_check_token_ids_host": (C.c_int, [vp, sz, i32]),
             "sd2_drafter_forward_status": (C.c_int, [vp, i32, vp, vp]),
             "sd2_calibration_copy": (C.c_int, [vp, vp, sz, vp]),
+            "sd2_lm_head_workspace_size": (C.c_int, [i32, i32, i32, C.POINTER(sz)]),
+            "sd2_lm_head_argmax": (C.c_int, [vp, i32, i32, vp, i32, vp, vp, vp, vp, sz, vp]),
         }
         for name, (res, args) in sig.items():
             fn = getattr(L, name)
@@ -263,6 +265,21 @@ def greedy_verify(draft_ptr, target_ptr, batch, k, vocab, accepted_ptr, out_toke
     _check(lib().sd2_greedy_verify(C.c_void_p(draft_ptr), C.c_void_p(target_ptr), batch, k, vocab,
                                    C.c_void_p(accepted_ptr), C.c_void_p(out_tokens_ptr), C.c_void_p(stream)),
            "sd2_greedy_verify")
+
+
+def lm_head_workspace_size(vocab, hidden, k_tok):
+    n = C.c_size_t(0)
+    _check(lib().sd2_lm_head_workspace_size(vocab, hidden, k_tok, C.byref(n)), "sd2_lm_head_workspace_size")
+    return n.value
+
+
+def lm_head_argmax(w_ptr, vocab, hidden, h_ptr, k_tok, token_ids_ptr, ws_ptr, ws_bytes, stream=0, max_logit_ptr=0,
+                   logits_ptr=0):
+    """Device pointers as integers; max_logit_ptr / logits_ptr 0 = not wanted."""
+    _check(lib().sd2_lm_head_argmax(C.c_void_p(w_ptr), vocab, hidden, C.c_void_p(h_ptr), k_tok,
+                                    C.c_void_p(token_ids_ptr), C.c_void_p(max_logit_ptr or None),
+                                    C.c_void_p(logits_ptr or None), C.c_void_p(ws_ptr), ws_bytes, C.c_void_p(stream)),
+           "sd2_lm_head_argmax")
 
 
 def calibration_copy(dst_ptr, src_ptr, nbytes, stream=0):

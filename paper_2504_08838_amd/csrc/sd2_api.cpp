@@ -494,4 +494,39 @@ int sd2_calibration_copy(void* dst, const void* src, size_t bytes, void* stream)
     return SD2_OK;
 }
 
+// ---- LM head with greedy choice
+
+static int lm_head_check(int32_t vocab, int32_t hidden, int32_t k_tok) {
+    if (vocab < 1 || hidden < 128 || hidden % 128 != 0 || hidden > kLmMaxHidden) return SD2_ERR_SHAPE;
+    if (k_tok < 1 || k_tok > SD2_MAX_TOKENS) return SD2_ERR_RANGE;
+    return SD2_OK;
+}
+
+int sd2_lm_head_workspace_size(int32_t vocab, int32_t hidden, int32_t k_tok, size_t* bytes_out) {
+    if (!bytes_out) return SD2_ERR_NULL;
+    const int rc = lm_head_check(vocab, hidden, k_tok);
+    if (rc != SD2_OK) return rc;
+    *bytes_out = (size_t)kLmMaxWorkgroups * 16 * 8;
+    return SD2_OK;
+}
+
+int sd2_lm_head_argmax(const uint16_t* w_lm, int32_t vocab, int32_t hidden, const float* h, int32_t k_tok,
+                       int32_t* token_ids, float* max_logit, float* logits, void* workspace, size_t workspace_bytes,
+                       void* stream) {
+    if (!w_lm || !h || !token_ids || !workspace) return SD2_ERR_NULL;
+    const int rc = lm_head_check(vocab, hidden, k_tok);
+    if (rc != SD2_OK) return rc;
+    if (!aligned16(w_lm) || !aligned16(h) || !aligned16(workspace)) return SD2_ERR_BUFFER;
+    if (workspace_bytes < (size_t)kLmMaxWorkgroups * 16 * 8) return SD2_ERR_BUFFER;
+    // the matrix cores take 16 tokens at a time; a larger k_tok streams the head once per group of 16
+    for (int32_t t0 = 0; t0 < k_tok; t0 += 16) {
+        const int32_t kt = std::min<int32_t>(16, k_tok - t0);
+        if (launch_lm_head(w_lm, h + (size_t)t0 * hidden, vocab, hidden, kt, workspace, token_ids + t0,
+                           max_logit ? max_logit + t0 : nullptr, logits ? logits + (size_t)t0 * vocab : nullptr,
+                           static_cast<hipStream_t>(stream)) != hipSuccess)
+            return SD2_ERR_HIP;
+    }
+    return SD2_OK;
+}
+
 }  // extern "C"

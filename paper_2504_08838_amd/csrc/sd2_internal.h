@@ -106,4 +106,11 @@ bool mega_plan(MegaGeo (&geo)[4], int layers, int hidden, int head_dim, int k_to
 hipError_t launch_mega_forward(const MegaArgs& a, const uint16_t* h_in, void* zero_base, size_t zero_bytes, bool probe,
                                hipStream_t s);
 
+// ---- LM head with greedy choice: tokens [0, k_tok), k_tok <= 16, hidden a multiple of 128 and <= 8192.
+// part_ws: kLmMaxWorkgroups * 16 candidates of 8 bytes.  max_logit and logits ([k_tok][vocab]) may be null.
+constexpr int kLmMaxWorkgroups = 1024;
+constexpr int kLmMaxHidden = 8192;
+hipError_t launch_lm_head(const uint16_t* w, const float* h, int vocab, int hidden, int k_tok, void* part_ws,
+                          int32_t* token_ids, float* max_logit, float* logits, hipStream_t s);
+
 }  // namespace sd2

@@ -24,6 +24,8 @@ from .gen import (  # noqa: F401
     gen_weight_dense,
     gen_x,
     gen_verify,
+    gen_lm_head,
+    gen_final_hidden,
     stack_matrices,
     layer_matrix_shapes,
 )

@@ -189,6 +189,28 @@ def gen_x(cfg_id: int, layer: int, proj: str, k_tok: int, k_in: int) -> np.ndarr
     return f32_to_bf16_bits(z)
 
 
+_LM_HEAD_ID = 300
+_LM_H_ID = 301
+
+
+def gen_lm_head(cfg_id: int, vocab: int, hidden: int) -> np.ndarray:
+    """Dense (never pruned) LM-head weight bits [vocab][hidden], W = 0.02 * z, drawn in blocks of 8192 rows."""
+    rng = _rng(cfg_id, 0, _LM_HEAD_ID)
+    out = np.empty((vocab, hidden), dtype=np.uint16)
+    for r0 in range(0, vocab, 8192):
+        r1 = min(vocab, r0 + 8192)
+        z = rng.standard_normal((r1 - r0, hidden), dtype=np.float32)
+        z *= np.float32(0.02)
+        out[r0:r1] = f32_to_bf16_bits(z)
+    return out
+
+
+def gen_final_hidden(cfg_id: int, k_tok: int, hidden: int) -> np.ndarray:
+    """Final residual stream [k_tok][hidden] as float32, H = 3 * z (what the decoder stack hands to the head)."""
+    z = _rng(cfg_id, 0, _LM_H_ID).standard_normal((k_tok, hidden), dtype=np.float32)
+    return z * np.float32(3.0)
+
+
 def gen_verify(
     cfg_id: int, batch: int, k: int, vocab: int, alpha: float, stream: int = 0
 ) -> Tuple[np.ndarray, np.ndarray]:

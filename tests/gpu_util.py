@@ -98,3 +98,18 @@ def run_forward_trace(model, h_in_bits, shape):
     x = raw[:x_bytes].view(np.uint16).reshape(n_lin, k_tok, kmax)
     src = raw[src_off:src_off + n_lin * k_tok * smax * 4].view(np.float32).reshape(n_lin, k_tok, smax)
     return h_out.cpu().numpy(), x, src
+
+
+def run_lm_head(w_dev, vocab, hidden, h: np.ndarray, want_logits=True):
+    """-> (token ids int32 [k], max logit fp32 [k], logits fp32 [k][vocab] or None) through the C ABI."""
+    k_tok = h.shape[0]
+    h_dev = torch.from_numpy(np.ascontiguousarray(h, dtype=np.float32)).cuda()
+    ids = torch.full((k_tok,), -7, dtype=torch.int32, device="cuda")
+    mx = torch.full((k_tok,), float("nan"), dtype=torch.float32, device="cuda")
+    logits = torch.full((k_tok, vocab), float("nan"), dtype=torch.float32, device="cuda") if want_logits else None
+    ws_bytes = sd2.lm_head_workspace_size(vocab, hidden, k_tok)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+    sd2.lm_head_argmax(w_dev.data_ptr(), vocab, hidden, h_dev.data_ptr(), k_tok, ids.data_ptr(), ws.data_ptr(), ws_bytes,
+                       stream_ptr(), max_logit_ptr=mx.data_ptr(), logits_ptr=logits.data_ptr() if want_logits else 0)
+    torch.cuda.synchronize()
+    return ids.cpu().numpy(), mx.cpu().numpy(), (logits.cpu().numpy() if want_logits else None)

@@ -102,3 +102,26 @@ def test_verify_argument_checks():
     assert e.value.status == -6
     with pytest.raises(sd2.SD2Error):
         sd2.check_token_ids_host(np.array([-1], dtype=np.int32), 100)
+
+
+def test_lm_head_argument_checks():
+    """Every rejection happens on the host, before any launch."""
+    L = sd2.lib()
+    fake = C.c_void_p(0x2000)
+    n = sd2.lm_head_workspace_size(128256, 3072, 5)
+    assert n > 0 and n % 16 == 0
+    args = lambda **kw: [kw.get("w", fake), kw.get("vocab", 1000), kw.get("hidden", 1024), kw.get("h", fake),
+                         kw.get("k", 5), kw.get("ids", fake), None, None, kw.get("ws", fake), kw.get("wsb", n), None]
+    assert L.sd2_lm_head_argmax(*args(w=None)) == -1
+    assert L.sd2_lm_head_argmax(*args(h=None)) == -1
+    assert L.sd2_lm_head_argmax(*args(ids=None)) == -1
+    assert L.sd2_lm_head_argmax(*args(ws=None)) == -1
+    assert L.sd2_lm_head_argmax(*args(vocab=0)) == -2
+    assert L.sd2_lm_head_argmax(*args(hidden=1000)) == -2      # not a multiple of 128
+    assert L.sd2_lm_head_argmax(*args(hidden=8192 + 128)) == -2
+    assert L.sd2_lm_head_argmax(*args(k=0)) == -6
+    assert L.sd2_lm_head_argmax(*args(k=65)) == -6
+    assert L.sd2_lm_head_argmax(*args(wsb=n - 1)) == -4
+    assert L.sd2_lm_head_argmax(*args(w=C.c_void_p(0x2008))) == -4  # misaligned
+    with pytest.raises(sd2.SD2Error):
+        sd2.lm_head_workspace_size(1000, 100, 5)
