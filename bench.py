@@ -43,6 +43,7 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true")
     ap.add_argument("--dense", action="store_true", help="also time the dense bf16 stack")
+    ap.add_argument("--no-lm-head", action="store_true", help="skip the separately timed LM head + greedy choice")
     ap.add_argument("--calibrate", action="store_true",
                     help="also launch three plain 256 MiB copies (reference dispatches for profiler HBM counters)")
     return ap.parse_args()
@@ -257,6 +258,45 @@ def main():
             },
         },
     }
+
+    if not args.no_lm_head:
+        # The drafter's dense LM head with the final norm and the greedy choice fused in, timed on its own
+        # (it is not part of `value`): one graph replay per call, an event pair around each.
+        vocab = shape.vocab
+        w_lm = to_dev(wl.gen_lm_head(args.config, vocab, shape.hidden))
+        lm_ws_bytes = sd2.lm_head_workspace_size(vocab, shape.hidden, k_tok)
+        lm_ws = torch.empty(lm_ws_bytes, dtype=torch.uint8, device=dev)
+        lm = {}
+        with torch.cuda.stream(stream):
+            for kt in sorted({1, k_tok}):
+                h_fin = torch.from_numpy(wl.gen_final_hidden(args.config, kt, shape.hidden)).to(dev)
+                ids = torch.empty(kt, dtype=torch.int32, device=dev)
+                call = lambda spp: sd2.lm_head_argmax(w_lm.data_ptr(), vocab, shape.hidden, h_fin.data_ptr(), kt,
+                                                      ids.data_ptr(), lm_ws.data_ptr(), lm_ws_bytes, spp)
+                call(stream.cuda_stream)
+                stream.synchronize()
+                g_lm = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g_lm, stream=stream):
+                    call(torch.cuda.current_stream().cuda_stream)
+                n_rep = 30
+                evl = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_rep)]
+                for _ in range(3):
+                    g_lm.replay()
+                for e0, e1 in evl:
+                    e0.record(stream)
+                    g_lm.replay()
+                    e1.record(stream)
+                stream.synchronize()
+                us = float(np.mean([e0.elapsed_time(e1) for e0, e1 in evl])) * 1e3
+                lm_bytes = 2 * vocab * shape.hidden + 4 * kt * shape.hidden + 8 * kt
+                lm[f"k{kt}"] = {"us": round(us, 2), "achieved_GBps": round(lm_bytes / us / 1e3, 1),
+                                "frac": round(lm_bytes / us / 1e3 / HBM_PEAK_GBS, 4), "algorithmic_bytes": lm_bytes}
+                ids_host = ids.cpu().numpy()
+                assert ids_host.min() >= 0 and ids_host.max() < vocab
+                del g_lm
+        record["lm_head"] = {"kernel": f"lm_head_kernel (dense bf16 {vocab}x{shape.hidden}, final norm + argmax fused)",
+                             "bound": "hbm", "peak": HBM_PEAK_GBS, "unit": "GB/s", **lm}
+        del w_lm
 
     if args.dense:
         dkeep, dmats = [], []

@@ -73,6 +73,12 @@ def lib():
         path = lib_path()
         if not os.path.exists(path):
             raise ImportError(f"{path} is missing: run `python -m paper_2504_08838_amd.build` (there is no CPU fallback)")
+        # One HIP runtime per process: torch ships its own copy, and streams and device pointers of one runtime
+        # mean nothing to another.  Loading torch first makes libsd2 bind the runtime torch uses.
+        try:
+            import torch  # noqa: F401
+        except ImportError:
+            pass
         L = C.CDLL(path)
         vp, i32, sz = C.c_void_p, C.c_int32, C.c_size_t
         psz = C.POINTER(C.c_size_t)

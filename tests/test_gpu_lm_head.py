@@ -123,3 +123,43 @@ def test_last_row_can_win():
     ids, mx, logits = gu.run_lm_head(gu.dev(w_bits), vocab, hidden, h, want_logits=True)
     _check(w_bits, h, ids, mx, logits, ref_ids, ref_logits)
     assert ids[0] == vocab - 1
+
+
+def test_full_size_head_eager_and_graph_replays():
+    """The 3B drafter's head (vocabulary 128256 x hidden 3072, k = 5) in the launch configuration bench.py times:
+    captured in a HIP graph on a side stream, without the logits output; and once eagerly with it."""
+    import torch
+    import paper_2504_08838_amd as sd2
+    import gpu_util as gu
+    shape = wl.CONFIGS[3]["shape"]
+    vocab, hidden, k_tok = shape.vocab, shape.hidden, 5
+    assert (vocab, hidden) == (128256, 3072)
+    w_bits = wl.gen_lm_head(3, vocab, hidden)
+    h = wl.gen_final_hidden(3, k_tok, hidden)
+    ref_ids, ref_logits = olm.lm_head_argmax(w_bits, h)
+    w_dev = gu.dev(w_bits)
+    ids, mx, logits = gu.run_lm_head(w_dev, vocab, hidden, h, want_logits=True)
+    _check(w_bits, h, ids, mx, logits, ref_ids, ref_logits)
+
+    h_dev = torch.from_numpy(h).cuda()
+    ids_dev = torch.full((k_tok,), -7, dtype=torch.int32, device="cuda")
+    mx_dev = torch.full((k_tok,), float("nan"), dtype=torch.float32, device="cuda")
+    ws_bytes = sd2.lm_head_workspace_size(vocab, hidden, k_tok)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+    stream = torch.cuda.Stream()  # default priority
+    with torch.cuda.stream(stream):
+        call = lambda s: sd2.lm_head_argmax(w_dev.data_ptr(), vocab, hidden, h_dev.data_ptr(), k_tok, ids_dev.data_ptr(),
+                                            ws.data_ptr(), ws_bytes, s, max_logit_ptr=mx_dev.data_ptr())
+        call(stream.cuda_stream)  # loads the kernels before the capture
+        stream.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=stream):
+            call(torch.cuda.current_stream().cuda_stream)
+        for _ in range(3):
+            ids_dev.fill_(-7)
+            mx_dev.fill_(float("nan"))
+            ws.fill_(0xFF)  # the workspace carries nothing from call to call
+            graph.replay()
+            torch.cuda.synchronize()
+            assert np.array_equal(ids_dev.cpu().numpy(), ids)
+            assert np.array_equal(mx_dev.cpu().numpy(), mx)
