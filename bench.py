@@ -26,8 +26,9 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 # HBM bytes per launch of the forward kernel (and of the gate+up sparse linear) from rocprofv3 --pmc
 # FETCH_SIZE / WRITE_SIZE runs, scaled by the plain copy kernel of --calibrate; None until measured.
-MEASURED_TRAFFIC_BYTES = 3447977452
-MEASURED_LINEAR_TRAFFIC_BYTES = 63313736
+MEASURED_TRAFFIC_BYTES = 3446944946
+MEASURED_LINEAR_TRAFFIC_BYTES = 63320629
+MEASURED_LM_HEAD_TRAFFIC_BYTES = 788437870
 CALIBRATION_BYTES = 256 << 20  # size of the plain copies launched by --calibrate
 
 
@@ -295,7 +296,8 @@ def main():
                 assert ids_host.min() >= 0 and ids_host.max() < vocab
                 del g_lm
         record["lm_head"] = {"kernel": f"lm_head_kernel (dense bf16 {vocab}x{shape.hidden}, final norm + argmax fused)",
-                             "bound": "hbm", "peak": HBM_PEAK_GBS, "unit": "GB/s", **lm}
+                             "bound": "hbm", "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                             "traffic": MEASURED_LM_HEAD_TRAFFIC_BYTES if (args.config == 3) else None, **lm}
         del w_lm
 
     if args.dense:

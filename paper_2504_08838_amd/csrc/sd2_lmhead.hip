@@ -73,7 +73,10 @@ __global__ __launch_bounds__(64 * kLmWaves) void lm_head_kernel(const uint16_t* 
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int r = 4 * i + g;
-            const int row = min(strip * 16 + r, vocab - 1);
+            // rows past the end of a ragged last strip read the row 16 above instead (results unused): valid, and
+            // distinct from every other address this wavefront has in flight
+            int row = strip * 16 + r;
+            if (row >= vocab) row = max(row - 16, 0);
             const uint16_t* src = w + (size_t)row * hidden + colchunk * kLmChunkCols + ((n ^ r) * 8);
             __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
                                              (__attribute__((address_space(3))) void*)(dst + i * 256), 16, 0, 0);
