@@ -54,6 +54,7 @@ enum sd2_status {
 #define SD2_FORMAT_AUTO 0
 #define SD2_FORMAT_BITMASK 1
 #define SD2_FORMAT_INDEX16 2 /* reserved: returns SD2_ERR_UNSUPPORTED */
+#define SD2_FORMAT_NM24 3    /* 2:4 semi-structured: at most two non-zeros in every aligned group of four columns */
 
 /* Static, never freed. */
 const char* sd2_strerror(int status);
@@ -63,7 +64,12 @@ int sd2_version(void);
  * The sparse representation: Sec. 1 and Sec. 3.3 require one but do not define it.
  * The byte layout is specified in docs/FORMAT.md (tiles of 16 rows x 256 columns,
  * one 16-bit mask per lane and 64-column step, compacted bf16 values in the order
- * a wavefront consumes them, a per-tile directory with the offsets of its 16 runs). */
+ * a wavefront consumes them, a per-tile directory with the offsets of its 16 runs).
+ * SD2_FORMAT_NM24 is the 2:4 pattern the paper evaluates next to unstructured sparsity
+ * (Sec. 3, Sec. 3.3): two bf16 values and two 2-bit column indices per group of four weights,
+ * 1.125 bytes per dense weight, laid out as the operands of the structured-sparse matrix
+ * instruction.  It must be asked for explicitly (SD2_FORMAT_AUTO never chooses it), and packing
+ * a matrix that is not 2:4 returns SD2_ERR_FORMAT. */
 
 typedef struct sd2_blob_info {
     int32_t format, n_out, k_in;
@@ -72,7 +78,7 @@ typedef struct sd2_blob_info {
     int32_t reserved0;
     uint64_t nnz;          /* non-zero weights */
     uint64_t total_bytes;  /* size of the blob */
-    uint64_t useful_bytes; /* 2*nnz + n_out*k_in/8: values plus one mask bit per position */
+    uint64_t useful_bytes; /* bitmask: 2*nnz + n_out*k_in/8 (values plus one mask bit per position); 2:4: 9*n_out*k_in/8 */
     uint64_t mask_off, val_off;
     uint32_t checksum;
     uint32_t reserved;

@@ -147,3 +147,118 @@ def unpack(blob: np.ndarray) -> np.ndarray:
     w = np.zeros((h["n_out"], h["k_in"]), dtype=np.uint16)
     w[rows, cols] = bits
     return w
+
+
+# --------------------------------------------------------------------------- format 3: 2:4 semi-structured
+# Written from the "Format 3" section of docs/FORMAT.md alone.
+
+TILE24 = 4608
+
+
+def _group_of(a: int, p: int) -> int:
+    return 8 * (a % 2) + 2 * (a // 2) + 4 * (p // 2) + (p % 2)
+
+
+def _stored_pair(nz):
+    """Columns (c0 < c1) a group stores, given the sorted list of its non-zero columns."""
+    if len(nz) > 2:
+        raise ValueError("matrix is not 2:4")
+    if len(nz) == 2:
+        return nz[0], nz[1]
+    if len(nz) == 0:
+        return 0, 1
+    return (0, 1) if nz[0] == 0 else (0, nz[0])
+
+
+def pack24(w_bits: np.ndarray) -> np.ndarray:
+    """Blob of format 3 for a 2:4 matrix (literal loops over groups vectorised over rows)."""
+    w_bits = np.ascontiguousarray(w_bits, dtype=np.uint16)
+    n_out, k_in = w_bits.shape
+    if n_out < 1 or k_in < 64 or k_in % 64:
+        raise ValueError("k_in must be a positive multiple of 64")
+    n_strips, n_slabs = _ceil_div(n_out, 16), _ceil_div(k_in, 256)
+    n_tiles = n_strips * n_slabs
+    wp = np.zeros((n_strips * 16, n_slabs * 256), dtype=np.uint16)
+    wp[:n_out, :k_in] = w_bits
+    grp = wp.reshape(n_strips * 16, n_slabs * 64, 4)
+    nzm = (grp & np.uint16(0x7FFF)) != 0
+    cnt = nzm.sum(axis=-1)
+    if (cnt > 2).any():
+        raise ValueError("matrix is not 2:4")
+    # stored columns per group from the table of the 11 admissible non-zero patterns
+    c0 = np.zeros(cnt.shape, dtype=np.int64)
+    c1 = np.ones(cnt.shape, dtype=np.int64)
+    code = (nzm * np.array([1, 2, 4, 8])).sum(axis=-1)
+    for pat in range(16):
+        nz = [c for c in range(4) if pat >> c & 1]
+        if len(nz) > 2:
+            continue
+        a, b = _stored_pair(nz)
+        sel = code == pat
+        c0[sel], c1[sel] = a, b
+    v0 = np.take_along_axis(grp, c0[..., None], axis=-1)[..., 0]
+    v1 = np.take_along_axis(grp, c1[..., None], axis=-1)[..., 0]
+    v0 = np.where((v0 & np.uint16(0x7FFF)) != 0, v0, np.uint16(0))  # a stored column that is zero holds +0
+    v1 = np.where((v1 & np.uint16(0x7FFF)) != 0, v1, np.uint16(0))
+
+    payload = np.zeros((n_tiles, TILE24), dtype=np.uint8)
+    vals = payload[:, :4096].view("<u2").reshape(n_tiles, 4, 64, 8)  # tile, q, lane, slot
+    idx = np.zeros((n_tiles, 64), dtype=np.uint64)
+    for slab in range(n_slabs):
+        for strip in range(n_strips):
+            t = slab * n_strips + strip
+            rows = slice(16 * strip, 16 * strip + 16)
+            for q in range(4):
+                for a in range(4):
+                    lanes = slice(16 * a, 16 * a + 16)  # lane = 16 a + (row mod 16)
+                    for p in range(4):
+                        g = 64 * slab + 16 * q + _group_of(a, p)
+                        vals[t, q, lanes, 2 * p] = v0[rows, g]
+                        vals[t, q, lanes, 2 * p + 1] = v1[rows, g]
+                        idx[t, lanes] |= (c0[rows, g].astype(np.uint64) << np.uint64(16 * q + 4 * p)) | (
+                            c1[rows, g].astype(np.uint64) << np.uint64(16 * q + 4 * p + 2))
+    payload[:, 4096:] = idx.astype("<u8").view(np.uint8).reshape(n_tiles, 512)
+    payload = payload.reshape(-1)
+
+    nnz_tile = cnt.reshape(n_strips, 16, n_slabs, 64).sum(axis=(1, 3))
+    nnz = int(cnt.sum())
+    total = HEADER + TILE24 * n_tiles
+    hdr = np.zeros(HEADER, dtype=np.uint8)
+    h32 = hdr.view("<u4")
+    h32[0:9] = [MAGIC, 2, 3, n_out, k_in, n_strips, n_slabs, n_tiles, int(nnz_tile.max())]
+    h64 = hdr.view("<u8")
+    h64[5] = nnz
+    h64[6] = 0
+    h64[7] = 0
+    h64[8] = HEADER
+    h64[9] = total
+    h64[10] = 9 * n_out * k_in // 8
+    h32[22] = checksum(payload)
+    return np.concatenate([hdr, payload])
+
+
+def unpack24(blob: np.ndarray) -> np.ndarray:
+    """Position by position (slow, literal)."""
+    b = np.ascontiguousarray(blob, dtype=np.uint8)
+    h = header(b)
+    if h["magic"] != MAGIC or h["version"] != 2 or h["format"] != 3:
+        raise ValueError("not a format-3 blob")
+    n_out, k_in, n_strips = h["n_out"], h["k_in"], h["n_strips"]
+    w = np.zeros((n_out, k_in), dtype=np.uint16)
+    for t in range(h["n_tiles"]):
+        slab, strip = divmod(t, n_strips)
+        tile = b[HEADER + TILE24 * t:HEADER + TILE24 * (t + 1)]
+        vals = tile[:4096].view("<u2").reshape(4, 64, 8)
+        idx = tile[4096:].view("<u8")
+        for q in range(4):
+            for lane in range(64):
+                row = 16 * strip + lane % 16
+                for v in range(8):
+                    c = (int(idx[lane]) >> (16 * q + 2 * v)) & 3
+                    col = 256 * slab + 64 * q + 4 * _group_of(lane // 16, v // 2) + c
+                    bits = int(vals[q, lane, v])
+                    if bits & 0x7FFF:
+                        if row >= n_out or col >= k_in:
+                            raise ValueError("value outside the matrix")
+                        w[row, col] = bits
+    return w

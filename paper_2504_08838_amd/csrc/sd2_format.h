@@ -15,6 +15,7 @@ constexpr int kStripRows = 16;       // rows of one MFMA tile
 constexpr int kSlabCols = 256;       // columns of one tile = 4 super-steps of 64
 constexpr int kTileMaskBytes = 512;  // 64 lanes x 4 x uint16
 constexpr int kDirEntryBytes = 48;
+constexpr int kNm24TileBytes = 4608;  // format 3: 4096 bytes of values + 512 bytes of column indices per tile
 
 struct Header {
     uint32_t magic, version, format;
@@ -39,5 +40,11 @@ inline uint64_t round_up(uint64_t a, uint64_t b) { return (a + b - 1) / b * b; }
 uint32_t checksum_words(const uint8_t* p, size_t bytes);
 int parse_header(const void* blob, size_t blob_bytes, Header* h);
 void info_from_header(const Header& h, sd2_blob_info_t* out);
+
+// format 3 (2:4 semi-structured)
+int nm24_fill_geometry(int32_t n_out, int32_t k_in, Header* h);
+int nm24_walk(const uint16_t* w, Header* h, uint8_t* out);
+int nm24_check_header(const Header* h, size_t blob_bytes);
+int nm24_decode(const void* blob, const Header& h, uint16_t* w_out);
 
 }  // namespace sd2

@@ -99,6 +99,7 @@ int parse_header(const void* blob, size_t blob_bytes, Header* h) {
     if (blob_bytes < kHeaderBytes) return SD2_ERR_BLOB;
     memcpy(h, blob, sizeof(*h));
     if (h->magic != kMagic || h->version != kVersion) return SD2_ERR_BLOB;
+    if (h->format == SD2_FORMAT_NM24) return nm24_check_header(h, blob_bytes);
     if (h->format != SD2_FORMAT_BITMASK) return SD2_ERR_FORMAT;
     Header g;
     if (h->n_out > 0x7fffffffu || h->k_in > 0x7fffffffu ||
@@ -147,6 +148,14 @@ extern "C" {
 int sd2_pack_sparse_size(const uint16_t* w, int32_t n_out, int32_t k_in, int32_t format, size_t* bytes_out) {
     if (!w || !bytes_out) return SD2_ERR_NULL;
     if (format == SD2_FORMAT_INDEX16) return SD2_ERR_UNSUPPORTED;
+    if (format == SD2_FORMAT_NM24) {
+        Header h;
+        int rc = nm24_fill_geometry(n_out, k_in, &h);
+        if (rc != SD2_OK) return rc;
+        if ((rc = nm24_walk(w, &h, nullptr)) != SD2_OK) return rc;
+        *bytes_out = (size_t)h.total_bytes;
+        return SD2_OK;
+    }
     if (format != SD2_FORMAT_AUTO && format != SD2_FORMAT_BITMASK) return SD2_ERR_FORMAT;
     Header h;
     int rc = fill_geometry(n_out, k_in, &h);
@@ -160,6 +169,20 @@ int sd2_pack_sparse(const uint16_t* w, int32_t n_out, int32_t k_in, int32_t form
                     size_t* bytes_written) {
     if (!w || !blob) return SD2_ERR_NULL;
     if (format == SD2_FORMAT_INDEX16) return SD2_ERR_UNSUPPORTED;
+    if (format == SD2_FORMAT_NM24) {
+        Header h;
+        int rc = nm24_fill_geometry(n_out, k_in, &h);
+        if (rc != SD2_OK) return rc;
+        if ((rc = nm24_walk(w, &h, nullptr)) != SD2_OK) return rc;
+        if (blob_bytes < h.total_bytes) return SD2_ERR_BUFFER;
+        uint8_t* out = static_cast<uint8_t*>(blob);
+        memset(out, 0, (size_t)h.total_bytes);
+        nm24_walk(w, &h, out);
+        h.checksum = checksum_words(out + kHeaderBytes, (size_t)(h.total_bytes - kHeaderBytes));
+        memcpy(out, &h, sizeof(h));
+        if (bytes_written) *bytes_written = (size_t)h.total_bytes;
+        return SD2_OK;
+    }
     if (format != SD2_FORMAT_AUTO && format != SD2_FORMAT_BITMASK) return SD2_ERR_FORMAT;
     Header h;
     int rc = fill_geometry(n_out, k_in, &h);
@@ -192,6 +215,7 @@ int sd2_blob_validate(const void* blob, size_t blob_bytes) {
     const uint8_t* p = static_cast<const uint8_t*>(blob);
     if (checksum_words(p + kHeaderBytes, (size_t)(h.total_bytes - kHeaderBytes)) != h.checksum)
         return SD2_ERR_BLOB;
+    if (h.format == SD2_FORMAT_NM24) return nm24_decode(blob, h, nullptr);
     const DirEntry* dir = reinterpret_cast<const DirEntry*>(p + h.dir_off);
     const uint16_t* masks = reinterpret_cast<const uint16_t*>(p + h.mask_off);
     uint64_t next = 0, nnz = 0;
@@ -220,6 +244,7 @@ int sd2_unpack_sparse(const void* blob, size_t blob_bytes, uint16_t* w_out, int3
     Header h;
     parse_header(blob, blob_bytes, &h);
     if ((uint32_t)n_out != h.n_out || (uint32_t)k_in != h.k_in) return SD2_ERR_SHAPE;
+    if (h.format == SD2_FORMAT_NM24) return nm24_decode(blob, h, w_out);
     const uint8_t* p = static_cast<const uint8_t*>(blob);
     const DirEntry* dir = reinterpret_cast<const DirEntry*>(p + h.dir_off);
     const uint16_t* masks = reinterpret_cast<const uint16_t*>(p + h.mask_off);

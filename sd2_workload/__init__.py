@@ -20,6 +20,7 @@ from .gen import (  # noqa: F401
     n_keep,
     magnitude_mask_per_row,
     magnitude_mask_global,
+    mask_2of4,
     gen_weight,
     gen_weight_dense,
     gen_x,

@@ -145,6 +145,19 @@ def magnitude_mask_global(w_bits: np.ndarray, sparsity_pct: int) -> np.ndarray:
     return (gt | (eq & (rank <= need))).reshape(n, k)
 
 
+def mask_2of4(w_bits: np.ndarray) -> np.ndarray:
+    """Boolean mask keeping, in every aligned group of four columns, the two largest |w| (ties: lowest column)."""
+    n, k = w_bits.shape
+    if k % 4:
+        raise ValueError("k_in must be a multiple of 4")
+    mag = (w_bits & np.uint16(0x7FFF)).astype(np.int32).reshape(n, k // 4, 4)  # bf16 magnitudes order like their bits
+    # stable descending sort inside the group: the lowest column wins among equals
+    order = np.argsort(-mag, axis=-1, kind="stable")
+    keep = np.zeros_like(mag, dtype=bool)
+    np.put_along_axis(keep, order[..., :2], True, axis=-1)
+    return keep.reshape(n, k)
+
+
 # --------------------------------------------------------------------------- tensors
 
 
@@ -174,8 +187,12 @@ def gen_weight(
         m = magnitude_mask_per_row(w, sparsity_pct)
     elif pattern == "global":
         m = magnitude_mask_global(w, sparsity_pct)
+    elif pattern == "2:4":
+        if sparsity_pct != 50:
+            raise ValueError("the 2:4 pattern is 50 % sparse")
+        m = mask_2of4(w)
     else:
-        raise ValueError("pattern must be 'row' or 'global'")
+        raise ValueError("pattern must be 'row', 'global' or '2:4'")
     w = np.where(m, w, np.uint16(0)).astype(np.uint16)
     # the sparsity pattern is the nonzero pattern: a kept +-0 would silently vanish
     if np.count_nonzero(w & np.uint16(0x7FFF)) != int(m.sum()):
