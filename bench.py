@@ -45,6 +45,8 @@ def parse_args():
     ap.add_argument("--no-graph", action="store_true")
     ap.add_argument("--dense", action="store_true", help="also time the dense bf16 stack")
     ap.add_argument("--no-lm-head", action="store_true", help="skip the separately timed LM head + greedy choice")
+    ap.add_argument("--no-nm24", action="store_true", help="skip the separately timed 2:4 semi-structured gate+up linear")
+    ap.add_argument("--nm24-stack", action="store_true", help="also time the whole stack with 2:4 matrices (multi-launch chain)")
     ap.add_argument("--calibrate", action="store_true",
                     help="also launch three plain 256 MiB copies (reference dispatches for profiler HBM counters)")
     return ap.parse_args()
@@ -306,6 +308,83 @@ def main():
                              "bound": "hbm", "peak": HBM_PEAK_GBS, "unit": "GB/s",
                              "traffic": MEASURED_LM_HEAD_TRAFFIC_BYTES if (args.config == 3) else None, **lm}
         del w_lm
+
+    if not args.no_nm24:
+        # The 2:4 semi-structured variant of the largest linear (fused gate+up), timed like the unstructured kernel
+        # above: one launch per distinct matrix (8 of them, 453 MB, more than the last-level cache holds), event pairs
+        # on the launch stream.  Not part of `value`.
+        n_gu, k_gu = 2 * shape.inter, shape.hidden
+
+        def gen24(l):
+            w24 = np.concatenate([wl.gen_weight(args.config, l, p, shape.inter, shape.hidden, 50, pattern="2:4")
+                                  for p in ("gate", "up")], axis=0)
+            return sd2.pack_sparse(w24, 3)
+
+        with ThreadPoolExecutor(max_workers=workers) as ex:
+            blobs24 = list(ex.map(gen24, range(8)))
+        keep24 = [torch.from_numpy(b).to(dev) for b in blobs24]
+        mats24 = [sd2.matrix_init_sparse(b, d.data_ptr()) for b, d in zip(blobs24, keep24)]
+        y24 = torch.empty((k_tok, n_gu), dtype=torch.float32, device=dev)
+        d24 = []
+        with torch.cuda.stream(stream):
+            for rep in range(4):
+                ev24 = [torch.cuda.Event(enable_timing=True) for _ in range(2 * len(mats24))]
+                for i, m in enumerate(mats24):
+                    ev24[2 * i].record(stream)
+                    sd2.sparse_linear(m, x_act.data_ptr(), k_tok, y24.data_ptr(), 0, 0, stream.cuda_stream)
+                    ev24[2 * i + 1].record(stream)
+                stream.synchronize()
+                if rep:
+                    d24 += [ev24[2 * i].elapsed_time(ev24[2 * i + 1]) * 1e3 for i in range(len(mats24))]
+        us24 = float(np.mean(d24))
+        b24 = int(mats24[0].info.useful_bytes) + 2 * k_tok * k_gu + 4 * k_tok * n_gu
+        record["nm24_linear"] = {"kernel": f"nm24_linear_kernel (2:4 semi-structured fused gate+up, {n_gu}x{k_gu}, "
+                                           "structured-sparse matrix instruction)",
+                                 "bound": "hbm", "peak": HBM_PEAK_GBS, "unit": "GB/s", "kernel_us": round(us24, 2),
+                                 "achieved": round(b24 / us24 / 1e3, 1), "frac": round(b24 / us24 / 1e3 / HBM_PEAK_GBS, 4),
+                                 "algorithmic_bytes": b24, "traffic": None}
+        assert np.isfinite(y24.cpu().numpy()).all()
+        del keep24, mats24, blobs24
+
+    if args.nm24_stack:
+        def gen24_fused(job):
+            l, projs = job
+            return sd2.pack_sparse(np.concatenate([wl.gen_weight(args.config, l, p, table_nk[p][0], table_nk[p][1], 50,
+                                                                 pattern="2:4") for p in projs], axis=0), 3)
+
+        table_nk = {p: (n, k) for p, n, k in wl.layer_matrix_shapes(shape)}
+        jobs = [(l, g) for l in range(layers) for g in (("q", "k", "v"), ("o",), ("gate", "up"), ("down",))]
+        with ThreadPoolExecutor(max_workers=workers) as ex:
+            sblobs = list(ex.map(gen24_fused, jobs))
+        skeep = [torch.from_numpy(b).to(dev) for b in sblobs]
+        smats = [sd2.matrix_init_sparse(b, d.data_ptr()) for b, d in zip(sblobs, skeep)]
+        smodel = sd2.model_create(ms, smats, keep=skeep)
+        sws_bytes = sd2.drafter_workspace_size(smodel, k_tok)
+        sws = torch.empty(sws_bytes, dtype=torch.uint8, device=dev)
+        with torch.cuda.stream(stream):
+            def sstep(spp):
+                sd2.sparse_drafter_forward(smodel, h_in.data_ptr(), k_tok, h_out.data_ptr(), sws.data_ptr(), sws_bytes, spp)
+            sstep(stream.cuda_stream)
+            stream.synchronize()
+            sgraph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(sgraph, stream=stream):
+                sstep(torch.cuda.current_stream().cuda_stream)
+            for _ in range(5):
+                sgraph.replay()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            n24 = max(args.steps // 4, 10)
+            for _ in range(n24):
+                sgraph.replay()
+            torch.cuda.synchronize()
+            s24_us = (time.perf_counter() - t0) / n24 * 1e6
+        sbytes = sum(int(m.info.useful_bytes) for m in smats)
+        record["config"]["nm24_stack_us"] = round(s24_us, 2)
+        record["config"]["nm24_stack_GBps"] = round(sbytes / s24_us / 1e3, 1)
+        assert np.isfinite(h_out.cpu().numpy()).all()
+        del sgraph
+        sd2.model_destroy(smodel)
+        del skeep, sws
 
     if args.dense:
         dkeep, dmats = [], []

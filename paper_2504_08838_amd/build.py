@@ -5,7 +5,7 @@ import subprocess
 import sys
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-SOURCES = ["csrc/sd2_pack.cpp", "csrc/sd2_pack24.cpp", "csrc/sd2_api.cpp", "csrc/sd2_kernels.hip", "csrc/sd2_mega.hip", "csrc/sd2_lmhead.hip"]
+SOURCES = ["csrc/sd2_pack.cpp", "csrc/sd2_pack24.cpp", "csrc/sd2_api.cpp", "csrc/sd2_kernels.hip", "csrc/sd2_mega.hip", "csrc/sd2_lmhead.hip", "csrc/sd2_nm24.hip"]
 LIB = os.path.join(HERE, "libsd2.so")
 
 

@@ -21,6 +21,8 @@ namespace {
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
+inline bool is_nm24(const sd2_matrix_t* m) { return m->kind == SD2_KIND_SPARSE && m->info.format == SD2_FORMAT_NM24; }
+
 int check_matrix(const sd2_matrix_t* m, int kind) {
     if (!m) return SD2_ERR_NULL;
     if (m->kind != kind) return SD2_ERR_FORMAT;
@@ -32,6 +34,8 @@ int check_matrix(const sd2_matrix_t* m, int kind) {
         i.n_slabs != (int32_t)ceil_div((uint32_t)i.k_in, kSlabCols) || (int64_t)i.n_strips * i.n_slabs != i.n_tiles)
         return SD2_ERR_FORMAT;
     if (i.max_tile_nnz < 0 || i.max_tile_nnz > kStripRows * kSlabCols) return SD2_ERR_FORMAT;
+    if (kind == SD2_KIND_SPARSE && i.format != SD2_FORMAT_BITMASK && i.format != SD2_FORMAT_NM24) return SD2_ERR_FORMAT;
+    if (is_nm24(m) && !nm24_supported(i.n_slabs)) return SD2_ERR_UNSUPPORTED;  // k_in beyond 9216
     return SD2_OK;
 }
 
@@ -55,14 +59,27 @@ MatArgs mat_args(const sd2_matrix_t* m) {
     return a;
 }
 
+// Partial results a linear leaves for the next kernel to add: one per slab, except that the 2:4 kernel adds the
+// slabs up inside the workgroup and writes final values.
+inline int n_partials(const sd2_matrix_t* m) { return is_nm24(m) ? 1 : m->info.n_slabs; }
+
 size_t partial_bytes(const sd2_matrix_t* m, int k_tok) {
-    return (size_t)m->info.n_slabs * (size_t)k_tok * (size_t)m->info.n_out * sizeof(float);
+    return (size_t)n_partials(m) * (size_t)k_tok * (size_t)m->info.n_out * sizeof(float);
 }
 
 int check_tokens(int32_t k_tok) { return (k_tok < 1 || k_tok > SD2_MAX_TOKENS) ? SD2_ERR_RANGE : SD2_OK; }
 
 hipError_t run_linear(const sd2_matrix_t* m, const uint16_t* x, int k_tok, float* out, hipStream_t s) {
     MatArgs ma = mat_args(m);
+    if (is_nm24(m)) {
+        // the structured-sparse matrix instruction takes 16 tokens; more tokens stream the matrix once per group
+        for (int t0 = 0; t0 < k_tok; t0 += 16) {
+            LinArgs la{x + (size_t)t0 * ma.k_in, std::min(16, k_tok - t0), out + (size_t)t0 * ma.n_out};
+            const hipError_t e = launch_nm24_linear(ma, la, s);
+            if (e != hipSuccess) return e;
+        }
+        return hipSuccess;
+    }
     LinArgs la{x, k_tok, out};
     return m->kind == SD2_KIND_SPARSE ? launch_sparse_linear(ma, la, s) : launch_dense_linear(ma, la, s);
 }
@@ -75,14 +92,14 @@ int linear_entry(const sd2_matrix_t* m, int kind, const uint16_t* x, int32_t k_t
     if ((rc = check_tokens(k_tok)) != SD2_OK) return rc;
     if (!aligned16(x) || !aligned16(y)) return SD2_ERR_BUFFER;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    if (m->info.n_slabs == 1) {
+    if (n_partials(m) == 1) {
         return run_linear(m, x, k_tok, y, s) == hipSuccess ? SD2_OK : SD2_ERR_HIP;
     }
     if (!ws) return SD2_ERR_NULL;
     if (!aligned16(ws) || ws_bytes < partial_bytes(m, k_tok)) return SD2_ERR_BUFFER;
     float* part = static_cast<float*>(ws);
     if (run_linear(m, x, k_tok, part, s) != hipSuccess) return SD2_ERR_HIP;
-    if (launch_reduce_partials(part, m->info.n_slabs, (size_t)k_tok * m->info.n_out, y, s) != hipSuccess)
+    if (launch_reduce_partials(part, n_partials(m), (size_t)k_tok * m->info.n_out, y, s) != hipSuccess)
         return SD2_ERR_HIP;
     return SD2_OK;
 }
@@ -129,7 +146,7 @@ bool plan_mega_path(const sd2_model* md, int k_tok, MegaGeo (&geo)[4]) {
     for (size_t i = 0; i < md->mats.size(); ++i) {
         const sd2_matrix_t& m = md->mats[i];
         const sd2_matrix_t& ref = md->mats[i % 4];
-        if (m.kind != SD2_KIND_SPARSE) return false;
+        if (m.kind != SD2_KIND_SPARSE || m.info.format != SD2_FORMAT_BITMASK) return false;
         if (m.info.mask_off != ref.info.mask_off || m.info.val_off != ref.info.val_off) return false;
         max_nnz = std::max(max_nnz, m.info.max_tile_nnz);
     }
@@ -197,7 +214,7 @@ int sd2_linear_workspace_size(const sd2_matrix_t* m, int32_t k_tok, size_t* byte
     if (m->kind != SD2_KIND_SPARSE && m->kind != SD2_KIND_DENSE) return SD2_ERR_FORMAT;
     int rc = check_tokens(k_tok);
     if (rc != SD2_OK) return rc;
-    *bytes_out = m->info.n_slabs > 1 ? partial_bytes(m, k_tok) : 0;
+    *bytes_out = n_partials(m) > 1 ? partial_bytes(m, k_tok) : 0;
     return SD2_OK;
 }
 
@@ -253,10 +270,10 @@ int sd2_sparse_mlp_forward(const sd2_matrix_t* gu, const sd2_matrix_t* dn, const
     uint16_t* act = static_cast<uint16_t*>(ws);
     float* part = reinterpret_cast<float*>(static_cast<uint8_t*>(ws) + align256((size_t)k_tok * inter * sizeof(uint16_t)));
     if (run_linear(gu, x, k_tok, part, s) != hipSuccess) return SD2_ERR_HIP;
-    if (launch_silu_mul(part, gu->info.n_slabs, k_tok, inter, act, s) != hipSuccess) return SD2_ERR_HIP;
-    if (dn->info.n_slabs == 1) return run_linear(dn, act, k_tok, y, s) == hipSuccess ? SD2_OK : SD2_ERR_HIP;
+    if (launch_silu_mul(part, n_partials(gu), k_tok, inter, act, s) != hipSuccess) return SD2_ERR_HIP;
+    if (n_partials(dn) == 1) return run_linear(dn, act, k_tok, y, s) == hipSuccess ? SD2_OK : SD2_ERR_HIP;
     if (run_linear(dn, act, k_tok, part, s) != hipSuccess) return SD2_ERR_HIP;
-    if (launch_reduce_partials(part, dn->info.n_slabs, (size_t)k_tok * dn->info.n_out, y, s) != hipSuccess)
+    if (launch_reduce_partials(part, n_partials(dn), (size_t)k_tok * dn->info.n_out, y, s) != hipSuccess)
         return SD2_ERR_HIP;
     return SD2_OK;
 }
@@ -413,17 +430,17 @@ static int forward_impl(const sd2_model_t* md, const uint16_t* h_in, int32_t k_t
         const sd2_matrix_t* dn = &md->mats[4 * l + 3];
         SD2_TRY(record(4 * l + 0, h, nullptr, 0, sh.hidden, sh.hidden));
         SD2_TRY(run_linear(qkv, act, k_tok, part, s));
-        SD2_TRY(launch_inflight_attention(part, qkv->info.n_slabs, k_tok, sh.q_out, sh.kv_out, sh.n_heads, sh.n_kv,
+        SD2_TRY(launch_inflight_attention(part, n_partials(qkv), k_tok, sh.q_out, sh.kv_out, sh.n_heads, sh.n_kv,
                                           sh.head_dim, act, s));
-        SD2_TRY(record(4 * l + 1, nullptr, part, qkv->info.n_slabs, sh.q_out + 2 * sh.kv_out, sh.q_out));
+        SD2_TRY(record(4 * l + 1, nullptr, part, n_partials(qkv), sh.q_out + 2 * sh.kv_out, sh.q_out));
         SD2_TRY(run_linear(o, act, k_tok, part, s));
-        SD2_TRY(launch_residual_rmsnorm(h, nullptr, part, o->info.n_slabs, k_tok, sh.hidden, act, ssq, s));
+        SD2_TRY(launch_residual_rmsnorm(h, nullptr, part, n_partials(o), k_tok, sh.hidden, act, ssq, s));
         SD2_TRY(record(4 * l + 2, h, nullptr, 0, sh.hidden, sh.hidden));
         SD2_TRY(run_linear(gu, act, k_tok, part, s));
-        SD2_TRY(launch_silu_mul(part, gu->info.n_slabs, k_tok, sh.inter, act, s));
-        SD2_TRY(record(4 * l + 3, nullptr, part, gu->info.n_slabs, 2 * sh.inter, sh.inter));
+        SD2_TRY(launch_silu_mul(part, n_partials(gu), k_tok, sh.inter, act, s));
+        SD2_TRY(record(4 * l + 3, nullptr, part, n_partials(gu), 2 * sh.inter, sh.inter));
         SD2_TRY(run_linear(dn, act, k_tok, part, s));
-        SD2_TRY(launch_residual_rmsnorm(h, nullptr, part, dn->info.n_slabs, k_tok, sh.hidden,
+        SD2_TRY(launch_residual_rmsnorm(h, nullptr, part, n_partials(dn), k_tok, sh.hidden,
                                         l + 1 < sh.layers ? act : nullptr, ssq, s));
     }
 #undef SD2_TRY

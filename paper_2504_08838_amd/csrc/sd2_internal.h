@@ -106,6 +106,10 @@ bool mega_plan(MegaGeo (&geo)[4], int layers, int hidden, int head_dim, int k_to
 hipError_t launch_mega_forward(const MegaArgs& a, const uint16_t* h_in, void* zero_base, size_t zero_bytes, bool probe,
                                hipStream_t s);
 
+// ---- 2:4 semi-structured linear (blob format 3): final y for tokens [0, k_tok), k_tok <= 16; m.dir = first tile
+bool nm24_supported(int n_slabs);
+hipError_t launch_nm24_linear(const MatArgs& m, const LinArgs& a, hipStream_t s);
+
 // ---- LM head with greedy choice: tokens [0, k_tok), k_tok <= 16, hidden a multiple of 128 and <= 8192.
 // part_ws: kLmMaxWorkgroups * 16 candidates of 8 bytes.  max_logit and logits ([k_tok][vocab]) may be null.
 constexpr int kLmMaxWorkgroups = 1024;

@@ -20,8 +20,8 @@ def stream_ptr() -> int:
 
 
 class SparseMat:
-    def __init__(self, w_bits):
-        self.blob = sd2.pack_sparse(w_bits, 1)
+    def __init__(self, w_bits, fmt=1):
+        self.blob = sd2.pack_sparse(w_bits, fmt)
         self.blob_dev = dev(self.blob)
         self.m = sd2.matrix_init_sparse(self.blob, self.blob_dev.data_ptr())
         self.n_out, self.k_in = w_bits.shape
@@ -46,7 +46,7 @@ def run_linear(mat, x_bits, sparse=True) -> np.ndarray:
     return y.cpu().numpy()
 
 
-def build_model(shape, weight_bits, sparse=True, n_layers=None):
+def build_model(shape, weight_bits, sparse=True, n_layers=None, fmt=1):
     """shape: sd2_workload.StackShape-like; weight_bits(layer, proj) -> bf16 bits.  Returns (Model, keep-alive list)."""
     layers = shape.layers if n_layers is None else n_layers
     mats, keep = [], []
@@ -58,7 +58,7 @@ def build_model(shape, weight_bits, sparse=True, n_layers=None):
             weight_bits(l, "down"),
         ]
         for w in fused:
-            mat = SparseMat(w) if sparse else DenseMat(w)
+            mat = SparseMat(w, fmt) if sparse else DenseMat(w)
             keep.append(mat)
             mats.append(mat.m)
     ms = sd2.ModelShape(layers, shape.hidden, shape.q_out, shape.kv_out, shape.inter, shape.n_heads, shape.n_kv,
