@@ -137,7 +137,7 @@ MegaGeo mega_geo(const sd2_matrix_t& m) {
 // The single-launch persistent kernel serves the decode regime (k_tok <= 8) of an all-sparse model
 // whose layers share one geometry; everything else runs as one launch per linear and glue step.
 // SD2_FORWARD=multi forces the latter (used by tests to cover both).
-bool plan_mega_path(const sd2_model* md, int k_tok, MegaGeo (&geo)[4]) {
+bool plan_mega_path(const sd2_model* md, int k_tok, MegaGeo (&geo)[4], bool* nm24_out = nullptr) {
     const char* force = getenv("SD2_FORWARD");
     if (force && strcmp(force, "multi") == 0) return false;
     const sd2_model_shape_t& sh = md->shape;
@@ -146,12 +146,15 @@ bool plan_mega_path(const sd2_model* md, int k_tok, MegaGeo (&geo)[4]) {
     for (size_t i = 0; i < md->mats.size(); ++i) {
         const sd2_matrix_t& m = md->mats[i];
         const sd2_matrix_t& ref = md->mats[i % 4];
-        if (m.kind != SD2_KIND_SPARSE || m.info.format != SD2_FORMAT_BITMASK) return false;
+        if (m.kind != SD2_KIND_SPARSE || m.info.format != md->mats[0].info.format) return false;  // one format throughout
+        if (m.info.format != SD2_FORMAT_BITMASK && m.info.format != SD2_FORMAT_NM24) return false;
         if (m.info.mask_off != ref.info.mask_off || m.info.val_off != ref.info.val_off) return false;
         max_nnz = std::max(max_nnz, m.info.max_tile_nnz);
     }
     for (int kd = 0; kd < 4; ++kd) geo[kd] = mega_geo(md->mats[kd]);
-    return mega_plan(geo, sh.layers, sh.hidden, sh.head_dim, k_tok, max_nnz);
+    const bool nm24 = md->mats[0].info.format == SD2_FORMAT_NM24;
+    if (nm24_out) *nm24_out = nm24;
+    return mega_plan(geo, sh.layers, sh.hidden, sh.head_dim, k_tok, max_nnz, nm24);
 }
 
 }  // namespace
@@ -355,7 +358,8 @@ static int forward_impl(const sd2_model_t* md, const uint16_t* h_in, int32_t k_t
     hipStream_t s = static_cast<hipStream_t>(stream);
     MegaArgs ma;
     memset(&ma, 0, sizeof(ma));
-    if (plan_mega_path(md, k_tok, ma.geo)) {
+    bool nm24 = false;
+    if (plan_mega_path(md, k_tok, ma.geo, &nm24)) {
         ma.layers = sh.layers;
         ma.hidden = sh.hidden;
         ma.q_out = sh.q_out;
@@ -391,9 +395,9 @@ static int forward_impl(const sd2_model_t* md, const uint16_t* h_in, int32_t k_t
             // =2: the same plus wavefront 0's split into waiting for streams and decoding
             const char* tonly = getenv("SD2_MEGA_TIMING");
             if (tonly && (tonly[0] == '1' || tonly[0] == '2')) ma.trace_x = nullptr;
-            probe = tonly && tonly[0] == '2';
+            probe = tonly && tonly[0] == '2' && !nm24;  // the wait/decode split exists for the bitmask format only
         }
-        return launch_mega_forward(ma, h_in, base, ML.hv_off, probe, s) == hipSuccess ? SD2_OK : SD2_ERR_HIP;
+        return launch_mega_forward(ma, h_in, base, ML.hv_off, probe, nm24, s) == hipSuccess ? SD2_OK : SD2_ERR_HIP;
     }
     uint16_t* act = reinterpret_cast<uint16_t*>(static_cast<uint8_t*>(ws) + L.act_off);
     float* part = reinterpret_cast<float*>(static_cast<uint8_t*>(ws) + L.part_off);

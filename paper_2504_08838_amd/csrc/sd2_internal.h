@@ -101,9 +101,9 @@ MegaLayout mega_layout(int layers, int hidden, int q_out, int kv_out, int inter,
 // workgroups of the persistent kernel on the current device (0 when it cannot run here)
 int mega_grid_size();
 // Chooses the workgroup tiling of each matrix kind; false when the persistent kernel cannot run this model here.
-bool mega_plan(MegaGeo (&geo)[4], int layers, int hidden, int head_dim, int k_tok, int max_tile_nnz);
+bool mega_plan(MegaGeo (&geo)[4], int layers, int hidden, int head_dim, int k_tok, int max_tile_nnz, bool nm24);
 // probe: timestamps only, plus wavefront 0's wait/decode split (needs a.trace_time, a.trace_x == nullptr)
-hipError_t launch_mega_forward(const MegaArgs& a, const uint16_t* h_in, void* zero_base, size_t zero_bytes, bool probe,
+hipError_t launch_mega_forward(const MegaArgs& a, const uint16_t* h_in, void* zero_base, size_t zero_bytes, bool probe, bool nm24,
                                hipStream_t s);
 
 // ---- 2:4 semi-structured linear (blob format 3): final y for tokens [0, k_tok), k_tok <= 16; m.dir = first tile

@@ -98,6 +98,7 @@ struct PhaseTiles {
 
 constexpr uint32_t kKeyFirst = 1u << 24, kKeyLast = 1u << 25, kKeyEmpty = 1u << 26;
 
+template <bool NM24>
 __device__ __forceinline__ void plan_phase(PhaseTiles& pt, KArgs ka, const uint32_t* plans, int p, int n_phases, int wave,
                                            int lane) {
     pt.t = pt.key = pt.ra = pt.rb = 0u;
@@ -127,19 +128,35 @@ __device__ __forceinline__ void plan_phase(PhaseTiles& pt, KArgs ka, const uint3
         pt.key = (uint32_t)ss | ((uint32_t)sl << 8) | ((uint32_t)u << 16) | (r == 0 ? kKeyFirst : 0u) |
                  (r == grp_slabs - 1 ? kKeyLast : 0u) | (empty ? kKeyEmpty : 0u);
         if (!empty) {
-            const uint32_t* d = reinterpret_cast<const uint32_t*>(blob + 128) + (size_t)t * 12;
             pt.t = t;
-            pt.ra = d[lane & 7];
-            pt.rb = d[8 + (lane & 3)];
+            if (!NM24) {  // the 2:4 format has no directory: tiles have one size
+                const uint32_t* d = reinterpret_cast<const uint32_t*>(blob + 128) + (size_t)t * 12;
+                pt.ra = d[lane & 7];
+                pt.rb = d[8 + (lane & 3)];
+            }
         }
     }
 }
 
 __device__ __forceinline__ uint32_t lane_word(uint32_t v, int l) { return (uint32_t)__builtin_amdgcn_readlane((int)v, l); }
 
-// Requests the value stream (straight into LDS) and the masks of tile j of a phase.
+// Requests the value stream (straight into LDS) and the masks of tile j of a phase.  A 2:4 tile is 4608 bytes in
+// the layout of the structured-sparse matrix instruction: four KiB of values, then 512 bytes of column indices.
+template <bool NM24>
 __device__ __forceinline__ void issue_phase_tile(const PhaseTiles& pt, int j, uint32_t* lds_buf, uint2& mk, int lane) {
     if (lane_word(pt.key, 8 * j) & kKeyEmpty) {  // nothing stored for it: all-zero masks expand to zeros
+        mk = make_uint2(0u, 0u);
+        return;
+    }
+    if (NM24) {
+        const u32x4* src = reinterpret_cast<const u32x4*>(pt.vals + (size_t)lane_word(pt.t, 8 * j) * 4608);
+#pragma unroll
+        for (int c = 0; c < 4; ++c)
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src + c * 64 + lane),
+                                             (__attribute__((address_space(3))) void*)(lds_buf + c * 256), 16, 0, 0);
+        if (lane < 32)
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src + 256 + lane),
+                                             (__attribute__((address_space(3))) void*)(lds_buf + 1024), 16, 0, 0);
         mk = make_uint2(0u, 0u);
         return;
     }
@@ -201,7 +218,24 @@ __device__ __forceinline__ void barrier_wait(unsigned* bar, unsigned* err, unsig
     __syncthreads();
 }
 
-template <bool TRACE, bool PROBE>
+// A 2:4 tile in registers: the sparse operands of its four matrix instructions and their column indices.
+struct Tile24 {
+    u32x4 v[4];
+    uint2 idx;
+};
+typedef __attribute__((__vector_size__(16 * sizeof(__bf16)))) __bf16 bf16x16;
+union Frag16 {
+    u32x4 q[2];
+    bf16x16 v;
+};
+
+__device__ __forceinline__ void read_tile24(Tile24& t, const uint8_t* bufb, int lane) {
+#pragma unroll
+    for (int q = 0; q < 4; ++q) t.v[q] = *reinterpret_cast<const u32x4*>(bufb + (64 * q + lane) * 16);
+    t.idx = *reinterpret_cast<const uint2*>(bufb + 4096 + 8 * lane);
+}
+
+template <bool TRACE, bool PROBE, bool NM24>
 __global__ __launch_bounds__(kMegaThreads) void mega_forward_kernel(const MegaArgs a) {
     extern __shared__ uint32_t mega_lds[];
     __shared__ uint2 lut[16];
@@ -258,9 +292,9 @@ __global__ __launch_bounds__(kMegaThreads) void mega_forward_kernel(const MegaAr
     __syncthreads();
     // this wave's tiles of the first phase; the first one's stream is requested right away
     PhaseTiles ct, nt;
-    plan_phase(ct, ka, plans, 0, n_phases, wave, lane);
+    plan_phase<NM24>(ct, ka, plans, 0, n_phases, wave, lane);
     uint2 mk_next = make_uint2(0, 0);
-    if (ct.n > 0) issue_phase_tile(ct, 0, bufs, mk_next, lane);
+    if (ct.n > 0) issue_phase_tile<NM24>(ct, 0, bufs, mk_next, lane);
     unsigned gen = 0;
     int spin_limit = a.spin_limit;
     const bool copies_residual = (tid % ncu) == cu;  // this thread's columns of the residual are copied by this workgroup
@@ -279,7 +313,7 @@ __global__ __launch_bounds__(kMegaThreads) void mega_forward_kernel(const MegaAr
         if (tt && tid == 0) tt[0] = __builtin_amdgcn_s_memrealtime();
         if (p > 0) barrier_arrive(a.bar, gen);
         // next phase's tiles: planned now so that the directory loads have the whole phase to arrive
-        plan_phase(nt, ka, plans, p + 1, n_phases, wave, lane);
+        plan_phase<NM24>(nt, ka, plans, p + 1, n_phases, wave, lane);
 
         // Waits for tile j's stream, requests the stream of the tile after it (the next one of this phase, else the
         // first one of the next phase: weights do not depend on activations) and returns what the expansion needs.
@@ -289,29 +323,44 @@ __global__ __launch_bounds__(kMegaThreads) void mega_forward_kernel(const MegaAr
             const uint8_t* bufb = reinterpret_cast<const uint8_t*>(bufs + cb * kTileDw);
             cb ^= 1;
             if (j + 1 < ct.n)
-                issue_phase_tile(ct, j + 1, bufs + cb * kTileDw, mk_next, lane);
+                issue_phase_tile<NM24>(ct, j + 1, bufs + cb * kTileDw, mk_next, lane);
             else if (nt.n > 0)
-                issue_phase_tile(nt, 0, bufs + cb * kTileDw, mk_next, lane);
-            tile_bases(ct, j, lane, base);
+                issue_phase_tile<NM24>(nt, 0, bufs + cb * kTileDw, mk_next, lane);
+            if (!NM24) tile_bases(ct, j, lane, base);
             key = lane_word(ct.key, 8 * j);
             return bufb;
         };
 
         // While the barrier settles, this wave's first tile of the phase is expanded into its eight MFMA operands.
         Frag fpre[4][2];
+        Tile24 tpre;
         const bool have_pre = ct.n > 0;
         uint32_t pre_key = 0;
         if (have_pre) {
             uint2 mk;
-            uint32_t base[8];
+            uint32_t base[8] = {0, 0, 0, 0, 0, 0, 0, 0};
             const uint8_t* bufb = stage_tile(0, mk, base, pre_key);
-            expand_tile<SD2_MEGA_STEPS>(bufb, lut, base, mk, [&](int q, const Frag& f0, const Frag& f1) {
-                fpre[q][0].q = f0.q;
-                fpre[q][1].q = f1.q;
-            });
-        } else {
+            if (NM24) {
+                if (pre_key & kKeyEmpty) {
+                    tpre.v[0] = tpre.v[1] = tpre.v[2] = tpre.v[3] = u32x4{0, 0, 0, 0};
+                    tpre.idx = make_uint2(0x44444444u, 0x44444444u);
+                } else {
+                    read_tile24(tpre, bufb, lane);
+                }
+            } else {
+                expand_tile<SD2_MEGA_STEPS>(bufb, lut, base, mk, [&](int q, const Frag& f0, const Frag& f1) {
+                    fpre[q][0].q = f0.q;
+                    fpre[q][1].q = f1.q;
+                });
+            }
+        }
+        if (NM24 || !have_pre) {
 #pragma unroll
             for (int q = 0; q < 4; ++q) fpre[q][0].q = fpre[q][1].q = u32x4{0, 0, 0, 0};  // defined in every path
+        }
+        if (!NM24 || !have_pre) {
+            tpre.v[0] = tpre.v[1] = tpre.v[2] = tpre.v[3] = u32x4{0, 0, 0, 0};
+            tpre.idx = make_uint2(0u, 0u);
         }
         if (PROBE && tt && tid == 0) tt[4] = __builtin_amdgcn_s_memrealtime();
         if (p > 0) barrier_wait(a.bar, a.err, (unsigned)ncu, gen, spin_limit);
@@ -524,13 +573,31 @@ __global__ __launch_bounds__(kMegaThreads) void mega_forward_kernel(const MegaAr
                 *reinterpret_cast<f32x4*>(red + (unit * kMegaMaxTok + n) * 16 + 4 * g) = acc0 + acc1;
             }
         };
-        if (have_pre) {
-            load_b((int)((pre_key >> 8) & 255u));
-            // two accumulators: consecutive MFMAs do not wait for each other's result
+        // 2:4: one matrix instruction per 64-column step; the dense operand of a step is the pair (b[q][0], b[q][1])
+        auto multiply24 = [&](const Tile24& t) {
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fpre[q][0].v, b[q][0].v, acc0, 0, 0, 0);
-                acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fpre[q][1].v, b[q][1].v, acc1, 0, 0, 0);
+                Frag16 bq;
+                bq.q[0] = b[q][0].q;
+                bq.q[1] = b[q][1].q;
+                const int ix = (int)(q < 2 ? t.idx.x : t.idx.y);
+                if (q & 1)
+                    acc1 = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(__builtin_bit_cast(bf16x8, t.v[q]), bq.v, acc1, ix, 0, 1);
+                else
+                    acc0 = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(__builtin_bit_cast(bf16x8, t.v[q]), bq.v, acc0, ix, 0, 0);
+            }
+        };
+        if (have_pre) {
+            load_b((int)((pre_key >> 8) & 255u));
+            if (NM24) {
+                multiply24(tpre);
+            } else {
+                // two accumulators: consecutive MFMAs do not wait for each other's result
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fpre[q][0].v, b[q][0].v, acc0, 0, 0, 0);
+                    acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fpre[q][1].v, b[q][1].v, acc1, 0, 0, 0);
+                }
             }
             if (pre_key & kKeyLast) unit_done(pre_key);
         }
@@ -538,18 +605,26 @@ __global__ __launch_bounds__(kMegaThreads) void mega_forward_kernel(const MegaAr
         for (int j = 1; j < ct.n; ++j) {
             uint32_t key;
             uint2 mk;
-            uint32_t base[8];
+            uint32_t base[8] = {0, 0, 0, 0, 0, 0, 0, 0};
             const uint8_t* bufb = stage_tile(j, mk, base, key);
             load_b((int)((key >> 8) & 255u));
             if (key & kKeyFirst) acc0 = acc1 = f32x4{0.f, 0.f, 0.f, 0.f};
-            expand_tile<SD2_MEGA_STEPS>(bufb, lut, base, mk, [&](int q, const Frag& f0, const Frag& f1) {
-                acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f0.v, b[q][0].v, acc0, 0, 0, 0);
-                acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f1.v, b[q][1].v, acc1, 0, 0, 0);
-            });
+            if (NM24) {
+                if (!(key & kKeyEmpty)) {  // an empty tile adds nothing
+                    Tile24 t;
+                    read_tile24(t, bufb, lane);
+                    multiply24(t);
+                }
+            } else {
+                expand_tile<SD2_MEGA_STEPS>(bufb, lut, base, mk, [&](int q, const Frag& f0, const Frag& f1) {
+                    acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f0.v, b[q][0].v, acc0, 0, 0, 0);
+                    acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f1.v, b[q][1].v, acc1, 0, 0, 0);
+                });
+            }
             if (key & kKeyLast) unit_done(key);
         }
         // a wavefront without tiles in this phase starts the stream of its first tile of the next one here
-        if (ct.n == 0 && nt.n > 0) issue_phase_tile(nt, 0, bufs + cb * kTileDw, mk_next, lane);
+        if (ct.n == 0 && nt.n > 0) issue_phase_tile<NM24>(nt, 0, bufs + cb * kTileDw, mk_next, lane);
         ct = nt;
         if (PROBE && tt && tid == 0) tt[7] = __builtin_amdgcn_s_memrealtime();
         __syncthreads();
@@ -614,16 +689,22 @@ static int mega_grid() {
         if (hipGetDevice(&dev) == hipSuccess &&
             hipDeviceGetAttribute(&coop, hipDeviceAttributeCooperativeLaunch, dev) == hipSuccess && coop &&
             hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0 &&
-            hipFuncSetAttribute(reinterpret_cast<const void*>(mega_forward_kernel<false, false>),
+            hipFuncSetAttribute(reinterpret_cast<const void*>(mega_forward_kernel<false, false, false>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMegaLds) == hipSuccess &&
-            hipFuncSetAttribute(reinterpret_cast<const void*>(mega_forward_kernel<true, false>),
+            hipFuncSetAttribute(reinterpret_cast<const void*>(mega_forward_kernel<true, false, false>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMegaLds) == hipSuccess &&
-            hipFuncSetAttribute(reinterpret_cast<const void*>(mega_forward_kernel<false, true>),
+            hipFuncSetAttribute(reinterpret_cast<const void*>(mega_forward_kernel<false, true, false>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMegaLds) == hipSuccess &&
+            hipFuncSetAttribute(reinterpret_cast<const void*>(mega_forward_kernel<false, false, true>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMegaLds) == hipSuccess &&
+            hipFuncSetAttribute(reinterpret_cast<const void*>(mega_forward_kernel<true, false, true>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMegaLds) == hipSuccess) {
-            int per_cu = 0, per_cu_t = 0;
-            if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, mega_forward_kernel<false, false>, kMegaThreads, kMegaLds) == hipSuccess &&
-                hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu_t, mega_forward_kernel<true, false>, kMegaThreads, kMegaLds) == hipSuccess &&
-                per_cu >= 1 && per_cu_t >= 1)
+            int per_cu = 0, per_cu_t = 0, per_cu_s = 0, per_cu_st = 0;
+            if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, mega_forward_kernel<false, false, false>, kMegaThreads, kMegaLds) == hipSuccess &&
+                hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu_t, mega_forward_kernel<true, false, false>, kMegaThreads, kMegaLds) == hipSuccess &&
+                hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu_s, mega_forward_kernel<false, false, true>, kMegaThreads, kMegaLds) == hipSuccess &&
+                hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu_st, mega_forward_kernel<true, false, true>, kMegaThreads, kMegaLds) == hipSuccess &&
+                per_cu >= 1 && per_cu_t >= 1 && per_cu_s >= 1 && per_cu_st >= 1)
                 cus = n;
         }
     }
@@ -666,9 +747,10 @@ static bool plan_kind(MegaGeo& g, int ncu, int max_b) {
     return best_wave > 0;
 }
 
-bool mega_plan(MegaGeo (&geo)[4], int layers, int hidden, int head_dim, int k_tok, int max_tile_nnz) {
+bool mega_plan(MegaGeo (&geo)[4], int layers, int hidden, int head_dim, int k_tok, int max_tile_nnz, bool nm24) {
     if (layers < 1 || layers > kMegaMaxLayers || head_dim != 128 || k_tok < 1 || k_tok > kMegaMaxTok) return false;
-    if (hidden > kMegaMaxHidden || max_tile_nnz * 2 + 8 > kMegaCh * 1024) return false;
+    // a tile's stream must fit a 5 KiB buffer (a 2:4 tile always takes 4608 bytes)
+    if (hidden > kMegaMaxHidden || (!nm24 && max_tile_nnz * 2 + 8 > kMegaCh * 1024)) return false;
     const int ncu = mega_grid();
     if (ncu < 1) return false;
     for (int k = 0; k < 4; ++k)
@@ -677,7 +759,7 @@ bool mega_plan(MegaGeo (&geo)[4], int layers, int hidden, int head_dim, int k_to
 }
 
 hipError_t launch_mega_forward(const MegaArgs& a, const uint16_t* h_in, void* zero_base, size_t zero_bytes, bool probe,
-                               hipStream_t s) {
+                               bool nm24, hipStream_t s) {
     const int ncu = mega_grid();
     if (ncu < 1) return hipErrorNotSupported;
     const size_t nh = (size_t)a.k_tok * a.hidden;
@@ -687,9 +769,14 @@ hipError_t launch_mega_forward(const MegaArgs& a, const uint16_t* h_in, void* ze
     if (e != hipSuccess) return e;
     MegaArgs args = a;
     void* params[] = {&args};
-    const void* fn = a.trace_x ? reinterpret_cast<const void*>(mega_forward_kernel<true, false>)
-                    : probe ? reinterpret_cast<const void*>(mega_forward_kernel<false, true>)
-                            : reinterpret_cast<const void*>(mega_forward_kernel<false, false>);
+    const void* fn;
+    if (nm24)
+        fn = a.trace_x ? reinterpret_cast<const void*>(mega_forward_kernel<true, false, true>)
+                       : reinterpret_cast<const void*>(mega_forward_kernel<false, false, true>);
+    else
+        fn = a.trace_x ? reinterpret_cast<const void*>(mega_forward_kernel<true, false, false>)
+             : probe   ? reinterpret_cast<const void*>(mega_forward_kernel<false, true, false>)
+                       : reinterpret_cast<const void*>(mega_forward_kernel<false, false, false>);
     return hipLaunchCooperativeKernel(fn, dim3((unsigned)ncu), dim3(kMegaThreads), params, kMegaLds, s);
 }
 

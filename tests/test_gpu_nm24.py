@@ -89,21 +89,54 @@ def test_run_to_run_determinism():
     assert np.array_equal(_run(w, x), _run(w, x))  # fixed summation order, no atomics
 
 
-def test_stack_of_2of4_linears_end_to_end():
-    """The multi-launch chain with every decoder linear in format 3 (two layers of a reduced 3B-like shape)."""
-    import gpu_util as gu
-    shape = SimpleNamespace(layers=2, hidden=1024, q_out=1024, kv_out=256, inter=2048, n_heads=8, n_kv=2, head_dim=128)
+@pytest.fixture(params=["single-launch", "multi-launch"])
+def forward_path(request, monkeypatch):
+    """Both forwards: the persistent kernel (its 2:4 variant) and the chain of one launch per linear and glue step."""
+    if request.param == "multi-launch":
+        monkeypatch.setenv("SD2_FORWARD", "multi")
+    else:
+        monkeypatch.delenv("SD2_FORWARD", raising=False)
+    return request.param
+
+
+def _stack24(shape, seed):
     table = {p: (n, k) for p, n, k in wl.layer_matrix_shapes(shape)}
     cache = {}
 
     def get(layer, proj):
         if (layer, proj) not in cache:
-            cache[(layer, proj)] = wl.gen_weight(54, layer, proj, table[proj][0], table[proj][1], 50, pattern="2:4")
+            cache[(layer, proj)] = wl.gen_weight(seed, layer, proj, table[proj][0], table[proj][1], 50, pattern="2:4")
         return cache[(layer, proj)]
 
-    h_in = wl.gen_x(54, 0, "q", 5, shape.hidden)
+    return get
+
+
+@pytest.mark.parametrize("k_tok", [1, 5, 8])
+def test_stack_of_2of4_linears_end_to_end(k_tok, forward_path):
+    """Every decoder linear in format 3 (two layers of a reduced 3B-like shape)."""
+    import gpu_util as gu
+    shape = SimpleNamespace(layers=2, hidden=1024, q_out=1024, kv_out=256, inter=2048, n_heads=8, n_kv=2, head_dim=128)
+    get = _stack24(shape, 54)
+    h_in = wl.gen_x(54, 0, "q", k_tok, shape.hidden)
     ref = os_.drafter_forward(shape, get, h_in)
     model = gu.build_model(shape, get, sparse=True, fmt=NM24)
     out = gu.run_forward(model, h_in, shape.hidden)
     assert np.isfinite(out).all()
-    assert ol.rel_l2(out, ref) <= 5e-3  # end to end over rounding points; each linear is inside 1e-3 (cases above)
+    assert ol.rel_l2(out, ref) <= 5e-3  # end to end over rounding points; each linear is inside 1e-3 (below)
+
+
+@pytest.mark.parametrize("which", ["small-3-layers", "llama3b-2-layers"])
+def test_stack_of_2of4_linears_link_by_link(which, forward_path):
+    """Every linear and glue step against the oracle on the GPU's own recorded inputs (bar 1e-3 per linear)."""
+    import gpu_util as gu
+    from test_gpu_stack import _verify_steps
+    if which == "small-3-layers":
+        shape = SimpleNamespace(layers=3, hidden=768, q_out=768, kv_out=256, inter=1536, n_heads=6, n_kv=2, head_dim=128)
+    else:
+        shape = SimpleNamespace(**{**wl.CONFIGS[3]["shape"].__dict__, "layers": 2})
+    get = _stack24(shape, 55)
+    h_in = wl.gen_x(55, 0, "q", 5, shape.hidden)
+    model = gu.build_model(shape, get, sparse=True, fmt=NM24)
+    h_out, x, src = gu.run_forward_trace(model, h_in, shape)
+    assert np.isfinite(h_out).all()
+    _verify_steps(shape, get, h_in, h_out, x, src)
