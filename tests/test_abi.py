@@ -125,3 +125,18 @@ def test_lm_head_argument_checks():
     assert L.sd2_lm_head_argmax(*args(w=C.c_void_p(0x2008))) == -4  # misaligned
     with pytest.raises(sd2.SD2Error):
         sd2.lm_head_workspace_size(1000, 100, 5)
+
+
+def test_format_3_descriptors():
+    """A 2:4 blob gives a sparse descriptor; a width the 2:4 kernel cannot split over its wavefronts is refused."""
+    import sd2_workload as wl
+    w = wl.gen_weight(71, 0, "q", 32, 512, 50, pattern="2:4")
+    blob = sd2.pack_sparse(w, 3)
+    m = sd2.matrix_init_sparse(blob, 0x10000)
+    assert m.info.format == 3 and m.info.n_slabs == 2 and m.info.total_bytes == 128 + 4608 * m.info.n_tiles
+    assert sd2.linear_workspace_size(m, 5) == 0  # the 2:4 kernel writes final values: no split-K partials
+    L = sd2.lib()
+    fake = C.c_void_p(0x2000)
+    wide = wl.gen_weight(71, 0, "q", 16, 9216 + 256, 50, pattern="2:4")  # 37 slabs
+    mw = sd2.matrix_init_sparse(sd2.pack_sparse(wide, 3), 0x10000)
+    assert L.sd2_sparse_linear(C.byref(mw), fake, 5, fake, None, 0, None) == -8
