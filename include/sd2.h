@@ -142,7 +142,8 @@ int sd2_sparse_linear(const sd2_matrix_t* m, const uint16_t* x_bf16_dev, int32_t
  * what the stack's glue kernels consume; with n_slabs == 1 it equals sd2_sparse_linear. */
 int sd2_sparse_linear_partials(const sd2_matrix_t* m, const uint16_t* x_bf16_dev, int32_t k_tok,
                                float* partials_dev, size_t partials_bytes, void* stream);
-/* Hand-written dense bf16 baseline for the same shapes; `m` must be a dense descriptor. */
+/* Hand-written dense bf16 baseline for the same shapes; `m` must be a dense descriptor.  For k_in a multiple of
+ * 128 up to 9216 it streams the matrix like the LM head does and needs no workspace. */
 int sd2_dense_linear(const sd2_matrix_t* m, const uint16_t* x_bf16_dev, int32_t k_tok, float* y_dev,
                      void* workspace_dev, size_t workspace_bytes, void* stream);
 
@@ -208,7 +209,7 @@ int sd2_sparse_drafter_forward_trace(const sd2_model_t* model, const uint16_t* h
  * h_dev: device fp32 [k_tok][hidden] (what sd2_sparse_drafter_forward writes).  token_ids_dev: device
  * int32 [k_tok].  max_logit_dev (fp32 [k_tok]) and logits_dev (fp32 [k_tok][vocab], every entry
  * written) are optional: NULL skips them, and without logits_dev nothing of size vocab is written.
- * hidden: a multiple of 128, at most 8192.  vocab >= 1 (need not be a multiple of 16).  k_tok > 16
+ * hidden: a multiple of 128, at most 9216.  vocab >= 1 (need not be a multiple of 16).  k_tok > 16
  * streams the matrix once per 16 tokens.  workspace_dev: >= the reported size, 16-byte aligned,
  * contents irrelevant before and after.  A row whose logits are all NaN yields token 0.
  * Asynchronous on `stream`; all checks happen on the host before the first launch. */

@@ -60,8 +60,9 @@ MatArgs mat_args(const sd2_matrix_t* m) {
 }
 
 // Partial results a linear leaves for the next kernel to add: one per slab, except that the 2:4 kernel adds the
-// slabs up inside the workgroup and writes final values.
-inline int n_partials(const sd2_matrix_t* m) { return is_nm24(m) ? 1 : m->info.n_slabs; }
+// slabs up inside the workgroup and writes final values, and so does the streaming dense kernel.
+inline bool is_dense_stream(const sd2_matrix_t* m) { return m->kind == SD2_KIND_DENSE && dense_stream_ok(m->info.k_in); }
+inline int n_partials(const sd2_matrix_t* m) { return (is_nm24(m) || is_dense_stream(m)) ? 1 : m->info.n_slabs; }
 
 size_t partial_bytes(const sd2_matrix_t* m, int k_tok) {
     return (size_t)n_partials(m) * (size_t)k_tok * (size_t)m->info.n_out * sizeof(float);
@@ -76,6 +77,14 @@ hipError_t run_linear(const sd2_matrix_t* m, const uint16_t* x, int k_tok, float
         for (int t0 = 0; t0 < k_tok; t0 += 16) {
             LinArgs la{x + (size_t)t0 * ma.k_in, std::min(16, k_tok - t0), out + (size_t)t0 * ma.n_out};
             const hipError_t e = launch_nm24_linear(ma, la, s);
+            if (e != hipSuccess) return e;
+        }
+        return hipSuccess;
+    }
+    if (is_dense_stream(m)) {
+        for (int t0 = 0; t0 < k_tok; t0 += 16) {
+            const hipError_t e = launch_dense_stream_linear(ma.w, x + (size_t)t0 * ma.k_in, ma.n_out, ma.k_in,
+                                                            std::min(16, k_tok - t0), out + (size_t)t0 * ma.n_out, s);
             if (e != hipSuccess) return e;
         }
         return hipSuccess;

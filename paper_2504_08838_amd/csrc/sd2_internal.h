@@ -110,11 +110,16 @@ hipError_t launch_mega_forward(const MegaArgs& a, const uint16_t* h_in, void* ze
 bool nm24_supported(int n_slabs);
 hipError_t launch_nm24_linear(const MatArgs& m, const LinArgs& a, hipStream_t s);
 
-// ---- LM head with greedy choice: tokens [0, k_tok), k_tok <= 16, hidden a multiple of 128 and <= 8192.
+// ---- LM head with greedy choice: tokens [0, k_tok), k_tok <= 16, hidden a multiple of 128 and <= 9216.
 // part_ws: kLmMaxWorkgroups * 16 candidates of 8 bytes.  max_logit and logits ([k_tok][vocab]) may be null.
 constexpr int kLmMaxWorkgroups = 1024;
-constexpr int kLmMaxHidden = 8192;
+constexpr int kLmMaxHidden = 9216;
 hipError_t launch_lm_head(const uint16_t* w, const float* h, int vocab, int hidden, int k_tok, void* part_ws,
                           int32_t* token_ids, float* max_logit, float* logits, hipStream_t s);
+
+// the same streaming kernel as a plain dense linear (final y, tokens [0, k_tok), k_tok <= 16; k_in % 128 == 0, <= 9216)
+hipError_t launch_dense_stream_linear(const uint16_t* w, const uint16_t* x, int n_out, int k_in, int k_tok, float* y,
+                                      hipStream_t s);
+inline bool dense_stream_ok(int k_in) { return k_in % 128 == 0 && k_in <= kLmMaxHidden; }
 
 }  // namespace sd2

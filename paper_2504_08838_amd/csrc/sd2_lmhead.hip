@@ -43,9 +43,13 @@ __device__ __forceinline__ void lm_better(float& a, int32_t& ia, float b, int32_
     }
 }
 
-template <int CPW>
+// HEAD = true: the LM head (fp32 residual in `h`, final norm, greedy choice, logits optional).
+// HEAD = false: the same stream as a plain dense linear, y = x W^T with bf16 activations `x` and every result
+// written to `logits` ([k_tok][vocab] with vocab = n_out): the dense baseline of the sparse linears.
+template <int CPW, bool HEAD>
 __global__ __launch_bounds__(64 * kLmWaves) void lm_head_kernel(const uint16_t* __restrict__ w,
-                                                                const float* __restrict__ h, int vocab, int hidden,
+                                                                const float* __restrict__ h,
+                                                                const uint16_t* __restrict__ x, int vocab, int hidden,
                                                                 int k_tok, int n_strips, LmCand* __restrict__ part,
                                                                 float* __restrict__ logits) {
     extern __shared__ __attribute__((aligned(16))) uint32_t lm_smem[];
@@ -99,40 +103,52 @@ __global__ __launch_bounds__(64 * kLmWaves) void lm_head_kernel(const uint16_t* 
 #pragma unroll
     for (int c = 0; c < kLmRing; ++c) issue_chunk(c);
 
-    // ---- final norm of the residual stream, straight into operand B: a = bf16(h / sqrt(mean(h^2) + eps))
-    for (int t = 0; t < k_tok; ++t) {
-        float s = 0.f;
-        for (int c = tid * 4; c < hidden; c += 64 * kLmWaves * 4) {
-            const f32x4 v = *reinterpret_cast<const f32x4*>(h + (size_t)t * hidden + c);
-            s += v[0] * v[0] + v[1] * v[1] + v[2] * v[2] + v[3] * v[3];
-        }
-#pragma unroll
-        for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o);
-        if (lane == 0) misc[wave * 16 + t] = s;
-    }
-    __syncthreads();
     const int tok = min(n, k_tok - 1);  // lanes past the last token repeat it; their results are never used
-    float tot = 0.f;
-#pragma unroll
-    for (int ww = 0; ww < kLmWaves; ++ww) tot += misc[ww * 16 + tok];
-    const float inv = 1.0f / sqrtf(tot / (float)hidden + 1e-5f);
     Frag b[CPW][4];
-#pragma unroll
-    for (int cc = 0; cc < CPW; ++cc) {
-        const int colchunk = wave + kLmWaves * cc;
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            if (colchunk < n_colchunks) {
-                const float* src = h + (size_t)tok * hidden + colchunk * kLmChunkCols + (q * 4 + g) * 8;
-                const f32x4 lo = *reinterpret_cast<const f32x4*>(src);
-                const f32x4 hi = *reinterpret_cast<const f32x4*>(src + 4);
-                b[cc][q].u[0] = pack_bf16(lo[0] * inv, lo[1] * inv);
-                b[cc][q].u[1] = pack_bf16(lo[2] * inv, lo[3] * inv);
-                b[cc][q].u[2] = pack_bf16(hi[0] * inv, hi[1] * inv);
-                b[cc][q].u[3] = pack_bf16(hi[2] * inv, hi[3] * inv);
-            } else {
-                b[cc][q].q = u32x4{0u, 0u, 0u, 0u};  // column chunk past the matrix: contributes nothing
+    if (HEAD) {
+        // ---- final norm of the residual stream, straight into operand B: a = bf16(h / sqrt(mean(h^2) + eps))
+        for (int t = 0; t < k_tok; ++t) {
+            float s = 0.f;
+            for (int c = tid * 4; c < hidden; c += 64 * kLmWaves * 4) {
+                const f32x4 v = *reinterpret_cast<const f32x4*>(h + (size_t)t * hidden + c);
+                s += v[0] * v[0] + v[1] * v[1] + v[2] * v[2] + v[3] * v[3];
             }
+#pragma unroll
+            for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o);
+            if (lane == 0) misc[wave * 16 + t] = s;
+        }
+        __syncthreads();
+        float tot = 0.f;
+#pragma unroll
+        for (int ww = 0; ww < kLmWaves; ++ww) tot += misc[ww * 16 + tok];
+        const float inv = 1.0f / sqrtf(tot / (float)hidden + 1e-5f);
+#pragma unroll
+        for (int cc = 0; cc < CPW; ++cc) {
+            const int colchunk = wave + kLmWaves * cc;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                if (colchunk < n_colchunks) {
+                    const float* src = h + (size_t)tok * hidden + colchunk * kLmChunkCols + (q * 4 + g) * 8;
+                    const f32x4 lo = *reinterpret_cast<const f32x4*>(src);
+                    const f32x4 hi = *reinterpret_cast<const f32x4*>(src + 4);
+                    b[cc][q].u[0] = pack_bf16(lo[0] * inv, lo[1] * inv);
+                    b[cc][q].u[1] = pack_bf16(lo[2] * inv, lo[3] * inv);
+                    b[cc][q].u[2] = pack_bf16(hi[0] * inv, hi[1] * inv);
+                    b[cc][q].u[3] = pack_bf16(hi[2] * inv, hi[3] * inv);
+                } else {
+                    b[cc][q].q = u32x4{0u, 0u, 0u, 0u};  // column chunk past the matrix: contributes nothing
+                }
+            }
+        }
+    } else {
+#pragma unroll
+        for (int cc = 0; cc < CPW; ++cc) {
+            const int colchunk = wave + kLmWaves * cc;
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                b[cc][q].q = colchunk < n_colchunks
+                                 ? *reinterpret_cast<const u32x4*>(x + (size_t)tok * hidden + colchunk * kLmChunkCols + (q * 4 + g) * 8)
+                                 : u32x4{0u, 0u, 0u, 0u};
         }
     }
 
@@ -172,14 +188,15 @@ __global__ __launch_bounds__(64 * kLmWaves) void lm_head_kernel(const uint16_t* 
             for (int ww = 0; ww < kLmWaves; ++ww) v += mine[ww * 256 + wave * 64 + lane];
             const int row = ((int)blockIdx.x + si * (int)gridDim.x) * 16 + red_row;
             if (row < vocab && red_tok < k_tok) {
-                if (v > best) {  // rows come in increasing order: '>' keeps the lowest index among equals
+                if (HEAD && v > best) {  // rows come in increasing order: '>' keeps the lowest index among equals
                     best = v;
                     best_i = row;
                 }
-                if (logits) logits[(size_t)red_tok * vocab + row] = v;
+                if (!HEAD || logits) logits[(size_t)red_tok * vocab + row] = v;
             }
         }
     }
+    if (!HEAD) return;
     // ---- 16 threads per token hold candidates: pick one per token and workgroup
     LmCand* cand = reinterpret_cast<LmCand*>(misc + kLmWaves * 16);
     if (wave < 4) cand[wave * 64 + lane] = LmCand{best, best_i};
@@ -228,20 +245,36 @@ static int lm_cu_count() {
     return 256;
 }
 
-template <int CPW>
-static hipError_t launch_lm_t(const uint16_t* w, const float* h, int vocab, int hidden, int k_tok, int n_strips, int n_wg,
-                              LmCand* part, float* logits, hipStream_t s) {
+template <int CPW, bool HEAD>
+static hipError_t launch_lm_t(const uint16_t* w, const float* h, const uint16_t* x, int vocab, int hidden, int k_tok,
+                              int n_strips, int n_wg, LmCand* part, float* logits, hipStream_t s) {
     static bool attr_set = false;  // more than the default 64 KiB of dynamic LDS needs opting in, once per kernel
     const size_t lds = (size_t)kLmLdsDw * 4;
     if (!attr_set) {
-        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&lm_head_kernel<CPW>),
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&lm_head_kernel<CPW, HEAD>),
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL((lm_head_kernel<CPW>), dim3((unsigned)n_wg), dim3(64 * kLmWaves), lds, s, w, h, vocab, hidden, k_tok,
-                       n_strips, part, logits);
+    hipLaunchKernelGGL((lm_head_kernel<CPW, HEAD>), dim3((unsigned)n_wg), dim3(64 * kLmWaves), lds, s, w, h, x, vocab, hidden,
+                       k_tok, n_strips, part, logits);
     return hipGetLastError();
+}
+
+template <bool HEAD>
+static hipError_t launch_lm_cpw(const uint16_t* w, const float* h, const uint16_t* x, int vocab, int hidden, int k_tok,
+                                int n_strips, int n_wg, LmCand* part, float* logits, hipStream_t s) {
+    const int cpw = (hidden / kLmChunkCols + kLmWaves - 1) / kLmWaves;
+    switch (cpw) {
+        case 1: return launch_lm_t<1, HEAD>(w, h, x, vocab, hidden, k_tok, n_strips, n_wg, part, logits, s);
+        case 2: return launch_lm_t<2, HEAD>(w, h, x, vocab, hidden, k_tok, n_strips, n_wg, part, logits, s);
+        case 3: return launch_lm_t<3, HEAD>(w, h, x, vocab, hidden, k_tok, n_strips, n_wg, part, logits, s);
+        case 4: return launch_lm_t<4, HEAD>(w, h, x, vocab, hidden, k_tok, n_strips, n_wg, part, logits, s);
+        case 5: case 6: return launch_lm_t<6, HEAD>(w, h, x, vocab, hidden, k_tok, n_strips, n_wg, part, logits, s);
+        case 7: case 8: return launch_lm_t<8, HEAD>(w, h, x, vocab, hidden, k_tok, n_strips, n_wg, part, logits, s);
+        case 9: return launch_lm_t<9, HEAD>(w, h, x, vocab, hidden, k_tok, n_strips, n_wg, part, logits, s);
+        default: return hipErrorInvalidValue;
+    }
 }
 
 // tokens [0, k_tok) with k_tok <= 16; `part` holds kLmMaxWorkgroups * 16 candidates
@@ -249,21 +282,20 @@ hipError_t launch_lm_head(const uint16_t* w, const float* h, int vocab, int hidd
                           int32_t* token_ids, float* max_logit, float* logits, hipStream_t s) {
     const int n_strips = (vocab + 15) / 16;
     const int n_wg = std::min(std::min(n_strips, lm_cu_count()), kLmMaxWorkgroups);
-    const int cpw = (hidden / kLmChunkCols + kLmWaves - 1) / kLmWaves;
     LmCand* part = static_cast<LmCand*>(part_ws);
-    hipError_t e;
-    switch (cpw) {
-        case 1: e = launch_lm_t<1>(w, h, vocab, hidden, k_tok, n_strips, n_wg, part, logits, s); break;
-        case 2: e = launch_lm_t<2>(w, h, vocab, hidden, k_tok, n_strips, n_wg, part, logits, s); break;
-        case 3: e = launch_lm_t<3>(w, h, vocab, hidden, k_tok, n_strips, n_wg, part, logits, s); break;
-        case 4: e = launch_lm_t<4>(w, h, vocab, hidden, k_tok, n_strips, n_wg, part, logits, s); break;
-        case 5: case 6: e = launch_lm_t<6>(w, h, vocab, hidden, k_tok, n_strips, n_wg, part, logits, s); break;
-        case 7: case 8: e = launch_lm_t<8>(w, h, vocab, hidden, k_tok, n_strips, n_wg, part, logits, s); break;
-        default: return hipErrorInvalidValue;
-    }
+    const hipError_t e = launch_lm_cpw<true>(w, h, nullptr, vocab, hidden, k_tok, n_strips, n_wg, part, logits, s);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(lm_head_pick_kernel, dim3(1), dim3(1024), 0, s, part, n_wg, k_tok, token_ids, max_logit);
     return hipGetLastError();
+}
+
+// y[t][n] = sum_c W[n][c] x[t][c] for a dense row-major bf16 matrix and tokens [0, k_tok), k_tok <= 16; every entry
+// of y written (final values: the contraction is added up inside the workgroup).  k_in a multiple of 128, <= 9216.
+hipError_t launch_dense_stream_linear(const uint16_t* w, const uint16_t* x, int n_out, int k_in, int k_tok, float* y,
+                                      hipStream_t s) {
+    const int n_strips = (n_out + 15) / 16;
+    const int n_wg = std::min(n_strips, lm_cu_count());
+    return launch_lm_cpw<false>(w, nullptr, x, n_out, k_in, k_tok, n_strips, n_wg, nullptr, y, s);
 }
 
 }  // namespace sd2

@@ -118,7 +118,7 @@ def test_lm_head_argument_checks():
     assert L.sd2_lm_head_argmax(*args(ws=None)) == -1
     assert L.sd2_lm_head_argmax(*args(vocab=0)) == -2
     assert L.sd2_lm_head_argmax(*args(hidden=1000)) == -2      # not a multiple of 128
-    assert L.sd2_lm_head_argmax(*args(hidden=8192 + 128)) == -2
+    assert L.sd2_lm_head_argmax(*args(hidden=9216 + 128)) == -2
     assert L.sd2_lm_head_argmax(*args(k=0)) == -6
     assert L.sd2_lm_head_argmax(*args(k=65)) == -6
     assert L.sd2_lm_head_argmax(*args(wsb=n - 1)) == -4

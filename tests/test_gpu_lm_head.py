@@ -49,7 +49,8 @@ def _check(w_bits, h, ids, mx, logits, ref_ids, ref_logits):
         (777, 640, 3),      # fewer column chunks than wavefronts
         (2048, 1152, 7),    # ragged column chunks (9 over 8 wavefronts)
         (513, 4096, 2),
-        (300, 8192, 4),     # the widest supported hidden size
+        (300, 8192, 4),
+        (200, 9216, 3),     # the widest supported hidden size
         (5, 128, 1),        # less than one strip, one chunk
         (1, 256, 2),
         (3000, 1024, 17),   # more than one token block: the head is streamed per 16 tokens
