@@ -26,9 +26,10 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 # HBM bytes per launch of the forward kernel (and of the gate+up sparse linear) from rocprofv3 --pmc
 # FETCH_SIZE / WRITE_SIZE runs, scaled by the plain copy kernel of --calibrate; None until measured.
-MEASURED_TRAFFIC_BYTES = 3446944946
-MEASURED_LINEAR_TRAFFIC_BYTES = 63320629
-MEASURED_LM_HEAD_TRAFFIC_BYTES = 788437870
+MEASURED_TRAFFIC_BYTES = 3446887205
+MEASURED_LINEAR_TRAFFIC_BYTES = 63321685
+MEASURED_LM_HEAD_TRAFFIC_BYTES = 788435743
+MEASURED_NM24_TRAFFIC_BYTES = 57262551
 CALIBRATION_BYTES = 256 << 20  # size of the plain copies launched by --calibrate
 
 
@@ -342,7 +343,8 @@ def main():
                                            "structured-sparse matrix instruction)",
                                  "bound": "hbm", "peak": HBM_PEAK_GBS, "unit": "GB/s", "kernel_us": round(us24, 2),
                                  "achieved": round(b24 / us24 / 1e3, 1), "frac": round(b24 / us24 / 1e3 / HBM_PEAK_GBS, 4),
-                                 "algorithmic_bytes": b24, "traffic": None}
+                                 "algorithmic_bytes": b24,
+                                 "traffic": MEASURED_NM24_TRAFFIC_BYTES if (args.config == 3 and k_tok == 5) else None}
         assert np.isfinite(y24.cpu().numpy()).all()
         del keep24, mats24, blobs24
 
