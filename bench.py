@@ -310,6 +310,30 @@ def main():
                              "traffic": MEASURED_LM_HEAD_TRAFFIC_BYTES if (args.config == 3) else None, **lm}
         del w_lm
 
+    if not args.no_lm_head:
+        # Masked-gradient step of sparse fine-tuning on the fused gate+up shape (fp32 gradient, in place), two
+        # gradient buffers alternating so that the last-level cache cannot hold the working set.  Not part of `value`.
+        gsh = (int(gi.n_out), int(gi.k_in))
+        grads = [torch.randn(gsh, dtype=torch.float32, device=dev) for _ in range(2)]
+        dmg = []
+        with torch.cuda.stream(stream):
+            for rep in range(3):
+                evg = [torch.cuda.Event(enable_timing=True) for _ in range(2 * 8)]
+                for i in range(8):
+                    evg[2 * i].record(stream)
+                    sd2.mask_gradient(gu[i % layers], grads[i & 1].data_ptr(), False, stream.cuda_stream)
+                    evg[2 * i + 1].record(stream)
+                stream.synchronize()
+                if rep:
+                    dmg += [evg[2 * i].elapsed_time(evg[2 * i + 1]) * 1e3 for i in range(8)]
+        us_mg = float(np.mean(dmg))
+        b_mg = 2 * 4 * gsh[0] * gsh[1] + gsh[0] * gsh[1] // 8
+        record["mask_gradient"] = {"kernel": f"mask_gradient_kernel (fp32 gradient {gsh[0]}x{gsh[1]}, in place)", "bound": "hbm",
+                                   "peak": HBM_PEAK_GBS, "unit": "GB/s", "kernel_us": round(us_mg, 2),
+                                   "achieved": round(b_mg / us_mg / 1e3, 1), "frac": round(b_mg / us_mg / 1e3 / HBM_PEAK_GBS, 4),
+                                   "algorithmic_bytes": b_mg, "traffic": None}
+        del grads
+
     if not args.no_nm24:
         # The 2:4 semi-structured variant of the largest linear (fused gate+up), timed like the unstructured kernel
         # above: one launch per distinct matrix (8 of them, 453 MB, more than the last-level cache holds), event pairs

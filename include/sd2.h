@@ -230,6 +230,14 @@ int sd2_greedy_verify(const int32_t* draft_dev, const int32_t* target_dev, int32
 /* SD2_ERR_RANGE if any of the n host ids lies outside [0, vocab). */
 int sd2_check_token_ids_host(const int32_t* ids, size_t n, int32_t vocab);
 
+/* ------------------------------------------------------------------ sparse fine-tuning: masked gradient
+ * Sec. 2.4 (and the sparse fine-tuning algorithm it refers to): the mask stays fixed during fine-tuning because
+ * the gradients of pruned parameters are set to zero.  grad_dev: device, row-major [n_out][k_in], fp32
+ * (grad_is_bf16 = 0) or bf16 (1), 16-byte aligned, updated in place: entries whose weight is pruned become +0
+ * (a selection, so a NaN there vanishes), all others keep their bits.  `m`: a sparse descriptor in the bitmask
+ * format (SD2_ERR_UNSUPPORTED for the 2:4 format), whose mask section is the mask.  Asynchronous on `stream`. */
+int sd2_mask_gradient(const sd2_matrix_t* m, void* grad_dev, int32_t grad_is_bf16, void* stream);
+
 /* ------------------------------------------------------------------ measurement aid
  * Plain device-to-device copy kernel (16 bytes per lane, grid-stride): dst[0..bytes) = src[0..bytes).
  * It moves exactly `bytes` in and `bytes` out, so the HBM counters it produces under a profiler give

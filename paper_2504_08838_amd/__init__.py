@@ -39,5 +39,6 @@ from .binding import (  # noqa: F401
     check_token_ids_host,
     calibration_copy,
     lm_head_argmax,
+    mask_gradient,
     lm_head_workspace_size,
 )

@@ -109,6 +109,7 @@ def lib():
             "sd2_check_token_ids_host": (C.c_int, [vp, sz, i32]),
             "sd2_drafter_forward_status": (C.c_int, [vp, i32, vp, vp]),
             "sd2_calibration_copy": (C.c_int, [vp, vp, sz, vp]),
+            "sd2_mask_gradient": (C.c_int, [vp, vp, i32, vp]),
             "sd2_lm_head_workspace_size": (C.c_int, [i32, i32, i32, C.POINTER(sz)]),
             "sd2_lm_head_argmax": (C.c_int, [vp, i32, i32, vp, i32, vp, vp, vp, vp, sz, vp]),
         }
@@ -286,6 +287,11 @@ def lm_head_argmax(w_ptr, vocab, hidden, h_ptr, k_tok, token_ids_ptr, ws_ptr, ws
                                     C.c_void_p(token_ids_ptr), C.c_void_p(max_logit_ptr or None),
                                     C.c_void_p(logits_ptr or None), C.c_void_p(ws_ptr), ws_bytes, C.c_void_p(stream)),
            "sd2_lm_head_argmax")
+
+
+def mask_gradient(m, grad_ptr, grad_is_bf16, stream=0):
+    _check(lib().sd2_mask_gradient(C.byref(m), C.c_void_p(grad_ptr), int(grad_is_bf16), C.c_void_p(stream)),
+           "sd2_mask_gradient")
 
 
 def calibration_copy(dst_ptr, src_ptr, nbytes, stream=0):

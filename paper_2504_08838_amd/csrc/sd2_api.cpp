@@ -524,6 +524,20 @@ int sd2_calibration_copy(void* dst, const void* src, size_t bytes, void* stream)
     return SD2_OK;
 }
 
+// ---- masked gradient of sparse fine-tuning
+
+int sd2_mask_gradient(const sd2_matrix_t* m, void* grad, int32_t grad_is_bf16, void* stream) {
+    int rc = check_matrix(m, SD2_KIND_SPARSE);
+    if (rc != SD2_OK) return rc;
+    if (m->info.format != SD2_FORMAT_BITMASK) return SD2_ERR_UNSUPPORTED;
+    if (!grad) return SD2_ERR_NULL;
+    if (!aligned16(grad)) return SD2_ERR_BUFFER;
+    if (grad_is_bf16 != 0 && grad_is_bf16 != 1) return SD2_ERR_RANGE;
+    return launch_mask_gradient(mat_args(m), grad, grad_is_bf16 != 0, static_cast<hipStream_t>(stream)) == hipSuccess
+               ? SD2_OK
+               : SD2_ERR_HIP;
+}
+
 // ---- LM head with greedy choice
 
 static int lm_head_check(int32_t vocab, int32_t hidden, int32_t k_tok) {

@@ -50,6 +50,9 @@ hipError_t launch_silu_mul(const float* part, int n_splits, int k_tok, int inter
 hipError_t launch_greedy_verify(const int32_t* draft, const int32_t* target, int batch, int k,
                                 int32_t* accepted, int32_t* out_tokens, hipStream_t s);
 
+// g <- g where the blob's mask bit is set, +0 elsewhere; grad is [n_out][k_in] fp32 or bf16 (bitmask format only)
+hipError_t launch_mask_gradient(const MatArgs& m, void* grad, bool bf16, hipStream_t s);
+
 // dst[0..bytes) = src[0..bytes), bytes a multiple of 16 (traffic calibration for profiler counters)
 hipError_t launch_calibration_copy(void* dst, const void* src, size_t bytes, hipStream_t s);
 

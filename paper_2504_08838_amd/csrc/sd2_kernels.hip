@@ -11,6 +11,8 @@
 // through v_mfma_f32_16x16x32_bf16 against the activations held in registers.  The MFMA is used
 // for the multiply because the decode already leaves a dense fragment in registers and the vector
 // ALU is the scarce unit here; HBM traffic is the compacted stream and nothing else.
+#include <algorithm>
+
 #include "sd2_device.h"
 #include "sd2_internal.h"
 
@@ -251,6 +253,55 @@ hipError_t launch_dense_linear(const MatArgs& m, const LinArgs& a, hipStream_t s
     if (tg == 1) return launch_dense_t<1>(m, a, s);
     if (tg == 2) return launch_dense_t<2>(m, a, s);
     return launch_dense_t<4>(m, a, s);
+}
+
+// ------------------------------------------------------------------ masked gradient (sparse fine-tuning)
+// Sec. 2.4: the mask is fixed and the gradients of pruned parameters are set to zero.  One thread owns eight
+// consecutive columns of a row (consecutive threads: consecutive chunks, so loads and stores are full runs); its
+// eight mask bits are one byte of the blob's mask section (tile, lane, 64-column step).  Selection, not a product.
+template <typename T>
+__global__ __launch_bounds__(256) void mask_gradient_kernel(const uint16_t* __restrict__ masks, T* __restrict__ grad,
+                                                            int n_out, int k_in, int n_strips) {
+    const size_t chunks_per_row = (size_t)k_in / 8;
+    const size_t n_chunks = (size_t)n_out * chunks_per_row;
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n_chunks; i += (size_t)gridDim.x * 256) {
+        const uint32_t row = (uint32_t)(i / chunks_per_row), col = (uint32_t)(i % chunks_per_row) * 8;
+        const uint32_t tile = (col >> 8) * (uint32_t)n_strips + (row >> 4);
+        const uint32_t lane = (row & 15u) + 16u * ((col & 63u) >> 4), q = (col & 255u) >> 6;
+        const uint32_t bits = ((uint32_t)masks[(size_t)tile * 256 + lane * 4 + q] >> (col & 8u)) & 0xffu;
+        T* p = grad + (size_t)row * k_in + col;
+        if (sizeof(T) == 4) {
+            u32x4 lo = reinterpret_cast<u32x4*>(p)[0], hi = reinterpret_cast<u32x4*>(p)[1];
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+                lo[b] = (bits >> b) & 1u ? lo[b] : 0u;
+                hi[b] = (bits >> (4 + b)) & 1u ? hi[b] : 0u;
+            }
+            reinterpret_cast<u32x4*>(p)[0] = lo;
+            reinterpret_cast<u32x4*>(p)[1] = hi;
+        } else {
+            u32x4 v = *reinterpret_cast<u32x4*>(p);
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+                const uint32_t keep = ((bits >> (2 * b)) & 1u ? 0x0000ffffu : 0u) | ((bits >> (2 * b + 1)) & 1u ? 0xffff0000u : 0u);
+                v[b] &= keep;
+            }
+            *reinterpret_cast<u32x4*>(p) = v;
+        }
+    }
+}
+
+hipError_t launch_mask_gradient(const MatArgs& m, void* grad, bool bf16, hipStream_t s) {
+    const size_t n_chunks = (size_t)m.n_out * (size_t)(m.k_in / 8);
+    const unsigned grid = (unsigned)std::min<size_t>((n_chunks + 255) / 256, (size_t)device_cu_count() * 16);
+    const uint16_t* masks = reinterpret_cast<const uint16_t*>(m.masks);
+    if (bf16)
+        hipLaunchKernelGGL(mask_gradient_kernel<uint16_t>, dim3(grid), dim3(256), 0, s, masks, static_cast<uint16_t*>(grad),
+                           m.n_out, m.k_in, m.n_strips);
+    else
+        hipLaunchKernelGGL(mask_gradient_kernel<uint32_t>, dim3(grid), dim3(256), 0, s, masks, static_cast<uint32_t*>(grad),
+                           m.n_out, m.k_in, m.n_strips);
+    return hipGetLastError();
 }
 
 // ------------------------------------------------------------------ glue

@@ -140,3 +140,18 @@ def test_format_3_descriptors():
     wide = wl.gen_weight(71, 0, "q", 16, 9216 + 256, 50, pattern="2:4")  # 37 slabs
     mw = sd2.matrix_init_sparse(sd2.pack_sparse(wide, 3), 0x10000)
     assert L.sd2_sparse_linear(C.byref(mw), fake, 5, fake, None, 0, None) == -8
+
+
+def test_mask_gradient_argument_checks():
+    import sd2_workload as wl
+    L = sd2.lib()
+    fake = C.c_void_p(0x2000)
+    m = sd2.matrix_init_sparse(sd2.pack_sparse(wl.gen_weight(72, 0, "q", 32, 256, 50), 1), 0x10000)
+    assert L.sd2_mask_gradient(C.byref(m), None, 0, None) == -1
+    assert L.sd2_mask_gradient(C.byref(m), C.c_void_p(0x2004), 0, None) == -4
+    assert L.sd2_mask_gradient(C.byref(m), fake, 2, None) == -6
+    assert L.sd2_mask_gradient(None, fake, 0, None) == -1
+    m24 = sd2.matrix_init_sparse(sd2.pack_sparse(wl.gen_weight(72, 0, "q", 32, 256, 50, pattern="2:4"), 3), 0x10000)
+    assert L.sd2_mask_gradient(C.byref(m24), fake, 0, None) == -8
+    d = sd2.matrix_init_dense(0x10000, 32, 256)
+    assert L.sd2_mask_gradient(C.byref(d), fake, 0, None) == -3
