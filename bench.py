@@ -8,7 +8,10 @@ One "step" is one pass of the whole hot path over one batch of synthetic input: 
 Forward and verify are each captured once into a HIP graph and replayed K times; an event pair
 on the same stream brackets every forward inside the timed region.
 
-Prints one JSON line; see the design doc for the meaning of `roofline` and `cpu_baseline`.
+Prints one JSON line.  `roofline` describes the dominant kernel: algorithmic bytes per launch divided by the
+live event-timed duration, against the published 8 TB/s of HBM3E (`traffic` = HBM bytes per launch measured with
+profiler counters in separate runs).  `cpu_baseline` is the NumPy fp64 oracle timed on the host's cores.  The
+other keys (`lm_head`, `nm24_linear`, `mask_gradient`) time further kernels on their own; they are not in `value`.
 """
 
 import argparse

@@ -47,8 +47,8 @@ static_assert(kMaxBAtt * 256 <= kAttHeads * 128, "attention block fits the head 
 
 #define SD2_AGENT __HIP_MEMORY_SCOPE_AGENT
 
-// Activations written by other CUs: read with ordinary loads after the barrier's cache invalidate.
-__device__ __forceinline__ float aload(const float* p) { return *p; }
+// Activations cross compute units through memory: written by agent-scope stores and float atomics, read (after a
+// grid barrier, at addresses no compute unit has read before in this launch) with ordinary loads.
 __device__ __forceinline__ void astore(float* p, float v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, SD2_AGENT); }
 __device__ __forceinline__ void aadd(float* p, float v) { (void)__hip_atomic_fetch_add(p, v, __ATOMIC_RELAXED, SD2_AGENT); }
 
