@@ -230,6 +230,19 @@ int sd2_greedy_verify(const int32_t* draft_dev, const int32_t* target_dev, int32
 /* SD2_ERR_RANGE if any of the n host ids lies outside [0, vocab). */
 int sd2_check_token_ids_host(const int32_t* ids, size_t n, int32_t vocab);
 
+/* ------------------------------------------------------------------ one-shot pruning
+ * Sec. 2.3: every decoder linear is pruned one-shot to a uniform per-layer sparsity.  The paper's criterion is
+ * second-order and needs calibration data; this call prunes by weight magnitude, in place, on the device:
+ *   SD2_PRUNE_ROWS: per output row keep the k_in - (sparsity_pct * k_in) div 100 entries of largest |w|
+ *                   (k_in a multiple of 256, at most 9216; SD2_ERR_UNSUPPORTED otherwise);
+ *   SD2_PRUNE_2OF4: in every aligned group of four columns keep the two of largest |w| (sparsity_pct must be 50).
+ * Ties go to the lower column; pruned entries become +0, kept ones keep their bits.  w_bf16_dev: device, row-major
+ * [n_out][k_in] bf16, 16-byte aligned.  The result is what sd2_pack_sparse expects (after a copy to the host). */
+#define SD2_PRUNE_ROWS 0
+#define SD2_PRUNE_2OF4 1
+int sd2_prune_magnitude(uint16_t* w_bf16_dev, int32_t n_out, int32_t k_in, int32_t sparsity_pct, int32_t pattern,
+                        void* stream);
+
 /* ------------------------------------------------------------------ sparse fine-tuning: masked gradient
  * Sec. 2.4 (and the sparse fine-tuning algorithm it refers to): the mask stays fixed during fine-tuning because
  * the gradients of pruned parameters are set to zero.  grad_dev: device, row-major [n_out][k_in], fp32

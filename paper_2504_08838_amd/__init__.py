@@ -40,5 +40,6 @@ from .binding import (  # noqa: F401
     calibration_copy,
     lm_head_argmax,
     mask_gradient,
+    prune_magnitude,
     lm_head_workspace_size,
 )

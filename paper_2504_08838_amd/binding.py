@@ -110,6 +110,7 @@ def lib():
             "sd2_drafter_forward_status": (C.c_int, [vp, i32, vp, vp]),
             "sd2_calibration_copy": (C.c_int, [vp, vp, sz, vp]),
             "sd2_mask_gradient": (C.c_int, [vp, vp, i32, vp]),
+            "sd2_prune_magnitude": (C.c_int, [vp, i32, i32, i32, i32, vp]),
             "sd2_lm_head_workspace_size": (C.c_int, [i32, i32, i32, C.POINTER(sz)]),
             "sd2_lm_head_argmax": (C.c_int, [vp, i32, i32, vp, i32, vp, vp, vp, vp, sz, vp]),
         }
@@ -287,6 +288,12 @@ def lm_head_argmax(w_ptr, vocab, hidden, h_ptr, k_tok, token_ids_ptr, ws_ptr, ws
                                     C.c_void_p(token_ids_ptr), C.c_void_p(max_logit_ptr or None),
                                     C.c_void_p(logits_ptr or None), C.c_void_p(ws_ptr), ws_bytes, C.c_void_p(stream)),
            "sd2_lm_head_argmax")
+
+
+def prune_magnitude(w_ptr, n_out, k_in, sparsity_pct, pattern=0, stream=0):
+    """In place on the device; pattern 0 = per row, 1 = 2:4."""
+    _check(lib().sd2_prune_magnitude(C.c_void_p(w_ptr), n_out, k_in, sparsity_pct, pattern, C.c_void_p(stream)),
+           "sd2_prune_magnitude")
 
 
 def mask_gradient(m, grad_ptr, grad_is_bf16, stream=0):

@@ -524,6 +524,24 @@ int sd2_calibration_copy(void* dst, const void* src, size_t bytes, void* stream)
     return SD2_OK;
 }
 
+// ---- one-shot magnitude pruning
+
+int sd2_prune_magnitude(uint16_t* w, int32_t n_out, int32_t k_in, int32_t sparsity_pct, int32_t pattern, void* stream) {
+    if (!w) return SD2_ERR_NULL;
+    if (!aligned16(w)) return SD2_ERR_BUFFER;
+    if (n_out < 1 || k_in < 64 || k_in % 64 || (uint64_t)n_out * (uint64_t)k_in > (1ull << 36)) return SD2_ERR_SHAPE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (pattern == SD2_PRUNE_2OF4) {
+        if (sparsity_pct != 50) return SD2_ERR_RANGE;
+        return launch_prune_2of4(w, n_out, k_in, s) == hipSuccess ? SD2_OK : SD2_ERR_HIP;
+    }
+    if (pattern != SD2_PRUNE_ROWS) return SD2_ERR_FORMAT;
+    if (sparsity_pct < 0 || sparsity_pct > 99) return SD2_ERR_RANGE;
+    if (k_in % 256 || k_in > 9216) return SD2_ERR_UNSUPPORTED;
+    const int n_keep = k_in - (int)(((int64_t)sparsity_pct * k_in) / 100);
+    return launch_prune_rows(w, n_out, k_in, n_keep, s) == hipSuccess ? SD2_OK : SD2_ERR_HIP;
+}
+
 // ---- masked gradient of sparse fine-tuning
 
 int sd2_mask_gradient(const sd2_matrix_t* m, void* grad, int32_t grad_is_bf16, void* stream) {

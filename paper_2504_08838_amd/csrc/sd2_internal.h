@@ -50,6 +50,10 @@ hipError_t launch_silu_mul(const float* part, int n_splits, int k_tok, int inter
 hipError_t launch_greedy_verify(const int32_t* draft, const int32_t* target, int batch, int k,
                                 int32_t* accepted, int32_t* out_tokens, hipStream_t s);
 
+// one-shot magnitude pruning in place (bf16 [n_out][k_in]): rows keeps n_keep per row (k_in a multiple of 256, <= 9216)
+hipError_t launch_prune_rows(uint16_t* w, int n_out, int k_in, int n_keep, hipStream_t s);
+hipError_t launch_prune_2of4(uint16_t* w, int n_out, int k_in, hipStream_t s);
+
 // g <- g where the blob's mask bit is set, +0 elsewhere; grad is [n_out][k_in] fp32 or bf16 (bitmask format only)
 hipError_t launch_mask_gradient(const MatArgs& m, void* grad, bool bf16, hipStream_t s);
 

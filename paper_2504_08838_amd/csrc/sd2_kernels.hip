@@ -304,6 +304,116 @@ hipError_t launch_mask_gradient(const MatArgs& m, void* grad, bool bf16, hipStre
     return hipGetLastError();
 }
 
+// ------------------------------------------------------------------ one-shot magnitude pruning
+// Sec. 2.3 prunes every decoder linear one-shot to a uniform sparsity.  Criterion here: weight magnitude; ties go
+// to the lower column; pruned entries become +0.  bf16 magnitudes order like their low 15 bits, so the threshold
+// of a row is found exactly by a two-level radix select (256 + 128 bins in LDS), and the ties at the threshold are
+// resolved in column order with a prefix count: thread i owns the contiguous columns [i cpt, (i + 1) cpt).
+constexpr int kPruneThreads = 256;
+constexpr int kPruneMaxPerThread = 36;  // k_in <= 9216
+
+__global__ __launch_bounds__(kPruneThreads) void prune_rows_kernel(uint16_t* __restrict__ w, int n_out, int k_in, int n_keep) {
+    __shared__ uint32_t hist[256];
+    __shared__ uint32_t scan[kPruneThreads];
+    __shared__ uint32_t pick[2];  // chosen bin, entries strictly above it
+    const int tid = threadIdx.x;
+    const int cpt = k_in / kPruneThreads;  // k_in is a multiple of 256 here
+    for (int row = blockIdx.x; row < n_out; row += gridDim.x) {
+        uint16_t* wr = w + (size_t)row * k_in + (size_t)tid * cpt;
+        uint16_t v[kPruneMaxPerThread];
+#pragma unroll
+        for (int i = 0; i < kPruneMaxPerThread; ++i) v[i] = i < cpt ? wr[i] : (uint16_t)0;
+        uint32_t above = 0;  // entries with a magnitude above the bins examined so far
+        uint32_t prefix = 0, prefix_mask = 0;  // magnitude bits fixed so far
+        // level 0: bits 14..7 (256 bins); level 1: bits 6..0 (128 bins) among the entries of the chosen bin
+#pragma unroll 1
+        for (int level = 0; level < 2; ++level) {
+            const int shift = level ? 0 : 7;
+            const uint32_t bins = level ? 128u : 256u;
+            hist[tid] = 0;
+            __syncthreads();
+#pragma unroll
+            for (int i = 0; i < kPruneMaxPerThread; ++i)
+                if (i < cpt) {
+                    const uint32_t m = v[i] & 0x7fffu;
+                    if ((m & prefix_mask) == prefix) atomicAdd(&hist[(m >> shift) & (bins - 1)], 1u);
+                }
+            __syncthreads();
+            if (tid == 0) {  // walk down from the largest bin until n_keep entries are covered
+                uint32_t acc = above, b = bins;
+                while (b > 0 && acc + hist[b - 1] < (uint32_t)n_keep) acc += hist[--b];
+                pick[0] = b > 0 ? b - 1 : 0u;  // the bin that holds the threshold
+                pick[1] = acc;
+            }
+            __syncthreads();
+            prefix |= pick[0] << shift;
+            prefix_mask |= (bins - 1) << shift;
+            above = pick[1];
+            __syncthreads();
+        }
+        const uint32_t thr = prefix;                   // magnitude of the last kept entry
+        const uint32_t ties_kept = (uint32_t)n_keep - above;  // entries equal to it that stay, in column order
+        uint32_t mine = 0;
+#pragma unroll
+        for (int i = 0; i < kPruneMaxPerThread; ++i)
+            if (i < cpt && (uint32_t)(v[i] & 0x7fffu) == thr) ++mine;
+        scan[tid] = mine;
+        __syncthreads();
+        if (tid == 0) {  // exclusive prefix of the tie counts (256 entries: a serial pass is cheap next to the row's traffic)
+            uint32_t run = 0;
+            for (int t = 0; t < kPruneThreads; ++t) {
+                const uint32_t c = scan[t];
+                scan[t] = run;
+                run += c;
+            }
+        }
+        __syncthreads();
+        uint32_t seen = scan[tid];
+#pragma unroll
+        for (int i = 0; i < kPruneMaxPerThread; ++i)
+            if (i < cpt) {
+                const uint32_t m = v[i] & 0x7fffu;
+                bool keep = m > thr;
+                if (m == thr) keep = seen++ < ties_kept;
+                if (!keep) wr[i] = 0;
+            }
+        __syncthreads();
+    }
+}
+
+__global__ __launch_bounds__(256) void prune_2of4_kernel(uint16_t* __restrict__ w, size_t n_groups) {
+    for (size_t gidx = (size_t)blockIdx.x * 256 + threadIdx.x; gidx < n_groups; gidx += (size_t)gridDim.x * 256) {
+        uint2 raw = reinterpret_cast<uint2*>(w)[gidx];
+        uint32_t v[4] = {raw.x & 0xffffu, raw.x >> 16, raw.y & 0xffffu, raw.y >> 16};
+        // rank of each entry: how many others beat it (larger magnitude, or equal magnitude at a lower column)
+        uint32_t out[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            uint32_t rank = 0;
+#pragma unroll
+            for (int o = 0; o < 4; ++o) {
+                const uint32_t mc = v[c] & 0x7fffu, mo = v[o] & 0x7fffu;
+                rank += (o != c && (mo > mc || (mo == mc && o < c))) ? 1u : 0u;
+            }
+            out[c] = rank < 2 ? v[c] : 0u;
+        }
+        reinterpret_cast<uint2*>(w)[gidx] = make_uint2(out[0] | (out[1] << 16), out[2] | (out[3] << 16));
+    }
+}
+
+hipError_t launch_prune_rows(uint16_t* w, int n_out, int k_in, int n_keep, hipStream_t s) {
+    const unsigned grid = (unsigned)std::min(n_out, device_cu_count() * 8);
+    hipLaunchKernelGGL(prune_rows_kernel, dim3(grid), dim3(kPruneThreads), 0, s, w, n_out, k_in, n_keep);
+    return hipGetLastError();
+}
+
+hipError_t launch_prune_2of4(uint16_t* w, int n_out, int k_in, hipStream_t s) {
+    const size_t n_groups = (size_t)n_out * (size_t)(k_in / 4);
+    const unsigned grid = (unsigned)std::min<size_t>((n_groups + 255) / 256, (size_t)device_cu_count() * 16);
+    hipLaunchKernelGGL(prune_2of4_kernel, dim3(grid), dim3(256), 0, s, w, n_groups);
+    return hipGetLastError();
+}
+
 // ------------------------------------------------------------------ glue
 
 __global__ __launch_bounds__(256) void reduce_partials_kernel(const float* __restrict__ part, int n_splits, size_t split_stride,

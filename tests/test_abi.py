@@ -155,3 +155,17 @@ def test_mask_gradient_argument_checks():
     assert L.sd2_mask_gradient(C.byref(m24), fake, 0, None) == -8
     d = sd2.matrix_init_dense(0x10000, 32, 256)
     assert L.sd2_mask_gradient(C.byref(d), fake, 0, None) == -3
+
+
+def test_prune_argument_checks():
+    L = sd2.lib()
+    fake = C.c_void_p(0x2000)
+    assert L.sd2_prune_magnitude(None, 16, 256, 50, 0, None) == -1
+    assert L.sd2_prune_magnitude(C.c_void_p(0x2002), 16, 256, 50, 0, None) == -4
+    assert L.sd2_prune_magnitude(fake, 0, 256, 50, 0, None) == -2
+    assert L.sd2_prune_magnitude(fake, 16, 100, 50, 0, None) == -2
+    assert L.sd2_prune_magnitude(fake, 16, 256, 100, 0, None) == -6
+    assert L.sd2_prune_magnitude(fake, 16, 256, 60, 1, None) == -6      # 2:4 is 50 %
+    assert L.sd2_prune_magnitude(fake, 16, 320, 50, 0, None) == -8      # rows need k_in % 256 == 0
+    assert L.sd2_prune_magnitude(fake, 16, 9216 + 256, 50, 0, None) == -8
+    assert L.sd2_prune_magnitude(fake, 16, 256, 50, 7, None) == -3
