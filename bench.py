@@ -44,6 +44,8 @@ def parse_args():
     ap.add_argument("--config", type=int, default=3, help="3 = Llama-3B-shape stack (headline), 4 = Qwen-1.5B-shape")
     ap.add_argument("--sparsity", type=int, default=50)
     ap.add_argument("--k-tok", type=int, default=5)
+    ap.add_argument("--pattern", default="row", choices=["row", "global"],
+                    help="mask of the synthetic weights: per-row magnitude (headline) or one threshold per matrix (rows of unequal population)")
     ap.add_argument("--layers", type=int, default=0, help="debug: fewer layers (reported as such)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true")
@@ -56,7 +58,7 @@ def parse_args():
     return ap.parse_args()
 
 
-def build_weights(shape, cfg_id, pct, layers, workers):
+def build_weights(shape, cfg_id, pct, layers, workers, pattern="row"):
     """Per layer the four fused bf16 matrices (qkv, o, gate_up, down), generated from the seed recipe."""
     import sd2_workload as wl
 
@@ -64,7 +66,7 @@ def build_weights(shape, cfg_id, pct, layers, workers):
 
     def one(job):
         layer, projs = job
-        mats = [wl.gen_weight(cfg_id, layer, p, table[p][0], table[p][1], pct) for p in projs]
+        mats = [wl.gen_weight(cfg_id, layer, p, table[p][0], table[p][1], pct, pattern=pattern) for p in projs]
         return layer, projs, (mats[0] if len(mats) == 1 else np.concatenate(mats, axis=0))
 
     jobs = [(l, g) for l in range(layers) for g in (("q", "k", "v"), ("o",), ("gate", "up"), ("down",))]
@@ -97,7 +99,7 @@ def main():
     workers = min(16, os.cpu_count() or 8)
 
     t_setup = time.time()
-    fused = build_weights(shape, args.config, pct, layers, workers)
+    fused = build_weights(shape, args.config, pct, layers, workers, args.pattern)
     with ThreadPoolExecutor(max_workers=workers) as ex:
         blobs = list(ex.map(lambda w: sd2.pack_sparse(w, 1), fused))
     keep, mats, useful, total = [], [], 0, 0
@@ -237,6 +239,7 @@ def main():
             "workload": f"{shape.name} drafter linear stack, {layers} layers, {pct}% unstructured sparse bf16, "
                         f"k={k_tok} tokens + greedy verify batch {vcfg['batch']} k={vcfg['k']}",
             "config_id": args.config,
+            "mask_pattern": args.pattern,
             "hip_graph": use_graph,
             "forward_path": forward_path,
             "forward_us": round(fwd_us, 2),
