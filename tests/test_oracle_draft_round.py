@@ -1,0 +1,58 @@
+"""Pins for the drafting-round oracle (Eq. 1, greedy)."""
+from types import SimpleNamespace
+
+import numpy as np
+
+import sd2_workload as wl
+from oracle import draft_round as odr
+from oracle import lm_head as olm
+from oracle import stack as ostack
+
+
+def _setup(layers=1):
+    shape = SimpleNamespace(layers=layers, hidden=256, q_out=256, kv_out=128, inter=512, n_heads=2, n_kv=1, head_dim=128)
+    table = {p: (n, k) for p, n, k in wl.layer_matrix_shapes(shape)}
+    cache = {}
+
+    def get(layer, proj):
+        if (layer, proj) not in cache:
+            cache[(layer, proj)] = wl.gen_weight(77, layer, proj, table[proj][0], table[proj][1], 50)
+        return cache[(layer, proj)]
+
+    emb = wl.gen_lm_head(77, 300, shape.hidden)
+    return shape, get, emb
+
+
+def test_zero_layers_is_a_lookup_and_an_argmax():
+    """Without decoder layers step i is: embed the last token, normalise, multiply with the (tied) head."""
+    shape, get, emb = _setup(layers=0)
+    ids, logits = odr.draft_round(shape, get, emb, t_start=7, k=3)
+    cur = 7
+    for i in range(3):
+        ref_id, ref_logits = olm.lm_head_argmax(emb, wl.bf16_bits_to_f32(emb[cur:cur + 1]).astype(np.float64))
+        assert ids[i] == ref_id[0] and np.array_equal(logits[i], ref_logits[0])
+        cur = int(ids[i])
+
+
+def test_each_step_sees_the_window_so_far():
+    """Step i equals a fresh forward over [t_start, d_0..d_{i-1}] -- and, the stack being causal, the rows of the
+    earlier positions in that forward equal what the earlier steps computed (recompute = cache)."""
+    shape, get, emb = _setup(layers=2)
+    ids, logits = odr.draft_round(shape, get, emb, t_start=11, k=4)
+    window = [11] + ids[:3].tolist()
+    h_full = ostack.drafter_forward(shape, get, emb[np.asarray(window)])
+    for i in range(4):
+        h_i = ostack.drafter_forward(shape, get, emb[np.asarray(window[:i + 1])])
+        assert np.array_equal(h_i, h_full[:i + 1])          # causality: a longer window does not change earlier rows
+        tok, lg = olm.lm_head_argmax(emb, h_i[-1:])
+        assert tok[0] == ids[i] and np.array_equal(lg[0], logits[i])
+
+
+def test_teacher_forcing_feeds_the_given_ids():
+    shape, get, emb = _setup(layers=1)
+    free_ids, _ = odr.draft_round(shape, get, emb, t_start=3, k=3)
+    forced = np.array([5, 9, 2], dtype=np.int32)
+    ids, _ = odr.draft_round(shape, get, emb, t_start=3, k=3, forced=forced)
+    assert ids[0] == free_ids[0]                             # the first step sees only t_start either way
+    h = ostack.drafter_forward(shape, get, emb[np.array([3, 5, 9])])
+    assert ids[2] == olm.lm_head_argmax(emb, h[-1:])[0][0]   # the third step saw the forced ids
