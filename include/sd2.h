@@ -218,6 +218,23 @@ int sd2_lm_head_argmax(const uint16_t* w_lm_bf16_dev, int32_t vocab, int32_t hid
                        int32_t k_tok, int32_t* token_ids_dev, float* max_logit_dev, float* logits_dev,
                        void* workspace_dev, size_t workspace_bytes, void* stream);
 
+/* ------------------------------------------------------------------ drafting round
+ * One round of drafting (Sec. 2.1, Eq. 1 with greedy decoding): k tokens, each chosen from the window extended by the
+ * tokens chosen so far.  Step i embeds the window [start, d_0 .. d_{i-1}] (rows of emb_bf16_dev), runs the decoder-linear
+ * stack on its i + 1 tokens (sd2_sparse_drafter_forward; the stack is causal and attends within the call, so recomputing
+ * the window equals caching its keys and values), and gives the last position to the LM head (sd2_lm_head_argmax with
+ * the tied matrix emb_bf16_dev as the head): d_i = lowest id among the largest logits.  Everything stays on the device
+ * and is enqueued on `stream`: 3 k small launches plus k forwards, no host synchronisation, no memset nodes.
+ * emb_bf16_dev: device [vocab][hidden] bf16, 16-byte aligned (embedding and LM head: the drafters of the paper tie them).
+ * start_token_dev: device int32[1]; ids outside [0, vocab) are clamped.  draft_ids_dev: device int32[k], written in
+ * order (entry i is read again by steps i+1..).  1 <= k <= 64.  The result feeds sd2_greedy_verify as `draft`.
+ * sd2_draft_round_status waits for `stream` and returns SD2_ERR_TIMEOUT if a bounded wait of any step's forward ran out. */
+int sd2_draft_round_workspace_size(const sd2_model_t* model, int32_t vocab, int32_t k, size_t* bytes_out);
+int sd2_draft_round(const sd2_model_t* model, const uint16_t* emb_bf16_dev, int32_t vocab,
+                    const int32_t* start_token_dev, int32_t k, int32_t* draft_ids_dev, void* workspace_dev,
+                    size_t workspace_bytes, void* stream);
+int sd2_draft_round_status(const sd2_model_t* model, int32_t vocab, int32_t k, const void* workspace_dev, void* stream);
+
 /* ------------------------------------------------------------------ verification
  * Strict top-1 verification (Eq. 2): accepted_len[b] = number of leading positions
  * where draft[b][i] == target[b][i]; out_tokens[b] = those drafts, then target[b][n],

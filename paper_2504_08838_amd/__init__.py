@@ -41,5 +41,8 @@ from .binding import (  # noqa: F401
     lm_head_argmax,
     mask_gradient,
     prune_magnitude,
+    draft_round,
+    draft_round_status,
+    draft_round_workspace_size,
     lm_head_workspace_size,
 )

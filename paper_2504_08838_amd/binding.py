@@ -110,6 +110,9 @@ def lib():
             "sd2_drafter_forward_status": (C.c_int, [vp, i32, vp, vp]),
             "sd2_calibration_copy": (C.c_int, [vp, vp, sz, vp]),
             "sd2_mask_gradient": (C.c_int, [vp, vp, i32, vp]),
+            "sd2_draft_round_workspace_size": (C.c_int, [vp, i32, i32, C.POINTER(sz)]),
+            "sd2_draft_round": (C.c_int, [vp, vp, i32, vp, i32, vp, vp, sz, vp]),
+            "sd2_draft_round_status": (C.c_int, [vp, i32, i32, vp, vp]),
             "sd2_prune_magnitude": (C.c_int, [vp, i32, i32, i32, i32, vp]),
             "sd2_lm_head_workspace_size": (C.c_int, [i32, i32, i32, C.POINTER(sz)]),
             "sd2_lm_head_argmax": (C.c_int, [vp, i32, i32, vp, i32, vp, vp, vp, vp, sz, vp]),
@@ -288,6 +291,23 @@ def lm_head_argmax(w_ptr, vocab, hidden, h_ptr, k_tok, token_ids_ptr, ws_ptr, ws
                                     C.c_void_p(token_ids_ptr), C.c_void_p(max_logit_ptr or None),
                                     C.c_void_p(logits_ptr or None), C.c_void_p(ws_ptr), ws_bytes, C.c_void_p(stream)),
            "sd2_lm_head_argmax")
+
+
+def draft_round_workspace_size(model, vocab, k):
+    n = C.c_size_t(0)
+    _check(lib().sd2_draft_round_workspace_size(model.handle, vocab, k, C.byref(n)), "sd2_draft_round_workspace_size")
+    return n.value
+
+
+def draft_round(model, emb_ptr, vocab, start_token_ptr, k, draft_ids_ptr, ws_ptr, ws_bytes, stream=0):
+    _check(lib().sd2_draft_round(model.handle, C.c_void_p(emb_ptr), vocab, C.c_void_p(start_token_ptr), k,
+                                 C.c_void_p(draft_ids_ptr), C.c_void_p(ws_ptr), ws_bytes, C.c_void_p(stream)),
+           "sd2_draft_round")
+
+
+def draft_round_status(model, vocab, k, ws_ptr, stream=0):
+    _check(lib().sd2_draft_round_status(model.handle, vocab, k, C.c_void_p(ws_ptr), C.c_void_p(stream)),
+           "sd2_draft_round_status")
 
 
 def prune_magnitude(w_ptr, n_out, k_in, sparsity_pct, pattern=0, stream=0):

@@ -591,4 +591,91 @@ int sd2_lm_head_argmax(const uint16_t* w_lm, int32_t vocab, int32_t hidden, cons
     return SD2_OK;
 }
 
+// ---- drafting round
+
+namespace {
+struct RoundLayout {
+    size_t hin_off, hout_off, flag_off, lm_off, fwd_off, fwd_bytes, total;
+};
+
+int round_layout(const sd2_model_t* md, int32_t vocab, int32_t k, RoundLayout* L) {
+    if (!md) return SD2_ERR_NULL;
+    if (k < 1 || k > SD2_MAX_TOKENS) return SD2_ERR_RANGE;
+    const sd2_model_shape_t& sh = md->shape;
+    int rc = lm_head_check(vocab, sh.hidden, 1);
+    if (rc != SD2_OK) return rc;
+    size_t fwd = 0;
+    for (int32_t kt = 1; kt <= k; ++kt) {
+        size_t b = 0;
+        if ((rc = sd2_drafter_workspace_size(md, kt, &b)) != SD2_OK) return rc;
+        fwd = std::max(fwd, b);
+    }
+    L->hin_off = 0;
+    L->hout_off = align256((size_t)k * sh.hidden * sizeof(uint16_t));
+    L->flag_off = L->hout_off + align256((size_t)k * sh.hidden * sizeof(float));
+    L->lm_off = L->flag_off + 256;
+    L->fwd_off = L->lm_off + align256((size_t)kLmMaxWorkgroups * 16 * 8);
+    L->fwd_bytes = fwd;
+    L->total = L->fwd_off + align256(fwd);
+    return SD2_OK;
+}
+}  // namespace
+
+int sd2_draft_round_workspace_size(const sd2_model_t* model, int32_t vocab, int32_t k, size_t* bytes_out) {
+    if (!bytes_out) return SD2_ERR_NULL;
+    RoundLayout L;
+    const int rc = round_layout(model, vocab, k, &L);
+    if (rc != SD2_OK) return rc;
+    *bytes_out = L.total;
+    return SD2_OK;
+}
+
+int sd2_draft_round(const sd2_model_t* model, const uint16_t* emb, int32_t vocab, const int32_t* start_token, int32_t k,
+                    int32_t* draft_ids, void* ws, size_t ws_bytes, void* stream) {
+    RoundLayout L;
+    int rc = round_layout(model, vocab, k, &L);
+    if (rc != SD2_OK) return rc;
+    if (!emb || !start_token || !draft_ids || !ws) return SD2_ERR_NULL;
+    if (!aligned16(emb) || !aligned16(ws) || ws_bytes < L.total) return SD2_ERR_BUFFER;
+    const sd2_model_shape_t& sh = model->shape;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    uint8_t* base = static_cast<uint8_t*>(ws);
+    uint16_t* h_in = reinterpret_cast<uint16_t*>(base + L.hin_off);
+    float* h_out = reinterpret_cast<float*>(base + L.hout_off);
+    unsigned* round_flag = reinterpret_cast<unsigned*>(base + L.flag_off);
+    void* lm_ws = base + L.lm_off;
+    void* fwd_ws = base + L.fwd_off;
+    // cleared by a kernel, not a memset: the caller may capture this call in a graph
+    if (launch_fold_flag(nullptr, round_flag, s) != hipSuccess) return SD2_ERR_HIP;
+    for (int32_t i = 0; i < k; ++i) {
+        // step i: the window so far goes through the stack, the head reads its last position
+        if (launch_embed_window(emb, vocab, sh.hidden, start_token, draft_ids, i + 1, h_in, s) != hipSuccess) return SD2_ERR_HIP;
+        rc = forward_impl(model, h_in, i + 1, h_out, fwd_ws, L.fwd_bytes, nullptr, stream);
+        if (rc != SD2_OK) return rc;
+        MegaGeo geo[4];
+        if (plan_mega_path(model, i + 1, geo)) {  // keep a give-up flag beyond the next forward's set-up
+            const MegaLayout ML = mega_layout(sh.layers, sh.hidden, sh.q_out, sh.kv_out, sh.inter, i + 1);
+            if (launch_fold_flag(reinterpret_cast<const unsigned*>(static_cast<uint8_t*>(fwd_ws) + ML.err_off), round_flag, s) !=
+                hipSuccess)
+                return SD2_ERR_HIP;
+        }
+        if (launch_lm_head(emb, h_out + (size_t)i * sh.hidden, vocab, sh.hidden, 1, lm_ws, draft_ids + i, nullptr, nullptr,
+                           s) != hipSuccess)
+            return SD2_ERR_HIP;
+    }
+    return SD2_OK;
+}
+
+int sd2_draft_round_status(const sd2_model_t* model, int32_t vocab, int32_t k, const void* ws, void* stream) {
+    RoundLayout L;
+    const int rc = round_layout(model, vocab, k, &L);
+    if (rc != SD2_OK) return rc;
+    if (!ws) return SD2_ERR_NULL;
+    if (hipStreamSynchronize(static_cast<hipStream_t>(stream)) != hipSuccess) return SD2_ERR_HIP;
+    unsigned flag = 0;
+    if (hipMemcpy(&flag, static_cast<const uint8_t*>(ws) + L.flag_off, sizeof(flag), hipMemcpyDeviceToHost) != hipSuccess)
+        return SD2_ERR_HIP;
+    return flag ? SD2_ERR_TIMEOUT : SD2_OK;
+}
+
 }  // extern "C"

@@ -50,6 +50,11 @@ hipError_t launch_silu_mul(const float* part, int n_splits, int k_tok, int inter
 hipError_t launch_greedy_verify(const int32_t* draft, const int32_t* target, int batch, int k,
                                 int32_t* accepted, int32_t* out_tokens, hipStream_t s);
 
+// drafting round helpers: rows of the embedding for the window [*start, drafts[0..n_tok-1)); *acc |= *flag
+hipError_t launch_embed_window(const uint16_t* emb, int vocab, int hidden, const int32_t* start, const int32_t* drafts,
+                               int n_tok, uint16_t* h_in, hipStream_t s);
+hipError_t launch_fold_flag(const unsigned* flag, unsigned* acc, hipStream_t s);
+
 // one-shot magnitude pruning in place (bf16 [n_out][k_in]): rows keeps n_keep per row (k_in a multiple of 256, <= 9216)
 hipError_t launch_prune_rows(uint16_t* w, int n_out, int k_in, int n_keep, hipStream_t s);
 hipError_t launch_prune_2of4(uint16_t* w, int n_out, int k_in, hipStream_t s);

@@ -304,6 +304,40 @@ hipError_t launch_mask_gradient(const MatArgs& m, void* grad, bool bf16, hipStre
     return hipGetLastError();
 }
 
+// ------------------------------------------------------------------ drafting round: embedding rows, flag folding
+// h_in[j] = E[id_j] for the round's window: id_0 = *start, id_j = drafts[j - 1].  Ids outside [0, vocab) are clamped
+// (they cannot be reported from the device).  One workgroup per window position, 16 bytes per thread and step.
+__global__ __launch_bounds__(256) void embed_window_kernel(const uint16_t* __restrict__ emb, int vocab, int hidden,
+                                                           const int32_t* __restrict__ start,
+                                                           const int32_t* __restrict__ drafts, uint16_t* __restrict__ h_in) {
+    const int j = blockIdx.x;
+    int id = j == 0 ? start[0] : drafts[j - 1];
+    id = min(max(id, 0), vocab - 1);
+    const u32x4* src = reinterpret_cast<const u32x4*>(emb + (size_t)id * hidden);
+    u32x4* dst = reinterpret_cast<u32x4*>(h_in + (size_t)j * hidden);
+    for (int c = threadIdx.x; c < hidden / 8; c += 256) dst[c] = src[c];
+}
+
+// *acc |= *flag (keeps a give-up flag of one forward beyond the next forward's set-up); flag == nullptr: *acc = 0
+__global__ void fold_flag_kernel(const unsigned* __restrict__ flag, unsigned* __restrict__ acc) {
+    if (threadIdx.x != 0) return;
+    if (!flag)
+        *acc = 0u;
+    else if (*flag)
+        *acc = 1u;
+}
+
+hipError_t launch_embed_window(const uint16_t* emb, int vocab, int hidden, const int32_t* start, const int32_t* drafts,
+                               int n_tok, uint16_t* h_in, hipStream_t s) {
+    hipLaunchKernelGGL(embed_window_kernel, dim3((unsigned)n_tok), dim3(256), 0, s, emb, vocab, hidden, start, drafts, h_in);
+    return hipGetLastError();
+}
+
+hipError_t launch_fold_flag(const unsigned* flag, unsigned* acc, hipStream_t s) {
+    hipLaunchKernelGGL(fold_flag_kernel, dim3(1), dim3(64), 0, s, flag, acc);
+    return hipGetLastError();
+}
+
 // ------------------------------------------------------------------ one-shot magnitude pruning
 // Sec. 2.3 prunes every decoder linear one-shot to a uniform sparsity.  Criterion here: weight magnitude; ties go
 // to the lower column; pruned entries become +0.  bf16 magnitudes order like their low 15 bits, so the threshold

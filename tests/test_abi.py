@@ -169,3 +169,27 @@ def test_prune_argument_checks():
     assert L.sd2_prune_magnitude(fake, 16, 320, 50, 0, None) == -8      # rows need k_in % 256 == 0
     assert L.sd2_prune_magnitude(fake, 16, 9216 + 256, 50, 0, None) == -8
     assert L.sd2_prune_magnitude(fake, 16, 256, 50, 7, None) == -3
+
+
+def test_draft_round_argument_checks():
+    import sd2_workload as wl
+    L = sd2.lib()
+    fake = C.c_void_p(0x2000)
+    shape = sd2.ModelShape(1, 256, 256, 128, 512, 2, 1, 128)
+    ws = {"qkv": (512, 256), "o": (256, 256), "gu": (1024, 256), "dn": (256, 512)}
+    mats = [sd2.matrix_init_sparse(sd2.pack_sparse(wl.gen_weight(73, 0, "q", n, k, 50), 1), 0x10000) for n, k in ws.values()]
+    model = sd2.model_create(shape, mats)
+    n = sd2.draft_round_workspace_size(model, 1000, 5)
+    assert n > 0 and n % 256 == 0
+    args = lambda **kw: [kw.get("model", model.handle), kw.get("emb", fake), kw.get("vocab", 1000), kw.get("start", fake),
+                         kw.get("k", 5), kw.get("ids", fake), kw.get("ws", fake), kw.get("wsb", n), None]
+    assert L.sd2_draft_round(*args(emb=None)) == -1
+    assert L.sd2_draft_round(*args(start=None)) == -1
+    assert L.sd2_draft_round(*args(ids=None)) == -1
+    assert L.sd2_draft_round(*args(ws=None)) == -1
+    assert L.sd2_draft_round(*args(k=0)) == -6
+    assert L.sd2_draft_round(*args(k=65)) == -6
+    assert L.sd2_draft_round(*args(vocab=0)) == -2
+    assert L.sd2_draft_round(*args(wsb=n - 1)) == -4
+    assert L.sd2_draft_round(*args(model=None)) == -1
+    sd2.model_destroy(model)
