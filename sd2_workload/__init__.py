@@ -27,6 +27,7 @@ from .gen import (  # noqa: F401
     gen_verify,
     gen_lm_head,
     gen_final_hidden,
+    gen_kv_history,
     stack_matrices,
     layer_matrix_shapes,
 )

@@ -228,6 +228,22 @@ def gen_final_hidden(cfg_id: int, k_tok: int, hidden: int) -> np.ndarray:
     return z * np.float32(3.0)
 
 
+_KV_ID = 310
+
+
+def gen_kv_history(cfg_id: int, layers: int, n_kv: int, max_pos: int, head_dim: int, n_hist: int):
+    """Key and value caches [layers][n_kv][max_pos][head_dim] as bf16 bits: positions below n_hist hold a synthetic
+    history (K = z, V = z: the size the keys and values of these stacks have), the rest is zero."""
+    caches = []
+    for which in (0, 1):
+        c = np.zeros((layers, n_kv, max_pos, head_dim), dtype=np.uint16)
+        for l in range(layers):
+            z = _rng(cfg_id, l, _KV_ID + which).standard_normal((n_kv, n_hist, head_dim), dtype=np.float32)
+            c[l, :, :n_hist] = f32_to_bf16_bits(z)
+        caches.append(c)
+    return caches[0], caches[1]
+
+
 def gen_verify(
     cfg_id: int, batch: int, k: int, vocab: int, alpha: float, stream: int = 0
 ) -> Tuple[np.ndarray, np.ndarray]:
