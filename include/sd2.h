@@ -198,6 +198,28 @@ int sd2_sparse_drafter_forward_trace(const sd2_model_t* model, const uint16_t* h
                                      size_t workspace_bytes, void* trace_dev, size_t trace_bytes,
                                      void* stream);
 
+/* ------------------------------------------------------------------ decode step with a key/value cache
+ * The drafter conditions each candidate on the prompt and on the candidates before it (Sec. 2.1, the definition of
+ * p_{n+j+1}); for the Llama / Qwen decoders of Sec. 3 that is rotary position embedding and attention over the keys
+ * and values of every earlier position.  This call runs the decoder-linear stack on k_tok new tokens at positions
+ * pos0 .. pos0 + k_tok - 1 against a cache of the positions before them.  Differences from
+ * sd2_sparse_drafter_forward, per layer:
+ *   q, k  <- rotary embedding, half-split pairing: within a head, dimensions i and i + head_dim/2 (i < head_dim/2)
+ *            rotate by the angle position * rope_theta^(-2 i / head_dim); values are not rotated
+ *   cache <- bf16(k rotated), bf16(v) at positions pos0 + t
+ *   token t attends to cache positions 0 .. pos0 + t (old and new positions alike are read from the cache)
+ * k_cache_dev, v_cache_dev: device bf16 [layers][n_kv][max_pos][head_dim], 16-byte aligned, owned by the caller;
+ * positions below pos0 must hold the history, positions from pos0 + k_tok on are neither read nor written.
+ * 0 <= pos0, pos0 + k_tok <= max_pos; head_dim a multiple of 8; at most 8 query heads per key/value head;
+ * max_pos limited by the attention kernel's LDS (about 12000 positions at 3 query heads per key/value head):
+ * SD2_ERR_UNSUPPORTED beyond.  rope_theta > 1.  h_in, h_out, workspace as for sd2_sparse_drafter_forward, with the
+ * size reported here.  Runs as one launch per linear and glue step (no waits inside kernels); asynchronous on
+ * `stream`; all checks happen on the host before the first launch. */
+int sd2_drafter_decode_workspace_size(const sd2_model_t* model, int32_t k_tok, size_t* bytes_out);
+int sd2_sparse_drafter_decode(const sd2_model_t* model, const uint16_t* h_in_bf16_dev, int32_t k_tok, int32_t pos0,
+                              uint16_t* k_cache_dev, uint16_t* v_cache_dev, int32_t max_pos, double rope_theta,
+                              float* h_out_dev, void* workspace_dev, size_t workspace_bytes, void* stream);
+
 /* ------------------------------------------------------------------ LM head with greedy choice
  * The drafter's next-token choice (Eq. 1 with greedy decoding, as in the footnote to Eq. 3): the
  * largest logit of the LM head, the one linear of the drafter that stays dense (Sec. 2.3 prunes

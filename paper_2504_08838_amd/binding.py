@@ -110,6 +110,8 @@ def lib():
             "sd2_drafter_forward_status": (C.c_int, [vp, i32, vp, vp]),
             "sd2_calibration_copy": (C.c_int, [vp, vp, sz, vp]),
             "sd2_mask_gradient": (C.c_int, [vp, vp, i32, vp]),
+            "sd2_drafter_decode_workspace_size": (C.c_int, [vp, i32, C.POINTER(sz)]),
+            "sd2_sparse_drafter_decode": (C.c_int, [vp, vp, i32, i32, vp, vp, i32, C.c_double, vp, vp, sz, vp]),
             "sd2_draft_round_workspace_size": (C.c_int, [vp, i32, i32, C.POINTER(sz)]),
             "sd2_draft_round": (C.c_int, [vp, vp, i32, vp, i32, vp, vp, sz, vp]),
             "sd2_draft_round_status": (C.c_int, [vp, i32, i32, vp, vp]),
@@ -291,6 +293,20 @@ def lm_head_argmax(w_ptr, vocab, hidden, h_ptr, k_tok, token_ids_ptr, ws_ptr, ws
                                     C.c_void_p(token_ids_ptr), C.c_void_p(max_logit_ptr or None),
                                     C.c_void_p(logits_ptr or None), C.c_void_p(ws_ptr), ws_bytes, C.c_void_p(stream)),
            "sd2_lm_head_argmax")
+
+
+def drafter_decode_workspace_size(model, k_tok):
+    n = C.c_size_t(0)
+    _check(lib().sd2_drafter_decode_workspace_size(model.handle, k_tok, C.byref(n)), "sd2_drafter_decode_workspace_size")
+    return n.value
+
+
+def sparse_drafter_decode(model, h_in_ptr, k_tok, pos0, k_cache_ptr, v_cache_ptr, max_pos, rope_theta, h_out_ptr, ws_ptr,
+                          ws_bytes, stream=0):
+    _check(lib().sd2_sparse_drafter_decode(model.handle, C.c_void_p(h_in_ptr), k_tok, pos0, C.c_void_p(k_cache_ptr),
+                                           C.c_void_p(v_cache_ptr), max_pos, float(rope_theta), C.c_void_p(h_out_ptr),
+                                           C.c_void_p(ws_ptr), ws_bytes, C.c_void_p(stream)),
+           "sd2_sparse_drafter_decode")
 
 
 def draft_round_workspace_size(model, vocab, k):

@@ -497,6 +497,79 @@ int sd2_sparse_drafter_forward_trace(const sd2_model_t* md, const uint16_t* h_in
     return forward_impl(md, h_in, k_tok, h_out, ws, ws_bytes, trace, stream);
 }
 
+// ------------------------------------------------------------------ decode step with a key/value cache
+
+struct DecodeLayout {
+    size_t q_off, table_off, total;
+};
+
+static DecodeLayout decode_layout(const sd2_model* md, int k_tok) {
+    const sd2_model_shape_t& sh = md->shape;
+    DecodeLayout D;
+    D.q_off = stack_layout(md, k_tok).total;
+    D.table_off = D.q_off + align256((size_t)k_tok * sh.q_out * sizeof(float));
+    D.total = D.table_off + align256((size_t)k_tok * (sh.head_dim / 2 + 1) * sizeof(float2));
+    return D;
+}
+
+int sd2_drafter_decode_workspace_size(const sd2_model_t* model, int32_t k_tok, size_t* bytes_out) {
+    if (!model || !bytes_out) return SD2_ERR_NULL;
+    int rc = check_tokens(k_tok);
+    if (rc != SD2_OK) return rc;
+    *bytes_out = decode_layout(model, k_tok).total;
+    return SD2_OK;
+}
+
+int sd2_sparse_drafter_decode(const sd2_model_t* md, const uint16_t* h_in, int32_t k_tok, int32_t pos0, uint16_t* k_cache,
+                              uint16_t* v_cache, int32_t max_pos, double rope_theta, float* h_out, void* ws, size_t ws_bytes,
+                              void* stream) {
+    if (!md || !h_in || !h_out || !ws || !k_cache || !v_cache) return SD2_ERR_NULL;
+    int rc = check_tokens(k_tok);
+    if (rc != SD2_OK) return rc;
+    const sd2_model_shape_t& sh = md->shape;
+    if (max_pos < 1 || pos0 < 0 || (int64_t)pos0 + k_tok > max_pos || !(rope_theta > 1.0)) return SD2_ERR_RANGE;
+    if (!cached_attention_supported(sh.n_heads, sh.n_kv, sh.head_dim, max_pos)) return SD2_ERR_UNSUPPORTED;
+    const StackLayout L = stack_layout(md, k_tok);
+    const DecodeLayout DL = decode_layout(md, k_tok);
+    if (!aligned16(h_in) || !aligned16(h_out) || !aligned16(ws) || !aligned16(k_cache) || !aligned16(v_cache) ||
+        ws_bytes < DL.total)
+        return SD2_ERR_BUFFER;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    uint8_t* base = static_cast<uint8_t*>(ws);
+    uint16_t* act = reinterpret_cast<uint16_t*>(base + L.act_off);
+    float* part = reinterpret_cast<float*>(base + L.part_off);
+    float* ssq = reinterpret_cast<float*>(base + L.ssq_off);
+    float* q_rot = reinterpret_cast<float*>(base + DL.q_off);
+    float2* table = reinterpret_cast<float2*>(base + DL.table_off);
+    float* h = h_out;  // the residual stream lives in the output buffer
+    const size_t layer_elems = (size_t)sh.n_kv * max_pos * sh.head_dim;
+#define SD2_TRY(expr) \
+    if ((expr) != hipSuccess) return SD2_ERR_HIP
+    SD2_TRY(launch_rope_table(pos0, k_tok, sh.head_dim, rope_theta, table, s));
+    SD2_TRY(launch_residual_rmsnorm(h, h_in, nullptr, 0, k_tok, sh.hidden, sh.layers > 0 ? act : nullptr, ssq, s));
+    for (int l = 0; l < sh.layers; ++l) {
+        const sd2_matrix_t* qkv = &md->mats[4 * l + 0];
+        const sd2_matrix_t* o = &md->mats[4 * l + 1];
+        const sd2_matrix_t* gu = &md->mats[4 * l + 2];
+        const sd2_matrix_t* dn = &md->mats[4 * l + 3];
+        uint16_t* kc = k_cache + (size_t)l * layer_elems;
+        uint16_t* vc = v_cache + (size_t)l * layer_elems;
+        SD2_TRY(run_linear(qkv, act, k_tok, part, s));
+        SD2_TRY(launch_rope_append(part, n_partials(qkv), k_tok, sh.q_out, sh.kv_out, sh.n_heads, sh.n_kv, sh.head_dim, table,
+                                   pos0, max_pos, q_rot, kc, vc, s));
+        SD2_TRY(launch_cached_attention(q_rot, kc, vc, max_pos, pos0, k_tok, sh.q_out, sh.n_heads, sh.n_kv, sh.head_dim, act, s));
+        SD2_TRY(run_linear(o, act, k_tok, part, s));
+        SD2_TRY(launch_residual_rmsnorm(h, nullptr, part, n_partials(o), k_tok, sh.hidden, act, ssq, s));
+        SD2_TRY(run_linear(gu, act, k_tok, part, s));
+        SD2_TRY(launch_silu_mul(part, n_partials(gu), k_tok, sh.inter, act, s));
+        SD2_TRY(run_linear(dn, act, k_tok, part, s));
+        SD2_TRY(launch_residual_rmsnorm(h, nullptr, part, n_partials(dn), k_tok, sh.hidden,
+                                        l + 1 < sh.layers ? act : nullptr, ssq, s));
+    }
+#undef SD2_TRY
+    return SD2_OK;
+}
+
 int sd2_greedy_verify(const int32_t* draft, const int32_t* target, int32_t batch, int32_t k, int32_t vocab,
                       int32_t* accepted, int32_t* out_tokens, void* stream) {
     if (batch < 0 || k < 0) return SD2_ERR_SHAPE;

@@ -50,6 +50,17 @@ hipError_t launch_silu_mul(const float* part, int n_splits, int k_tok, int inter
 hipError_t launch_greedy_verify(const int32_t* draft, const int32_t* target, int batch, int k,
                                 int32_t* accepted, int32_t* out_tokens, hipStream_t s);
 
+// decode step with rotary embedding and a key/value cache (bf16 [n_kv][max_pos][head_dim] per layer): the angle table
+// [k_tok][head_dim / 2] of the call's positions; q rotated into q_rot (fp32 [k_tok][q_out]), rotated keys and values
+// appended at positions pos0 .. pos0 + k_tok - 1; attention of token t over positions 0 .. pos0 + t into ctx (bf16)
+hipError_t launch_rope_table(int pos0, int k_tok, int head_dim, double theta, float2* table, hipStream_t s);
+hipError_t launch_rope_append(const float* part, int n_splits, int k_tok, int q_out, int kv_out, int n_heads, int n_kv,
+                              int head_dim, const float2* table, int pos0, int max_pos, float* q_rot, uint16_t* k_cache,
+                              uint16_t* v_cache, hipStream_t s);
+bool cached_attention_supported(int n_heads, int n_kv, int head_dim, int max_pos);
+hipError_t launch_cached_attention(const float* q_rot, const uint16_t* k_cache, const uint16_t* v_cache, int max_pos, int pos0,
+                                   int k_tok, int q_out, int n_heads, int n_kv, int head_dim, uint16_t* ctx, hipStream_t s);
+
 // drafting round helpers: rows of the embedding for the window [*start, drafts[0..n_tok-1)); *acc |= *flag
 hipError_t launch_embed_window(const uint16_t* emb, int vocab, int hidden, const int32_t* start, const int32_t* drafts,
                                int n_tok, uint16_t* h_in, hipStream_t s);

@@ -601,6 +601,191 @@ hipError_t launch_inflight_attention(const float* part, int n_splits, int k_tok,
     return hipGetLastError();
 }
 
+// ------------------------------------------------------------------ decode step: rotary embedding, key/value cache
+//
+// The drafter conditions every candidate on the prompt and the candidates before it (Sec. 2); for the Llama / Qwen
+// decoders of Sec. 3 that is rotary position embedding on queries and keys and attention over the cached keys and
+// values of all earlier positions.  Half-split pairing: dimension i < D/2 of a head rotates with dimension i + D/2 by
+// the angle position * theta^(-2 i / D).  The cache holds bf16: rotated keys, plain values.
+
+// cos and sin of the angles of the call's tokens, [k_tok][D/2].  Double precision: positions reach thousands of
+// radians, where a float product has already lost the low bits of the angle.
+__global__ __launch_bounds__(256) void rope_table_kernel(int pos0, int k_tok, int D, double theta, float2* __restrict__ table) {
+    const int idx = blockIdx.x * 256 + threadIdx.x;
+    const int half = D / 2;
+    if (idx >= k_tok * half) return;
+    const int t = idx / half, i = idx % half;
+    const double ang = (double)(pos0 + t) * pow(theta, -2.0 * (double)i / (double)D);
+    table[idx] = make_float2((float)cos(ang), (float)sin(ang));
+}
+
+hipError_t launch_rope_table(int pos0, int k_tok, int head_dim, double theta, float2* table, hipStream_t s) {
+    const int n = k_tok * (head_dim / 2);
+    hipLaunchKernelGGL(rope_table_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, pos0, k_tok, head_dim, theta, table);
+    return hipGetLastError();
+}
+
+// Block (head slot, token): slots below n_heads are query heads (summed from the split-K partials, rotated, kept as
+// fp32 in q_rot [k_tok][q_out]); the others are key/value heads (key rotated, both rounded to bf16 and written to
+// position pos0 + token of the layer's caches [n_kv][max_pos][D]).  Thread i < D/2 owns the pair (i, i + D/2).
+__global__ __launch_bounds__(128) void rope_append_kernel(const float* __restrict__ part, int n_splits, int k_tok, int q_out,
+                                                         int kv_out, int n_heads, int D, const float2* __restrict__ table,
+                                                         int pos0, int max_pos, float* __restrict__ q_rot,
+                                                         uint16_t* __restrict__ k_cache, uint16_t* __restrict__ v_cache) {
+    const int slot = blockIdx.x, t = blockIdx.y, i = threadIdx.x, half = D / 2;
+    if (i >= half) return;
+    const int n_out = q_out + 2 * kv_out;
+    const size_t stride = (size_t)k_tok * n_out;
+    const float* row = part + (size_t)t * n_out;
+    const float2 cs = table[t * half + i];
+    if (slot < n_heads) {
+        const float lo = sum_splits(row + slot * D + i, n_splits, stride);
+        const float hi = sum_splits(row + slot * D + half + i, n_splits, stride);
+        float* dst = q_rot + (size_t)t * q_out + slot * D;
+        dst[i] = lo * cs.x - hi * cs.y;
+        dst[half + i] = hi * cs.x + lo * cs.y;
+    } else {
+        const int g = slot - n_heads;
+        const float lo = sum_splits(row + q_out + g * D + i, n_splits, stride);
+        const float hi = sum_splits(row + q_out + g * D + half + i, n_splits, stride);
+        const float v0 = sum_splits(row + q_out + kv_out + g * D + i, n_splits, stride);
+        const float v1 = sum_splits(row + q_out + kv_out + g * D + half + i, n_splits, stride);
+        const size_t at = ((size_t)g * max_pos + (size_t)(pos0 + t)) * D;
+        k_cache[at + i] = f32_to_bf16(lo * cs.x - hi * cs.y);
+        k_cache[at + half + i] = f32_to_bf16(hi * cs.x + lo * cs.y);
+        v_cache[at + i] = f32_to_bf16(v0);
+        v_cache[at + half + i] = f32_to_bf16(v1);
+    }
+}
+
+hipError_t launch_rope_append(const float* part, int n_splits, int k_tok, int q_out, int kv_out, int n_heads, int n_kv,
+                              int head_dim, const float2* table, int pos0, int max_pos, float* q_rot, uint16_t* k_cache,
+                              uint16_t* v_cache, hipStream_t s) {
+    if (head_dim < 2 || head_dim > 256 || (head_dim & 1)) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(rope_append_kernel, dim3((unsigned)(n_heads + n_kv), (unsigned)k_tok), dim3(128), 0, s, part, n_splits,
+                       k_tok, q_out, kv_out, n_heads, head_dim, table, pos0, max_pos, q_rot, k_cache, v_cache);
+    return hipGetLastError();
+}
+
+constexpr int kAttMaxRep = 8;  // query heads per key/value head
+
+// LDS of the attention kernel in floats: queries [rep][D], scores [rep][n_max], partial outputs [256 / D][rep][D],
+// per-head scalars
+static size_t cached_attention_lds(int rep, int D, int n_max) {
+    const int groups = std::max(1, 256 / D);
+    return ((size_t)rep * D + (size_t)rep * n_max + (size_t)groups * rep * D + 2 * kAttMaxRep) * sizeof(float);
+}
+
+// Block (key/value head g, token t): the rep query heads of the group attend to cache positions 0 .. pos0 + t.
+// Scores: thread = position (a key row is D bf16, read as 16-byte pieces; the queries sit in LDS and are read as
+// broadcasts).  Softmax: one wavefront per head.  Values: thread = (position group, dimension), so a row of the
+// value cache is read by consecutive lanes; the groups' sums meet in LDS.
+__global__ __launch_bounds__(256) void cached_attention_kernel(const float* __restrict__ q_rot, const uint16_t* __restrict__ k_cache,
+                                                              const uint16_t* __restrict__ v_cache, int max_pos, int pos0,
+                                                              int n_max, int q_out, int rep, int D, uint16_t* __restrict__ ctx) {
+    extern __shared__ float smem[];
+    const int g = blockIdx.x, t = blockIdx.y, tid = threadIdx.x;
+    const int n = pos0 + t + 1;
+    const int groups = max(1, 256 / D);
+    float* sq = smem;                        // [rep][D]
+    float* sc = sq + rep * D;                // [rep][n_max]
+    float* so = sc + (size_t)rep * n_max;    // [groups][rep][D]
+    float* smx = so + groups * rep * D;      // [kAttMaxRep] inverse sums
+    for (int idx = tid; idx < rep * D; idx += 256) sq[idx] = q_rot[(size_t)t * q_out + (size_t)g * rep * D + idx];
+    __syncthreads();
+    const uint16_t* kg = k_cache + (size_t)g * max_pos * D;
+    const uint16_t* vg = v_cache + (size_t)g * max_pos * D;
+    const float scale = 1.0f / sqrtf((float)D);
+    for (int j = tid; j < n; j += 256) {
+        float dot[kAttMaxRep];
+#pragma unroll
+        for (int r = 0; r < kAttMaxRep; ++r) dot[r] = 0.f;
+        const u32x4* row = reinterpret_cast<const u32x4*>(kg + (size_t)j * D);
+        for (int c = 0; c < D / 8; ++c) {
+            const u32x4 w = row[c];
+            float kf[8];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                kf[2 * e] = __uint_as_float(w[e] << 16);
+                kf[2 * e + 1] = __uint_as_float(w[e] & 0xffff0000u);
+            }
+#pragma unroll
+            for (int r = 0; r < kAttMaxRep; ++r)
+                if (r < rep) {
+                    const float* qr = sq + r * D + 8 * c;
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) dot[r] += kf[e] * qr[e];
+                }
+        }
+#pragma unroll
+        for (int r = 0; r < kAttMaxRep; ++r)
+            if (r < rep) sc[(size_t)r * n_max + j] = dot[r] * scale;
+    }
+    __syncthreads();
+    const int wave = tid >> 6, lane = tid & 63;
+    for (int r = wave; r < rep; r += 4) {
+        float* row = sc + (size_t)r * n_max;
+        float mx = -3.0e38f;
+        for (int j = lane; j < n; j += 64) mx = fmaxf(mx, row[j]);
+        for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
+        float sum = 0.f;
+        for (int j = lane; j < n; j += 64) {
+            const float e = expf(row[j] - mx);
+            row[j] = e;
+            sum += e;
+        }
+        for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o);
+        if (lane == 0) smx[r] = 1.0f / sum;
+    }
+    __syncthreads();
+    if (tid < groups * D) {
+        const int grp = tid / D, d = tid % D;
+        float acc[kAttMaxRep];
+#pragma unroll
+        for (int r = 0; r < kAttMaxRep; ++r) acc[r] = 0.f;
+        for (int j = grp; j < n; j += groups) {
+            const float v = bf16_to_f32(vg[(size_t)j * D + d]);
+#pragma unroll
+            for (int r = 0; r < kAttMaxRep; ++r)
+                if (r < rep) acc[r] += sc[(size_t)r * n_max + j] * v;
+        }
+#pragma unroll
+        for (int r = 0; r < kAttMaxRep; ++r)
+            if (r < rep) so[(grp * rep + r) * D + d] = acc[r];
+    }
+    __syncthreads();
+    for (int idx = tid; idx < rep * D; idx += 256) {
+        float o = 0.f;
+        for (int grp = 0; grp < groups; ++grp) o += so[grp * rep * D + idx];
+        const int r = idx / D;
+        ctx[(size_t)t * q_out + (size_t)g * rep * D + idx] = f32_to_bf16(o * smx[r]);
+    }
+}
+
+bool cached_attention_supported(int n_heads, int n_kv, int head_dim, int max_pos) {
+    if (n_kv < 1 || n_heads % n_kv || n_heads / n_kv > kAttMaxRep) return false;
+    if (head_dim < 8 || head_dim > 256 || head_dim % 8) return false;
+    return max_pos >= 1 && cached_attention_lds(n_heads / n_kv, head_dim, max_pos) <= 160 * 1024 - 256;
+}
+
+hipError_t launch_cached_attention(const float* q_rot, const uint16_t* k_cache, const uint16_t* v_cache, int max_pos, int pos0,
+                                   int k_tok, int q_out, int n_heads, int n_kv, int head_dim, uint16_t* ctx, hipStream_t s) {
+    if (!cached_attention_supported(n_heads, n_kv, head_dim, max_pos) || pos0 < 0 || pos0 + k_tok > max_pos)
+        return hipErrorInvalidValue;
+    const int rep = n_heads / n_kv, n_max = pos0 + k_tok;
+    const size_t lds = cached_attention_lds(rep, head_dim, n_max);
+    static bool lds_raised = false;  // once, at the first call (a warm-up call precedes any graph capture)
+    if (!lds_raised) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(cached_attention_kernel),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 256);
+        if (e != hipSuccess) return e;
+        lds_raised = true;
+    }
+    hipLaunchKernelGGL(cached_attention_kernel, dim3((unsigned)n_kv, (unsigned)k_tok), dim3(256), lds, s, q_rot, k_cache, v_cache,
+                       max_pos, pos0, n_max, q_out, rep, head_dim, ctx);
+    return hipGetLastError();
+}
+
 __global__ __launch_bounds__(256) void silu_mul_kernel(const float* __restrict__ part, int n_splits, int k_tok, int inter,
                                                       uint16_t* __restrict__ mo) {
     const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
