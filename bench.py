@@ -11,7 +11,7 @@ on the same stream brackets every forward inside the timed region.
 Prints one JSON line.  `roofline` describes the dominant kernel: algorithmic bytes per launch divided by the
 live event-timed duration, against the published 8 TB/s of HBM3E (`traffic` = HBM bytes per launch measured with
 profiler counters in separate runs).  `cpu_baseline` is the NumPy fp64 oracle timed on the host's cores.  The
-other keys (`lm_head`, `nm24_linear`, `mask_gradient`) time further kernels on their own; they are not in `value`.
+other keys (`lm_head`, `draft_round`, `decode`, `nm24_linear`, `mask_gradient`) time further kernels on their own; they are not in `value`.
 """
 
 import argparse
@@ -348,6 +348,54 @@ def main():
                                  "achieved_GBps": round(dr_alg / dr_us / 1e3, 1),
                                  "frac": round(dr_alg / dr_us / 1e3 / HBM_PEAK_GBS, 4)}
         del g_dr, w_lm
+
+        # One decode step with rotary embedding and a key/value cache: one new token at position 428 (a 300-token prompt
+        # and 128 generated tokens: the middle of the request shape of the paper's serving measurements), synthetic history.
+        # Runs as one launch per linear and glue step.  Beside it: the window forward (no cache) on one token, which is the
+        # single-launch kernel.  Not part of `value`.
+        dpos, dmax = 428, 1024
+        kc_np, vc_np = wl.gen_kv_history(args.config, layers, shape.n_kv, dmax, shape.head_dim, dpos)
+        kc_dev, vc_dev = to_dev(kc_np), to_dev(vc_np)
+        del kc_np, vc_np
+        dh_in = to_dev(wl.gen_x(args.config, 1, "q", 1, shape.hidden))
+        dh_out = torch.empty((1, shape.hidden), dtype=torch.float32, device=dev)
+        dec_bytes = sd2.drafter_decode_workspace_size(model, 1)
+        dec_ws = torch.empty(dec_bytes, dtype=torch.uint8, device=dev)
+        w1_bytes = sd2.drafter_workspace_size(model, 1)
+        w1_ws = torch.empty(w1_bytes, dtype=torch.uint8, device=dev)
+        dec_call = lambda spp: sd2.sparse_drafter_decode(model, dh_in.data_ptr(), 1, dpos, kc_dev.data_ptr(), vc_dev.data_ptr(),
+                                                         dmax, 500000.0, dh_out.data_ptr(), dec_ws.data_ptr(), dec_bytes, spp)
+        win_call = lambda spp: sd2.sparse_drafter_forward(model, dh_in.data_ptr(), 1, dh_out.data_ptr(), w1_ws.data_ptr(),
+                                                          w1_bytes, spp)
+        dec_us = {}
+        with torch.cuda.stream(stream):
+            for name, call in (("decode", dec_call), ("window", win_call)):
+                call(stream.cuda_stream)
+                stream.synchronize()
+                g_dec = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g_dec, stream=stream):
+                    call(torch.cuda.current_stream().cuda_stream)
+                for _ in range(3):
+                    g_dec.replay()
+                evq = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(30)]
+                for e0, e1 in evq:
+                    e0.record(stream)
+                    g_dec.replay()
+                    e1.record(stream)
+                stream.synchronize()
+                dec_us[name] = float(np.mean([e0.elapsed_time(e1) for e0, e1 in evq])) * 1e3
+                assert torch.isfinite(dh_out).all()
+                del g_dec
+        sd2.drafter_forward_status(model, 1, w1_ws.data_ptr(), stream.cuda_stream)
+        kv_bytes = 2 * 2 * layers * shape.n_kv * (dpos + 1) * shape.head_dim  # keys and values of the positions read, bf16
+        dec_alg = useful + kv_bytes
+        record["decode"] = {"what": f"one token at position {dpos}: rotary embedding, append to the bf16 key/value cache, attention "
+                                    f"over {dpos + 1} positions, one launch per linear and glue step",
+                            "us": round(dec_us["decode"], 1), "algorithmic_bytes": dec_alg, "kv_cache_bytes_read": kv_bytes,
+                            "achieved_GBps": round(dec_alg / dec_us["decode"] / 1e3, 1),
+                            "frac": round(dec_alg / dec_us["decode"] / 1e3 / HBM_PEAK_GBS, 4),
+                            "window_forward_k1_us": round(dec_us["window"], 1)}
+        del kc_dev, vc_dev
 
     if not args.no_lm_head:
         # Masked-gradient step of sparse fine-tuning on the fused gate+up shape (fp32 gradient, in place), two

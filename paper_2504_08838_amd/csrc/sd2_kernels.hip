@@ -669,61 +669,81 @@ hipError_t launch_rope_append(const float* part, int n_splits, int k_tok, int q_
 
 constexpr int kAttMaxRep = 8;  // query heads per key/value head
 
-// LDS of the attention kernel in floats: queries [rep][D], scores [rep][n_max], partial outputs [256 / D][rep][D],
-// per-head scalars
+constexpr int kAttWaves = 16;  // wavefronts per attention block
+
+// LDS of the attention kernel in floats: scores [rep][n_max], per-wavefront partial outputs [waves][rep][D], inverse sums
 static size_t cached_attention_lds(int rep, int D, int n_max) {
-    const int groups = std::max(1, 256 / D);
-    return ((size_t)rep * D + (size_t)rep * n_max + (size_t)groups * rep * D + 2 * kAttMaxRep) * sizeof(float);
+    return ((size_t)rep * n_max + (size_t)kAttWaves * rep * D + kAttMaxRep) * sizeof(float);
+}
+
+__device__ __forceinline__ void bf16x8_to_f32(const u32x4 w, float (&f)[8]) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        f[2 * e] = __uint_as_float(w[e] << 16);
+        f[2 * e + 1] = __uint_as_float(w[e] & 0xffff0000u);
+    }
 }
 
 // Block (key/value head g, token t): the rep query heads of the group attend to cache positions 0 .. pos0 + t.
-// Scores: thread = position (a key row is D bf16, read as 16-byte pieces; the queries sit in LDS and are read as
-// broadcasts).  Softmax: one wavefront per head.  Values: thread = (position group, dimension), so a row of the
-// value cache is read by consecutive lanes; the groups' sums meet in LDS.
-__global__ __launch_bounds__(256) void cached_attention_kernel(const float* __restrict__ q_rot, const uint16_t* __restrict__ k_cache,
+// A cache row (one position, D = 8 LPR bf16) is read by LPR consecutive lanes, 16 bytes each, so a wavefront reads
+// 64 / LPR consecutive positions = one contiguous KiB per load instruction, and the block's sixteen wavefronts
+// cover 1024 / LPR positions per pass; four passes of loads are in flight at once.  Scores: each lane multiplies its eight
+// dimensions with the queries it holds in registers, the LPR lanes of a row add up across lanes.  Softmax: one
+// wavefront per head over the scores in LDS.  Values: each lane accumulates its eight dimensions over the rows it
+// reads; the row slots of a wavefront add up across lanes, the wavefronts through LDS.
+template <int LPR, int REP>
+__global__ __launch_bounds__(64 * kAttWaves) void cached_attention_kernel(const float* __restrict__ q_rot, const uint16_t* __restrict__ k_cache,
                                                               const uint16_t* __restrict__ v_cache, int max_pos, int pos0,
-                                                              int n_max, int q_out, int rep, int D, uint16_t* __restrict__ ctx) {
+                                                              int n_max, int q_out, int rep, uint16_t* __restrict__ ctx) {
+    constexpr int D = 8 * LPR, RPW = 64 / LPR, RPI = kAttWaves * RPW, UNR = 4;
     extern __shared__ float smem[];
     const int g = blockIdx.x, t = blockIdx.y, tid = threadIdx.x;
+    const int wave = tid >> 6, lane = tid & 63;
+    const int piece = lane % LPR, slot = wave * RPW + lane / LPR;  // 16-byte piece of a row, row slot within a pass
     const int n = pos0 + t + 1;
-    const int groups = max(1, 256 / D);
-    float* sq = smem;                        // [rep][D]
-    float* sc = sq + rep * D;                // [rep][n_max]
-    float* so = sc + (size_t)rep * n_max;    // [groups][rep][D]
-    float* smx = so + groups * rep * D;      // [kAttMaxRep] inverse sums
-    for (int idx = tid; idx < rep * D; idx += 256) sq[idx] = q_rot[(size_t)t * q_out + (size_t)g * rep * D + idx];
-    __syncthreads();
-    const uint16_t* kg = k_cache + (size_t)g * max_pos * D;
-    const uint16_t* vg = v_cache + (size_t)g * max_pos * D;
+    float* sc = smem;                        // [rep][n_max]
+    float* so = sc + (size_t)rep * n_max;    // [waves][rep][D]
+    float* sinv = so + kAttWaves * rep * D;  // [kAttMaxRep]
+    const u32x4* kg = reinterpret_cast<const u32x4*>(k_cache + (size_t)g * max_pos * D) + piece;
+    const u32x4* vg = reinterpret_cast<const u32x4*>(v_cache + (size_t)g * max_pos * D) + piece;
     const float scale = 1.0f / sqrtf((float)D);
-    for (int j = tid; j < n; j += 256) {
-        float dot[kAttMaxRep];
+
+    float qr[REP][8];
 #pragma unroll
-        for (int r = 0; r < kAttMaxRep; ++r) dot[r] = 0.f;
-        const u32x4* row = reinterpret_cast<const u32x4*>(kg + (size_t)j * D);
-        for (int c = 0; c < D / 8; ++c) {
-            const u32x4 w = row[c];
-            float kf[8];
+    for (int r = 0; r < REP; ++r) {
+        const float* src = q_rot + (size_t)t * q_out + ((size_t)g * rep + min(r, rep - 1)) * D + 8 * piece;
+        const f32x4 lo = *reinterpret_cast<const f32x4*>(src), hi = *reinterpret_cast<const f32x4*>(src + 4);
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                kf[2 * e] = __uint_as_float(w[e] << 16);
-                kf[2 * e + 1] = __uint_as_float(w[e] & 0xffff0000u);
-            }
+        for (int e = 0; e < 4; ++e) {
+            qr[r][e] = lo[e] * scale;
+            qr[r][4 + e] = hi[e] * scale;
+        }
+    }
+    for (int j0 = 0; j0 < n; j0 += RPI * UNR) {
+        u32x4 w[UNR];
 #pragma unroll
-            for (int r = 0; r < kAttMaxRep; ++r)
-                if (r < rep) {
-                    const float* qr = sq + r * D + 8 * c;
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) dot[r] += kf[e] * qr[e];
-                }
+        for (int u = 0; u < UNR; ++u) {
+            const int j = j0 + u * RPI + slot;
+            w[u] = j < n ? kg[(size_t)j * LPR] : u32x4{0u, 0u, 0u, 0u};
         }
 #pragma unroll
-        for (int r = 0; r < kAttMaxRep; ++r)
-            if (r < rep) sc[(size_t)r * n_max + j] = dot[r] * scale;
+        for (int u = 0; u < UNR; ++u) {
+            const int j = j0 + u * RPI + slot;
+            float kf[8];
+            bf16x8_to_f32(w[u], kf);
+#pragma unroll
+            for (int r = 0; r < REP; ++r) {
+                float dot = 0.f;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) dot += kf[e] * qr[r][e];
+#pragma unroll
+                for (int o = 1; o < LPR; o <<= 1) dot += __shfl_xor(dot, o);
+                if (piece == 0 && j < n && r < rep) sc[(size_t)r * n_max + j] = dot;
+            }
+        }
     }
     __syncthreads();
-    const int wave = tid >> 6, lane = tid & 63;
-    for (int r = wave; r < rep; r += 4) {
+    for (int r = wave; r < rep; r += kAttWaves) {
         float* row = sc + (size_t)r * n_max;
         float mx = -3.0e38f;
         for (int j = lane; j < n; j += 64) mx = fmaxf(mx, row[j]);
@@ -735,55 +755,91 @@ __global__ __launch_bounds__(256) void cached_attention_kernel(const float* __re
             sum += e;
         }
         for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o);
-        if (lane == 0) smx[r] = 1.0f / sum;
+        if (lane == 0) sinv[r] = 1.0f / sum;
     }
     __syncthreads();
-    if (tid < groups * D) {
-        const int grp = tid / D, d = tid % D;
-        float acc[kAttMaxRep];
+    float acc[REP][8];
 #pragma unroll
-        for (int r = 0; r < kAttMaxRep; ++r) acc[r] = 0.f;
-        for (int j = grp; j < n; j += groups) {
-            const float v = bf16_to_f32(vg[(size_t)j * D + d]);
+    for (int r = 0; r < REP; ++r)
 #pragma unroll
-            for (int r = 0; r < kAttMaxRep; ++r)
-                if (r < rep) acc[r] += sc[(size_t)r * n_max + j] * v;
+        for (int e = 0; e < 8; ++e) acc[r][e] = 0.f;
+    for (int j0 = 0; j0 < n; j0 += RPI * UNR) {
+        u32x4 w[UNR];
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) {
+            const int j = j0 + u * RPI + slot;
+            w[u] = j < n ? vg[(size_t)j * LPR] : u32x4{0u, 0u, 0u, 0u};
         }
 #pragma unroll
-        for (int r = 0; r < kAttMaxRep; ++r)
-            if (r < rep) so[(grp * rep + r) * D + d] = acc[r];
+        for (int u = 0; u < UNR; ++u) {
+            const int j = j0 + u * RPI + slot;
+            if (j < n) {
+                float vf[8];
+                bf16x8_to_f32(w[u], vf);
+#pragma unroll
+                for (int r = 0; r < REP; ++r) {
+                    const float p = sc[(size_t)min(r, rep - 1) * n_max + j];
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) acc[r][e] += p * vf[e];
+                }
+            }
+        }
     }
+#pragma unroll
+    for (int r = 0; r < REP; ++r)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            float v = acc[r][e];
+#pragma unroll
+            for (int o = LPR; o < 64; o <<= 1) v += __shfl_xor(v, o);
+            if (lane < LPR && r < rep) so[(wave * rep + r) * D + 8 * piece + e] = v;
+        }
     __syncthreads();
-    for (int idx = tid; idx < rep * D; idx += 256) {
+    for (int idx = tid; idx < rep * D; idx += 64 * kAttWaves) {
         float o = 0.f;
-        for (int grp = 0; grp < groups; ++grp) o += so[grp * rep * D + idx];
-        const int r = idx / D;
-        ctx[(size_t)t * q_out + (size_t)g * rep * D + idx] = f32_to_bf16(o * smx[r]);
+#pragma unroll
+        for (int w = 0; w < kAttWaves; ++w) o += so[w * rep * D + idx];
+        ctx[(size_t)t * q_out + (size_t)g * rep * D + idx] = f32_to_bf16(o * sinv[idx / D]);
     }
 }
 
 bool cached_attention_supported(int n_heads, int n_kv, int head_dim, int max_pos) {
     if (n_kv < 1 || n_heads % n_kv || n_heads / n_kv > kAttMaxRep) return false;
-    if (head_dim < 8 || head_dim > 256 || head_dim % 8) return false;
+    if (head_dim != 64 && head_dim != 128 && head_dim != 256) return false;
     return max_pos >= 1 && cached_attention_lds(n_heads / n_kv, head_dim, max_pos) <= 160 * 1024 - 256;
+}
+
+template <int LPR, int REP>
+static hipError_t launch_cached_attention_t(const float* q_rot, const uint16_t* k_cache, const uint16_t* v_cache, int max_pos,
+                                            int pos0, int k_tok, int q_out, int rep, int n_kv, uint16_t* ctx, hipStream_t s) {
+    static bool lds_raised = false;  // once, at the first call (a warm-up call precedes any graph capture)
+    if (!lds_raised) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(cached_attention_kernel<LPR, REP>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 256);
+        if (e != hipSuccess) return e;
+        lds_raised = true;
+    }
+    const int n_max = pos0 + k_tok;
+    hipLaunchKernelGGL((cached_attention_kernel<LPR, REP>), dim3((unsigned)n_kv, (unsigned)k_tok), dim3(64 * kAttWaves),
+                       cached_attention_lds(rep, 8 * LPR, n_max), s, q_rot, k_cache, v_cache, max_pos, pos0, n_max, q_out, rep, ctx);
+    return hipGetLastError();
 }
 
 hipError_t launch_cached_attention(const float* q_rot, const uint16_t* k_cache, const uint16_t* v_cache, int max_pos, int pos0,
                                    int k_tok, int q_out, int n_heads, int n_kv, int head_dim, uint16_t* ctx, hipStream_t s) {
     if (!cached_attention_supported(n_heads, n_kv, head_dim, max_pos) || pos0 < 0 || pos0 + k_tok > max_pos)
         return hipErrorInvalidValue;
-    const int rep = n_heads / n_kv, n_max = pos0 + k_tok;
-    const size_t lds = cached_attention_lds(rep, head_dim, n_max);
-    static bool lds_raised = false;  // once, at the first call (a warm-up call precedes any graph capture)
-    if (!lds_raised) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(cached_attention_kernel),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 256);
-        if (e != hipSuccess) return e;
-        lds_raised = true;
-    }
-    hipLaunchKernelGGL(cached_attention_kernel, dim3((unsigned)n_kv, (unsigned)k_tok), dim3(256), lds, s, q_rot, k_cache, v_cache,
-                       max_pos, pos0, n_max, q_out, rep, head_dim, ctx);
-    return hipGetLastError();
+    const int rep = n_heads / n_kv;
+    // register arrays are sized for 4 or 8 query heads per key/value head
+#define SD2_ATT_CASE(L) \
+    if (head_dim == 8 * L) \
+        return rep <= 4 ? launch_cached_attention_t<L, 4>(q_rot, k_cache, v_cache, max_pos, pos0, k_tok, q_out, rep, n_kv, ctx, s) \
+                        : launch_cached_attention_t<L, 8>(q_rot, k_cache, v_cache, max_pos, pos0, k_tok, q_out, rep, n_kv, ctx, s)
+    SD2_ATT_CASE(8);
+    SD2_ATT_CASE(16);
+    SD2_ATT_CASE(32);
+#undef SD2_ATT_CASE
+    return hipErrorInvalidValue;
 }
 
 __global__ __launch_bounds__(256) void silu_mul_kernel(const float* __restrict__ part, int n_splits, int k_tok, int inter,

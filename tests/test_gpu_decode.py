@@ -127,6 +127,22 @@ def test_grouped_heads_six_per_kv_head_and_other_theta():
     assert rel_l2(got, want) <= 1e-3
 
 
+@pytest.mark.parametrize("head_dim,n_heads,n_kv", [(64, 8, 2), (256, 2, 1), (64, 16, 2)])
+def test_other_head_sizes(head_dim, n_heads, n_kv):
+    import gpu_util as gu
+    shape = SimpleNamespace(layers=1, hidden=512, q_out=n_heads * head_dim, kv_out=n_kv * head_dim, inter=1024,
+                            n_heads=n_heads, n_kv=n_kv, head_dim=head_dim)
+    max_pos, n_hist, k_tok = 192, 131, 3
+    get, model = _model(shape, 87)
+    kc, vc = wl.gen_kv_history(87, shape.layers, shape.n_kv, max_pos, shape.head_dim, n_hist)
+    h_bits = wl.gen_x(87, 0, "q", k_tok, shape.hidden)
+    kc_dev, vc_dev = gu.dev(kc), gu.dev(vc)
+    got = _decode(model, shape, h_bits, kc_dev, vc_dev, max_pos, n_hist)
+    want = od.drafter_decode(shape, get, h_bits, kc, vc, n_hist, THETA)
+    assert rel_l2(got, want) <= 1e-3
+    _cache_close(kc_dev.cpu().numpy().view(np.uint16)[0, :, n_hist:n_hist + k_tok], kc[0, :, n_hist:n_hist + k_tok])
+
+
 def test_far_positions_keep_their_angles():
     # position 8000: a float product pos * frequency would be off by 5e-4 rad; the table is built in double precision
     import gpu_util as gu
