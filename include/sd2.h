@@ -213,9 +213,14 @@ int sd2_sparse_drafter_forward_trace(const sd2_model_t* model, const uint16_t* h
  * 0 <= pos0, pos0 + k_tok <= max_pos; head_dim a multiple of 8; at most 8 query heads per key/value head;
  * max_pos limited by the attention kernel's LDS (about 12000 positions at 3 query heads per key/value head):
  * SD2_ERR_UNSUPPORTED beyond.  rope_theta > 1.  h_in, h_out, workspace as for sd2_sparse_drafter_forward, with the
- * size reported here.  Runs as one launch per linear and glue step (no waits inside kernels); asynchronous on
- * `stream`; all checks happen on the host before the first launch. */
+ * size reported here.  Asynchronous on `stream`; all checks happen on the host before the first launch.
+ * Where the single-launch kernel of sd2_sparse_drafter_forward serves the model (k_tok <= 8, head_dim 128, at most 4
+ * query heads per key/value head) it runs here too, with one more step per layer: after the q|k|v linear the
+ * workgroups share the attention over the cache (a stretch of positions each), and the linear that follows combines
+ * their partial results.  Otherwise: one launch per linear and glue step.  sd2_drafter_decode_status is to this call
+ * what sd2_drafter_forward_status is to the forward: it waits for `stream` and reports a bounded wait that ran out. */
 int sd2_drafter_decode_workspace_size(const sd2_model_t* model, int32_t k_tok, size_t* bytes_out);
+int sd2_drafter_decode_status(const sd2_model_t* model, int32_t k_tok, const void* workspace_dev, void* stream);
 int sd2_sparse_drafter_decode(const sd2_model_t* model, const uint16_t* h_in_bf16_dev, int32_t k_tok, int32_t pos0,
                               uint16_t* k_cache_dev, uint16_t* v_cache_dev, int32_t max_pos, double rope_theta,
                               float* h_out_dev, void* workspace_dev, size_t workspace_bytes, void* stream);

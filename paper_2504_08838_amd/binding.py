@@ -111,6 +111,7 @@ def lib():
             "sd2_calibration_copy": (C.c_int, [vp, vp, sz, vp]),
             "sd2_mask_gradient": (C.c_int, [vp, vp, i32, vp]),
             "sd2_drafter_decode_workspace_size": (C.c_int, [vp, i32, C.POINTER(sz)]),
+            "sd2_drafter_decode_status": (C.c_int, [vp, i32, vp, vp]),
             "sd2_sparse_drafter_decode": (C.c_int, [vp, vp, i32, i32, vp, vp, i32, C.c_double, vp, vp, sz, vp]),
             "sd2_draft_round_workspace_size": (C.c_int, [vp, i32, i32, C.POINTER(sz)]),
             "sd2_draft_round": (C.c_int, [vp, vp, i32, vp, i32, vp, vp, sz, vp]),
@@ -299,6 +300,11 @@ def drafter_decode_workspace_size(model, k_tok):
     n = C.c_size_t(0)
     _check(lib().sd2_drafter_decode_workspace_size(model.handle, k_tok, C.byref(n)), "sd2_drafter_decode_workspace_size")
     return n.value
+
+
+def drafter_decode_status(model, k_tok, ws_ptr, stream=0):
+    _check(lib().sd2_drafter_decode_status(model.handle, k_tok, C.c_void_p(ws_ptr), C.c_void_p(stream)),
+           "sd2_drafter_decode_status")
 
 
 def sparse_drafter_decode(model, h_in_ptr, k_tok, pos0, k_cache_ptr, v_cache_ptr, max_pos, rope_theta, h_out_ptr, ws_ptr,

@@ -354,6 +354,33 @@ static TraceLayout trace_layout(const sd2_model* md, int k_tok) {
     return T;
 }
 
+// Everything of the persistent kernel's argument block that the model, the token count and the workspace fix.
+static void fill_mega_args(MegaArgs& ma, const sd2_model* md, int k_tok, const MegaLayout& ML, uint8_t* base, float* h_out) {
+    const sd2_model_shape_t& sh = md->shape;
+    ma.layers = sh.layers;
+    ma.hidden = sh.hidden;
+    ma.q_out = sh.q_out;
+    ma.kv_out = sh.kv_out;
+    ma.inter = sh.inter;
+    ma.n_heads = sh.n_heads;
+    ma.n_kv = sh.n_kv;
+    ma.head_dim = sh.head_dim;
+    ma.k_tok = k_tok;
+    // about a second of polling per barrier before the forward is given up (SD2_MEGA_SPIN_LIMIT overrides: tests)
+    ma.spin_limit = 1 << 20;
+    if (const char* sl = getenv("SD2_MEGA_SPIN_LIMIT")) ma.spin_limit = std::max(0, atoi(sl));
+    ma.h_out = h_out;
+    ma.bar = reinterpret_cast<unsigned*>(base + ML.bar_off);
+    ma.err = reinterpret_cast<unsigned*>(base + ML.err_off);
+    ma.yqkv = reinterpret_cast<float*>(base + ML.yqkv_off);
+    ma.ygu = reinterpret_cast<float*>(base + ML.ygu_off);
+    ma.hv = reinterpret_cast<float*>(base + ML.hv_off);
+    ma.h_stride = ML.h_stride;
+    ma.yqkv_stride = ML.yqkv_stride;
+    ma.ygu_stride = ML.ygu_stride;
+    for (size_t i = 0; i < md->mats.size(); ++i) ma.blob[i] = static_cast<const unsigned char*>(md->mats[i].data_dev);
+}
+
 static int forward_impl(const sd2_model_t* md, const uint16_t* h_in, int32_t k_tok, float* h_out, void* ws,
                         size_t ws_bytes, void* trace, void* stream) {
     if (!md || !h_in || !h_out || !ws) return SD2_ERR_NULL;
@@ -369,29 +396,8 @@ static int forward_impl(const sd2_model_t* md, const uint16_t* h_in, int32_t k_t
     memset(&ma, 0, sizeof(ma));
     bool nm24 = false;
     if (plan_mega_path(md, k_tok, ma.geo, &nm24)) {
-        ma.layers = sh.layers;
-        ma.hidden = sh.hidden;
-        ma.q_out = sh.q_out;
-        ma.kv_out = sh.kv_out;
-        ma.inter = sh.inter;
-        ma.n_heads = sh.n_heads;
-        ma.n_kv = sh.n_kv;
-        ma.head_dim = sh.head_dim;
-        ma.k_tok = k_tok;
-        // about a second of polling per barrier before the forward is given up (SD2_MEGA_SPIN_LIMIT overrides: tests)
-        ma.spin_limit = 1 << 20;
-        if (const char* sl = getenv("SD2_MEGA_SPIN_LIMIT")) ma.spin_limit = std::max(0, atoi(sl));
         uint8_t* base = static_cast<uint8_t*>(ws);
-        ma.h_out = h_out;
-        ma.bar = reinterpret_cast<unsigned*>(base + ML.bar_off);
-        ma.err = reinterpret_cast<unsigned*>(base + ML.err_off);
-        ma.yqkv = reinterpret_cast<float*>(base + ML.yqkv_off);
-        ma.ygu = reinterpret_cast<float*>(base + ML.ygu_off);
-        ma.hv = reinterpret_cast<float*>(base + ML.hv_off);
-        ma.h_stride = ML.h_stride;
-        ma.yqkv_stride = ML.yqkv_stride;
-        ma.ygu_stride = ML.ygu_stride;
-        for (size_t i = 0; i < md->mats.size(); ++i) ma.blob[i] = static_cast<const unsigned char*>(md->mats[i].data_dev);
+        fill_mega_args(ma, md, k_tok, ML, base, h_out);
         bool probe = false;
         if (trace) {
             const TraceLayout T = trace_layout(md, k_tok);
@@ -500,7 +506,10 @@ int sd2_sparse_drafter_forward_trace(const sd2_model_t* md, const uint16_t* h_in
 // ------------------------------------------------------------------ decode step with a key/value cache
 
 struct DecodeLayout {
-    size_t q_off, table_off, total;
+    size_t q_off, table_off;               // one launch per step: rotated queries, angle table
+    size_t mega_table_off, mega_part_off;  // single launch: angle table and partial attention results after its own workspace
+    int chunks;                            // workgroups per (key/value head, token) of the single-launch attention step, 0: not served
+    size_t total;
 };
 
 static DecodeLayout decode_layout(const sd2_model* md, int k_tok) {
@@ -508,7 +517,20 @@ static DecodeLayout decode_layout(const sd2_model* md, int k_tok) {
     DecodeLayout D;
     D.q_off = stack_layout(md, k_tok).total;
     D.table_off = D.q_off + align256((size_t)k_tok * sh.q_out * sizeof(float));
-    D.total = D.table_off + align256((size_t)k_tok * (sh.head_dim / 2 + 1) * sizeof(float2));
+    const size_t table_bytes = align256((size_t)k_tok * (sh.head_dim / 2 + 1) * sizeof(float2));
+    D.total = D.table_off + table_bytes;
+    D.chunks = 0;
+    D.mega_table_off = D.mega_part_off = 0;
+    MegaGeo geo[4];
+    if (k_tok <= kMegaMaxTok && plan_mega_path(md, k_tok, geo)) {
+        D.chunks = mega_attention_chunks(sh.n_heads, sh.n_kv, k_tok);
+        if (D.chunks > 0) {
+            D.mega_table_off = mega_layout(sh.layers, sh.hidden, sh.q_out, sh.kv_out, sh.inter, k_tok).total;
+            D.mega_part_off = D.mega_table_off + table_bytes;
+            const size_t part = (size_t)sh.layers * k_tok * sh.n_heads * D.chunks * kMegaAttPartDw * sizeof(float);
+            D.total = std::max(D.total, D.mega_part_off + align256(part));
+        }
+    }
     return D;
 }
 
@@ -518,6 +540,20 @@ int sd2_drafter_decode_workspace_size(const sd2_model_t* model, int32_t k_tok, s
     if (rc != SD2_OK) return rc;
     *bytes_out = decode_layout(model, k_tok).total;
     return SD2_OK;
+}
+
+int sd2_drafter_decode_status(const sd2_model_t* md, int32_t k_tok, const void* ws, void* stream) {
+    if (!md || !ws) return SD2_ERR_NULL;
+    int rc = check_tokens(k_tok);
+    if (rc != SD2_OK) return rc;
+    if (hipStreamSynchronize(static_cast<hipStream_t>(stream)) != hipSuccess) return SD2_ERR_HIP;
+    if (decode_layout(md, k_tok).chunks == 0) return SD2_OK;  // one launch per step: no waits inside kernels
+    const sd2_model_shape_t& sh = md->shape;
+    const MegaLayout ML = mega_layout(sh.layers, sh.hidden, sh.q_out, sh.kv_out, sh.inter, k_tok);
+    unsigned flag = 0;
+    if (hipMemcpy(&flag, static_cast<const uint8_t*>(ws) + ML.err_off, sizeof(flag), hipMemcpyDeviceToHost) != hipSuccess)
+        return SD2_ERR_HIP;
+    return flag ? SD2_ERR_TIMEOUT : SD2_OK;
 }
 
 int sd2_sparse_drafter_decode(const sd2_model_t* md, const uint16_t* h_in, int32_t k_tok, int32_t pos0, uint16_t* k_cache,
@@ -536,6 +572,26 @@ int sd2_sparse_drafter_decode(const sd2_model_t* md, const uint16_t* h_in, int32
         return SD2_ERR_BUFFER;
     hipStream_t s = static_cast<hipStream_t>(stream);
     uint8_t* base = static_cast<uint8_t*>(ws);
+    if (DL.chunks > 0) {
+        // single launch: the persistent kernel with an attention step over the cache after each q|k|v linear
+        MegaArgs ma;
+        memset(&ma, 0, sizeof(ma));
+        bool nm24 = false;
+        if (!plan_mega_path(md, k_tok, ma.geo, &nm24)) return SD2_ERR_UNSUPPORTED;
+        const MegaLayout ML = mega_layout(sh.layers, sh.hidden, sh.q_out, sh.kv_out, sh.inter, k_tok);
+        fill_mega_args(ma, md, k_tok, ML, base, h_out);
+        float2* table = reinterpret_cast<float2*>(base + DL.mega_table_off);
+        ma.k_cache = k_cache;
+        ma.v_cache = v_cache;
+        ma.rope = table;
+        ma.att_part = reinterpret_cast<float*>(base + DL.mega_part_off);
+        ma.max_pos = max_pos;
+        ma.pos0 = pos0;
+        // a stretch of about a hundred positions per workgroup (two passes of its loads), as far as the workgroups go
+        ma.att_chunks = std::max(1, std::min(DL.chunks, (pos0 + 95) / 96));
+        if (launch_rope_table(pos0, k_tok, sh.head_dim, rope_theta, table, s) != hipSuccess) return SD2_ERR_HIP;
+        return launch_mega_forward(ma, h_in, base, ML.hv_off, false, nm24, s) == hipSuccess ? SD2_OK : SD2_ERR_HIP;
+    }
     uint16_t* act = reinterpret_cast<uint16_t*>(base + L.act_off);
     float* part = reinterpret_cast<float*>(base + L.part_off);
     float* ssq = reinterpret_cast<float*>(base + L.ssq_off);

@@ -112,8 +112,18 @@ struct MegaArgs {
     int trace_kmax, trace_smax;
     unsigned long long* trace_time;  // optional [workgroup][phase][8] 100 MHz clock: start, barrier, prologue, tiles (timestamps);
                                      // wavefront 0's ticks spent waiting for streams, ticks decoding, tiles; spare
+    // Decode with a key/value cache (k_cache == nullptr: attention among the call's tokens only).  After the q|k|v
+    // linear, att_chunks workgroups per (key/value head, token) each attend to one stretch of the positions and
+    // leave a partial softmax result; the linear that follows combines them.
+    uint16_t* k_cache;    // [layers][n_kv][max_pos][128] bf16, rotated keys
+    uint16_t* v_cache;    // the same shape, values
+    const float2* rope;   // [k_tok][64] cos and sin of the call's positions
+    float* att_part;      // [layers][k_tok][n_heads][att_chunks][kMegaAttPartDw]: running maximum, sum, 2 spare, 128 sums
+    int max_pos, pos0, att_chunks, pad2;
     const unsigned char* blob[4 * kMegaMaxLayers];
 };
+constexpr int kMegaAttPartDw = 132;
+constexpr int kMegaMaxChunks = 32;
 
 struct MegaLayout {
     size_t bar_off, err_off, yqkv_off, ygu_off, hv_off, total;  // [0, hv_off) starts as zero
@@ -128,6 +138,8 @@ bool mega_plan(MegaGeo (&geo)[4], int layers, int hidden, int head_dim, int k_to
 // probe: timestamps only, plus wavefront 0's wait/decode split (needs a.trace_time, a.trace_x == nullptr)
 hipError_t launch_mega_forward(const MegaArgs& a, const uint16_t* h_in, void* zero_base, size_t zero_bytes, bool probe, bool nm24,
                                hipStream_t s);
+// Workgroups per (key/value head, token) of the cached attention step, 0 when the persistent kernel cannot serve it.
+int mega_attention_chunks(int n_heads, int n_kv, int k_tok);
 
 // ---- 2:4 semi-structured linear (blob format 3): final y for tokens [0, k_tok), k_tok <= 16; m.dir = first tile
 bool nm24_supported(int n_slabs);

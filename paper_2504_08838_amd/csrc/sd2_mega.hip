@@ -13,6 +13,8 @@
 // rebuilds in LDS exactly the bf16 activation columns its tiles need: the RMS-normed residual
 // (every workgroup sums the squares of the whole residual itself), causal attention over the
 // in-flight tokens for the heads of its slabs, or the SiLU-gated product.
+#include <algorithm>
+
 #include "sd2_device.h"
 #include "sd2_internal.h"
 
@@ -235,7 +237,214 @@ __device__ __forceinline__ void read_tile24(Tile24& t, const uint8_t* bufb, int 
     t.idx = *reinterpret_cast<const uint2*>(bufb + 4096 + 8 * lane);
 }
 
-template <bool TRACE, bool PROBE, bool NM24>
+// ---- attention over the key/value cache, one stretch of positions per workgroup
+//
+// Work item (key/value head g, token t, chunk c): the group's query heads of token t against the cache positions of
+// chunk c (the history is cut into att_chunks equal stretches; the last chunk also takes the call's own tokens
+// 0 .. t, whose keys and values come from this layer's q|k|v result: rotated, rounded to bf16 as the cache holds
+// them; the item of token t stores that token's row in the cache for later calls).  A cache row is read by 16
+// consecutive lanes (16 bytes each), a wavefront reads four consecutive rows, the workgroup 48 per pass, four passes
+// in flight.  Scores stay in registers; the running maximum is agreed across the workgroup per 192 rows (online
+// softmax), sums and weighted values meet in LDS at the end.  Result per head: maximum, sum of exponentials and the
+// unnormalised weighted values, which the workgroups of the next linear combine over the chunks.
+constexpr int kAttSo = 0, kAttMax = kMegaWaves * 4 * 128, kAttSum = kAttMax + kMegaWaves * 8;
+static_assert(kAttSum + kMegaWaves * 8 <= kXldsDw, "attention scratch fits the activation area");
+
+__device__ __forceinline__ void bf16x8_unpack(const u32x4 w, float (&f)[8]) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        f[2 * e] = __uint_as_float(w[e] << 16);
+        f[2 * e + 1] = __uint_as_float(w[e] & 0xffff0000u);
+    }
+}
+
+// dimensions 8 piece .. 8 piece + 7 of a head (fp32, 128 dimensions at `head`) after the rotation of token u
+__device__ __forceinline__ void rotated_piece(const float* __restrict__ head, const float2* __restrict__ rope, int u, int piece,
+                                              float (&out)[8]) {
+    const int d0 = 8 * piece, i0 = d0 & 63;
+    const f32x4 a0 = *reinterpret_cast<const f32x4*>(head + d0), a1 = *reinterpret_cast<const f32x4*>(head + d0 + 4);
+    const f32x4 b0 = *reinterpret_cast<const f32x4*>(head + (d0 ^ 64)), b1 = *reinterpret_cast<const f32x4*>(head + (d0 ^ 64) + 4);
+    const f32x4* cs = reinterpret_cast<const f32x4*>(rope + (size_t)u * 64 + i0);  // (cos, sin) pairs, two per load
+    const float sgn = d0 < 64 ? -1.f : 1.f;  // lower half: x cos - y sin; upper half: x cos + y sin
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const f32x4 c2 = cs[e >> 1];
+        const float co = c2[2 * (e & 1)], si = c2[2 * (e & 1) + 1];
+        const float x = e < 4 ? a0[e & 3] : a1[e & 3], y = e < 4 ? b0[e & 3] : b1[e & 3];
+        out[e] = x * co + sgn * (y * si);
+    }
+}
+
+__device__ __forceinline__ u32x4 pack_bf16x8(const float (&f)[8]) {
+    return u32x4{pack_bf16(f[0], f[1]), pack_bf16(f[2], f[3]), pack_bf16(f[4], f[5]), pack_bf16(f[6], f[7])};
+}
+
+template <int REP>
+__device__ __forceinline__ void attention_item(KArgs ka, int layer, int item, float* scratch, int tid) {
+    constexpr int D = 128, RPW = 4, RPI = kMegaWaves * RPW, UNR = 2;
+    const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int piece = lane & 15, slot = wave * RPW + (lane >> 4);
+    const int k_tok = ka->k_tok, C = ka->att_chunks, n_kv = ka->n_kv, n_heads = ka->n_heads;
+    const int rep = n_heads / n_kv;
+    const int c = item % C, t = (item / C) % k_tok, g = item / (C * k_tok);
+    const int pos0 = ka->pos0, max_pos = ka->max_pos, q_out = ka->q_out, kv_out = ka->kv_out;
+    const int nqkv = q_out + 2 * kv_out;
+    const float* yq = ka->yqkv + (size_t)layer * ka->yqkv_stride;
+    const float2* rope = ka->rope;
+    const int per = (pos0 + C - 1) / C;
+    const int j_lo = min(c * per, pos0);
+    const int j_hi = c == C - 1 ? pos0 + t + 1 : min(pos0, j_lo + per);
+    uint16_t* kc = ka->k_cache + ((size_t)layer * n_kv + g) * max_pos * D;
+    uint16_t* vc = ka->v_cache + ((size_t)layer * n_kv + g) * max_pos * D;
+    const u32x4* kg = reinterpret_cast<const u32x4*>(kc) + piece;
+    const u32x4* vg = reinterpret_cast<const u32x4*>(vc) + piece;
+    float* so = scratch + kAttSo;
+    float* smax = scratch + kAttMax;
+    float* ssum = scratch + kAttSum;
+    const float scale = 0.08838834764831845f;  // 1 / sqrt(128)
+
+    // The call's own tokens 0 .. t (last chunk only): keys rotated, keys and values rounded to bf16 as the cache holds
+    // them, kept in LDS for the loop below; token t's row also goes to the cache, for later calls.
+    u32x4* own_k = reinterpret_cast<u32x4*>(scratch);  // [kMegaMaxTok][16 pieces]
+    u32x4* own_v = own_k + kMegaMaxTok * 16;
+    if (c == C - 1 && slot <= t) {
+        const int tok = slot;
+        float f[8];
+        rotated_piece(yq + (size_t)tok * nqkv + q_out + (size_t)g * D, rope, tok, piece, f);
+        const u32x4 pk = pack_bf16x8(f);
+        own_k[tok * 16 + piece] = pk;
+        const float* src = yq + (size_t)tok * nqkv + q_out + kv_out + (size_t)g * D + 8 * piece;
+        const f32x4 v0 = *reinterpret_cast<const f32x4*>(src), v1 = *reinterpret_cast<const f32x4*>(src + 4);
+        const u32x4 pv = u32x4{pack_bf16(v0[0], v0[1]), pack_bf16(v0[2], v0[3]), pack_bf16(v1[0], v1[1]), pack_bf16(v1[2], v1[3])};
+        own_v[tok * 16 + piece] = pv;
+        if (tok == t) {
+            *reinterpret_cast<u32x4*>(kc + (size_t)(pos0 + t) * D + 8 * piece) = pk;
+            *reinterpret_cast<u32x4*>(vc + (size_t)(pos0 + t) * D + 8 * piece) = pv;
+        }
+    }
+
+    // the group's queries of token t, rotated and scaled, in LDS behind those rows: [REP][128] floats, read back
+    // piece by piece in the loop (registers go to the running sums instead)
+    f32x4* sq = reinterpret_cast<f32x4*>(scratch + 2 * kMegaMaxTok * 64);
+    if (slot < REP) {
+        float f[8];
+        rotated_piece(yq + (size_t)t * nqkv + (size_t)(g * rep + min(slot, rep - 1)) * D, rope, t, piece, f);
+        sq[slot * 32 + 2 * piece] = f32x4{f[0] * scale, f[1] * scale, f[2] * scale, f[3] * scale};
+        sq[slot * 32 + 2 * piece + 1] = f32x4{f[4] * scale, f[5] * scale, f[6] * scale, f[7] * scale};
+    }
+    __syncthreads();
+    float M[REP], L[REP], acc[REP][8];
+#pragma unroll
+    for (int r = 0; r < REP; ++r) {
+        M[r] = -3.0e38f;
+        L[r] = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[r][e] = 0.f;
+    }
+    for (int base = j_lo; base < j_hi; base += RPI * UNR) {
+        u32x4 w[UNR];
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) {
+            const int j = base + u * RPI + slot;
+            w[u] = j >= j_hi ? u32x4{0u, 0u, 0u, 0u} : (j < pos0 ? kg[(size_t)j * 16] : own_k[(j - pos0) * 16 + piece]);
+        }
+        float sdot[REP][UNR], mx[REP];
+#pragma unroll
+        for (int r = 0; r < REP; ++r) mx[r] = -3.0e38f;
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) {
+            const int j = base + u * RPI + slot;
+            float kf[8];
+            bf16x8_unpack(w[u], kf);
+#pragma unroll
+            for (int r = 0; r < REP; ++r) {
+                const f32x4 q0 = sq[r * 32 + 2 * piece], q1 = sq[r * 32 + 2 * piece + 1];
+                float dot = 0.f;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) dot += kf[e] * q0[e] + kf[4 + e] * q1[e];
+                dot += __shfl_xor(dot, 1);
+                dot += __shfl_xor(dot, 2);
+                dot += __shfl_xor(dot, 4);
+                dot += __shfl_xor(dot, 8);
+                sdot[r][u] = j < j_hi ? dot : -3.0e38f;
+                mx[r] = fmaxf(mx[r], sdot[r][u]);
+            }
+        }
+#pragma unroll
+        for (int r = 0; r < REP; ++r) {
+            float m = fmaxf(mx[r], __shfl_xor(mx[r], 16));
+            m = fmaxf(m, __shfl_xor(m, 32));
+            if (lane == 0) smax[wave * 8 + r] = m;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int r = 0; r < REP; ++r) {
+            float m = M[r];
+#pragma unroll
+            for (int ww = 0; ww < kMegaWaves; ++ww) m = fmaxf(m, smax[ww * 8 + r]);
+            const float f = __expf(M[r] - m);
+            M[r] = m;
+            L[r] *= f;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc[r][e] *= f;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) {
+            const int j = base + u * RPI + slot;
+            w[u] = j >= j_hi ? u32x4{0u, 0u, 0u, 0u} : (j < pos0 ? vg[(size_t)j * 16] : own_v[(j - pos0) * 16 + piece]);
+        }
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) {
+            const int j = base + u * RPI + slot;
+            float vf[8];
+            bf16x8_unpack(w[u], vf);
+#pragma unroll
+            for (int r = 0; r < REP; ++r) {
+                const float pr = j < j_hi ? __expf(sdot[r][u] - M[r]) : 0.f;
+                L[r] += pr;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) acc[r][e] += pr * vf[e];
+            }
+        }
+    }
+    __syncthreads();  // the rows of the call's own tokens share LDS with the sums below
+    // the sixteen lanes of a row all counted its weight: a wavefront's total is the sum over its lanes / 16
+#pragma unroll
+    for (int r = 0; r < REP; ++r) {
+        const float l = wave_sum(L[r]) * 0.0625f;
+        if (lane == 0) {
+            ssum[wave * 8 + r] = l;
+            if (wave == 0) smax[r] = M[r];  // the same in every thread
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            float v = acc[r][e];
+            v += __shfl_xor(v, 16);
+            v += __shfl_xor(v, 32);
+            if (lane < 16) so[(wave * 4 + r) * D + 8 * piece + e] = v;
+        }
+    }
+    __syncthreads();
+    for (int idx = tid; idx < rep * D; idx += kMegaThreads) {
+        const int r = idx >> 7, d = idx & 127;
+        float o = 0.f;
+#pragma unroll
+        for (int ww = 0; ww < kMegaWaves; ++ww) o += so[(ww * 4 + r) * D + d];
+        float* dst = ka->att_part + ((((size_t)layer * k_tok + t) * n_heads + (size_t)g * rep + r) * C + c) * kMegaAttPartDw;
+        astore(dst + 4 + d, o);
+        if (d == 0) {
+            float l = 0.f;
+#pragma unroll
+            for (int ww = 0; ww < kMegaWaves; ++ww) l += ssum[ww * 8 + r];
+            astore(dst, smax[r]);
+            astore(dst + 1, l);
+        }
+    }
+    __syncthreads();
+}
+
+template <bool TRACE, bool PROBE, bool NM24, bool KV = false>
 __global__ __launch_bounds__(kMegaThreads) void mega_forward_kernel(const MegaArgs a) {
     extern __shared__ uint32_t mega_lds[];
     __shared__ uint2 lut[16];
@@ -314,6 +523,27 @@ __global__ __launch_bounds__(kMegaThreads) void mega_forward_kernel(const MegaAr
         if (p > 0) barrier_arrive(a.bar, gen);
         // next phase's tiles: planned now so that the directory loads have the whole phase to arrive
         plan_phase<NM24>(nt, ka, plans, p + 1, n_phases, wave, lane);
+
+        if (KV && kind == 1) {
+            // q, k and v of this layer are complete: the attention step over the cache, then a barrier of its own;
+            // the first tile of the linear is expanded while that one settles
+            barrier_wait(a.bar, a.err, (unsigned)ncu, gen, spin_limit);
+            if (cu < a.n_kv * k_tok * a.att_chunks) {
+                // register arrays sized for the group's query heads (wave-uniform choice)
+                const int rep = a.n_heads / a.n_kv;
+                if (rep == 1)
+                    attention_item<1>(ka, layer, cu, reinterpret_cast<float*>(xlds), tid);
+                else if (rep == 2)
+                    attention_item<2>(ka, layer, cu, reinterpret_cast<float*>(xlds), tid);
+                else if (rep == 3)
+                    attention_item<3>(ka, layer, cu, reinterpret_cast<float*>(xlds), tid);
+                else
+                    attention_item<4>(ka, layer, cu, reinterpret_cast<float*>(xlds), tid);
+            }
+            // the scratch was the activation area, whose rows of unused token slots must read as zero
+            for (int i = tid; i < kXldsDw; i += kMegaThreads) (mega_lds + kAreaDw)[i] = 0u;
+            barrier_arrive(a.bar, gen);
+        }
 
         // Waits for tile j's stream, requests the stream of the tile after it (the next one of this phase, else the
         // first one of the next phase: weights do not depend on activations) and returns what the expansion needs.
@@ -466,6 +696,47 @@ __global__ __launch_bounds__(kMegaThreads) void mega_forward_kernel(const MegaAr
                             *reinterpret_cast<f32x2*>(ts + a.inter) = uv[t];
                             *reinterpret_cast<uint32_t*>(a.trace_x + tr_x + (size_t)t * a.trace_kmax + col_lo + c) = pk;
                         }
+                    }
+            }
+        } else if (KV) {
+            // kind == 1 with a cache: the attention step left, per head, token and chunk, a maximum, a sum and 128
+            // weighted values; thread (head slot hh, dimension d) combines the chunks of its head
+            const int D = 128;
+            const int hh = wave >> 1, d = (wave & 1) * 64 + lane;
+            const int head = col_lo / D + hh;
+            if (hh * D < n_col) {
+                const int cc = hh * D + d, C = a.att_chunks;
+#pragma unroll
+                for (int t = 0; t < kMegaMaxTok; ++t)
+                    if (t < k_tok) {
+                        const float* pp = a.att_part + (((size_t)layer * k_tok + t) * a.n_heads + head) * C * kMegaAttPartDw;
+                        // eight chunks at a time: their loads are in flight together, the running maximum rescales
+                        float mx = -3.0e38f, num = 0.f, den = 0.f;
+                        for (int c0 = 0; c0 < C; c0 += 8) {
+                            float pm[8], pl[8], po[8];
+#pragma unroll
+                            for (int i = 0; i < 8; ++i) {
+                                const float* q = pp + min(c0 + i, C - 1) * kMegaAttPartDw;
+                                pm[i] = q[0];
+                                pl[i] = q[1];
+                                po[i] = q[4 + d];
+                            }
+                            float gm = mx;
+#pragma unroll
+                            for (int i = 0; i < 8; ++i)
+                                if (c0 + i < C) gm = fmaxf(gm, pm[i]);
+                            const float f = __expf(mx - gm);
+                            num *= f;
+                            den *= f;
+                            mx = gm;
+#pragma unroll
+                            for (int i = 0; i < 8; ++i) {
+                                const float wgt = c0 + i < C ? __expf(pm[i] - mx) : 0.f;
+                                num += wgt * po[i];
+                                den += wgt * pl[i];
+                            }
+                        }
+                        xlds[((cc >> 8) * kMegaMaxTok + t) * kXRow + (cc & 255)] = f32_to_bf16(num * __builtin_amdgcn_rcpf(den));
                     }
             }
         } else {
@@ -698,13 +969,19 @@ static int mega_grid() {
             hipFuncSetAttribute(reinterpret_cast<const void*>(mega_forward_kernel<false, false, true>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMegaLds) == hipSuccess &&
             hipFuncSetAttribute(reinterpret_cast<const void*>(mega_forward_kernel<true, false, true>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMegaLds) == hipSuccess &&
+            hipFuncSetAttribute(reinterpret_cast<const void*>(mega_forward_kernel<false, false, false, true>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMegaLds) == hipSuccess &&
+            hipFuncSetAttribute(reinterpret_cast<const void*>(mega_forward_kernel<false, false, true, true>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMegaLds) == hipSuccess) {
-            int per_cu = 0, per_cu_t = 0, per_cu_s = 0, per_cu_st = 0;
+            int per_cu = 0, per_cu_t = 0, per_cu_s = 0, per_cu_st = 0, per_cu_k = 0, per_cu_sk = 0;
             if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, mega_forward_kernel<false, false, false>, kMegaThreads, kMegaLds) == hipSuccess &&
                 hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu_t, mega_forward_kernel<true, false, false>, kMegaThreads, kMegaLds) == hipSuccess &&
                 hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu_s, mega_forward_kernel<false, false, true>, kMegaThreads, kMegaLds) == hipSuccess &&
                 hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu_st, mega_forward_kernel<true, false, true>, kMegaThreads, kMegaLds) == hipSuccess &&
-                per_cu >= 1 && per_cu_t >= 1 && per_cu_s >= 1 && per_cu_st >= 1)
+                hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu_k, mega_forward_kernel<false, false, false, true>, kMegaThreads, kMegaLds) == hipSuccess &&
+                hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu_sk, mega_forward_kernel<false, false, true, true>, kMegaThreads, kMegaLds) == hipSuccess &&
+                per_cu >= 1 && per_cu_t >= 1 && per_cu_s >= 1 && per_cu_st >= 1 && per_cu_k >= 1 && per_cu_sk >= 1)
                 cus = n;
         }
     }
@@ -758,6 +1035,12 @@ bool mega_plan(MegaGeo (&geo)[4], int layers, int hidden, int head_dim, int k_to
     return true;
 }
 
+int mega_attention_chunks(int n_heads, int n_kv, int k_tok) {
+    const int ncu = mega_grid();
+    if (ncu < 1 || n_kv < 1 || k_tok < 1 || n_heads % n_kv || n_heads / n_kv > 4) return 0;
+    return std::max(0, std::min(kMegaMaxChunks, ncu / (n_kv * k_tok)));
+}
+
 hipError_t launch_mega_forward(const MegaArgs& a, const uint16_t* h_in, void* zero_base, size_t zero_bytes, bool probe,
                                bool nm24, hipStream_t s) {
     const int ncu = mega_grid();
@@ -770,7 +1053,13 @@ hipError_t launch_mega_forward(const MegaArgs& a, const uint16_t* h_in, void* ze
     MegaArgs args = a;
     void* params[] = {&args};
     const void* fn;
-    if (nm24)
+    if (a.k_cache) {
+        if (a.trace_x || a.trace_time || probe || a.att_chunks < 1 || a.att_chunks > kMegaMaxChunks ||
+            a.n_kv * a.k_tok * a.att_chunks > ncu || a.n_heads > 4 * a.n_kv || !a.v_cache || !a.rope || !a.att_part)
+            return hipErrorInvalidValue;
+        fn = nm24 ? reinterpret_cast<const void*>(mega_forward_kernel<false, false, true, true>)
+                  : reinterpret_cast<const void*>(mega_forward_kernel<false, false, false, true>);
+    } else if (nm24)
         fn = a.trace_x ? reinterpret_cast<const void*>(mega_forward_kernel<true, false, true>)
                        : reinterpret_cast<const void*>(mega_forward_kernel<false, false, true>);
     else
