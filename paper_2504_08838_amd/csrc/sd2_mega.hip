@@ -279,60 +279,103 @@ __device__ __forceinline__ u32x4 pack_bf16x8(const float (&f)[8]) {
     return u32x4{pack_bf16(f[0], f[1]), pack_bf16(f[2], f[3]), pack_bf16(f[4], f[5]), pack_bf16(f[6], f[7])};
 }
 
-template <int REP>
-__device__ __forceinline__ void attention_item(KArgs ka, int layer, int item, float* scratch, int tid) {
-    constexpr int D = 128, RPW = 4, RPI = kMegaWaves * RPW, UNR = 2;
+// Workgroup barrier that orders LDS traffic only: the wavefront's own LDS operations have completed, loads and stores
+// to memory stay in flight (a __syncthreads would also wait for every store acknowledgement: about a microsecond).
+__device__ __forceinline__ void lds_barrier() {
+    __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+}
+
+constexpr int kAttUnr = 2;                 // passes of a workgroup's cache loads in flight
+constexpr int kAttRpi = kMegaWaves * 4;    // cache rows per pass: four per wavefront
+
+struct AttItem {
+    int c, t, g;     // chunk, token, key/value head
+    int j_lo, j_hi;  // positions [j_lo, j_hi): cache rows below pos0, the call's own tokens from pos0 on
+};
+
+__device__ __forceinline__ AttItem att_geometry(KArgs ka, int item) {
+    const int k_tok = ka->k_tok, C = ka->att_chunks, pos0 = ka->pos0;
+    AttItem it;
+    it.c = item % C;
+    it.t = (item / C) % k_tok;
+    it.g = item / (C * k_tok);
+    const int per = (pos0 + C - 1) / C;
+    it.j_lo = min(it.c * per, pos0);
+    it.j_hi = it.c == C - 1 ? pos0 + it.t + 1 : min(pos0, it.j_lo + per);
+    return it;
+}
+
+// The cache rows of one pass group starting at `base` (this lane's 16 bytes of each): nothing of them depends on the
+// current layer, so the first group is requested before the barrier that completes q|k|v.
+__device__ __forceinline__ void attention_loads(KArgs ka, int layer, const AttItem& it, int base, int tid, u32x4 (&kw)[kAttUnr],
+                                                u32x4 (&vw)[kAttUnr]) {
     const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int piece = lane & 15, slot = wave * RPW + (lane >> 4);
+    const int piece = lane & 15, slot = wave * 4 + (lane >> 4);
+    const size_t head = ((size_t)layer * ka->n_kv + it.g) * ka->max_pos * 128;
+    const u32x4* kg = reinterpret_cast<const u32x4*>(ka->k_cache + head) + piece;
+    const u32x4* vg = reinterpret_cast<const u32x4*>(ka->v_cache + head) + piece;
+    const int lim = min(it.j_hi, ka->pos0);
+#pragma unroll
+    for (int u = 0; u < kAttUnr; ++u) {
+        const int j = base + u * kAttRpi + slot;
+        kw[u] = j < lim ? kg[(size_t)j * 16] : u32x4{0u, 0u, 0u, 0u};
+        vw[u] = j < lim ? vg[(size_t)j * 16] : u32x4{0u, 0u, 0u, 0u};
+    }
+}
+
+template <int REP>
+__device__ __forceinline__ void attention_item(KArgs ka, int layer, const AttItem& it, float* scratch, int tid,
+                                               u32x4 (&kw)[kAttUnr], u32x4 (&vw)[kAttUnr]) {
+    constexpr int D = 128, RPI = kAttRpi, UNR = kAttUnr;
+    const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int piece = lane & 15, slot = wave * 4 + (lane >> 4);
     const int k_tok = ka->k_tok, C = ka->att_chunks, n_kv = ka->n_kv, n_heads = ka->n_heads;
     const int rep = n_heads / n_kv;
-    const int c = item % C, t = (item / C) % k_tok, g = item / (C * k_tok);
+    const int c = it.c, t = it.t, g = it.g, j_lo = it.j_lo, j_hi = it.j_hi;
     const int pos0 = ka->pos0, max_pos = ka->max_pos, q_out = ka->q_out, kv_out = ka->kv_out;
     const int nqkv = q_out + 2 * kv_out;
     const float* yq = ka->yqkv + (size_t)layer * ka->yqkv_stride;
     const float2* rope = ka->rope;
-    const int per = (pos0 + C - 1) / C;
-    const int j_lo = min(c * per, pos0);
-    const int j_hi = c == C - 1 ? pos0 + t + 1 : min(pos0, j_lo + per);
-    uint16_t* kc = ka->k_cache + ((size_t)layer * n_kv + g) * max_pos * D;
-    uint16_t* vc = ka->v_cache + ((size_t)layer * n_kv + g) * max_pos * D;
-    const u32x4* kg = reinterpret_cast<const u32x4*>(kc) + piece;
-    const u32x4* vg = reinterpret_cast<const u32x4*>(vc) + piece;
     float* so = scratch + kAttSo;
     float* smax = scratch + kAttMax;
     float* ssum = scratch + kAttSum;
     const float scale = 0.08838834764831845f;  // 1 / sqrt(128)
 
-    // The call's own tokens 0 .. t (last chunk only): keys rotated, keys and values rounded to bf16 as the cache holds
-    // them, kept in LDS for the loop below; token t's row also goes to the cache, for later calls.
+    // One rotation per row slot, all requested at once: slots below REP take the group's queries of token t (scaled,
+    // kept in LDS as [REP][128] floats and read back piece by piece in the loop: registers go to the running sums);
+    // in the last chunk the next t + 1 slots take the call's own tokens 0 .. t: key rotated, key and value rounded to
+    // bf16 as the cache holds them, kept in LDS for the loop; token t's row also goes to the cache, for later calls.
     u32x4* own_k = reinterpret_cast<u32x4*>(scratch);  // [kMegaMaxTok][16 pieces]
     u32x4* own_v = own_k + kMegaMaxTok * 16;
-    if (c == C - 1 && slot <= t) {
-        const int tok = slot;
+    f32x4* sq = reinterpret_cast<f32x4*>(scratch + 2 * kMegaMaxTok * 64);
+    const int n_own = c == C - 1 ? t + 1 : 0;
+    if (slot < REP + n_own) {
+        const bool is_q = slot < REP;
+        const int tok = is_q ? t : slot - REP;
+        const float* head = yq + (size_t)tok * nqkv + (is_q ? (size_t)(g * rep + min(slot, rep - 1)) * D : q_out + (size_t)g * D);
         float f[8];
-        rotated_piece(yq + (size_t)tok * nqkv + q_out + (size_t)g * D, rope, tok, piece, f);
-        const u32x4 pk = pack_bf16x8(f);
-        own_k[tok * 16 + piece] = pk;
-        const float* src = yq + (size_t)tok * nqkv + q_out + kv_out + (size_t)g * D + 8 * piece;
-        const f32x4 v0 = *reinterpret_cast<const f32x4*>(src), v1 = *reinterpret_cast<const f32x4*>(src + 4);
-        const u32x4 pv = u32x4{pack_bf16(v0[0], v0[1]), pack_bf16(v0[2], v0[3]), pack_bf16(v1[0], v1[1]), pack_bf16(v1[2], v1[3])};
-        own_v[tok * 16 + piece] = pv;
-        if (tok == t) {
-            *reinterpret_cast<u32x4*>(kc + (size_t)(pos0 + t) * D + 8 * piece) = pk;
-            *reinterpret_cast<u32x4*>(vc + (size_t)(pos0 + t) * D + 8 * piece) = pv;
+        rotated_piece(head, rope, tok, piece, f);
+        if (is_q) {
+            sq[slot * 32 + 2 * piece] = f32x4{f[0] * scale, f[1] * scale, f[2] * scale, f[3] * scale};
+            sq[slot * 32 + 2 * piece + 1] = f32x4{f[4] * scale, f[5] * scale, f[6] * scale, f[7] * scale};
+        } else {
+            const float* src = head + kv_out + 8 * piece;  // the value head sits kv_out floats after the key head
+            const f32x4 v0 = *reinterpret_cast<const f32x4*>(src), v1 = *reinterpret_cast<const f32x4*>(src + 4);
+            const u32x4 pk = pack_bf16x8(f);
+            const u32x4 pv = u32x4{pack_bf16(v0[0], v0[1]), pack_bf16(v0[2], v0[3]), pack_bf16(v1[0], v1[1]), pack_bf16(v1[2], v1[3])};
+            own_k[tok * 16 + piece] = pk;
+            own_v[tok * 16 + piece] = pv;
+            if (tok == t) {
+                const size_t at = (((size_t)layer * n_kv + g) * max_pos + (size_t)(pos0 + t)) * D + 8 * piece;
+                *reinterpret_cast<u32x4*>(ka->k_cache + at) = pk;
+                *reinterpret_cast<u32x4*>(ka->v_cache + at) = pv;
+            }
         }
     }
+    lds_barrier();
 
-    // the group's queries of token t, rotated and scaled, in LDS behind those rows: [REP][128] floats, read back
-    // piece by piece in the loop (registers go to the running sums instead)
-    f32x4* sq = reinterpret_cast<f32x4*>(scratch + 2 * kMegaMaxTok * 64);
-    if (slot < REP) {
-        float f[8];
-        rotated_piece(yq + (size_t)t * nqkv + (size_t)(g * rep + min(slot, rep - 1)) * D, rope, t, piece, f);
-        sq[slot * 32 + 2 * piece] = f32x4{f[0] * scale, f[1] * scale, f[2] * scale, f[3] * scale};
-        sq[slot * 32 + 2 * piece + 1] = f32x4{f[4] * scale, f[5] * scale, f[6] * scale, f[7] * scale};
-    }
-    __syncthreads();
     float M[REP], L[REP], acc[REP][8];
 #pragma unroll
     for (int r = 0; r < REP; ++r) {
@@ -342,12 +385,7 @@ __device__ __forceinline__ void attention_item(KArgs ka, int layer, int item, fl
         for (int e = 0; e < 8; ++e) acc[r][e] = 0.f;
     }
     for (int base = j_lo; base < j_hi; base += RPI * UNR) {
-        u32x4 w[UNR];
-#pragma unroll
-        for (int u = 0; u < UNR; ++u) {
-            const int j = base + u * RPI + slot;
-            w[u] = j >= j_hi ? u32x4{0u, 0u, 0u, 0u} : (j < pos0 ? kg[(size_t)j * 16] : own_k[(j - pos0) * 16 + piece]);
-        }
+        if (base != j_lo) attention_loads(ka, layer, it, base, tid, kw, vw);  // the first group is already on its way
         float sdot[REP][UNR], mx[REP];
 #pragma unroll
         for (int r = 0; r < REP; ++r) mx[r] = -3.0e38f;
@@ -355,7 +393,7 @@ __device__ __forceinline__ void attention_item(KArgs ka, int layer, int item, fl
         for (int u = 0; u < UNR; ++u) {
             const int j = base + u * RPI + slot;
             float kf[8];
-            bf16x8_unpack(w[u], kf);
+            bf16x8_unpack((j >= pos0 && j < j_hi) ? own_k[(j - pos0) * 16 + piece] : kw[u], kf);
 #pragma unroll
             for (int r = 0; r < REP; ++r) {
                 const f32x4 q0 = sq[r * 32 + 2 * piece], q1 = sq[r * 32 + 2 * piece + 1];
@@ -376,11 +414,11 @@ __device__ __forceinline__ void attention_item(KArgs ka, int layer, int item, fl
             m = fmaxf(m, __shfl_xor(m, 32));
             if (lane == 0) smax[wave * 8 + r] = m;
         }
-        __syncthreads();
+        lds_barrier();
 #pragma unroll
         for (int r = 0; r < REP; ++r) {
             float m = M[r];
-#pragma unroll
+#pragma unroll 4
             for (int ww = 0; ww < kMegaWaves; ++ww) m = fmaxf(m, smax[ww * 8 + r]);
             const float f = __expf(M[r] - m);
             M[r] = m;
@@ -388,17 +426,12 @@ __device__ __forceinline__ void attention_item(KArgs ka, int layer, int item, fl
 #pragma unroll
             for (int e = 0; e < 8; ++e) acc[r][e] *= f;
         }
-        __syncthreads();
-#pragma unroll
-        for (int u = 0; u < UNR; ++u) {
-            const int j = base + u * RPI + slot;
-            w[u] = j >= j_hi ? u32x4{0u, 0u, 0u, 0u} : (j < pos0 ? vg[(size_t)j * 16] : own_v[(j - pos0) * 16 + piece]);
-        }
+        lds_barrier();
 #pragma unroll
         for (int u = 0; u < UNR; ++u) {
             const int j = base + u * RPI + slot;
             float vf[8];
-            bf16x8_unpack(w[u], vf);
+            bf16x8_unpack((j >= pos0 && j < j_hi) ? own_v[(j - pos0) * 16 + piece] : vw[u], vf);
 #pragma unroll
             for (int r = 0; r < REP; ++r) {
                 const float pr = j < j_hi ? __expf(sdot[r][u] - M[r]) : 0.f;
@@ -408,7 +441,7 @@ __device__ __forceinline__ void attention_item(KArgs ka, int layer, int item, fl
             }
         }
     }
-    __syncthreads();  // the rows of the call's own tokens share LDS with the sums below
+    lds_barrier();  // the rows of the call's own tokens and the queries share LDS with the sums below
     // the sixteen lanes of a row all counted its weight: a wavefront's total is the sum over its lanes / 16
 #pragma unroll
     for (int r = 0; r < REP; ++r) {
@@ -425,26 +458,26 @@ __device__ __forceinline__ void attention_item(KArgs ka, int layer, int item, fl
             if (lane < 16) so[(wave * 4 + r) * D + 8 * piece + e] = v;
         }
     }
-    __syncthreads();
+    lds_barrier();
     for (int idx = tid; idx < rep * D; idx += kMegaThreads) {
         const int r = idx >> 7, d = idx & 127;
         float o = 0.f;
-#pragma unroll
+#pragma unroll 4
         for (int ww = 0; ww < kMegaWaves; ++ww) o += so[(ww * 4 + r) * D + d];
         float* dst = ka->att_part + ((((size_t)layer * k_tok + t) * n_heads + (size_t)g * rep + r) * C + c) * kMegaAttPartDw;
         astore(dst + 4 + d, o);
         if (d == 0) {
             float l = 0.f;
-#pragma unroll
+#pragma unroll 4
             for (int ww = 0; ww < kMegaWaves; ++ww) l += ssum[ww * 8 + r];
             astore(dst, smax[r]);
             astore(dst + 1, l);
         }
     }
-    __syncthreads();
+    lds_barrier();
 }
 
-template <bool TRACE, bool PROBE, bool NM24, bool KV = false>
+template <bool TRACE, bool PROBE, bool NM24, int KV = 0>
 __global__ __launch_bounds__(kMegaThreads) void mega_forward_kernel(const MegaArgs a) {
     extern __shared__ uint32_t mega_lds[];
     __shared__ uint2 lut[16];
@@ -525,23 +558,20 @@ __global__ __launch_bounds__(kMegaThreads) void mega_forward_kernel(const MegaAr
         plan_phase<NM24>(nt, ka, plans, p + 1, n_phases, wave, lane);
 
         if (KV && kind == 1) {
-            // q, k and v of this layer are complete: the attention step over the cache, then a barrier of its own;
-            // the first tile of the linear is expanded while that one settles
+            // The attention step over the cache, then a barrier of its own; the first tile of the linear is expanded
+            // while that one settles.  The item's first cache rows are requested before q, k and v are complete.
+            const bool has_item = cu < a.n_kv * k_tok * a.att_chunks;
+            const AttItem it = att_geometry(ka, has_item ? cu : 0);
+            u32x4 kw[kAttUnr], vw[kAttUnr];
+#pragma unroll
+            for (int u = 0; u < kAttUnr; ++u) kw[u] = vw[u] = u32x4{0u, 0u, 0u, 0u};
+            if (has_item) attention_loads(ka, layer, it, it.j_lo, tid, kw, vw);
             barrier_wait(a.bar, a.err, (unsigned)ncu, gen, spin_limit);
-            if (cu < a.n_kv * k_tok * a.att_chunks) {
-                // register arrays sized for the group's query heads (wave-uniform choice)
-                const int rep = a.n_heads / a.n_kv;
-                if (rep == 1)
-                    attention_item<1>(ka, layer, cu, reinterpret_cast<float*>(xlds), tid);
-                else if (rep == 2)
-                    attention_item<2>(ka, layer, cu, reinterpret_cast<float*>(xlds), tid);
-                else if (rep == 3)
-                    attention_item<3>(ka, layer, cu, reinterpret_cast<float*>(xlds), tid);
-                else
-                    attention_item<4>(ka, layer, cu, reinterpret_cast<float*>(xlds), tid);
+            if (has_item) {
+                attention_item<(KV > 0 ? KV : 1)>(ka, layer, it, reinterpret_cast<float*>(xlds), tid, kw, vw);
+                // the scratch was the activation area, whose rows of unused token slots must read as zero
+                for (int i = tid; i < kXldsDw; i += kMegaThreads) (mega_lds + kAreaDw)[i] = 0u;
             }
-            // the scratch was the activation area, whose rows of unused token slots must read as zero
-            for (int i = tid; i < kXldsDw; i += kMegaThreads) (mega_lds + kAreaDw)[i] = 0u;
             barrier_arrive(a.bar, gen);
         }
 
@@ -952,6 +982,35 @@ MegaLayout mega_layout(int layers, int hidden, int q_out, int kv_out, int inter,
     return L;
 }
 
+// The kernel with the attention step over a cache, compiled per number of query heads per key/value head (its
+// register arrays have that size, and one variant per kernel keeps the code within the instruction cache).
+static const void* mega_kv_kernel(bool nm24, int rep) {
+#define SD2_KV_CASE(R) \
+    case R: \
+        return nm24 ? reinterpret_cast<const void*>(mega_forward_kernel<false, false, true, R>) \
+                    : reinterpret_cast<const void*>(mega_forward_kernel<false, false, false, R>)
+    switch (rep) {
+        SD2_KV_CASE(1);
+        SD2_KV_CASE(2);
+        SD2_KV_CASE(3);
+        SD2_KV_CASE(4);
+    }
+#undef SD2_KV_CASE
+    return nullptr;
+}
+
+static bool mega_kv_kernels_fit() {
+    for (int nm24 = 0; nm24 < 2; ++nm24)
+        for (int rep = 1; rep <= 4; ++rep) {
+            const void* fn = mega_kv_kernel(nm24 != 0, rep);
+            int per_cu = 0;
+            if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMegaLds) != hipSuccess ||
+                hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, kMegaThreads, kMegaLds) != hipSuccess || per_cu < 1)
+                return false;
+        }
+    return true;
+}
+
 static int mega_grid() {
     static int cus = -1;
     if (cus < 0) {
@@ -970,18 +1029,13 @@ static int mega_grid() {
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMegaLds) == hipSuccess &&
             hipFuncSetAttribute(reinterpret_cast<const void*>(mega_forward_kernel<true, false, true>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMegaLds) == hipSuccess &&
-            hipFuncSetAttribute(reinterpret_cast<const void*>(mega_forward_kernel<false, false, false, true>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMegaLds) == hipSuccess &&
-            hipFuncSetAttribute(reinterpret_cast<const void*>(mega_forward_kernel<false, false, true, true>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMegaLds) == hipSuccess) {
-            int per_cu = 0, per_cu_t = 0, per_cu_s = 0, per_cu_st = 0, per_cu_k = 0, per_cu_sk = 0;
+            mega_kv_kernels_fit()) {
+            int per_cu = 0, per_cu_t = 0, per_cu_s = 0, per_cu_st = 0;
             if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, mega_forward_kernel<false, false, false>, kMegaThreads, kMegaLds) == hipSuccess &&
                 hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu_t, mega_forward_kernel<true, false, false>, kMegaThreads, kMegaLds) == hipSuccess &&
                 hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu_s, mega_forward_kernel<false, false, true>, kMegaThreads, kMegaLds) == hipSuccess &&
                 hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu_st, mega_forward_kernel<true, false, true>, kMegaThreads, kMegaLds) == hipSuccess &&
-                hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu_k, mega_forward_kernel<false, false, false, true>, kMegaThreads, kMegaLds) == hipSuccess &&
-                hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu_sk, mega_forward_kernel<false, false, true, true>, kMegaThreads, kMegaLds) == hipSuccess &&
-                per_cu >= 1 && per_cu_t >= 1 && per_cu_s >= 1 && per_cu_st >= 1 && per_cu_k >= 1 && per_cu_sk >= 1)
+                per_cu >= 1 && per_cu_t >= 1 && per_cu_s >= 1 && per_cu_st >= 1)
                 cus = n;
         }
     }
@@ -1057,8 +1111,8 @@ hipError_t launch_mega_forward(const MegaArgs& a, const uint16_t* h_in, void* ze
         if (a.trace_x || a.trace_time || probe || a.att_chunks < 1 || a.att_chunks > kMegaMaxChunks ||
             a.n_kv * a.k_tok * a.att_chunks > ncu || a.n_heads > 4 * a.n_kv || !a.v_cache || !a.rope || !a.att_part)
             return hipErrorInvalidValue;
-        fn = nm24 ? reinterpret_cast<const void*>(mega_forward_kernel<false, false, true, true>)
-                  : reinterpret_cast<const void*>(mega_forward_kernel<false, false, false, true>);
+        fn = mega_kv_kernel(nm24, a.n_heads / a.n_kv);
+        if (!fn) return hipErrorInvalidValue;
     } else if (nm24)
         fn = a.trace_x ? reinterpret_cast<const void*>(mega_forward_kernel<true, false, true>)
                        : reinterpret_cast<const void*>(mega_forward_kernel<false, false, true>);
