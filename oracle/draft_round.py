@@ -33,3 +33,22 @@ def draft_round(shape, weight_bits, emb_bits: np.ndarray, t_start: int, k: int, 
         logits_all.append(logits[0])
         window.append(int(forced[i]) if forced is not None else int(tok[0]))
     return np.asarray(ids, dtype=np.int32), np.stack(logits_all)
+
+
+def draft_round_cached(shape, weight_bits, emb_bits: np.ndarray, t_start: int, k: int, k_cache_bits, v_cache_bits,
+                       pos0: int, theta: float, forced=None):
+    """The round against a key/value cache (rotary embedding, history of pos0 positions): k single-token decode steps.
+
+    The start token sits at position pos0; step i embeds one token (t_start, then the token chosen -- or forced --
+    at step i - 1), runs oracle/decode.py on it at position pos0 + i (which appends its key and value to the caches,
+    updated in place) and gives the result to the final norm and the tied head.  -> (ids [k], logits [k][vocab])."""
+    from . import decode as odec
+    cur = int(t_start)
+    ids, logits_all = [], []
+    for i in range(k):
+        h_out = odec.drafter_decode(shape, weight_bits, emb_bits[cur:cur + 1], k_cache_bits, v_cache_bits, pos0 + i, theta)
+        tok, logits = olm.lm_head_argmax(emb_bits, h_out)
+        ids.append(int(tok[0]))
+        logits_all.append(logits[0])
+        cur = int(forced[i]) if forced is not None else int(tok[0])
+    return np.asarray(ids, dtype=np.int32), np.stack(logits_all)

@@ -56,3 +56,37 @@ def test_teacher_forcing_feeds_the_given_ids():
     assert ids[0] == free_ids[0]                             # the first step sees only t_start either way
     h = ostack.drafter_forward(shape, get, emb[np.array([3, 5, 9])])
     assert ids[2] == olm.lm_head_argmax(emb, h[-1:])[0][0]   # the third step saw the forced ids
+
+
+def test_cached_round_equals_one_decode_call_over_the_window():
+    """k single-token steps against the cache give, position by position, what one decode call over the whole window
+    [t_start, d_0 .. d_{k-2}] gives (the cache makes the sequential forwards of a round equal one causal pass), and
+    leave the same cache."""
+    from oracle import decode as odec
+    shape, get, emb = _setup(layers=2)
+    theta, pos0, k = 500000.0, 6, 4
+    kc, vc = wl.gen_kv_history(77, shape.layers, shape.n_kv, 32, shape.head_dim, pos0)
+    ids, logits = odr.draft_round_cached(shape, get, emb, 11, k, kc, vc, pos0, theta)
+    window = [11] + ids[:k - 1].tolist()
+    kc2, vc2 = wl.gen_kv_history(77, shape.layers, shape.n_kv, 32, shape.head_dim, pos0)
+    h = odec.drafter_decode(shape, get, emb[np.asarray(window)], kc2, vc2, pos0, theta)
+    tok, lg = olm.lm_head_argmax(emb, h)
+    assert np.array_equal(tok, ids) and np.allclose(lg, logits, rtol=1e-10, atol=1e-10)
+    assert np.array_equal(kc, kc2) and np.array_equal(vc, vc2)
+
+
+def test_cached_round_depends_on_the_history_and_forcing_feeds_the_given_ids():
+    from oracle import decode as odec
+    shape, get, emb = _setup(layers=1)
+    theta, pos0 = 500000.0, 5
+    kc, vc = wl.gen_kv_history(77, shape.layers, shape.n_kv, 16, shape.head_dim, pos0)
+    _, lg_a = odr.draft_round_cached(shape, get, emb, 3, 2, kc, vc, pos0, theta)
+    kc, vc = wl.gen_kv_history(78, shape.layers, shape.n_kv, 16, shape.head_dim, pos0)  # another history
+    _, lg_b = odr.draft_round_cached(shape, get, emb, 3, 2, kc, vc, pos0, theta)
+    assert not np.allclose(lg_a, lg_b, rtol=1e-6)
+    kc, vc = wl.gen_kv_history(77, shape.layers, shape.n_kv, 16, shape.head_dim, pos0)
+    forced = np.array([5, 9], dtype=np.int32)
+    ids, _ = odr.draft_round_cached(shape, get, emb, 3, 3, kc, vc, pos0, theta, forced=np.array([5, 9, 0]))
+    kc2, vc2 = wl.gen_kv_history(77, shape.layers, shape.n_kv, 16, shape.head_dim, pos0)
+    h = odec.drafter_decode(shape, get, emb[np.array([3, 5, 9])], kc2, vc2, pos0, theta)
+    assert ids[2] == olm.lm_head_argmax(emb, h[-1:])[0][0]
