@@ -262,6 +262,21 @@ int sd2_draft_round(const sd2_model_t* model, const uint16_t* emb_bf16_dev, int3
                     size_t workspace_bytes, void* stream);
 int sd2_draft_round_status(const sd2_model_t* model, int32_t vocab, int32_t k, const void* workspace_dev, void* stream);
 
+/* The round against a key/value cache: k single-token steps of sd2_sparse_drafter_decode (the k sequential forwards of
+ * Sec. 2.1, each conditioned on the prompt through the cache).  The start token sits at position pos0, the cache holds
+ * positions 0 .. pos0 - 1; step i embeds one token (the start token, then d_{i-1}), decodes it at position pos0 + i
+ * (appending its key and value) and gives the result to the LM head: d_i.  Afterwards the cache holds positions
+ * pos0 .. pos0 + k - 1 (the start token and d_0 .. d_{k-2}).  pos0 + k <= max_pos.  Cache, rope_theta and limits as for
+ * sd2_sparse_drafter_decode; everything else as for sd2_draft_round.  2 k small launches plus k decode steps and k heads,
+ * no host synchronisation. */
+int sd2_draft_round_cached_workspace_size(const sd2_model_t* model, int32_t vocab, int32_t k, size_t* bytes_out);
+int sd2_draft_round_cached(const sd2_model_t* model, const uint16_t* emb_bf16_dev, int32_t vocab,
+                           const int32_t* start_token_dev, int32_t k, int32_t pos0, uint16_t* k_cache_dev,
+                           uint16_t* v_cache_dev, int32_t max_pos, double rope_theta, int32_t* draft_ids_dev,
+                           void* workspace_dev, size_t workspace_bytes, void* stream);
+int sd2_draft_round_cached_status(const sd2_model_t* model, int32_t vocab, int32_t k, const void* workspace_dev,
+                                  void* stream);
+
 /* ------------------------------------------------------------------ verification
  * Strict top-1 verification (Eq. 2): accepted_len[b] = number of leading positions
  * where draft[b][i] == target[b][i]; out_tokens[b] = those drafts, then target[b][n],

@@ -110,6 +110,9 @@ def lib():
             "sd2_drafter_forward_status": (C.c_int, [vp, i32, vp, vp]),
             "sd2_calibration_copy": (C.c_int, [vp, vp, sz, vp]),
             "sd2_mask_gradient": (C.c_int, [vp, vp, i32, vp]),
+            "sd2_draft_round_cached_workspace_size": (C.c_int, [vp, i32, i32, C.POINTER(sz)]),
+            "sd2_draft_round_cached": (C.c_int, [vp, vp, i32, vp, i32, i32, vp, vp, i32, C.c_double, vp, vp, sz, vp]),
+            "sd2_draft_round_cached_status": (C.c_int, [vp, i32, i32, vp, vp]),
             "sd2_drafter_decode_workspace_size": (C.c_int, [vp, i32, C.POINTER(sz)]),
             "sd2_drafter_decode_status": (C.c_int, [vp, i32, vp, vp]),
             "sd2_sparse_drafter_decode": (C.c_int, [vp, vp, i32, i32, vp, vp, i32, C.c_double, vp, vp, sz, vp]),
@@ -330,6 +333,26 @@ def draft_round(model, emb_ptr, vocab, start_token_ptr, k, draft_ids_ptr, ws_ptr
 def draft_round_status(model, vocab, k, ws_ptr, stream=0):
     _check(lib().sd2_draft_round_status(model.handle, vocab, k, C.c_void_p(ws_ptr), C.c_void_p(stream)),
            "sd2_draft_round_status")
+
+
+def draft_round_cached_workspace_size(model, vocab, k):
+    n = C.c_size_t(0)
+    _check(lib().sd2_draft_round_cached_workspace_size(model.handle, vocab, k, C.byref(n)),
+           "sd2_draft_round_cached_workspace_size")
+    return n.value
+
+
+def draft_round_cached(model, emb_ptr, vocab, start_token_ptr, k, pos0, k_cache_ptr, v_cache_ptr, max_pos, rope_theta,
+                       draft_ids_ptr, ws_ptr, ws_bytes, stream=0):
+    _check(lib().sd2_draft_round_cached(model.handle, C.c_void_p(emb_ptr), vocab, C.c_void_p(start_token_ptr), k, pos0,
+                                        C.c_void_p(k_cache_ptr), C.c_void_p(v_cache_ptr), max_pos, float(rope_theta),
+                                        C.c_void_p(draft_ids_ptr), C.c_void_p(ws_ptr), ws_bytes, C.c_void_p(stream)),
+           "sd2_draft_round_cached")
+
+
+def draft_round_cached_status(model, vocab, k, ws_ptr, stream=0):
+    _check(lib().sd2_draft_round_cached_status(model.handle, vocab, k, C.c_void_p(ws_ptr), C.c_void_p(stream)),
+           "sd2_draft_round_cached_status")
 
 
 def prune_magnitude(w_ptr, n_out, k_in, sparsity_pct, pattern=0, stream=0):

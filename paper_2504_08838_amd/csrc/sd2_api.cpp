@@ -807,4 +807,83 @@ int sd2_draft_round_status(const sd2_model_t* model, int32_t vocab, int32_t k, c
     return flag ? SD2_ERR_TIMEOUT : SD2_OK;
 }
 
+// ---- the round against a key/value cache: k single-token decode steps
+
+namespace {
+int cached_round_layout(const sd2_model_t* md, int32_t vocab, int32_t k, RoundLayout* L) {
+    if (!md) return SD2_ERR_NULL;
+    if (k < 1 || k > SD2_MAX_TOKENS) return SD2_ERR_RANGE;
+    const sd2_model_shape_t& sh = md->shape;
+    int rc = lm_head_check(vocab, sh.hidden, 1);
+    if (rc != SD2_OK) return rc;
+    L->hin_off = 0;
+    L->hout_off = align256((size_t)sh.hidden * sizeof(uint16_t));
+    L->flag_off = L->hout_off + align256((size_t)sh.hidden * sizeof(float));
+    L->lm_off = L->flag_off + 256;
+    L->fwd_off = L->lm_off + align256((size_t)kLmMaxWorkgroups * 16 * 8);
+    L->fwd_bytes = decode_layout(md, 1).total;
+    L->total = L->fwd_off + align256(L->fwd_bytes);
+    return SD2_OK;
+}
+}  // namespace
+
+int sd2_draft_round_cached_workspace_size(const sd2_model_t* model, int32_t vocab, int32_t k, size_t* bytes_out) {
+    if (!bytes_out) return SD2_ERR_NULL;
+    RoundLayout L;
+    const int rc = cached_round_layout(model, vocab, k, &L);
+    if (rc != SD2_OK) return rc;
+    *bytes_out = L.total;
+    return SD2_OK;
+}
+
+int sd2_draft_round_cached(const sd2_model_t* model, const uint16_t* emb, int32_t vocab, const int32_t* start_token, int32_t k,
+                           int32_t pos0, uint16_t* k_cache, uint16_t* v_cache, int32_t max_pos, double rope_theta,
+                           int32_t* draft_ids, void* ws, size_t ws_bytes, void* stream) {
+    RoundLayout L;
+    int rc = cached_round_layout(model, vocab, k, &L);
+    if (rc != SD2_OK) return rc;
+    if (!emb || !start_token || !draft_ids || !ws || !k_cache || !v_cache) return SD2_ERR_NULL;
+    if (max_pos < 1 || pos0 < 0 || (int64_t)pos0 + k > max_pos || !(rope_theta > 1.0)) return SD2_ERR_RANGE;
+    const sd2_model_shape_t& sh = model->shape;
+    if (!cached_attention_supported(sh.n_heads, sh.n_kv, sh.head_dim, max_pos)) return SD2_ERR_UNSUPPORTED;
+    if (!aligned16(emb) || !aligned16(ws) || !aligned16(k_cache) || !aligned16(v_cache) || ws_bytes < L.total)
+        return SD2_ERR_BUFFER;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    uint8_t* base = static_cast<uint8_t*>(ws);
+    uint16_t* h_in = reinterpret_cast<uint16_t*>(base + L.hin_off);
+    float* h_out = reinterpret_cast<float*>(base + L.hout_off);
+    unsigned* round_flag = reinterpret_cast<unsigned*>(base + L.flag_off);
+    void* lm_ws = base + L.lm_off;
+    void* dec_ws = base + L.fwd_off;
+    const bool single_launch = decode_layout(model, 1).chunks > 0;
+    const MegaLayout ML = mega_layout(sh.layers, sh.hidden, sh.q_out, sh.kv_out, sh.inter, 1);
+    if (launch_fold_flag(nullptr, round_flag, s) != hipSuccess) return SD2_ERR_HIP;
+    for (int32_t i = 0; i < k; ++i) {
+        // step i: one token (the start token, then the one chosen at step i - 1) at position pos0 + i
+        if (launch_embed_window(emb, vocab, sh.hidden, i == 0 ? start_token : draft_ids + (i - 1), nullptr, 1, h_in, s) != hipSuccess)
+            return SD2_ERR_HIP;
+        rc = sd2_sparse_drafter_decode(model, h_in, 1, pos0 + i, k_cache, v_cache, max_pos, rope_theta, h_out, dec_ws, L.fwd_bytes,
+                                       stream);
+        if (rc != SD2_OK) return rc;
+        if (single_launch &&
+            launch_fold_flag(reinterpret_cast<const unsigned*>(static_cast<uint8_t*>(dec_ws) + ML.err_off), round_flag, s) != hipSuccess)
+            return SD2_ERR_HIP;
+        if (launch_lm_head(emb, h_out, vocab, sh.hidden, 1, lm_ws, draft_ids + i, nullptr, nullptr, s) != hipSuccess)
+            return SD2_ERR_HIP;
+    }
+    return SD2_OK;
+}
+
+int sd2_draft_round_cached_status(const sd2_model_t* model, int32_t vocab, int32_t k, const void* ws, void* stream) {
+    RoundLayout L;
+    const int rc = cached_round_layout(model, vocab, k, &L);
+    if (rc != SD2_OK) return rc;
+    if (!ws) return SD2_ERR_NULL;
+    if (hipStreamSynchronize(static_cast<hipStream_t>(stream)) != hipSuccess) return SD2_ERR_HIP;
+    unsigned flag = 0;
+    if (hipMemcpy(&flag, static_cast<const uint8_t*>(ws) + L.flag_off, sizeof(flag), hipMemcpyDeviceToHost) != hipSuccess)
+        return SD2_ERR_HIP;
+    return flag ? SD2_ERR_TIMEOUT : SD2_OK;
+}
+
 }  // extern "C"

@@ -221,3 +221,28 @@ def test_decode_argument_checks():
     assert L.sd2_sparse_drafter_decode(*args(wsb=n - 1)) == -4
     assert L.sd2_sparse_drafter_decode(*args(kc=C.c_void_p(0x2004))) == -4
     sd2.model_destroy(model)
+
+
+def test_cached_round_argument_checks():
+    import sd2_workload as wl
+    L = sd2.lib()
+    fake = C.c_void_p(0x2000)
+    shape = sd2.ModelShape(1, 256, 256, 128, 512, 2, 1, 128)
+    ws = {"qkv": (512, 256), "o": (256, 256), "gu": (1024, 256), "dn": (256, 512)}
+    mats = [sd2.matrix_init_sparse(sd2.pack_sparse(wl.gen_weight(73, 0, "q", n, k, 50), 1), 0x10000) for n, k in ws.values()]
+    model = sd2.model_create(shape, mats)
+    n = sd2.draft_round_cached_workspace_size(model, 1000, 5)
+    assert n > 0 and n % 256 == 0
+    args = lambda **kw: [kw.get("model", model.handle), kw.get("emb", fake), kw.get("vocab", 1000), kw.get("start", fake),
+                         kw.get("k", 5), kw.get("pos0", 10), kw.get("kc", fake), kw.get("vc", fake), kw.get("max_pos", 64),
+                         kw.get("theta", 5.0e5), kw.get("ids", fake), kw.get("ws", fake), kw.get("wsb", n), None]
+    for name in ("model", "emb", "start", "kc", "vc", "ids", "ws"):
+        assert L.sd2_draft_round_cached(*args(**{name: None})) == -1, name
+    assert L.sd2_draft_round_cached(*args(k=0)) == -6
+    assert L.sd2_draft_round_cached(*args(k=65)) == -6
+    assert L.sd2_draft_round_cached(*args(pos0=-1)) == -6
+    assert L.sd2_draft_round_cached(*args(pos0=60)) == -6
+    assert L.sd2_draft_round_cached(*args(theta=0.5)) == -6
+    assert L.sd2_draft_round_cached(*args(vocab=0)) == -2
+    assert L.sd2_draft_round_cached(*args(wsb=n - 1)) == -4
+    sd2.model_destroy(model)

@@ -122,3 +122,90 @@ def test_round_in_a_graph_replays_identically_and_feeds_verify():
     sd2.greedy_verify(drafts.data_ptr(), target.data_ptr(), 1, k, vocab, acc.data_ptr(), out.data_ptr(), gu.stream_ptr())
     torch.cuda.synchronize()
     assert acc.item() == 2
+
+
+# ---- the round against a key/value cache
+
+def _run_cached_round(model, shape, emb_dev, vocab, t_start, k, kc_dev, vc_dev, max_pos, pos0, theta=500000.0):
+    import torch
+    import paper_2504_08838_amd as sd2
+    import gpu_util as gu
+    start = torch.tensor([t_start], dtype=torch.int32, device="cuda")
+    ids = torch.full((k,), -7, dtype=torch.int32, device="cuda")
+    nb = sd2.draft_round_cached_workspace_size(model, vocab, k)
+    ws = torch.empty(nb, dtype=torch.uint8, device="cuda")
+    call = lambda sp: sd2.draft_round_cached(model, emb_dev.data_ptr(), vocab, start.data_ptr(), k, pos0, kc_dev.data_ptr(),
+                                             vc_dev.data_ptr(), max_pos, theta, ids.data_ptr(), ws.data_ptr(), nb, sp)
+    call(gu.stream_ptr())
+    sd2.draft_round_cached_status(model, vocab, k, ws.data_ptr(), gu.stream_ptr())
+    return ids.cpu().numpy(), (start, ids, ws, call)
+
+
+def _check_cached(shape, get, emb, t_start, ids, kc, vc, pos0, theta=500000.0):
+    """Teacher-forced on the GPU's ids; updates kc, vc (the oracle's caches) in place."""
+    k = ids.size
+    assert ((ids >= 0) & (ids < emb.shape[0])).all()
+    ref_ids, ref_logits = odr.draft_round_cached(shape, get, emb, t_start, k, kc, vc, pos0, theta, forced=ids)
+    for i in range(k):
+        gap = ref_logits[i, ref_ids[i]] - ref_logits[i, ids[i]]
+        assert 0 <= gap <= 5e-3 * np.abs(ref_logits[i]).max(), (i, ids[i], ref_ids[i], gap)
+    return int((ids == ref_ids).sum())
+
+
+@pytest.mark.parametrize("forward", ["single-launch", "multi-launch"])
+@pytest.mark.parametrize("pos0", [0, 150])
+def test_cached_round_matches_oracle(forward, pos0, monkeypatch):
+    import gpu_util as gu
+    from oracle.bf16 import bits_to_f64
+    from oracle.linear import rel_l2
+    if forward == "multi-launch":
+        monkeypatch.setenv("SD2_FORWARD", "multi")
+    else:
+        monkeypatch.delenv("SD2_FORWARD", raising=False)
+    shape = SimpleNamespace(layers=2, hidden=512, q_out=512, kv_out=256, inter=1024, n_heads=4, n_kv=2, head_dim=128)
+    vocab, k, max_pos = 3000, 5, 256
+    get, model = _model(shape, 79)
+    emb = wl.gen_lm_head(79, vocab, shape.hidden)
+    kc, vc = wl.gen_kv_history(79, shape.layers, shape.n_kv, max_pos, shape.head_dim, pos0)
+    kc_dev, vc_dev = gu.dev(kc), gu.dev(vc)
+    ids, _ = _run_cached_round(model, shape, gu.dev(emb), vocab, 17, k, kc_dev, vc_dev, max_pos, pos0)
+    assert _check_cached(shape, get, emb, 17, ids, kc, vc, pos0) >= k - 1
+    # the caches after the round: positions pos0 .. pos0 + k - 1 written, the rest untouched
+    kg, vg = kc_dev.cpu().numpy().view(np.uint16), vc_dev.cpu().numpy().view(np.uint16)
+    assert np.array_equal(kg[:, :, :pos0], kc[:, :, :pos0]) and not kg[:, :, pos0 + k:].any()
+    assert rel_l2(bits_to_f64(kg[:, :, pos0:pos0 + k]), bits_to_f64(kc[:, :, pos0:pos0 + k])) <= 4e-3
+    assert rel_l2(bits_to_f64(vg[:, :, pos0:pos0 + k]), bits_to_f64(vc[:, :, pos0:pos0 + k])) <= 4e-3
+
+
+def test_cached_round_in_a_graph_and_into_verify():
+    import torch
+    import paper_2504_08838_amd as sd2
+    import gpu_util as gu
+    shape = SimpleNamespace(layers=2, hidden=512, q_out=512, kv_out=256, inter=1024, n_heads=4, n_kv=2, head_dim=128)
+    vocab, k, max_pos, pos0 = 2000, 4, 128, 60
+    get, model = _model(shape, 80)
+    emb = wl.gen_lm_head(80, vocab, shape.hidden)
+    kc, vc = wl.gen_kv_history(80, shape.layers, shape.n_kv, max_pos, shape.head_dim, pos0)
+    kc_dev, vc_dev = gu.dev(kc), gu.dev(vc)
+    emb_dev = gu.dev(emb)
+    eager, (start, ids, ws, call) = _run_cached_round(model, shape, emb_dev, vocab, 5, k, kc_dev, vc_dev, max_pos, pos0)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(g, stream=side):
+            call(side.cuda_stream)
+    torch.cuda.current_stream().wait_stream(side)
+    for _ in range(3):
+        ids.fill_(-1)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(ids.cpu().numpy(), eager)  # the round rewrites the same cache rows with the same values
+    # the drafts feed verification: a target that agrees on the first two positions
+    target = torch.tensor([[int(eager[0]), int(eager[1]), (int(eager[2]) + 1) % vocab, 7, 9]], dtype=torch.int32, device="cuda")
+    acc = torch.zeros(1, dtype=torch.int32, device="cuda")
+    out = torch.zeros((1, k + 1), dtype=torch.int32, device="cuda")
+    sd2.greedy_verify(ids.data_ptr(), target.data_ptr(), 1, k, vocab, acc.data_ptr(), out.data_ptr(), gu.stream_ptr())
+    torch.cuda.synchronize()
+    assert acc.item() == 2 and out.cpu().numpy()[0].tolist() == [int(eager[0]), int(eager[1]), (int(eager[2]) + 1) % vocab, -1, -1]
