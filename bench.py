@@ -11,7 +11,7 @@ on the same stream brackets every forward inside the timed region.
 Prints one JSON line.  `roofline` describes the dominant kernel: algorithmic bytes per launch divided by the
 live event-timed duration, against the published 8 TB/s of HBM3E (`traffic` = HBM bytes per launch measured with
 profiler counters in separate runs).  `cpu_baseline` is the NumPy fp64 oracle timed on the host's cores.  The
-other keys (`lm_head`, `draft_round`, `decode`, `nm24_linear`, `mask_gradient`) time further kernels on their own; they are not in `value`.
+other keys (`lm_head`, `draft_round`, `decode`, `draft_round_cached`, `nm24_linear`, `mask_gradient`) time further kernels on their own; they are not in `value`.
 """
 
 import argparse
@@ -347,7 +347,7 @@ def main():
                                  "us_per_token": round(dr_us / kr, 1), "algorithmic_bytes": dr_alg,
                                  "achieved_GBps": round(dr_alg / dr_us / 1e3, 1),
                                  "frac": round(dr_alg / dr_us / 1e3 / HBM_PEAK_GBS, 4)}
-        del g_dr, w_lm
+        del g_dr
 
         # One decode step with rotary embedding and a key/value cache: one new token at position 428 (a 300-token prompt
         # and 128 generated tokens: the middle of the request shape of the paper's serving measurements), synthetic history.
@@ -396,7 +396,38 @@ def main():
                             "achieved_GBps": round(dec_alg / dec_us["decode"] / 1e3, 1),
                             "frac": round(dec_alg / dec_us["decode"] / 1e3 / HBM_PEAK_GBS, 4),
                             "window_forward_k1_us": round(dec_us["window"], 1)}
-        del kc_dev, vc_dev
+        # The drafting round against the cache: k single-token decode steps from position dpos, each followed by the head.
+        rc_bytes = sd2.draft_round_cached_workspace_size(model, vocab, kr)
+        rc_ws = torch.empty(rc_bytes, dtype=torch.uint8, device=dev)
+        rc_ids = torch.full((kr,), -1, dtype=torch.int32, device=dev)
+        rc_call = lambda spp: sd2.draft_round_cached(model, w_lm.data_ptr(), vocab, start_tok.data_ptr(), kr, dpos,
+                                                     kc_dev.data_ptr(), vc_dev.data_ptr(), dmax, 500000.0, rc_ids.data_ptr(),
+                                                     rc_ws.data_ptr(), rc_bytes, spp)
+        with torch.cuda.stream(stream):
+            rc_call(stream.cuda_stream)
+            sd2.draft_round_cached_status(model, vocab, kr, rc_ws.data_ptr(), stream.cuda_stream)
+            g_rc = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g_rc, stream=stream):
+                rc_call(torch.cuda.current_stream().cuda_stream)
+            for _ in range(2):
+                g_rc.replay()
+            evr = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(20)]
+            for e0, e1 in evr:
+                e0.record(stream)
+                g_rc.replay()
+                e1.record(stream)
+            stream.synchronize()
+        rc_us = float(np.mean([e0.elapsed_time(e1) for e0, e1 in evr])) * 1e3
+        ids_host = rc_ids.cpu().numpy()
+        assert ids_host.min() >= 0 and ids_host.max() < vocab
+        rc_alg = kr * (useful + 2 * vocab * shape.hidden) + sum(
+            2 * 2 * layers * shape.n_kv * (dpos + i + 1) * shape.head_dim for i in range(kr))
+        record["draft_round_cached"] = {"what": f"k={kr} greedy draft tokens from position {dpos}: per step one embedding row, one "
+                                                "decode step against the cache, LM head", "us": round(rc_us, 1),
+                                        "us_per_token": round(rc_us / kr, 1), "algorithmic_bytes": rc_alg,
+                                        "achieved_GBps": round(rc_alg / rc_us / 1e3, 1),
+                                        "frac": round(rc_alg / rc_us / 1e3 / HBM_PEAK_GBS, 4)}
+        del g_rc, w_lm, kc_dev, vc_dev
 
     if not args.no_lm_head:
         # Masked-gradient step of sparse fine-tuning on the fused gate+up shape (fp32 gradient, in place), two
