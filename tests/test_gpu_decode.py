@@ -204,3 +204,31 @@ def test_decode_in_a_graph_replays(forward):
             assert np.array_equal(got, eager)
         else:  # the single-launch kernel sums its split-K parts with float atomics: the order varies from run to run
             assert rel_l2(got, eager) <= 1e-5
+
+
+def test_bounded_wait_gives_up_and_recovers(monkeypatch):
+    """Failure handling of the single-launch path: with a spin limit of zero every grid barrier (the attention step's
+    included) gives up at its first unsuccessful poll.  Every wavefront still runs to the end, the status call reports
+    the step as invalid, and the next step on a fresh cache is right again."""
+    import torch
+    import paper_2504_08838_amd as sd2
+    import gpu_util as gu
+    monkeypatch.delenv("SD2_FORWARD", raising=False)
+    shape, max_pos, n_hist, k_tok = SMALL, 128, 50, 3
+    get, model = _model(shape, 88)
+    kc, vc = wl.gen_kv_history(88, shape.layers, shape.n_kv, max_pos, shape.head_dim, n_hist)
+    h_bits = wl.gen_x(88, 0, "q", k_tok, shape.hidden)
+    h_in = gu.dev(h_bits)
+    h_out = torch.zeros((k_tok, shape.hidden), dtype=torch.float32, device="cuda")
+    nb = sd2.drafter_decode_workspace_size(model, k_tok)
+    ws = torch.empty(nb, dtype=torch.uint8, device="cuda")
+    kc_bad, vc_bad = gu.dev(kc), gu.dev(vc)
+    monkeypatch.setenv("SD2_MEGA_SPIN_LIMIT", "0")
+    sd2.sparse_drafter_decode(model, h_in.data_ptr(), k_tok, n_hist, kc_bad.data_ptr(), vc_bad.data_ptr(), max_pos, THETA,
+                              h_out.data_ptr(), ws.data_ptr(), nb, gu.stream_ptr())
+    with pytest.raises(sd2.SD2Error):
+        sd2.drafter_decode_status(model, k_tok, ws.data_ptr(), gu.stream_ptr())
+    monkeypatch.delenv("SD2_MEGA_SPIN_LIMIT")
+    got = _decode(model, shape, h_bits, gu.dev(kc), gu.dev(vc), max_pos, n_hist)
+    want = od.drafter_decode(shape, get, h_bits, kc, vc, n_hist, THETA)
+    assert rel_l2(got, want) <= 1e-3
