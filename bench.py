@@ -29,10 +29,11 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 # HBM bytes per launch of the forward kernel (and of the gate+up sparse linear) from rocprofv3 --pmc
 # FETCH_SIZE / WRITE_SIZE runs, scaled by the plain copy kernel of --calibrate; None until measured.
-MEASURED_TRAFFIC_BYTES = 3446887205
-MEASURED_LINEAR_TRAFFIC_BYTES = 63321685
-MEASURED_LM_HEAD_TRAFFIC_BYTES = 788435743
-MEASURED_NM24_TRAFFIC_BYTES = 57262551
+MEASURED_TRAFFIC_BYTES = 3446708318
+MEASURED_LINEAR_TRAFFIC_BYTES = 63338922
+MEASURED_LM_HEAD_TRAFFIC_BYTES = 788253236
+MEASURED_NM24_TRAFFIC_BYTES = 57260311
+MEASURED_DECODE_TRAFFIC_BYTES = 3348780524  # the single-launch decode step (one token, 429 cached positions)
 CALIBRATION_BYTES = 256 << 20  # size of the plain copies launched by --calibrate
 
 
@@ -395,7 +396,8 @@ def main():
                             "us": round(dec_us["decode"], 1), "algorithmic_bytes": dec_alg, "kv_cache_bytes_read": kv_bytes,
                             "achieved_GBps": round(dec_alg / dec_us["decode"] / 1e3, 1),
                             "frac": round(dec_alg / dec_us["decode"] / 1e3 / HBM_PEAK_GBS, 4),
-                            "window_forward_k1_us": round(dec_us["window"], 1)}
+                            "window_forward_k1_us": round(dec_us["window"], 1),
+                            "traffic": MEASURED_DECODE_TRAFFIC_BYTES if (args.config == 3) else None}
         # The drafting round against the cache: k single-token decode steps from position dpos, each followed by the head.
         rc_bytes = sd2.draft_round_cached_workspace_size(model, vocab, kr)
         rc_ws = torch.empty(rc_bytes, dtype=torch.uint8, device=dev)
