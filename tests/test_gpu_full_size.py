@@ -77,3 +77,85 @@ def test_cfg3_graph_replays_as_timed_by_the_benchmark(cfg3):
     # replays agree with the eager call up to the order of the float atomics (and the rounding flips that can follow)
     for o in outs[1:]:
         assert ol.rel_l2(o, outs[0]) <= FULL_E2E_TOL
+
+
+# ---- the decode step at full size (the configuration bench.py times: one token at position 428 of a 1024-slot cache)
+
+THETA = 500000.0
+
+
+def _decode_once(model, shape, h_bits, kc_dev, vc_dev, max_pos, pos0, graph=False):
+    import torch
+    import paper_2504_08838_amd as sd2
+    import gpu_util as gu
+    k_tok = h_bits.shape[0]
+    h_in = gu.dev(h_bits)
+    h_out = torch.full((k_tok, shape.hidden), float("nan"), dtype=torch.float32, device="cuda")
+    nb = sd2.drafter_decode_workspace_size(model, k_tok)
+    ws = torch.empty(nb, dtype=torch.uint8, device="cuda")
+    stream = torch.cuda.Stream()  # default priority
+    call = lambda sp: sd2.sparse_drafter_decode(model, h_in.data_ptr(), k_tok, pos0, kc_dev.data_ptr(), vc_dev.data_ptr(), max_pos,
+                                                THETA, h_out.data_ptr(), ws.data_ptr(), nb, sp)
+    outs = []
+    with torch.cuda.stream(stream):
+        call(stream.cuda_stream)
+        sd2.drafter_decode_status(model, k_tok, ws.data_ptr(), stream.cuda_stream)
+        outs.append(h_out.cpu().numpy().copy())
+        if graph:
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=stream):
+                call(torch.cuda.current_stream().cuda_stream)
+            for _ in range(2):
+                h_out.fill_(float("nan"))
+                g.replay()
+                sd2.drafter_decode_status(model, k_tok, ws.data_ptr(), stream.cuda_stream)
+                outs.append(h_out.cpu().numpy().copy())
+    return outs
+
+
+@pytest.mark.parametrize("k_tok", [1, 5])
+@pytest.mark.parametrize("forward", ["single-launch", "multi-launch"])
+def test_cfg3_decode_two_layers_at_full_width(cfg3, k_tok, forward, monkeypatch):
+    """Full-size matrices, two layers: tight enough for the 1e-3 bar (few rounding points), both implementations."""
+    import gpu_util as gu
+    from oracle import decode as od
+    from oracle.bf16 import bits_to_f64
+    if forward == "multi-launch":
+        monkeypatch.setenv("SD2_FORWARD", "multi")
+    else:
+        monkeypatch.delenv("SD2_FORWARD", raising=False)
+    shape, get, _, _ = cfg3
+    two = wl.StackShape("two-layers", 2, shape.hidden, shape.q_out, shape.kv_out, shape.inter, shape.n_heads, shape.n_kv,
+                        shape.head_dim, shape.vocab)
+    model = gu.build_model(two, get)
+    max_pos, pos0 = 1024, 428
+    kc, vc = wl.gen_kv_history(3, 2, shape.n_kv, max_pos, shape.head_dim, pos0)
+    kc_dev, vc_dev = gu.dev(kc), gu.dev(vc)
+    h_bits = wl.gen_x(3, 1, "q", k_tok, shape.hidden)
+    got = _decode_once(model, two, h_bits, kc_dev, vc_dev, max_pos, pos0)[0]
+    want = od.drafter_decode(two, get, h_bits, kc, vc, pos0, THETA)
+    assert ol.rel_l2(got, want) <= 1e-3
+    kg = kc_dev.cpu().numpy().view(np.uint16)
+    vg = vc_dev.cpu().numpy().view(np.uint16)
+    sl = slice(pos0, pos0 + k_tok)
+    assert np.array_equal(kg[:, :, :pos0], kc[:, :, :pos0]) and not kg[:, :, pos0 + k_tok:].any()
+    assert ol.rel_l2(bits_to_f64(kg[:, :, sl]), bits_to_f64(kc[:, :, sl])) <= 4e-3
+    assert ol.rel_l2(bits_to_f64(vg[:, :, sl]), bits_to_f64(vc[:, :, sl])) <= 4e-3
+    assert (kg[0, :, sl] != kc[0, :, sl]).mean() <= 0.01 and (vg[0, :, sl] != vc[0, :, sl]).mean() <= 0.01
+
+
+def test_cfg3_decode_28_layers_as_timed_by_the_benchmark(cfg3):
+    import gpu_util as gu
+    from oracle import decode as od
+    shape, get, _, model = cfg3
+    max_pos, pos0 = 1024, 428
+    kc, vc = wl.gen_kv_history(3, shape.layers, shape.n_kv, max_pos, shape.head_dim, pos0)
+    kc_dev, vc_dev = gu.dev(kc), gu.dev(vc)
+    h_bits = wl.gen_x(3, 1, "q", 1, shape.hidden)
+    outs = _decode_once(model, shape, h_bits, kc_dev, vc_dev, max_pos, pos0, graph=True)
+    want = od.drafter_decode(shape, get, h_bits, kc, vc, pos0, THETA)
+    for o in outs:
+        assert np.isfinite(o).all()
+        assert ol.rel_l2(o, want) <= FULL_E2E_TOL
+    for o in outs[1:]:
+        assert ol.rel_l2(o, outs[0]) <= FULL_E2E_TOL
