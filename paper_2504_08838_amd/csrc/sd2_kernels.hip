@@ -12,6 +12,7 @@
 // for the multiply because the decode already leaves a dense fragment in registers and the vector
 // ALU is the scarce unit here; HBM traffic is the compacted stream and nothing else.
 #include <algorithm>
+#include <atomic>
 
 #include "sd2_device.h"
 #include "sd2_internal.h"
@@ -194,14 +195,15 @@ __global__ __launch_bounds__(256) void dense_linear_kernel(const uint16_t* __res
 // ------------------------------------------------------------------ launch
 
 static int device_cu_count() {
-    static int cus = 0;
+    static std::atomic<int> cached{0};  // threads that race here compute the same value
+    int cus = cached.load(std::memory_order_relaxed);
     if (cus == 0) {
         int dev = 0, n = 0;
-        if (hipGetDevice(&dev) == hipSuccess &&
-            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
-            cus = n;
-        else
-            cus = 256;
+        cus = (hipGetDevice(&dev) == hipSuccess &&
+               hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
+                  ? n
+                  : 256;
+        cached.store(cus, std::memory_order_relaxed);
     }
     return cus;
 }
@@ -812,12 +814,12 @@ bool cached_attention_supported(int n_heads, int n_kv, int head_dim, int max_pos
 template <int LPR, int REP>
 static hipError_t launch_cached_attention_t(const float* q_rot, const uint16_t* k_cache, const uint16_t* v_cache, int max_pos,
                                             int pos0, int k_tok, int q_out, int rep, int n_kv, uint16_t* ctx, hipStream_t s) {
-    static bool lds_raised = false;  // once, at the first call (a warm-up call precedes any graph capture)
-    if (!lds_raised) {
+    static std::atomic<bool> lds_raised{false};  // once, at the first call (a warm-up call precedes any graph capture)
+    if (!lds_raised.load(std::memory_order_acquire)) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(cached_attention_kernel<LPR, REP>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 256);
         if (e != hipSuccess) return e;
-        lds_raised = true;
+        lds_raised.store(true, std::memory_order_release);
     }
     const int n_max = pos0 + k_tok;
     hipLaunchKernelGGL((cached_attention_kernel<LPR, REP>), dim3((unsigned)n_kv, (unsigned)k_tok), dim3(64 * kAttWaves),

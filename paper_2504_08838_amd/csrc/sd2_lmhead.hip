@@ -16,6 +16,7 @@
 // keep a running (largest logit, lowest row) per thread; nothing but 16 candidates per workgroup
 // ever goes back to HBM unless the caller asks for the logits.
 #include <algorithm>
+#include <atomic>
 
 #include "sd2_device.h"
 #include "sd2_internal.h"
@@ -248,13 +249,13 @@ static int lm_cu_count() {
 template <int CPW, bool HEAD>
 static hipError_t launch_lm_t(const uint16_t* w, const float* h, const uint16_t* x, int vocab, int hidden, int k_tok,
                               int n_strips, int n_wg, LmCand* part, float* logits, hipStream_t s) {
-    static bool attr_set = false;  // more than the default 64 KiB of dynamic LDS needs opting in, once per kernel
+    static std::atomic<bool> attr_set{false};  // more than the default 64 KiB of dynamic LDS needs opting in, once per kernel
     const size_t lds = (size_t)kLmLdsDw * 4;
-    if (!attr_set) {
+    if (!attr_set.load(std::memory_order_acquire)) {
         const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&lm_head_kernel<CPW, HEAD>),
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
-        attr_set = true;
+        attr_set.store(true, std::memory_order_release);
     }
     hipLaunchKernelGGL((lm_head_kernel<CPW, HEAD>), dim3((unsigned)n_wg), dim3(64 * kLmWaves), lds, s, w, h, x, vocab, hidden,
                        k_tok, n_strips, part, logits);

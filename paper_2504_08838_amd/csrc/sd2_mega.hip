@@ -14,6 +14,7 @@
 // (every workgroup sums the squares of the whole residual itself), causal attention over the
 // in-flight tokens for the heads of its slabs, or the SiLU-gated product.
 #include <algorithm>
+#include <atomic>
 
 #include "sd2_device.h"
 #include "sd2_internal.h"
@@ -999,45 +1000,40 @@ static const void* mega_kv_kernel(bool nm24, int rep) {
     return nullptr;
 }
 
-static bool mega_kv_kernels_fit() {
-    for (int nm24 = 0; nm24 < 2; ++nm24)
-        for (int rep = 1; rep <= 4; ++rep) {
-            const void* fn = mega_kv_kernel(nm24 != 0, rep);
-            int per_cu = 0;
-            if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMegaLds) != hipSuccess ||
-                hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, kMegaThreads, kMegaLds) != hipSuccess || per_cu < 1)
-                return false;
-        }
-    return true;
+// Prepares one kernel for launches with the full LDS and checks that a workgroup of it fits a compute unit.
+static bool mega_kernel_fits(const void* fn) {
+    int per_cu = 0;
+    return hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMegaLds) == hipSuccess &&
+           hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, kMegaThreads, kMegaLds) == hipSuccess && per_cu >= 1;
 }
 
+static int mega_probe_device() {
+    int dev = 0, n = 0, coop = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&coop, hipDeviceAttributeCooperativeLaunch, dev) != hipSuccess || !coop ||
+        hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1)
+        return 0;
+    const void* plain[] = {reinterpret_cast<const void*>(mega_forward_kernel<false, false, false>),
+                           reinterpret_cast<const void*>(mega_forward_kernel<true, false, false>),
+                           reinterpret_cast<const void*>(mega_forward_kernel<false, true, false>),
+                           reinterpret_cast<const void*>(mega_forward_kernel<false, false, true>),
+                           reinterpret_cast<const void*>(mega_forward_kernel<true, false, true>)};
+    for (const void* fn : plain)
+        if (!mega_kernel_fits(fn)) return 0;
+    for (int nm24 = 0; nm24 < 2; ++nm24)
+        for (int rep = 1; rep <= 4; ++rep)
+            if (!mega_kernel_fits(mega_kv_kernel(nm24 != 0, rep))) return 0;
+    return n;
+}
+
+// Workgroups of the persistent kernel (one per compute unit), 0 when it cannot run on this device.  Probed once;
+// threads that race here compute the same value.
 static int mega_grid() {
-    static int cus = -1;
+    static std::atomic<int> cached{-1};
+    int cus = cached.load(std::memory_order_acquire);
     if (cus < 0) {
-        int dev = 0, n = 0, coop = 0;
-        cus = 0;
-        if (hipGetDevice(&dev) == hipSuccess &&
-            hipDeviceGetAttribute(&coop, hipDeviceAttributeCooperativeLaunch, dev) == hipSuccess && coop &&
-            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0 &&
-            hipFuncSetAttribute(reinterpret_cast<const void*>(mega_forward_kernel<false, false, false>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMegaLds) == hipSuccess &&
-            hipFuncSetAttribute(reinterpret_cast<const void*>(mega_forward_kernel<true, false, false>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMegaLds) == hipSuccess &&
-            hipFuncSetAttribute(reinterpret_cast<const void*>(mega_forward_kernel<false, true, false>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMegaLds) == hipSuccess &&
-            hipFuncSetAttribute(reinterpret_cast<const void*>(mega_forward_kernel<false, false, true>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMegaLds) == hipSuccess &&
-            hipFuncSetAttribute(reinterpret_cast<const void*>(mega_forward_kernel<true, false, true>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMegaLds) == hipSuccess &&
-            mega_kv_kernels_fit()) {
-            int per_cu = 0, per_cu_t = 0, per_cu_s = 0, per_cu_st = 0;
-            if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, mega_forward_kernel<false, false, false>, kMegaThreads, kMegaLds) == hipSuccess &&
-                hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu_t, mega_forward_kernel<true, false, false>, kMegaThreads, kMegaLds) == hipSuccess &&
-                hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu_s, mega_forward_kernel<false, false, true>, kMegaThreads, kMegaLds) == hipSuccess &&
-                hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu_st, mega_forward_kernel<true, false, true>, kMegaThreads, kMegaLds) == hipSuccess &&
-                per_cu >= 1 && per_cu_t >= 1 && per_cu_s >= 1 && per_cu_st >= 1)
-                cus = n;
-        }
+        cus = mega_probe_device();
+        cached.store(cus, std::memory_order_release);
     }
     return cus;
 }

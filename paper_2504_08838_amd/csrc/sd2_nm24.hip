@@ -13,6 +13,7 @@
 // LDS (double buffered, one barrier), four wavefronts add them in a fixed order and write y -- final
 // values, no split-K partials in memory.
 #include <algorithm>
+#include <atomic>
 
 #include "sd2_device.h"
 #include "sd2_format.h"
@@ -162,13 +163,15 @@ template <int SPW, int WAVES>
 static hipError_t launch_nm24_t(const uint8_t* tiles, const uint16_t* x, float* y, int n_out, int k_in, int k_tok,
                                 int n_strips, int n_slabs, hipStream_t s) {
     // as many workgroups as fit on the chip at once (registers and LDS decide how many per compute unit)
-    static int resident = 0;
+    static std::atomic<int> cached{0};  // threads that race here compute the same value
+    int resident = cached.load(std::memory_order_relaxed);
     if (resident == 0) {
         int per_cu = 0;
         if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, nm24_linear_kernel<SPW, WAVES>, 64 * WAVES, 0) != hipSuccess ||
             per_cu < 1)
             per_cu = 1;
         resident = nm24_cu_count() * per_cu;
+        cached.store(resident, std::memory_order_relaxed);
     }
     const int grid = std::min(n_strips, resident);
     hipLaunchKernelGGL((nm24_linear_kernel<SPW, WAVES>), dim3((unsigned)grid), dim3(64 * WAVES), 0, s, tiles, x, y, n_out, k_in,
