@@ -180,6 +180,15 @@ __device__ __forceinline__ void tile_bases(const PhaseTiles& pt, int j, int lane
     base[7] = lane_word(rb, 1);
 }
 
+// Workgroup barrier that orders LDS traffic only: the wavefront's own LDS operations have completed, loads and stores
+// to memory stay in flight (a __syncthreads would also wait for every store acknowledgement: about a microsecond).
+__device__ __forceinline__ void lds_barrier() {
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+}
+
 // Grid barrier: the workgroups form 8 groups (by id mod 8), each with an arrival counter of its own in a separate
 // cache line.  Counters only grow; `gen` is the number of barriers passed, so after barrier number gen counter g
 // holds gen * (size of group g).  Arriving is one atomic add whose result nobody waits for; waiting is eight lanes
@@ -217,8 +226,8 @@ __device__ __forceinline__ void barrier_wait(unsigned* bar, unsigned* err, unsig
         }
     }
     // No cache invalidation: what is read after a barrier lies at addresses no CU has read before in this launch.
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-    __syncthreads();
+    // The workgroup goes on together; weight streams already requested for the coming tiles stay in flight.
+    lds_barrier();
 }
 
 // A 2:4 tile in registers: the sparse operands of its four matrix instructions and their column indices.
@@ -278,14 +287,6 @@ __device__ __forceinline__ void rotated_piece(const float* __restrict__ head, co
 
 __device__ __forceinline__ u32x4 pack_bf16x8(const float (&f)[8]) {
     return u32x4{pack_bf16(f[0], f[1]), pack_bf16(f[2], f[3]), pack_bf16(f[4], f[5]), pack_bf16(f[6], f[7])};
-}
-
-// Workgroup barrier that orders LDS traffic only: the wavefront's own LDS operations have completed, loads and stores
-// to memory stay in flight (a __syncthreads would also wait for every store acknowledgement: about a microsecond).
-__device__ __forceinline__ void lds_barrier() {
-    __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
-    __builtin_amdgcn_s_barrier();
-    asm volatile("" ::: "memory");
 }
 
 constexpr int kAttUnr = 2;                 // passes of a workgroup's cache loads in flight
@@ -677,14 +678,14 @@ __global__ __launch_bounds__(kMegaThreads) void mega_forward_kernel(const MegaAr
                         for (int e = 0; e < 4; ++e) astore(dst + e, hv[t][e]);
                     }
             }
-            __syncthreads();
+            lds_barrier();
             if (tid < k_tok) {
                 float tot = 0.f;
 #pragma unroll
                 for (int w = 0; w < kMegaWaves; ++w) tot += part_sums[w * kMegaMaxTok + tid];
                 sums[8 + tid] = 1.0f / sqrtf(tot / (float)a.hidden + 1e-5f);
             }
-            __syncthreads();
+            lds_barrier();
             const int c = c4 - col_lo;
             if (c >= 0 && c < n_col) {
 #pragma unroll
@@ -804,7 +805,7 @@ __global__ __launch_bounds__(kMegaThreads) void mega_forward_kernel(const MegaAr
                             if (lane == 0) ((wave & 1) ? sp_hi : sp)[i * (i + 1) / 2 + j] = part;  // plain stores, summed below
                         }
             }
-            __syncthreads();
+            lds_barrier();
             // softmax: wavefront = head, lane = (row i, column j); a row's maximum and sum go round its eight lanes
             if (wave < kAttHeads && wave * D < n_col) {
                 const int i = lane >> 3, j = lane & 7;
@@ -823,7 +824,7 @@ __global__ __launch_bounds__(kMegaThreads) void mega_forward_kernel(const MegaAr
                 sum += __shfl_xor(sum, 4);
                 if (on) row[j] = e * __builtin_amdgcn_rcpf(sum);
             }
-            __syncthreads();
+            lds_barrier();
             if (live) {
                 const int cc = hh * D + d;
 #pragma unroll
@@ -845,7 +846,7 @@ __global__ __launch_bounds__(kMegaThreads) void mega_forward_kernel(const MegaAr
                     }
             }
         }
-        __syncthreads();
+        lds_barrier();
         if (tt && tid == 0) tt[2] = __builtin_amdgcn_s_memrealtime();
 
         // ---------------- this wave's tiles of the phase
@@ -929,7 +930,7 @@ __global__ __launch_bounds__(kMegaThreads) void mega_forward_kernel(const MegaAr
         if (ct.n == 0 && nt.n > 0) issue_phase_tile<NM24>(nt, 0, bufs + cb * kTileDw, mk_next, lane);
         ct = nt;
         if (PROBE && tt && tid == 0) tt[7] = __builtin_amdgcn_s_memrealtime();
-        __syncthreads();
+        lds_barrier();
         if (tt && tid == 0) tt[3] = __builtin_amdgcn_s_memrealtime();
 
         // ---------------- the block's results leave the CU: split-K across the slab blocks by float atomics
