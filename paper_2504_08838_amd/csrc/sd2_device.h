@@ -58,6 +58,23 @@ __device__ __forceinline__ uint32_t wave_excl_scan(uint32_t x) {
     return wave_incl_scan(__builtin_amdgcn_update_dpp(0u, x, 0x138, 0xf, 0xf, true));  // wave_shr:1
 }
 
+// Exclusive prefix sums of N values at once, stage by stage: the N cross-lane adds of a stage are independent, so they
+// issue back to back instead of each waiting out the hazard slots behind the one before it.
+template <int N>
+__device__ __forceinline__ void wave_excl_scans(uint32_t (&x)[N]) {
+#define SD2_SCAN_STAGE(ctrl, rmask) \
+    _Pragma("unroll") for (int i = 0; i < N; ++i) x[i] += __builtin_amdgcn_update_dpp(0u, x[i], ctrl, rmask, 0xf, true)
+#pragma unroll
+    for (int i = 0; i < N; ++i) x[i] = __builtin_amdgcn_update_dpp(0u, x[i], 0x138, 0xf, 0xf, true);  // wave_shr:1
+    SD2_SCAN_STAGE(0x111, 0xf);  // row_shr:1
+    SD2_SCAN_STAGE(0x112, 0xf);  // row_shr:2
+    SD2_SCAN_STAGE(0x114, 0xf);  // row_shr:4
+    SD2_SCAN_STAGE(0x118, 0xf);  // row_shr:8
+    SD2_SCAN_STAGE(0x142, 0xa);  // row_bcast:15 -> rows 1,3
+    SD2_SCAN_STAGE(0x143, 0xc);  // row_bcast:31 -> rows 2,3
+#undef SD2_SCAN_STAGE
+}
+
 // Byte-permute selectors that spread up to four compacted bf16 values over four columns.
 // Entry [nib] = {selector for columns 0,1 ; selector for columns 2,3}; 0x0c yields a zero byte.
 __device__ __forceinline__ uint2 make_expand_selector(uint32_t nib) {
@@ -134,9 +151,10 @@ __device__ __forceinline__ void expand_tile(const uint8_t* __restrict__ bufb, co
         // v_perm_b32(hi, lo, sel): selector byte 0..3 picks from lo, 4..7 from hi
         const uint32_t lo_step = __builtin_amdgcn_perm(odd, even, 0x05010400u);  // [n0, n1, n2, n3]
         const uint32_t hi_step = __builtin_amdgcn_perm(odd, even, 0x07030602u);  // [n4, n5, n6, n7]
-        ex[2 * w] = wave_excl_scan(lo_step);      // per nibble: values of lower lanes (<= 252, no carry)
-        ex[2 * w + 1] = wave_excl_scan(hi_step);
+        ex[2 * w] = lo_step;
+        ex[2 * w + 1] = hi_step;
     }
+    wave_excl_scans(ex);  // per nibble: values of lower lanes (<= 252, no carry); the four scans advance together
 #pragma unroll
     for (int part = 0; part < 4 / STEPS; ++part) {
         Tri32 tr[4 * STEPS];

@@ -68,6 +68,22 @@ __device__ __forceinline__ float wave_sum(float v) {
     return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
 }
 
+// The same for N values at once, stage by stage: the N cross-lane adds of a stage are independent, so they issue back to
+// back and fill the wait states that a chain of dependent cross-lane operations would spend idle.  Result in lane 63.
+template <int N>
+__device__ __forceinline__ void wave_sums_lane63(float (&v)[N]) {
+#define SD2_DPP_STAGE(ctrl, rmask) \
+    _Pragma("unroll") for (int i = 0; i < N; ++i) \
+        v[i] += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v[i]), ctrl, rmask, 0xf, true))
+    SD2_DPP_STAGE(0x111, 0xf);  // row_shr:1
+    SD2_DPP_STAGE(0x112, 0xf);  // row_shr:2
+    SD2_DPP_STAGE(0x114, 0xf);  // row_shr:4
+    SD2_DPP_STAGE(0x118, 0xf);  // row_shr:8
+    SD2_DPP_STAGE(0x142, 0xa);  // row_bcast:15
+    SD2_DPP_STAGE(0x143, 0xc);  // row_bcast:31
+#undef SD2_DPP_STAGE
+}
+
 // The argument block as it sits in the kernarg segment: indexing it with a run-time (wave-uniform) index
 // gives scalar loads, where indexing the by-value parameter would make the compiler copy it to scratch.
 typedef const __attribute__((address_space(4))) MegaArgs* KArgs;
@@ -661,12 +677,18 @@ __global__ __launch_bounds__(kMegaThreads) void mega_forward_kernel(const MegaAr
                     __builtin_amdgcn_s_waitcnt(0);
                     if (tt && tid == 0) tt[5] = __builtin_amdgcn_s_memrealtime();
             }
+            {
+                // sums of squares of all token slots at once (unused slots hold zeros); lane 63 ends up with the totals
+                float ss[kMegaMaxTok];
 #pragma unroll
-            for (int t = 0; t < kMegaMaxTok; ++t)
-                if (t < k_tok) {
-                    const float ss = wave_sum(hv[t][0] * hv[t][0] + hv[t][1] * hv[t][1] + hv[t][2] * hv[t][2] + hv[t][3] * hv[t][3]);
-                    if (lane == 0) part_sums[wave * kMegaMaxTok + t] = ss;  // plain store: LDS float atomics are slow
+                for (int t = 0; t < kMegaMaxTok; ++t)
+                    ss[t] = hv[t][0] * hv[t][0] + hv[t][1] * hv[t][1] + hv[t][2] * hv[t][2] + hv[t][3] * hv[t][3];
+                wave_sums_lane63(ss);
+                if (lane == 63) {
+#pragma unroll
+                    for (int t = 0; t < kMegaMaxTok; ++t) part_sums[wave * kMegaMaxTok + t] = ss[t];  // plain stores: LDS float atomics are slow
                 }
+            }
             // the next version of the residual starts as a copy of this one (the linear after next adds into it); the
             // workgroups share the copying, written through to memory
             if (copies_residual && c4 < a.hidden) {
@@ -796,14 +818,20 @@ __global__ __launch_bounds__(kMegaThreads) void mega_forward_kernel(const MegaAr
             float* sp = misc + hh * 36;
             float* sp_hi = misc + 216 + hh * 36;
             if (live) {
+                // a row of the triangle at a time: its products are summed across the lanes together
+                float* share = (wave & 1) ? sp_hi : sp;
 #pragma unroll
                 for (int i = 0; i < kMegaMaxTok; ++i)
+                    if (i < k_tok) {
+                        float part[kMegaMaxTok];
 #pragma unroll
-                    for (int j = 0; j <= i; ++j)
-                        if (i < k_tok) {
-                            const float part = wave_sum(qv[i] * kv[j]);
-                            if (lane == 0) ((wave & 1) ? sp_hi : sp)[i * (i + 1) / 2 + j] = part;  // plain stores, summed below
+                        for (int j = 0; j < kMegaMaxTok; ++j) part[j] = j <= i ? qv[i] * kv[j] : 0.f;
+                        wave_sums_lane63(part);
+                        if (lane == 63) {
+#pragma unroll
+                            for (int j = 0; j <= i; ++j) share[i * (i + 1) / 2 + j] = part[j];  // plain stores, summed below
                         }
+                    }
             }
             lds_barrier();
             // softmax: wavefront = head, lane = (row i, column j); a row's maximum and sum go round its eight lanes
