@@ -551,10 +551,13 @@ __global__ __launch_bounds__(kMegaThreads) void mega_forward_kernel(const MegaAr
     }
     __syncthreads();
     // this wave's tiles of the first phase; the first one's stream is requested right away
-    PhaseTiles ct, nt;
+    // Plans run two phases ahead of the tiles (ct: this phase, nt: the next, nnt: the one after), so that the loads of a
+    // plan's directory entries have a whole phase to arrive and nobody waits for them between a barrier and the work.
+    PhaseTiles ct, nt, nnt;
     plan_phase<NM24>(ct, ka, plans, 0, n_phases, wave, lane);
     uint2 mk_next = make_uint2(0, 0);
     if (ct.n > 0) issue_phase_tile<NM24>(ct, 0, bufs, mk_next, lane);
+    plan_phase<NM24>(nt, ka, plans, 1, n_phases, wave, lane);
     unsigned gen = 0;
     int spin_limit = a.spin_limit;
     const bool copies_residual = (tid % ncu) == cu;  // this thread's columns of the residual are copied by this workgroup
@@ -572,8 +575,6 @@ __global__ __launch_bounds__(kMegaThreads) void mega_forward_kernel(const MegaAr
         unsigned long long* tt = a.trace_time ? a.trace_time + ((size_t)cu * n_phases + p) * 8 : nullptr;
         if (tt && tid == 0) tt[0] = __builtin_amdgcn_s_memrealtime();
         if (p > 0) barrier_arrive(a.bar, gen);
-        // next phase's tiles: planned now so that the directory loads have the whole phase to arrive
-        plan_phase<NM24>(nt, ka, plans, p + 1, n_phases, wave, lane);
 
         if (KV && kind == 1) {
             // The attention step over the cache, then a barrier of its own; the first tile of the linear is expanded
@@ -641,6 +642,7 @@ __global__ __launch_bounds__(kMegaThreads) void mega_forward_kernel(const MegaAr
             tpre.idx = make_uint2(0u, 0u);
         }
         if (PROBE && tt && tid == 0) tt[4] = __builtin_amdgcn_s_memrealtime();
+        plan_phase<NM24>(nnt, ka, plans, p + 2, n_phases, wave, lane);  // its loads travel during the barrier and the prologue
         if (p > 0) barrier_wait(a.bar, a.err, (unsigned)ncu, gen, spin_limit);
         if (tt && tid == 0) tt[1] = __builtin_amdgcn_s_memrealtime();
 
@@ -957,6 +959,7 @@ __global__ __launch_bounds__(kMegaThreads) void mega_forward_kernel(const MegaAr
         // a wavefront without tiles in this phase starts the stream of its first tile of the next one here
         if (ct.n == 0 && nt.n > 0) issue_phase_tile<NM24>(nt, 0, bufs + cb * kTileDw, mk_next, lane);
         ct = nt;
+        nt = nnt;
         if (PROBE && tt && tid == 0) tt[7] = __builtin_amdgcn_s_memrealtime();
         lds_barrier();
         if (tt && tid == 0) tt[3] = __builtin_amdgcn_s_memrealtime();
