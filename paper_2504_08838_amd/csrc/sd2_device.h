@@ -133,14 +133,10 @@ __device__ __forceinline__ void issue_tile(u32x4 (&st)[MAXCH], uint2& mk, const 
 //
 // The four scans run first and the LDS reads of STEPS super-steps are issued back to back before the
 // first is consumed, so that a wavefront pays the LDS latency 4 / STEPS times per tile, not per nibble.
-template <int STEPS = 2, typename F>
-__device__ __forceinline__ void expand_tile(const uint8_t* __restrict__ bufb, const uint2* __restrict__ lut,
-                                            const uint32_t (&base)[8], uint2 mk, F&& use) {
-    static_assert(STEPS == 1 || STEPS == 2 || STEPS == 4, "super-steps whose LDS reads are batched");
+// First stage of the expansion: per super-step q, the four 8-bit exclusive prefix counts of its nibbles in ex[q].
+__device__ __forceinline__ void expand_scans(uint2 mk, uint32_t (&ex)[4]) {
     // Nibble popcounts of a 32-bit mask word (two super-steps) at once: the classic pairwise sums give eight
     // 4-bit counts, two masks split them into bytes, and one byte permute per super-step lines up its four counts.
-    const uint32_t lds_base = (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) uint8_t*)bufb;  // LDS byte address
-    uint32_t ex[4];
 #pragma unroll
     for (int w = 0; w < 2; ++w) {
         const uint32_t m = w ? mk.y : mk.x;
@@ -149,44 +145,56 @@ __device__ __forceinline__ void expand_tile(const uint8_t* __restrict__ bufb, co
         const uint32_t even = x & 0x0f0f0f0fu;                 // bytes: counts of nibbles 0, 2, 4, 6
         const uint32_t odd = (x >> 4) & 0x0f0f0f0fu;           // bytes: counts of nibbles 1, 3, 5, 7
         // v_perm_b32(hi, lo, sel): selector byte 0..3 picks from lo, 4..7 from hi
-        const uint32_t lo_step = __builtin_amdgcn_perm(odd, even, 0x05010400u);  // [n0, n1, n2, n3]
-        const uint32_t hi_step = __builtin_amdgcn_perm(odd, even, 0x07030602u);  // [n4, n5, n6, n7]
-        ex[2 * w] = lo_step;
-        ex[2 * w + 1] = hi_step;
+        ex[2 * w] = __builtin_amdgcn_perm(odd, even, 0x05010400u);      // [n0, n1, n2, n3]
+        ex[2 * w + 1] = __builtin_amdgcn_perm(odd, even, 0x07030602u);  // [n4, n5, n6, n7]
     }
     wave_excl_scans(ex);  // per nibble: values of lower lanes (<= 252, no carry); the four scans advance together
+}
+
+// Second stage: super-steps STEPS * part .. STEPS * part + STEPS - 1, handed to use(q, f0, f1).
+template <int STEPS, typename F>
+__device__ __forceinline__ void expand_part(int part, const uint8_t* __restrict__ bufb, const uint2* __restrict__ lut,
+                                            const uint32_t (&base)[8], uint2 mk, const uint32_t (&ex)[4], F&& use) {
+    static_assert(STEPS == 1 || STEPS == 2 || STEPS == 4, "super-steps whose LDS reads are batched");
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) uint8_t*)bufb;  // LDS byte address
+    Tri32 tr[4 * STEPS];
+    uint2 sel[4 * STEPS];
+    uint32_t off[4 * STEPS];
 #pragma unroll
-    for (int part = 0; part < 4 / STEPS; ++part) {
-        Tri32 tr[4 * STEPS];
-        uint2 sel[4 * STEPS];
-        uint32_t off[4 * STEPS];
-#pragma unroll
-        for (int i = 0; i < 4 * STEPS; ++i) {
-            const int q = STEPS * part + (i >> 2), h = i & 3;
-            const uint32_t m = (q >> 1) ? mk.y : mk.x;
-            const uint32_t run_base = (base[(4 * q + h) >> 1] >> (16 * (h & 1))) & 0xffffu;
-            // LDS address of the lane's first value: the run's start is scalar arithmetic, the lane adds its prefix
-            // (the buffer is 4-byte aligned, so the low address bits are the byte offset's)
-            off[i] = (lds_base + run_base * 2u) + __builtin_amdgcn_ubfe(ex[q], 8 * h, 8) * 2u;
-            const __attribute__((address_space(3))) uint32_t* win =
-                (const __attribute__((address_space(3))) uint32_t*)(uintptr_t)(off[i] & ~3u);
-            tr[i].a = win[0];
-            tr[i].b = win[1];
-            tr[i].c = win[2];
-            sel[i] = lut[__builtin_amdgcn_ubfe(m, 16 * (q & 1) + 4 * h, 4)];
-        }
-        Frag f[STEPS][2];
-#pragma unroll
-        for (int i = 0; i < 4 * STEPS; ++i) {
-            const int h = i & 3;
-            const uint32_t w0 = __builtin_amdgcn_alignbyte(tr[i].b, tr[i].a, off[i]);
-            const uint32_t w1 = __builtin_amdgcn_alignbyte(tr[i].c, tr[i].b, off[i]);
-            f[i >> 2][h >> 1].u[2 * (h & 1) + 0] = __builtin_amdgcn_perm(w1, w0, sel[i].x);
-            f[i >> 2][h >> 1].u[2 * (h & 1) + 1] = __builtin_amdgcn_perm(w1, w0, sel[i].y);
-        }
-#pragma unroll
-        for (int j = 0; j < STEPS; ++j) use(STEPS * part + j, f[j][0], f[j][1]);
+    for (int i = 0; i < 4 * STEPS; ++i) {
+        const int q = STEPS * part + (i >> 2), h = i & 3;
+        const uint32_t m = (q >> 1) ? mk.y : mk.x;
+        const uint32_t run_base = (base[(4 * q + h) >> 1] >> (16 * (h & 1))) & 0xffffu;
+        // LDS address of the lane's first value: the run's start is scalar arithmetic, the lane adds its prefix
+        // (the buffer is 4-byte aligned, so the low address bits are the byte offset's)
+        off[i] = (lds_base + run_base * 2u) + __builtin_amdgcn_ubfe(ex[q], 8 * h, 8) * 2u;
+        const __attribute__((address_space(3))) uint32_t* win =
+            (const __attribute__((address_space(3))) uint32_t*)(uintptr_t)(off[i] & ~3u);
+        tr[i].a = win[0];
+        tr[i].b = win[1];
+        tr[i].c = win[2];
+        sel[i] = lut[__builtin_amdgcn_ubfe(m, 16 * (q & 1) + 4 * h, 4)];
     }
+    Frag f[STEPS][2];
+#pragma unroll
+    for (int i = 0; i < 4 * STEPS; ++i) {
+        const int h = i & 3;
+        const uint32_t w0 = __builtin_amdgcn_alignbyte(tr[i].b, tr[i].a, off[i]);
+        const uint32_t w1 = __builtin_amdgcn_alignbyte(tr[i].c, tr[i].b, off[i]);
+        f[i >> 2][h >> 1].u[2 * (h & 1) + 0] = __builtin_amdgcn_perm(w1, w0, sel[i].x);
+        f[i >> 2][h >> 1].u[2 * (h & 1) + 1] = __builtin_amdgcn_perm(w1, w0, sel[i].y);
+    }
+#pragma unroll
+    for (int j = 0; j < STEPS; ++j) use(STEPS * part + j, f[j][0], f[j][1]);
+}
+
+template <int STEPS = 2, typename F>
+__device__ __forceinline__ void expand_tile(const uint8_t* __restrict__ bufb, const uint2* __restrict__ lut,
+                                            const uint32_t (&base)[8], uint2 mk, F&& use) {
+    uint32_t ex[4];
+    expand_scans(mk, ex);
+#pragma unroll
+    for (int part = 0; part < 4 / STEPS; ++part) expand_part<STEPS>(part, bufb, lut, base, mk, ex, use);
 }
 
 // The same request with the value stream written straight into LDS (no staging registers): piece c of the
