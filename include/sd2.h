@@ -289,6 +289,12 @@ int sd2_greedy_verify(const int32_t* draft_dev, const int32_t* target_dev, int32
 /* SD2_ERR_RANGE if any of the n host ids lies outside [0, vocab). */
 int sd2_check_token_ids_host(const int32_t* ids, size_t n, int32_t vocab);
 
+/* Expected improvement factor of draft-then-verify over decoding with the target alone (Eq. 3): MAL / (k c + 1), with MAL the
+ * mean number of tokens emitted per round (accepted drafts plus the target's one), k the drafts per round and c the cost of a
+ * drafter step relative to a target step (a latency ratio in practice, a MAC ratio in theory: Sec. 2.1).  Host arithmetic in
+ * double precision.  mean_emitted >= 0, k >= 0, cost_ratio >= 0 and all finite, else SD2_ERR_RANGE. */
+int sd2_improvement_factor(double mean_emitted, int32_t k, double cost_ratio, double* factor_out);
+
 /* ------------------------------------------------------------------ one-shot pruning
  * Sec. 2.3: every decoder linear is pruned one-shot to a uniform per-layer sparsity.  The paper's criterion is
  * second-order and needs calibration data; this call prunes by weight magnitude, in place, on the device:

@@ -110,6 +110,7 @@ def lib():
             "sd2_drafter_forward_status": (C.c_int, [vp, i32, vp, vp]),
             "sd2_calibration_copy": (C.c_int, [vp, vp, sz, vp]),
             "sd2_mask_gradient": (C.c_int, [vp, vp, i32, vp]),
+            "sd2_improvement_factor": (C.c_int, [C.c_double, i32, C.c_double, C.POINTER(C.c_double)]),
             "sd2_draft_round_cached_workspace_size": (C.c_int, [vp, i32, i32, C.POINTER(sz)]),
             "sd2_draft_round_cached": (C.c_int, [vp, vp, i32, vp, i32, i32, vp, vp, i32, C.c_double, vp, vp, sz, vp]),
             "sd2_draft_round_cached_status": (C.c_int, [vp, i32, i32, vp, vp]),
@@ -369,6 +370,13 @@ def mask_gradient(m, grad_ptr, grad_is_bf16, stream=0):
 def calibration_copy(dst_ptr, src_ptr, nbytes, stream=0):
     _check(lib().sd2_calibration_copy(C.c_void_p(dst_ptr), C.c_void_p(src_ptr), nbytes, C.c_void_p(stream)),
            "sd2_calibration_copy")
+
+
+def improvement_factor(mean_emitted, k, cost_ratio):
+    """Eq. 3 on the host."""
+    out = C.c_double(0.0)
+    _check(lib().sd2_improvement_factor(float(mean_emitted), int(k), float(cost_ratio), C.byref(out)), "sd2_improvement_factor")
+    return out.value
 
 
 def check_token_ids_host(ids, vocab):

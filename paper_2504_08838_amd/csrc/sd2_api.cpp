@@ -3,6 +3,7 @@
 #include <string.h>
 
 #include <algorithm>
+#include <cmath>
 #include <new>
 #include <vector>
 
@@ -634,6 +635,14 @@ int sd2_greedy_verify(const int32_t* draft, const int32_t* target, int32_t batch
     if (!target || !accepted || !out_tokens || (k > 0 && !draft)) return SD2_ERR_NULL;
     if (launch_greedy_verify(draft, target, batch, k, accepted, out_tokens, static_cast<hipStream_t>(stream)) != hipSuccess)
         return SD2_ERR_HIP;
+    return SD2_OK;
+}
+
+int sd2_improvement_factor(double mean_emitted, int32_t k, double cost_ratio, double* factor_out) {
+    if (!factor_out) return SD2_ERR_NULL;
+    if (!(mean_emitted >= 0.0) || !(cost_ratio >= 0.0) || k < 0 || !std::isfinite(mean_emitted) || !std::isfinite(cost_ratio))
+        return SD2_ERR_RANGE;
+    *factor_out = mean_emitted / ((double)k * cost_ratio + 1.0);
     return SD2_OK;
 }
 

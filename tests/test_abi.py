@@ -246,3 +246,19 @@ def test_cached_round_argument_checks():
     assert L.sd2_draft_round_cached(*args(vocab=0)) == -2
     assert L.sd2_draft_round_cached(*args(wsb=n - 1)) == -4
     sd2.model_destroy(model)
+
+
+def test_improvement_factor_matches_eq3_and_the_oracle():
+    from oracle import macs
+    # Eq. 3 by hand: 4.16 tokens per round, 5 drafts, drafter step 5 % of a target step -> 4.16 / 1.25
+    assert sd2.improvement_factor(4.16, 5, 0.05) == pytest.approx(3.328, rel=1e-12)
+    assert sd2.improvement_factor(4.0, 5, 0.0) == 4.0
+    for mal, k, c in [(1.0, 0, 0.3), (3.61, 5, 0.11), (6.0, 8, 1.0), (2.5, 3, 2.0)]:
+        assert sd2.improvement_factor(mal, k, c) == pytest.approx(macs.improvement_factor(mal, k, c), rel=1e-15)
+    L = sd2.lib()
+    out = C.c_double(0.0)
+    assert L.sd2_improvement_factor(4.0, 5, 0.1, None) == -1
+    assert L.sd2_improvement_factor(-1.0, 5, 0.1, C.byref(out)) == -6
+    assert L.sd2_improvement_factor(4.0, -1, 0.1, C.byref(out)) == -6
+    assert L.sd2_improvement_factor(4.0, 5, float("nan"), C.byref(out)) == -6
+    assert L.sd2_improvement_factor(float("inf"), 5, 0.1, C.byref(out)) == -6
