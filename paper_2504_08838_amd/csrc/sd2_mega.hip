@@ -820,20 +820,33 @@ __global__ __launch_bounds__(kMegaThreads) void mega_forward_kernel(const MegaAr
             float* sp = misc + hh * 36;
             float* sp_hi = misc + 216 + hh * 36;
             if (live) {
-                // a row of the triangle at a time: its products are summed across the lanes together
+                // The triangle in batches whose sums cross the lanes together: rows 0..2 (six products), then a row at a
+                // time (four to eight products): wide enough to fill the hazard slots, without the unused half of a square.
                 float* share = (wave & 1) ? sp_hi : sp;
+                {
+                    float part[6] = {qv[0] * kv[0], qv[1] * kv[0], qv[1] * kv[1], qv[2] * kv[0], qv[2] * kv[1], qv[2] * kv[2]};
+                    wave_sums_lane63(part);  // (rows of unused token slots are zeros: nothing reads them)
+                    if (lane == 63) {
 #pragma unroll
-                for (int i = 0; i < kMegaMaxTok; ++i)
-                    if (i < k_tok) {
-                        float part[kMegaMaxTok];
-#pragma unroll
-                        for (int j = 0; j < kMegaMaxTok; ++j) part[j] = j <= i ? qv[i] * kv[j] : 0.f;
-                        wave_sums_lane63(part);
-                        if (lane == 63) {
-#pragma unroll
-                            for (int j = 0; j <= i; ++j) share[i * (i + 1) / 2 + j] = part[j];  // plain stores, summed below
-                        }
+                        for (int e = 0; e < 6; ++e) share[e] = part[e];  // plain stores, summed below
                     }
+                }
+#define SD2_SCORE_ROW(I) \
+    if (I < k_tok) { \
+        float part[I + 1]; \
+        _Pragma("unroll") for (int j = 0; j <= I; ++j) part[j] = qv[I] * kv[j]; \
+        wave_sums_lane63(part); \
+        if (lane == 63) { \
+            _Pragma("unroll") for (int j = 0; j <= I; ++j) share[I * (I + 1) / 2 + j] = part[j]; \
+        } \
+    }
+                SD2_SCORE_ROW(3)
+                SD2_SCORE_ROW(4)
+                SD2_SCORE_ROW(5)
+                SD2_SCORE_ROW(6)
+                SD2_SCORE_ROW(7)
+#undef SD2_SCORE_ROW
+                static_assert(kMegaMaxTok == 8, "one row of scores per token slot");
             }
             lds_barrier();
             // softmax: wavefront = head, lane = (row i, column j); a row's maximum and sum go round its eight lanes
