@@ -71,8 +71,25 @@ size_t partial_bytes(const sd2_matrix_t* m, int k_tok) {
 
 int check_tokens(int32_t k_tok) { return (k_tok < 1 || k_tok > SD2_MAX_TOKENS) ? SD2_ERR_RANGE : SD2_OK; }
 
-hipError_t run_linear(const sd2_matrix_t* m, const uint16_t* x, int k_tok, float* out, hipStream_t s) {
+// The bitmask format has a kernel that adds the slabs up inside the workgroup, too (up to 16 tokens, up to 32 slabs,
+// tiles that fit its buffers); SD2_LINEAR=partials keeps the kernel with one partial result per slab (tests cover both).
+inline bool sparse_final_ok(const sd2_matrix_t* m, int k_tok) {
+    if (m->kind != SD2_KIND_SPARSE || is_nm24(m)) return false;
+    const char* force = getenv("SD2_LINEAR");
+    if (force && strcmp(force, "partials") == 0) return false;
+    return sparse_strip_supported(mat_args(m), k_tok);
+}
+
+// Partial results run_linear leaves in `out` for this token count (1: final values).  Never more than n_partials(m),
+// which sizes the buffers.
+inline int n_splits(const sd2_matrix_t* m, int k_tok) { return sparse_final_ok(m, k_tok) ? 1 : n_partials(m); }
+
+hipError_t run_linear(const sd2_matrix_t* m, const uint16_t* x, int k_tok, float* out, hipStream_t s, bool allow_final = true) {
     MatArgs ma = mat_args(m);
+    if (allow_final && sparse_final_ok(m, k_tok)) {
+        LinArgs la{x, k_tok, out};
+        return launch_sparse_strip_linear(ma, la, s);
+    }
     if (is_nm24(m)) {
         // the structured-sparse matrix instruction takes 16 tokens; more tokens stream the matrix once per group
         for (int t0 = 0; t0 < k_tok; t0 += 16) {
@@ -102,11 +119,13 @@ int linear_entry(const sd2_matrix_t* m, int kind, const uint16_t* x, int32_t k_t
     if ((rc = check_tokens(k_tok)) != SD2_OK) return rc;
     if (!aligned16(x) || !aligned16(y)) return SD2_ERR_BUFFER;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    if (n_partials(m) == 1) {
+    if (n_partials(m) > 1) {  // the contract of the workspace does not depend on which kernel runs
+        if (!ws) return SD2_ERR_NULL;
+        if (!aligned16(ws) || ws_bytes < partial_bytes(m, k_tok)) return SD2_ERR_BUFFER;
+    }
+    if (n_splits(m, k_tok) == 1) {
         return run_linear(m, x, k_tok, y, s) == hipSuccess ? SD2_OK : SD2_ERR_HIP;
     }
-    if (!ws) return SD2_ERR_NULL;
-    if (!aligned16(ws) || ws_bytes < partial_bytes(m, k_tok)) return SD2_ERR_BUFFER;
     float* part = static_cast<float*>(ws);
     if (run_linear(m, x, k_tok, part, s) != hipSuccess) return SD2_ERR_HIP;
     if (launch_reduce_partials(part, n_partials(m), (size_t)k_tok * m->info.n_out, y, s) != hipSuccess)
@@ -243,7 +262,7 @@ int sd2_sparse_linear_partials(const sd2_matrix_t* m, const uint16_t* x, int32_t
     if (!x || !part) return SD2_ERR_NULL;
     if ((rc = check_tokens(k_tok)) != SD2_OK) return rc;
     if (!aligned16(x) || !aligned16(part) || part_bytes < partial_bytes(m, k_tok)) return SD2_ERR_BUFFER;
-    return run_linear(m, x, k_tok, part, static_cast<hipStream_t>(stream)) == hipSuccess ? SD2_OK : SD2_ERR_HIP;
+    return run_linear(m, x, k_tok, part, static_cast<hipStream_t>(stream), /*allow_final=*/false) == hipSuccess ? SD2_OK : SD2_ERR_HIP;
 }
 
 int sd2_dense_linear(const sd2_matrix_t* m, const uint16_t* x, int32_t k_tok, float* y, void* ws, size_t ws_bytes,
@@ -283,10 +302,10 @@ int sd2_sparse_mlp_forward(const sd2_matrix_t* gu, const sd2_matrix_t* dn, const
     uint16_t* act = static_cast<uint16_t*>(ws);
     float* part = reinterpret_cast<float*>(static_cast<uint8_t*>(ws) + align256((size_t)k_tok * inter * sizeof(uint16_t)));
     if (run_linear(gu, x, k_tok, part, s) != hipSuccess) return SD2_ERR_HIP;
-    if (launch_silu_mul(part, n_partials(gu), k_tok, inter, act, s) != hipSuccess) return SD2_ERR_HIP;
-    if (n_partials(dn) == 1) return run_linear(dn, act, k_tok, y, s) == hipSuccess ? SD2_OK : SD2_ERR_HIP;
+    if (launch_silu_mul(part, n_splits(gu, k_tok), k_tok, inter, act, s) != hipSuccess) return SD2_ERR_HIP;
+    if (n_splits(dn, k_tok) == 1) return run_linear(dn, act, k_tok, y, s) == hipSuccess ? SD2_OK : SD2_ERR_HIP;
     if (run_linear(dn, act, k_tok, part, s) != hipSuccess) return SD2_ERR_HIP;
-    if (launch_reduce_partials(part, n_partials(dn), (size_t)k_tok * dn->info.n_out, y, s) != hipSuccess)
+    if (launch_reduce_partials(part, n_splits(dn, k_tok), (size_t)k_tok * dn->info.n_out, y, s) != hipSuccess)
         return SD2_ERR_HIP;
     return SD2_OK;
 }
@@ -450,17 +469,17 @@ static int forward_impl(const sd2_model_t* md, const uint16_t* h_in, int32_t k_t
         const sd2_matrix_t* dn = &md->mats[4 * l + 3];
         SD2_TRY(record(4 * l + 0, h, nullptr, 0, sh.hidden, sh.hidden));
         SD2_TRY(run_linear(qkv, act, k_tok, part, s));
-        SD2_TRY(launch_inflight_attention(part, n_partials(qkv), k_tok, sh.q_out, sh.kv_out, sh.n_heads, sh.n_kv,
+        SD2_TRY(launch_inflight_attention(part, n_splits(qkv, k_tok), k_tok, sh.q_out, sh.kv_out, sh.n_heads, sh.n_kv,
                                           sh.head_dim, act, s));
-        SD2_TRY(record(4 * l + 1, nullptr, part, n_partials(qkv), sh.q_out + 2 * sh.kv_out, sh.q_out));
+        SD2_TRY(record(4 * l + 1, nullptr, part, n_splits(qkv, k_tok), sh.q_out + 2 * sh.kv_out, sh.q_out));
         SD2_TRY(run_linear(o, act, k_tok, part, s));
-        SD2_TRY(launch_residual_rmsnorm(h, nullptr, part, n_partials(o), k_tok, sh.hidden, act, ssq, s));
+        SD2_TRY(launch_residual_rmsnorm(h, nullptr, part, n_splits(o, k_tok), k_tok, sh.hidden, act, ssq, s));
         SD2_TRY(record(4 * l + 2, h, nullptr, 0, sh.hidden, sh.hidden));
         SD2_TRY(run_linear(gu, act, k_tok, part, s));
-        SD2_TRY(launch_silu_mul(part, n_partials(gu), k_tok, sh.inter, act, s));
-        SD2_TRY(record(4 * l + 3, nullptr, part, n_partials(gu), 2 * sh.inter, sh.inter));
+        SD2_TRY(launch_silu_mul(part, n_splits(gu, k_tok), k_tok, sh.inter, act, s));
+        SD2_TRY(record(4 * l + 3, nullptr, part, n_splits(gu, k_tok), 2 * sh.inter, sh.inter));
         SD2_TRY(run_linear(dn, act, k_tok, part, s));
-        SD2_TRY(launch_residual_rmsnorm(h, nullptr, part, n_partials(dn), k_tok, sh.hidden,
+        SD2_TRY(launch_residual_rmsnorm(h, nullptr, part, n_splits(dn, k_tok), k_tok, sh.hidden,
                                         l + 1 < sh.layers ? act : nullptr, ssq, s));
     }
 #undef SD2_TRY
@@ -612,15 +631,15 @@ int sd2_sparse_drafter_decode(const sd2_model_t* md, const uint16_t* h_in, int32
         uint16_t* kc = k_cache + (size_t)l * layer_elems;
         uint16_t* vc = v_cache + (size_t)l * layer_elems;
         SD2_TRY(run_linear(qkv, act, k_tok, part, s));
-        SD2_TRY(launch_rope_append(part, n_partials(qkv), k_tok, sh.q_out, sh.kv_out, sh.n_heads, sh.n_kv, sh.head_dim, table,
+        SD2_TRY(launch_rope_append(part, n_splits(qkv, k_tok), k_tok, sh.q_out, sh.kv_out, sh.n_heads, sh.n_kv, sh.head_dim, table,
                                    pos0, max_pos, q_rot, kc, vc, s));
         SD2_TRY(launch_cached_attention(q_rot, kc, vc, max_pos, pos0, k_tok, sh.q_out, sh.n_heads, sh.n_kv, sh.head_dim, act, s));
         SD2_TRY(run_linear(o, act, k_tok, part, s));
-        SD2_TRY(launch_residual_rmsnorm(h, nullptr, part, n_partials(o), k_tok, sh.hidden, act, ssq, s));
+        SD2_TRY(launch_residual_rmsnorm(h, nullptr, part, n_splits(o, k_tok), k_tok, sh.hidden, act, ssq, s));
         SD2_TRY(run_linear(gu, act, k_tok, part, s));
-        SD2_TRY(launch_silu_mul(part, n_partials(gu), k_tok, sh.inter, act, s));
+        SD2_TRY(launch_silu_mul(part, n_splits(gu, k_tok), k_tok, sh.inter, act, s));
         SD2_TRY(run_linear(dn, act, k_tok, part, s));
-        SD2_TRY(launch_residual_rmsnorm(h, nullptr, part, n_partials(dn), k_tok, sh.hidden,
+        SD2_TRY(launch_residual_rmsnorm(h, nullptr, part, n_splits(dn, k_tok), k_tok, sh.hidden,
                                         l + 1 < sh.layers ? act : nullptr, ssq, s));
     }
 #undef SD2_TRY

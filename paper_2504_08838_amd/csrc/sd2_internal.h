@@ -26,6 +26,9 @@ struct LinArgs {
 
 hipError_t launch_sparse_linear(const MatArgs& m, const LinArgs& a, hipStream_t s);
 hipError_t launch_dense_linear(const MatArgs& m, const LinArgs& a, hipStream_t s);
+// the sparse linear with final results in one launch (no partial sums): a.out is y [k_tok][n_out]
+bool sparse_strip_supported(const MatArgs& m, int k_tok);
+hipError_t launch_sparse_strip_linear(const MatArgs& m, const LinArgs& a, hipStream_t s);
 
 // y[i] = sum_s part[s][i], i < n  (n = k_tok * n_out)
 hipError_t launch_reduce_partials(const float* part, int n_splits, size_t n, float* y, hipStream_t s);

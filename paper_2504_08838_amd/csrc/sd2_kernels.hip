@@ -127,6 +127,121 @@ __global__ __launch_bounds__(256) void sparse_linear_kernel(const DirEnt* __rest
                                   k_in, k_tok, n_strips, n_tiles, t1 - 1, lane);
 }
 
+// ------------------------------------------------------------------ sparse linear, final results in one launch
+//
+// The same tiles, walked so that no partial sums leave the compute unit (k_tok <= 16).  A workgroup owns strips
+// b, b + G, ...; the contraction of a strip is split over its wavefronts by slab: wavefront w owns slabs w, w + WAVES, ...
+// (SPW of them) and sums their tiles of a strip in its accumulator.  The wavefronts' 16 x 16 blocks of a strip meet in
+// LDS; every few strips a barrier that waits for LDS only lets the threads add them in a fixed order and write y.  A wavefront with one slab keeps that slab's activation columns in registers for the whole kernel; with
+// more slabs it fetches them per tile (they stay in the caches).  The streams of the next two tiles are in flight in
+// registers while the current one is expanded.
+constexpr int kStripRound = 4;  // strips between two workgroup barriers of the kernel below
+
+template <int MAXCH, int SPW, int WAVES>
+__global__ __launch_bounds__(64 * WAVES) void sparse_strip_kernel(const DirEnt* __restrict__ dir, const uint2* __restrict__ masks,
+                                                                 const uint16_t* __restrict__ vals,
+                                                                 const uint16_t* __restrict__ x, float* __restrict__ y,
+                                                                 int n_out, int k_in, int k_tok, int n_strips, int n_slabs) {
+    extern __shared__ uint32_t strip_smem[];  // [WAVES][MAXCH * 256] tile buffers, then [kStripRound][WAVES][256] floats
+    __shared__ uint2 lut[16];
+    const int tid = threadIdx.x;
+    if (tid < 16) lut[tid] = make_expand_selector((uint32_t)tid);
+    __syncthreads();
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int n = lane & 15, g = lane >> 4;
+    uint32_t* buf = strip_smem + wave * (MAXCH * 256);
+    float* red = reinterpret_cast<float*>(strip_smem + WAVES * (MAXCH * 256));
+    const int my_strips = (n_strips - (int)blockIdx.x + (int)gridDim.x - 1) / (int)gridDim.x;
+    int n_mine = 0;  // this wavefront's slabs: wave + WAVES * j
+#pragma unroll
+    for (int j = 0; j < SPW; ++j) n_mine += (wave + WAVES * j < n_slabs) ? 1 : 0;
+    const int n_flat = my_strips * n_mine;  // its tiles, strip by strip
+    auto tile_of = [&](int f) {
+        const int i = f / max(n_mine, 1), j = f - i * max(n_mine, 1);
+        return (wave + WAVES * j) * n_strips + ((int)blockIdx.x + i * (int)gridDim.x);
+    };
+
+    // The strips are handled in rounds of kStripRound: every wavefront leaves its block of a strip in the strip's slot,
+    // one barrier (LDS only: streams stay in flight) ends the round, and the threads share the adding: entry e of a
+    // block is token (e & 63) >> 2, row 4 (e >> 6) + (e & 3) of the strip.  A second barrier frees the slots.
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    auto round_end = [&](int i_first, int n_in_round) {
+        __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        for (int idx = tid; idx < n_in_round * 256; idx += 64 * WAVES) {
+            const int r = idx >> 8, e = idx & 255;
+            const float* slot = red + (size_t)r * (WAVES * 256);
+            float v = 0.f;
+#pragma unroll
+            for (int ww = 0; ww < WAVES; ++ww) v += slot[ww * 256 + e];
+            const int tok = (e & 63) >> 2;
+            const int row = ((int)blockIdx.x + (i_first + r) * (int)gridDim.x) * 16 + 4 * (e >> 6) + (e & 3);
+            if (row < n_out && tok < k_tok) y[(size_t)tok * n_out + row] = v;
+        }
+        __builtin_amdgcn_s_waitcnt(0xC07F);
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+    };
+    auto strip_done = [&](int i) {  // lane (n, g) holds rows 4g..4g+3 of token n: entry (16 g + n) * 4 + v of the block
+        *reinterpret_cast<f32x4*>(red + (size_t)(i % kStripRound) * (WAVES * 256) + wave * 256 + lane * 4) = acc;
+        acc = f32x4{0.f, 0.f, 0.f, 0.f};
+        if ((i + 1) % kStripRound == 0 || i + 1 == my_strips) round_end(i - i % kStripRound, i % kStripRound + 1);
+    };
+    if (n_mine == 0) {  // a wavefront without slabs contributes zeros and joins every barrier
+#pragma unroll 1
+        for (int i = 0; i < my_strips; ++i) strip_done(i);
+        return;
+    }
+
+    Frag b[4][2];
+    auto load_b = [&](int slab) {
+        const int col0 = slab * 256 + 16 * g;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) load_row16(x, n, k_tok, col0 + 64 * q, k_in, b[q][0], b[q][1]);
+    };
+    if (SPW == 1) load_b(wave);
+
+    // two tiles' streams are in flight in registers while a third is expanded
+    u32x4 st[2][MAXCH];
+    uint2 mkn[2];
+    DirEnt den[2];
+    auto request = [&](int slot, int f) {
+        if (f < n_flat) {
+            const int t = tile_of(f);
+            den[slot] = dir[t];
+            issue_tile<MAXCH>(st[slot], mkn[slot], vals, masks, den[slot].val_start, den[slot].nnz, t, lane);
+        }
+    };
+    request(0, 0);
+    request(1, 1);
+    int j = 0, i = 0;
+    auto consume = [&](int slot, int f) {
+#pragma unroll
+        for (int c = 0; c < MAXCH; ++c) reinterpret_cast<u32x4*>(buf)[c * 64 + lane] = st[slot][c];
+        const uint2 mk = mkn[slot];
+        const DirEnt de = den[slot];
+        if (SPW > 1) load_b(wave + WAVES * j);
+        request(slot, f + 2);
+        expand_tile<SD2_LINEAR_STEPS>(reinterpret_cast<const uint8_t*>(buf), lut, de.base, mk,
+                                      [&](int q, const Frag& f0, const Frag& f1) {
+                                          acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f0.v, b[q][0].v, acc, 0, 0, 0);
+                                          acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f1.v, b[q][1].v, acc, 0, 0, 0);
+                                      });
+        if (++j == n_mine) {
+            j = 0;
+            strip_done(i);
+            ++i;
+        }
+    };
+#pragma unroll 1
+    for (int f = 0; f < n_flat; f += 2) {
+        consume(0, f);
+        if (f + 1 < n_flat) consume(1, f + 1);
+    }
+}
+
 // ------------------------------------------------------------------ dense bf16 baseline
 // Same tile walk, operand A read straight from the row-major matrix; the next tile's fragments
 // are in flight while the current one goes through the MFMAs.
@@ -224,6 +339,58 @@ static hipError_t launch_sparse_t(const MatArgs& m, const LinArgs& a, hipStream_
     hipLaunchKernelGGL((sparse_linear_kernel<MAXCH, TG>), grid, block, lds, s, static_cast<const DirEnt*>(m.dir), m.masks,
                        m.vals, a.x, a.out, m.n_out, m.k_in, a.k_tok, m.n_strips, m.n_tiles, tpw);
     return hipGetLastError();
+}
+
+// Slabs per wavefront and wavefronts per workgroup of the kernel that writes final results: one slab per wavefront up
+// to 16 slabs, two beyond (then with 16 wavefronts); more than 32 slabs, more than 16 tokens or tiles too dense for the
+// 5 KiB buffers go to the kernel with partial sums.
+static bool strip_shape(int n_slabs, int& spw, int& waves) {
+    if (n_slabs < 1 || n_slabs > 32) return false;
+    spw = n_slabs <= 16 ? 1 : 2;
+    const int need = (n_slabs + spw - 1) / spw;
+    waves = std::max(4, (need + 3) / 4 * 4);
+    return true;
+}
+
+bool sparse_strip_supported(const MatArgs& m, int k_tok) {
+    int spw, waves;
+    return k_tok >= 1 && k_tok <= 16 && (m.max_tile_nnz * 2 + 8 + 1023) / 1024 <= 5 && strip_shape(m.n_slabs, spw, waves);
+}
+
+template <int SPW, int WAVES>
+static hipError_t launch_strip_t(const MatArgs& m, const LinArgs& a, hipStream_t s) {
+    constexpr int kCh = 5;
+    const size_t lds = (size_t)WAVES * kCh * 1024 + (size_t)kStripRound * WAVES * 256 * sizeof(float);
+    static std::atomic<int> cached{0};  // workgroups resident on the chip; threads that race here compute the same value
+    int resident = cached.load(std::memory_order_acquire);
+    if (resident == 0) {
+        const void* fn = reinterpret_cast<const void*>(sparse_strip_kernel<kCh, SPW, WAVES>);
+        int per_cu = 0;
+        if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) return hipErrorInvalidValue;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, 64 * WAVES, lds) != hipSuccess || per_cu < 1) per_cu = 1;
+        resident = device_cu_count() * per_cu;
+        cached.store(resident, std::memory_order_release);
+    }
+    const int grid = std::min(m.n_strips, resident);
+    hipLaunchKernelGGL((sparse_strip_kernel<kCh, SPW, WAVES>), dim3((unsigned)grid), dim3(64 * WAVES), lds, s,
+                       static_cast<const DirEnt*>(m.dir), m.masks, m.vals, a.x, a.out, m.n_out, m.k_in, a.k_tok, m.n_strips, m.n_slabs);
+    return hipGetLastError();
+}
+
+// y[t][n] final (every entry written), k_tok <= 16; sparse_strip_supported(m, k_tok) must hold
+hipError_t launch_sparse_strip_linear(const MatArgs& m, const LinArgs& a, hipStream_t s) {
+    int spw, waves;
+    if (!sparse_strip_supported(m, a.k_tok) || !strip_shape(m.n_slabs, spw, waves)) return hipErrorInvalidValue;
+#define SD2_STRIP_CASE(S, W) \
+    if (spw == S && waves == W) return launch_strip_t<S, W>(m, a, s)
+    SD2_STRIP_CASE(1, 4);
+    SD2_STRIP_CASE(1, 8);
+    SD2_STRIP_CASE(1, 12);
+    SD2_STRIP_CASE(1, 16);
+    SD2_STRIP_CASE(2, 12);
+    SD2_STRIP_CASE(2, 16);
+#undef SD2_STRIP_CASE
+    return hipErrorInvalidValue;
 }
 
 hipError_t launch_sparse_linear(const MatArgs& m, const LinArgs& a, hipStream_t s) {

