@@ -29,11 +29,11 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 # HBM bytes per launch of the forward kernel (and of the gate+up sparse linear) from rocprofv3 --pmc
 # FETCH_SIZE / WRITE_SIZE runs, scaled by the plain copy kernel of --calibrate; None until measured.
-MEASURED_TRAFFIC_BYTES = 3447027293
-MEASURED_LINEAR_TRAFFIC_BYTES = 63340310
-MEASURED_LM_HEAD_TRAFFIC_BYTES = 788254349
-MEASURED_NM24_TRAFFIC_BYTES = 57260384
-MEASURED_DECODE_TRAFFIC_BYTES = 3349042084  # the single-launch decode step (one token, 429 cached positions)
+MEASURED_TRAFFIC_BYTES = 3448133254
+MEASURED_LINEAR_TRAFFIC_BYTES = 61260497
+MEASURED_LM_HEAD_TRAFFIC_BYTES = 788275309
+MEASURED_NM24_TRAFFIC_BYTES = 57261905
+MEASURED_DECODE_TRAFFIC_BYTES = 3351187117  # the single-launch decode step (one token, 429 cached positions)
 CALIBRATION_BYTES = 256 << 20  # size of the plain copies launched by --calibrate
 
 
