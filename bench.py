@@ -185,7 +185,8 @@ def main():
     # --- roofline of the dominant kernel.  With the single-launch forward that kernel is the whole stack:
     # algorithmic bytes = every matrix's useful bytes (2 B per nonzero + 1 mask bit per weight) plus the
     # activations each linear reads (bf16) and the sums it produces (fp32).
-    forward_path = os.environ.get("SD2_FORWARD", "single-launch")
+    # the single-launch kernel serves up to 8 tokens (and is switched off by SD2_FORWARD=multi)
+    forward_path = "multi" if (os.environ.get("SD2_FORWARD") == "multi" or k_tok > 8) else "single-launch"
     act_bytes = 0
     for m in mats:
         act_bytes += 2 * k_tok * int(m.info.k_in) + 4 * k_tok * int(m.info.n_out)
