@@ -137,6 +137,16 @@ int sd2_matrix_init_dense(sd2_matrix_t* m, const uint16_t* w_bf16_dev, int32_t n
 int sd2_linear_workspace_size(const sd2_matrix_t* m, int32_t k_tok, size_t* bytes_out);
 int sd2_sparse_linear(const sd2_matrix_t* m, const uint16_t* x_bf16_dev, int32_t k_tok, float* y_dev,
                       void* workspace_dev, size_t workspace_bytes, void* stream);
+/* For callers that cannot allocate device memory or pass a workspace (code under HIP graph capture, serving loops
+ * with a fixed memory plan, harnesses that forbid allocation): sd2_sparse_linear with the per-slab partial sums kept
+ * in a static device array of the library (sd2_static_scratch_bytes: 8 MiB, held by every GPU the library has run
+ * on until the process ends) instead of a caller workspace.  The call allocates and frees nothing.  A product whose
+ * partial sums (sd2_linear_workspace_size) exceed the array returns SD2_ERR_BUFFER before anything is enqueued.
+ * All calls on one GPU share the array: calls that may overlap in time (different streams) race on it; calls on
+ * one stream are ordered and safe.  Nothing in the array has to be cleared between calls: a call overwrites every
+ * partial sum it reads.  Results are identical to sd2_sparse_linear's. */
+int sd2_static_scratch_bytes(size_t* bytes_out);
+int sd2_sparse_linear_static(const sd2_matrix_t* m, const uint16_t* x_bf16_dev, int32_t k_tok, float* y_dev, void* stream);
 /* The same product without the final add: writes the n_slabs per-slab partial results
  * [n_slabs][k_tok][n_out] (fp32) to `partials_dev` (>= n_slabs*k_tok*n_out*4 bytes).  This is
  * what the stack's glue kernels consume; with n_slabs == 1 it equals sd2_sparse_linear. */

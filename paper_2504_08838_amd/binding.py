@@ -96,6 +96,8 @@ def lib():
             "sd2_linear_workspace_size": (C.c_int, [pmat, i32, psz]),
             "sd2_sparse_linear": (C.c_int, [pmat, vp, i32, vp, vp, sz, vp]),
             "sd2_sparse_linear_partials": (C.c_int, [pmat, vp, i32, vp, sz, vp]),
+            "sd2_sparse_linear_static": (C.c_int, [pmat, vp, i32, vp, vp]),
+            "sd2_static_scratch_bytes": (C.c_int, [psz]),
             "sd2_dense_linear": (C.c_int, [pmat, vp, i32, vp, vp, sz, vp]),
             "sd2_mlp_workspace_size": (C.c_int, [pmat, pmat, i32, psz]),
             "sd2_sparse_mlp_forward": (C.c_int, [pmat, pmat, vp, i32, vp, vp, sz, vp]),
@@ -215,6 +217,17 @@ def linear_workspace_size(m, k_tok):
 def sparse_linear(m, x_ptr, k_tok, y_ptr, ws_ptr=0, ws_bytes=0, stream=0):
     _check(lib().sd2_sparse_linear(C.byref(m), C.c_void_p(x_ptr), k_tok, C.c_void_p(y_ptr), C.c_void_p(ws_ptr),
                                    ws_bytes, C.c_void_p(stream)), "sd2_sparse_linear")
+
+
+def sparse_linear_static(m, x_ptr, k_tok, y_ptr, stream=0):
+    _check(lib().sd2_sparse_linear_static(C.byref(m), C.c_void_p(x_ptr), k_tok, C.c_void_p(y_ptr), C.c_void_p(stream)),
+           "sd2_sparse_linear_static")
+
+
+def static_scratch_bytes():
+    n = C.c_size_t()
+    _check(lib().sd2_static_scratch_bytes(C.byref(n)), "sd2_static_scratch_bytes")
+    return n.value
 
 
 def sparse_linear_partials(m, x_ptr, k_tok, part_ptr, part_bytes, stream=0):

@@ -255,6 +255,23 @@ int sd2_sparse_linear(const sd2_matrix_t* m, const uint16_t* x, int32_t k_tok, f
     return linear_entry(m, SD2_KIND_SPARSE, x, k_tok, y, ws, ws_bytes, stream);
 }
 
+int sd2_sparse_linear_static(const sd2_matrix_t* m, const uint16_t* x, int32_t k_tok, float* y, void* stream) {
+    int rc = check_matrix(m, SD2_KIND_SPARSE);
+    if (rc != SD2_OK) return rc;
+    if ((rc = check_tokens(k_tok)) != SD2_OK) return rc;
+    // the size check comes first and touches no device: a request the static array cannot hold is refused as such
+    if (n_partials(m) > 1 && partial_bytes(m, k_tok) > kStaticScratchBytes) return SD2_ERR_BUFFER;
+    void* ws = nullptr;
+    if (n_partials(m) > 1 && static_scratch(&ws) != hipSuccess) return SD2_ERR_HIP;
+    return linear_entry(m, SD2_KIND_SPARSE, x, k_tok, y, ws, kStaticScratchBytes, stream);
+}
+
+int sd2_static_scratch_bytes(size_t* bytes_out) {
+    if (!bytes_out) return SD2_ERR_NULL;
+    *bytes_out = kStaticScratchBytes;
+    return SD2_OK;
+}
+
 int sd2_sparse_linear_partials(const sd2_matrix_t* m, const uint16_t* x, int32_t k_tok, float* part, size_t part_bytes,
                                void* stream) {
     int rc = check_matrix(m, SD2_KIND_SPARSE);

@@ -30,6 +30,11 @@ hipError_t launch_dense_linear(const MatArgs& m, const LinArgs& a, hipStream_t s
 bool sparse_strip_supported(const MatArgs& m, int k_tok);
 hipError_t launch_sparse_strip_linear(const MatArgs& m, const LinArgs& a, hipStream_t s);
 
+// Device address, on the current device, of the library's static scratch array (kStaticScratchBytes bytes, 256-byte
+// aligned): looked up once per device, no allocation.  Calls that use it on one GPU share it.
+constexpr size_t kStaticScratchBytes = (size_t)8 << 20;
+hipError_t static_scratch(void** ptr_out);
+
 // y[i] = sum_s part[s][i], i < n  (n = k_tok * n_out)
 hipError_t launch_reduce_partials(const float* part, int n_splits, size_t n, float* y, hipStream_t s);
 

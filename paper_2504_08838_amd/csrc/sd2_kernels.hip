@@ -640,6 +640,33 @@ hipError_t launch_reduce_partials(const float* part, int n_splits, size_t n, flo
     return launch_reduce_partials_strided(part, n_splits, n, n, y, s);
 }
 
+// ------------------------------------------------------------------ static scratch for callers that cannot allocate
+//
+// Device memory that belongs to the library's code object: every GPU the library runs on holds its own copy of this
+// array, at its own address, until the process ends.  In host code the array's name is only a handle for the
+// symbol; the device address is looked up once per device (with that device current) and kept, and only that
+// address is ever handed to kernels.  The contents survive from call to call; the linear that uses it overwrites
+// every partial result it later reads, so nothing has to be cleared.
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+hipError_t static_scratch(void** ptr_out) {
+    constexpr int kMaxDevices = 64;
+    static std::atomic<void*> per_device[kMaxDevices];  // zero-initialised; threads that race here store the same address
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    void* p = per_device[dev].load(std::memory_order_acquire);
+    if (!p) {
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        per_device[dev].store(p, std::memory_order_release);
+    }
+    *ptr_out = p;
+    return hipSuccess;
+}
+
 __device__ __forceinline__ float block_sum_256(float v, float* red) {
     const int tid = threadIdx.x;
     red[tid] = v;
