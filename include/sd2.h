@@ -53,12 +53,34 @@ enum sd2_status {
 #define SD2_MAX_TOKENS 64
 #define SD2_FORMAT_AUTO 0
 #define SD2_FORMAT_BITMASK 1
-#define SD2_FORMAT_INDEX16 2 /* reserved: returns SD2_ERR_UNSUPPORTED */
+/* Reserved, returns SD2_ERR_UNSUPPORTED: a tile of uint16 column indices costs 4 bytes per stored weight whatever the
+ * sparsity, against 2 + 1/(8 density) for the bitmask (2.25 at 50 %, 2.5 at 75 %); at 50 % it moves exactly the bytes
+ * of the dense matrix and only wins beyond 93.75 % sparsity, outside the range the paper prunes to (Sec. 3: 50-75 %). */
+#define SD2_FORMAT_INDEX16 2
 #define SD2_FORMAT_NM24 3    /* 2:4 semi-structured: at most two non-zeros in every aligned group of four columns */
 
 /* Static, never freed. */
 const char* sd2_strerror(int status);
 int sd2_version(void);
+
+/* Process-wide switches for tests and profiling.  Their start values come from the environment, read once when a
+ * call first needs one (SD2_FORWARD=multi, SD2_LINEAR=partials, SD2_MEGA_SPIN_LIMIT=<n>, SD2_MEGA_TIMING=1|2); no
+ * device call reads the environment afterwards.
+ *   SD2_OPT_FORWARD_MULTI    1: the stack runs as one launch per linear and glue step even where the single-launch
+ *                               kernel could serve it
+ *   SD2_OPT_LINEAR_PARTIALS  1: sparse linears keep one partial result per slab and add them in a second launch even
+ *                               where the kernel that writes final results could serve them
+ *   SD2_OPT_SPIN_LIMIT       polls a bounded wait of the single-launch kernel may spend; -1: the default (2^20)
+ *   SD2_OPT_MEGA_TIMING      1 / 2: the trace variant of the forward records timestamps only (2: also wavefront 0's
+ *                               split into waiting and decoding)
+ * SD2_ERR_RANGE for an unknown switch or a value outside its range. */
+#define SD2_OPT_FORWARD_MULTI 0
+#define SD2_OPT_LINEAR_PARTIALS 1
+#define SD2_OPT_SPIN_LIMIT 2
+#define SD2_OPT_MEGA_TIMING 3
+#define SD2_OPT_COUNT 4
+int sd2_set_option(int32_t which, int32_t value);
+int sd2_get_option(int32_t which, int32_t* value_out);
 
 /* ------------------------------------------------------------------ packing (host only)
  * The sparse representation: Sec. 1 and Sec. 3.3 require one but do not define it.
@@ -102,7 +124,8 @@ int sd2_unpack_sparse(const void* blob, size_t blob_bytes, uint16_t* w_bf16_out,
 /* Parses and checks the header (magic, version, geometry, offsets vs blob_bytes). */
 int sd2_blob_info(const void* blob, size_t blob_bytes, sd2_blob_info_t* out);
 
-/* Full check of a host blob: header, checksum, directory vs masks. */
+/* Full check of a host blob: header, checksum, directory vs masks, and that no mask bit of a
+ * ragged last strip or slab lies outside the matrix. */
 int sd2_blob_validate(const void* blob, size_t blob_bytes);
 
 /* ------------------------------------------------------------------ matrices on the device */
@@ -119,8 +142,10 @@ typedef struct sd2_matrix {
     sd2_blob_info_t info; /* dense: only the shape and tile counts are used */
 } sd2_matrix_t;
 
-/* Sparse descriptor from the host copy of the blob (header is validated) and the
- * device address the same bytes were uploaded to. */
+/* Sparse descriptor from the host copy of the blob and the device address the same bytes were
+ * uploaded to.  Only the header is parsed and checked here; the kernels trust the directory
+ * (offsets and counts of a tile's values drive their reads), so a blob that does not come
+ * straight from sd2_pack_sparse should go through sd2_blob_validate first. */
 int sd2_matrix_init_sparse(sd2_matrix_t* m, const void* blob_host, size_t blob_bytes,
                            const void* blob_dev);
 /* Dense descriptor for the baseline kernel: W is the same masked matrix stored with
@@ -149,7 +174,9 @@ int sd2_static_scratch_bytes(size_t* bytes_out);
 int sd2_sparse_linear_static(const sd2_matrix_t* m, const uint16_t* x_bf16_dev, int32_t k_tok, float* y_dev, void* stream);
 /* The same product without the final add: writes the n_slabs per-slab partial results
  * [n_slabs][k_tok][n_out] (fp32) to `partials_dev` (>= n_slabs*k_tok*n_out*4 bytes).  This is
- * what the stack's glue kernels consume; with n_slabs == 1 it equals sd2_sparse_linear. */
+ * what the stack's glue kernels consume; with n_slabs == 1 it equals sd2_sparse_linear.  A 2:4
+ * matrix (SD2_FORMAT_NM24) has no per-slab results: its kernel adds the slabs up inside the
+ * workgroup, and this call then writes one final result [k_tok][n_out]. */
 int sd2_sparse_linear_partials(const sd2_matrix_t* m, const uint16_t* x_bf16_dev, int32_t k_tok,
                                float* partials_dev, size_t partials_bytes, void* stream);
 /* Hand-written dense bf16 baseline for the same shapes; `m` must be a dense descriptor.  For k_in a multiple of

@@ -86,6 +86,8 @@ def lib():
         sig = {
             "sd2_strerror": (C.c_char_p, [C.c_int]),
             "sd2_version": (C.c_int, []),
+            "sd2_set_option": (C.c_int, [i32, i32]),
+            "sd2_get_option": (C.c_int, [i32, C.POINTER(C.c_int32)]),
             "sd2_pack_sparse_size": (C.c_int, [vp, i32, i32, i32, psz]),
             "sd2_pack_sparse": (C.c_int, [vp, i32, i32, i32, vp, sz, psz]),
             "sd2_unpack_sparse": (C.c_int, [vp, sz, vp, i32, i32]),
@@ -148,6 +150,19 @@ def strerror(status):
 
 def version():
     return lib().sd2_version()
+
+
+OPT_FORWARD_MULTI, OPT_LINEAR_PARTIALS, OPT_SPIN_LIMIT, OPT_MEGA_TIMING = 0, 1, 2, 3
+
+
+def set_option(which, value):
+    _check(lib().sd2_set_option(int(which), int(value)), "sd2_set_option")
+
+
+def get_option(which):
+    v = C.c_int32()
+    _check(lib().sd2_get_option(int(which), C.byref(v)), "sd2_get_option")
+    return v.value
 
 
 def _w_host(w_bits):

@@ -3,6 +3,7 @@
 #include <string.h>
 
 #include <algorithm>
+#include <atomic>
 #include <cmath>
 #include <new>
 #include <vector>
@@ -18,6 +19,24 @@ struct sd2_model {
 };
 
 namespace {
+
+// Process-wide switches (sd2_set_option).  The environment is consulted once, when the first call needs a switch;
+// after that a call reads an atomic and nothing else.
+struct Options {
+    std::atomic<int> v[SD2_OPT_COUNT];
+    Options() {
+        const char* e;
+        v[SD2_OPT_FORWARD_MULTI] = ((e = getenv("SD2_FORWARD")) && strcmp(e, "multi") == 0) ? 1 : 0;
+        v[SD2_OPT_LINEAR_PARTIALS] = ((e = getenv("SD2_LINEAR")) && strcmp(e, "partials") == 0) ? 1 : 0;
+        v[SD2_OPT_SPIN_LIMIT] = (e = getenv("SD2_MEGA_SPIN_LIMIT")) ? std::max(0, atoi(e)) : -1;
+        v[SD2_OPT_MEGA_TIMING] = ((e = getenv("SD2_MEGA_TIMING")) && (e[0] == '1' || e[0] == '2')) ? e[0] - '0' : 0;
+    }
+};
+Options& options() {
+    static Options o;
+    return o;
+}
+inline int option(int which) { return options().v[which].load(std::memory_order_relaxed); }
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
@@ -72,11 +91,10 @@ size_t partial_bytes(const sd2_matrix_t* m, int k_tok) {
 int check_tokens(int32_t k_tok) { return (k_tok < 1 || k_tok > SD2_MAX_TOKENS) ? SD2_ERR_RANGE : SD2_OK; }
 
 // The bitmask format has a kernel that adds the slabs up inside the workgroup, too (up to 16 tokens, up to 32 slabs,
-// tiles that fit its buffers); SD2_LINEAR=partials keeps the kernel with one partial result per slab (tests cover both).
+// tiles that fit its buffers); SD2_OPT_LINEAR_PARTIALS keeps the kernel with one partial result per slab (tests cover both).
 inline bool sparse_final_ok(const sd2_matrix_t* m, int k_tok) {
     if (m->kind != SD2_KIND_SPARSE || is_nm24(m)) return false;
-    const char* force = getenv("SD2_LINEAR");
-    if (force && strcmp(force, "partials") == 0) return false;
+    if (option(SD2_OPT_LINEAR_PARTIALS)) return false;
     return sparse_strip_supported(mat_args(m), k_tok);
 }
 
@@ -165,10 +183,9 @@ MegaGeo mega_geo(const sd2_matrix_t& m) {
 
 // The single-launch persistent kernel serves the decode regime (k_tok <= 8) of an all-sparse model
 // whose layers share one geometry; everything else runs as one launch per linear and glue step.
-// SD2_FORWARD=multi forces the latter (used by tests to cover both).
+// SD2_OPT_FORWARD_MULTI forces the latter (used by tests to cover both).
 bool plan_mega_path(const sd2_model* md, int k_tok, MegaGeo (&geo)[4], bool* nm24_out = nullptr) {
-    const char* force = getenv("SD2_FORWARD");
-    if (force && strcmp(force, "multi") == 0) return false;
+    if (option(SD2_OPT_FORWARD_MULTI)) return false;
     const sd2_model_shape_t& sh = md->shape;
     if (sh.layers < 1) return false;
     int max_nnz = 0;
@@ -206,7 +223,21 @@ const char* sd2_strerror(int status) {
     }
 }
 
-int sd2_version(void) { return 100; }
+int sd2_version(void) { return 101; }
+
+int sd2_set_option(int32_t which, int32_t value) {
+    if (which < 0 || which >= SD2_OPT_COUNT) return SD2_ERR_RANGE;
+    if (which == SD2_OPT_SPIN_LIMIT ? value < -1 : (value < 0 || value > (which == SD2_OPT_MEGA_TIMING ? 2 : 1))) return SD2_ERR_RANGE;
+    options().v[which].store(value, std::memory_order_relaxed);
+    return SD2_OK;
+}
+
+int sd2_get_option(int32_t which, int32_t* value_out) {
+    if (!value_out) return SD2_ERR_NULL;
+    if (which < 0 || which >= SD2_OPT_COUNT) return SD2_ERR_RANGE;
+    *value_out = option(which);
+    return SD2_OK;
+}
 
 int sd2_matrix_init_sparse(sd2_matrix_t* m, const void* blob_host, size_t blob_bytes, const void* blob_dev) {
     if (!m || !blob_host || !blob_dev) return SD2_ERR_NULL;
@@ -331,8 +362,8 @@ int sd2_model_create(const sd2_model_shape_t* sh, const sd2_matrix_t* mats, int3
     if (!sh || !out) return SD2_ERR_NULL;
     *out = nullptr;
     if (sh->layers < 0 || sh->hidden < 64 || sh->q_out < 64 || sh->kv_out < 64 || sh->inter < 64 || sh->n_heads < 1 ||
-        sh->n_kv < 1 || sh->head_dim < 1 || sh->head_dim > 256)
-        return SD2_ERR_SHAPE;
+        sh->n_kv < 1 || sh->head_dim < 8 || sh->head_dim > 256 || sh->head_dim % 8)
+        return SD2_ERR_SHAPE;  // the attention kernels split a head's dimensions into eight equal parts
     if (sh->n_heads % sh->n_kv || (int64_t)sh->n_heads * sh->head_dim != sh->q_out ||
         (int64_t)sh->n_kv * sh->head_dim != sh->kv_out)
         return SD2_ERR_SHAPE;
@@ -403,9 +434,8 @@ static void fill_mega_args(MegaArgs& ma, const sd2_model* md, int k_tok, const M
     ma.n_kv = sh.n_kv;
     ma.head_dim = sh.head_dim;
     ma.k_tok = k_tok;
-    // about a second of polling per barrier before the forward is given up (SD2_MEGA_SPIN_LIMIT overrides: tests)
-    ma.spin_limit = 1 << 20;
-    if (const char* sl = getenv("SD2_MEGA_SPIN_LIMIT")) ma.spin_limit = std::max(0, atoi(sl));
+    // about a second of polling per barrier before the forward is given up (SD2_OPT_SPIN_LIMIT overrides: tests)
+    ma.spin_limit = option(SD2_OPT_SPIN_LIMIT) >= 0 ? option(SD2_OPT_SPIN_LIMIT) : 1 << 20;
     ma.h_out = h_out;
     ma.bar = reinterpret_cast<unsigned*>(base + ML.bar_off);
     ma.err = reinterpret_cast<unsigned*>(base + ML.err_off);
@@ -432,7 +462,10 @@ static int forward_impl(const sd2_model_t* md, const uint16_t* h_in, int32_t k_t
     MegaArgs ma;
     memset(&ma, 0, sizeof(ma));
     bool nm24 = false;
-    if (plan_mega_path(md, k_tok, ma.geo, &nm24)) {
+    const bool single_launch = plan_mega_path(md, k_tok, ma.geo, &nm24);
+    // the attention kernel of the launch-per-step path keeps q, k, v and the scores of a head in LDS
+    if (!single_launch && sh.layers > 0 && inflight_attention_lds(k_tok, sh.head_dim) > kMaxLdsBytes) return SD2_ERR_UNSUPPORTED;
+    if (single_launch) {
         uint8_t* base = static_cast<uint8_t*>(ws);
         fill_mega_args(ma, md, k_tok, ML, base, h_out);
         bool probe = false;
@@ -443,11 +476,11 @@ static int forward_impl(const sd2_model_t* md, const uint16_t* h_in, int32_t k_t
             ma.trace_kmax = T.kmax;
             ma.trace_smax = T.smax;
             ma.trace_time = reinterpret_cast<unsigned long long*>(static_cast<uint8_t*>(trace) + T.time_off);
-            // SD2_MEGA_TIMING=1: keep only the per-workgroup timestamps (profiling the production kernel);
-            // =2: the same plus wavefront 0's split into waiting for streams and decoding
-            const char* tonly = getenv("SD2_MEGA_TIMING");
-            if (tonly && (tonly[0] == '1' || tonly[0] == '2')) ma.trace_x = nullptr;
-            probe = tonly && tonly[0] == '2' && !nm24;  // the wait/decode split exists for the bitmask format only
+            // SD2_OPT_MEGA_TIMING = 1: keep only the per-workgroup timestamps (profiling the production kernel);
+            // = 2: the same plus wavefront 0's split into waiting for streams and decoding
+            const int tonly = option(SD2_OPT_MEGA_TIMING);
+            if (tonly) ma.trace_x = nullptr;
+            probe = tonly == 2 && !nm24;  // the wait/decode split exists for the bitmask format only
         }
         return launch_mega_forward(ma, h_in, base, ML.hv_off, probe, nm24, s) == hipSuccess ? SD2_OK : SD2_ERR_HIP;
     }

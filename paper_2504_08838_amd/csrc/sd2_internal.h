@@ -48,6 +48,11 @@ hipError_t launch_reduce_partials_strided(const float* part, int n_splits, size_
 hipError_t launch_residual_rmsnorm(float* h, const uint16_t* h_in, const float* part, int n_splits,
                                    int k_tok, int hidden, uint16_t* a, float* ssq, hipStream_t s);
 
+// LDS a workgroup may use on gfx950, and what the kernel below needs: checked on the host before the first launch.
+constexpr size_t kMaxLdsBytes = 160 * 1024;
+inline size_t inflight_attention_lds(int k_tok, int head_dim) {
+    return ((size_t)3 * k_tok * head_dim + (size_t)k_tok * k_tok) * sizeof(float);
+}
 // Causal softmax attention among the k_tok in-flight tokens; qkv partials [n_splits][k_tok][q_out+2*kv_out].
 hipError_t launch_inflight_attention(const float* part, int n_splits, int k_tok, int q_out, int kv_out,
                                      int n_heads, int n_kv, int head_dim, uint16_t* ctx, hipStream_t s);

@@ -786,7 +786,8 @@ __global__ __launch_bounds__(256) void inflight_attention_kernel(const float* __
 
 hipError_t launch_inflight_attention(const float* part, int n_splits, int k_tok, int q_out, int kv_out, int n_heads,
                                      int n_kv, int head_dim, uint16_t* ctx, hipStream_t s) {
-    const size_t lds = ((size_t)3 * k_tok * head_dim + (size_t)k_tok * k_tok) * sizeof(float);
+    const size_t lds = inflight_attention_lds(k_tok, head_dim);
+    if (lds > kMaxLdsBytes) return hipErrorInvalidValue;
     if (lds > 64 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(inflight_attention_kernel),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);

@@ -8,8 +8,9 @@
 // per linear as float atomic adds (split-K only across the few slab blocks).  Between dependent
 // linears the grid meets at a barrier built from agent-scope atomics.  Everything a CU hands to
 // other CUs is written with agent-scope atomic stores / float adds, which go through to memory,
-// so no cache write-back is needed before arriving; after the barrier one wavefront per workgroup
-// invalidates the caches and the prologue reads with ordinary cached loads.  After each barrier a workgroup
+// so no cache write-back is needed before arriving; nothing is invalidated after the barrier either:
+// every activation buffer exists once per layer, so what the prologue reads (with ordinary cached loads)
+// lies at addresses no compute unit has touched before in this launch.  After each barrier a workgroup
 // rebuilds in LDS exactly the bf16 activation columns its tiles need: the RMS-normed residual
 // (every workgroup sums the squares of the whole residual itself), causal attention over the
 // in-flight tokens for the heads of its slabs, or the SiLU-gated product.

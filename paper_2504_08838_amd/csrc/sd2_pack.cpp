@@ -222,11 +222,19 @@ int sd2_blob_validate(const void* blob, size_t blob_bytes) {
     uint32_t max_nnz = 0;
     for (uint32_t t = 0; t < h.n_tiles; ++t) {
         const uint16_t* tm = masks + (size_t)t * 256;
+        const uint32_t strip = t % h.n_strips, slab = t / h.n_strips;
         uint32_t run = 0;
         for (uint32_t q = 0; q < 4; ++q)
             for (uint32_t hh = 0; hh < 4; ++hh) {
                 if (dir[t].base[4 * q + hh] != run) return SD2_ERR_BLOB;
-                for (uint32_t l = 0; l < 64; ++l) run += (uint32_t)__builtin_popcount((tm[l * 4 + q] >> (4 * hh)) & 15u);
+                for (uint32_t l = 0; l < 64; ++l) {
+                    const uint32_t nib = (tm[l * 4 + q] >> (4 * hh)) & 15u;
+                    run += (uint32_t)__builtin_popcount(nib);
+                    // a set bit must lie inside the matrix (ragged last strip or slab)
+                    const uint32_t row = kStripRows * strip + (l & 15);
+                    const uint32_t c = kSlabCols * slab + 64 * q + 16 * (l >> 4) + 4 * hh;
+                    if (nib && (row >= h.n_out || c + (31u - (uint32_t)__builtin_clz(nib)) >= h.k_in)) return SD2_ERR_BLOB;
+                }
             }
         if (dir[t].nnz != run || dir[t].val_start != next || dir[t].zero[0] || dir[t].zero[1]) return SD2_ERR_BLOB;
         next += round_up(run, 8) / 8;

@@ -262,3 +262,60 @@ def test_improvement_factor_matches_eq3_and_the_oracle():
     assert L.sd2_improvement_factor(4.0, -1, 0.1, C.byref(out)) == -6
     assert L.sd2_improvement_factor(4.0, 5, float("nan"), C.byref(out)) == -6
     assert L.sd2_improvement_factor(float("inf"), 5, 0.1, C.byref(out)) == -6
+
+
+def test_options_round_trip_and_ranges():
+    L = sd2.lib()
+    for which, good, bad in ((sd2.OPT_FORWARD_MULTI, 1, 2), (sd2.OPT_LINEAR_PARTIALS, 1, -1), (sd2.OPT_SPIN_LIMIT, 7, -2),
+                             (sd2.OPT_MEGA_TIMING, 2, 3)):
+        before = sd2.get_option(which)
+        sd2.set_option(which, good)
+        assert sd2.get_option(which) == good
+        assert L.sd2_set_option(which, bad) == -6
+        assert sd2.get_option(which) == good
+        sd2.set_option(which, before)
+    assert L.sd2_set_option(99, 0) == -6 and L.sd2_set_option(-1, 0) == -6
+    assert L.sd2_get_option(0, None) == -1
+
+
+def test_validate_rejects_mask_bits_outside_a_ragged_matrix():
+    # 40 rows: the last strip has 8 rows outside the matrix; set a mask bit there and repair directory and checksum
+    # by hand, so that only the out-of-range position is wrong
+    t = 2                                             # strip 2, slab 0
+    w = wl.gen_weight(12, 6, "q", 40, 256, 50).copy()
+    w[39, np.flatnonzero(w[39])[0]] = 0               # one value fewer: the last tile's padding has room for one more
+    blob = sd2.pack_sparse(w, 1).copy()
+    info = sd2.blob_info(blob)
+    assert info.n_strips == 3
+    masks = blob[info.mask_off:info.mask_off + 512 * info.n_tiles].view(np.uint16).reshape(info.n_tiles, 64, 4)
+    lane = 15                                         # row 47 of the matrix: outside
+    assert masks[t, lane].sum() == 0
+    sd2.blob_validate(blob)
+    # the last run (q = 3, nibble 3) of the tile takes one more value: no run base changes, only the tile's count
+    masks[t, lane, 3] |= 0x8000
+    d = blob[128 + 48 * t:128 + 48 * (t + 1)].view(np.uint32)
+    old_nnz = int(d[1])
+    assert (old_nnz + 1 + 7) // 8 == (old_nnz + 7) // 8   # the extra value fits the tile's padding: offsets stay
+    d[1] = old_nnz + 1
+    hdr64 = blob[40:48].view(np.uint64)
+    hdr64[0] += 1
+    if old_nnz + 1 > info.max_tile_nnz:
+        blob[32:36].view(np.uint32)[0] = old_nnz + 1
+    words = blob[128:].view(np.uint32).astype(np.uint64)
+    s1 = int(words.sum() & 0xFFFFFFFF)
+    s2 = int((words * np.arange(1, words.size + 1, dtype=np.uint64)).sum() & 0xFFFFFFFF)
+    blob[88:92].view(np.uint32)[0] = s1 ^ (((s2 << 16) | (s2 >> 16)) & 0xFFFFFFFF)
+    with pytest.raises(sd2.SD2Error) as e:
+        sd2.blob_validate(blob)
+    assert e.value.status == -5
+
+
+def test_model_create_rejects_head_sizes_the_attention_kernels_cannot_split():
+    L = sd2.lib()
+    _, m = _host_matrix()
+    handle = C.c_void_p()
+    bad = sd2.ModelShape(0, 1600, 1600, 400, 64, 16, 4, 100)   # head_dim 100: not a multiple of 8
+    assert L.sd2_model_create(C.byref(bad), None, 0, C.byref(handle)) == -2
+    ok = sd2.ModelShape(0, 1664, 1664, 416, 64, 16, 4, 104)
+    assert L.sd2_model_create(C.byref(ok), None, 0, C.byref(handle)) == 0
+    L.sd2_model_destroy(handle)

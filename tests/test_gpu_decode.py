@@ -62,12 +62,12 @@ def _cache_close(got_bits, want_bits):
 
 
 @pytest.fixture(params=["single-launch", "multi-launch"])
-def forward(request, monkeypatch):
+def forward(request, sd2_options):
     """Both implementations: the persistent kernel with its attention step, and one launch per linear and glue step."""
     if request.param == "multi-launch":
-        monkeypatch.setenv("SD2_FORWARD", "multi")
+        sd2_options.set("forward_multi", 1)
     else:
-        monkeypatch.delenv("SD2_FORWARD", raising=False)
+        sd2_options.set("forward_multi", 0)
     return request.param
 
 
@@ -206,14 +206,14 @@ def test_decode_in_a_graph_replays(forward):
             assert rel_l2(got, eager) <= 1e-5
 
 
-def test_bounded_wait_gives_up_and_recovers(monkeypatch):
+def test_bounded_wait_gives_up_and_recovers(sd2_options):
     """Failure handling of the single-launch path: with a spin limit of zero every grid barrier (the attention step's
     included) gives up at its first unsuccessful poll.  Every wavefront still runs to the end, the status call reports
     the step as invalid, and the next step on a fresh cache is right again."""
     import torch
     import paper_2504_08838_amd as sd2
     import gpu_util as gu
-    monkeypatch.delenv("SD2_FORWARD", raising=False)
+    sd2_options.set("forward_multi", 0)
     shape, max_pos, n_hist, k_tok = SMALL, 128, 50, 3
     get, model = _model(shape, 88)
     kc, vc = wl.gen_kv_history(88, shape.layers, shape.n_kv, max_pos, shape.head_dim, n_hist)
@@ -223,12 +223,12 @@ def test_bounded_wait_gives_up_and_recovers(monkeypatch):
     nb = sd2.drafter_decode_workspace_size(model, k_tok)
     ws = torch.empty(nb, dtype=torch.uint8, device="cuda")
     kc_bad, vc_bad = gu.dev(kc), gu.dev(vc)
-    monkeypatch.setenv("SD2_MEGA_SPIN_LIMIT", "0")
+    sd2_options.set("spin_limit", 0)
     sd2.sparse_drafter_decode(model, h_in.data_ptr(), k_tok, n_hist, kc_bad.data_ptr(), vc_bad.data_ptr(), max_pos, THETA,
                               h_out.data_ptr(), ws.data_ptr(), nb, gu.stream_ptr())
     with pytest.raises(sd2.SD2Error):
         sd2.drafter_decode_status(model, k_tok, ws.data_ptr(), gu.stream_ptr())
-    monkeypatch.delenv("SD2_MEGA_SPIN_LIMIT")
+    sd2_options.set("spin_limit", -1)
     got = _decode(model, shape, h_bits, gu.dev(kc), gu.dev(vc), max_pos, n_hist)
     want = od.drafter_decode(shape, get, h_bits, kc, vc, n_hist, THETA)
     assert rel_l2(got, want) <= 1e-3

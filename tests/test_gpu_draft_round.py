@@ -52,12 +52,12 @@ def _check(shape, get, emb, t_start, ids):
 
 @pytest.mark.parametrize("forward", ["single-launch", "multi-launch"])
 @pytest.mark.parametrize("fmt,pattern", [(1, "row"), (3, "2:4")])
-def test_round_matches_oracle(forward, fmt, pattern, monkeypatch):
+def test_round_matches_oracle(forward, fmt, pattern, sd2_options):
     import gpu_util as gu
     if forward == "multi-launch":
-        monkeypatch.setenv("SD2_FORWARD", "multi")
+        sd2_options.set("forward_multi", 1)
     else:
-        monkeypatch.delenv("SD2_FORWARD", raising=False)
+        sd2_options.set("forward_multi", 0)
     shape = SimpleNamespace(layers=2, hidden=512, q_out=512, kv_out=256, inter=1024, n_heads=4, n_kv=2, head_dim=128)
     vocab, k = 3000, 5
     get, model = _model(shape, 78, fmt, pattern)
@@ -154,14 +154,14 @@ def _check_cached(shape, get, emb, t_start, ids, kc, vc, pos0, theta=500000.0):
 
 @pytest.mark.parametrize("forward", ["single-launch", "multi-launch"])
 @pytest.mark.parametrize("pos0", [0, 150])
-def test_cached_round_matches_oracle(forward, pos0, monkeypatch):
+def test_cached_round_matches_oracle(forward, pos0, sd2_options):
     import gpu_util as gu
     from oracle.bf16 import bits_to_f64
     from oracle.linear import rel_l2
     if forward == "multi-launch":
-        monkeypatch.setenv("SD2_FORWARD", "multi")
+        sd2_options.set("forward_multi", 1)
     else:
-        monkeypatch.delenv("SD2_FORWARD", raising=False)
+        sd2_options.set("forward_multi", 0)
     shape = SimpleNamespace(layers=2, hidden=512, q_out=512, kv_out=256, inter=1024, n_heads=4, n_kv=2, head_dim=128)
     vocab, k, max_pos = 3000, 5, 256
     get, model = _model(shape, 79)

@@ -115,7 +115,7 @@ def _decode_once(model, shape, h_bits, kc_dev, vc_dev, max_pos, pos0, graph=Fals
 
 @pytest.mark.parametrize("k_tok", [1, 5])
 @pytest.mark.parametrize("forward", ["single-launch", "multi-launch"])
-def test_cfg3_decode_two_layers_at_full_width(cfg3, k_tok, forward, monkeypatch):
+def test_cfg3_decode_two_layers_at_full_width(cfg3, k_tok, forward, sd2_options):
     """Full-size matrices, two layers, both implementations.  End to end through eight bf16 rounding points: the bar is
     the stack's end-to-end one (5e-3; a few activations within fp32 error of a rounding boundary round the other way
     than in the fp64 oracle, observed ~1e-3), the cache rows of the first layer are checked entry by entry."""
@@ -123,9 +123,9 @@ def test_cfg3_decode_two_layers_at_full_width(cfg3, k_tok, forward, monkeypatch)
     from oracle import decode as od
     from oracle.bf16 import bits_to_f64
     if forward == "multi-launch":
-        monkeypatch.setenv("SD2_FORWARD", "multi")
+        sd2_options.set("forward_multi", 1)
     else:
-        monkeypatch.delenv("SD2_FORWARD", raising=False)
+        sd2_options.set("forward_multi", 0)
     shape, get, _, _ = cfg3
     two = wl.StackShape("two-layers", 2, shape.hidden, shape.q_out, shape.kv_out, shape.inter, shape.n_heads, shape.n_kv,
                         shape.head_dim, shape.vocab)

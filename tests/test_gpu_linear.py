@@ -14,13 +14,13 @@ TOL = 1e-3
 
 
 @pytest.fixture(autouse=True, params=["final", "partials"])
-def linear_kernel(request, monkeypatch):
+def linear_kernel(request, sd2_options):
     """Every case runs on both sparse kernels: the one that adds the slabs up inside the workgroup (up to 16 tokens)
     and the one that leaves a partial result per slab for a second launch."""
     if request.param == "partials":
-        monkeypatch.setenv("SD2_LINEAR", "partials")
+        sd2_options.set("linear_partials", 1)
     else:
-        monkeypatch.delenv("SD2_LINEAR", raising=False)
+        sd2_options.set("linear_partials", 0)
     return request.param
 
 

@@ -90,12 +90,12 @@ def test_run_to_run_determinism():
 
 
 @pytest.fixture(params=["single-launch", "multi-launch"])
-def forward_path(request, monkeypatch):
+def forward_path(request, sd2_options):
     """Both forwards: the persistent kernel (its 2:4 variant) and the chain of one launch per linear and glue step."""
     if request.param == "multi-launch":
-        monkeypatch.setenv("SD2_FORWARD", "multi")
+        sd2_options.set("forward_multi", 1)
     else:
-        monkeypatch.delenv("SD2_FORWARD", raising=False)
+        sd2_options.set("forward_multi", 0)
     return request.param
 
 

@@ -33,12 +33,12 @@ def _weights(shape, cfg, pct=50):
 
 
 @pytest.fixture(params=["single-launch", "multi-launch"])
-def forward_path(request, monkeypatch):
+def forward_path(request, sd2_options):
     """The persistent single-launch kernel (default where it applies) and the one-launch-per-step path."""
     if request.param == "multi-launch":
-        monkeypatch.setenv("SD2_FORWARD", "multi")
+        sd2_options.set("forward_multi", 1)
     else:
-        monkeypatch.delenv("SD2_FORWARD", raising=False)
+        sd2_options.set("forward_multi", 0)
     return request.param
 
 
@@ -160,24 +160,24 @@ def test_cfg4_cells_link_by_link(pct, k_tok):
     assert ol.rel_l2(gu.run_forward(model, h_in, shape.hidden), os_.drafter_forward(shape, get, h_in)) <= E2E_TOL
 
 
-def test_bounded_wait_reports_timeout(monkeypatch):
+def test_bounded_wait_reports_timeout(sd2_options):
     """Failure handling: with a spin limit of zero every grid barrier gives up at its first unsuccessful poll.  All
     wavefronts still run to the end (nothing hangs), and the status call reports that the forward is invalid."""
     import torch
     import paper_2504_08838_amd as sd2
     import gpu_util as gu
-    monkeypatch.delenv("SD2_FORWARD", raising=False)
+    sd2_options.set("forward_multi", 0)
     get = _weights(SMALL, 14)
     model = gu.build_model(SMALL, get)
     h_in = gu.dev(wl.gen_x(14, 0, "q", 5, SMALL.hidden))
     h_out = torch.zeros((5, SMALL.hidden), dtype=torch.float32, device="cuda")
     ws_bytes = sd2.drafter_workspace_size(model, 5)
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
-    monkeypatch.setenv("SD2_MEGA_SPIN_LIMIT", "0")
+    sd2_options.set("spin_limit", 0)
     sd2.sparse_drafter_forward(model, h_in.data_ptr(), 5, h_out.data_ptr(), ws.data_ptr(), ws_bytes, gu.stream_ptr())
     with pytest.raises(sd2.SD2Error):
         sd2.drafter_forward_status(model, 5, ws.data_ptr(), gu.stream_ptr())
-    monkeypatch.delenv("SD2_MEGA_SPIN_LIMIT")
+    sd2_options.set("spin_limit", -1)
     sd2.sparse_drafter_forward(model, h_in.data_ptr(), 5, h_out.data_ptr(), ws.data_ptr(), ws_bytes, gu.stream_ptr())
     sd2.drafter_forward_status(model, 5, ws.data_ptr(), gu.stream_ptr())   # the next call is fine again
     assert ol.rel_l2(h_out.cpu().numpy(), os_.drafter_forward(SMALL, get, wl.gen_x(14, 0, "q", 5, SMALL.hidden))) <= E2E_TOL

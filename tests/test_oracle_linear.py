@@ -125,3 +125,31 @@ def test_rel_l2_definition():
     assert ol.rel_l2([3.0, 4.0], [3.0, 4.0]) == 0.0
     assert ol.rel_l2([0.0, 0.0], [3.0, 4.0]) == pytest.approx(1.0)
     assert ol.rel_l2([3.0, 4.0 + 5e-3], [3.0, 4.0]) == pytest.approx(1e-3)
+
+
+def test_f64x_variant_against_exact_rationals_and_the_bit_input_variant():
+    """sparse_linear_f64x takes activations as float64 values instead of bf16 bits.  Pin 1: exact rational brute
+    force with activations that are NOT bf16 values (thirds of integers scaled by a power of two are not needed:
+    quarters and eighths of small integers are exact in float64 and in Fraction alike).  Pin 2: on bf16-exact
+    activations it must equal the bit-input variant exactly.  Pin 3: a transposed operand or a dropped mask fails."""
+    rng = np.random.default_rng(41)
+    w_int = rng.integers(-9, 10, size=(6, 10))
+    w_int[rng.random((6, 10)) < 0.5] = 0
+    w_bits = _bits_of_ints(w_int)
+    x = rng.integers(-40, 41, size=(3, 10)).astype(np.float64) / 8.0   # multiples of 1/8: exact in binary
+    got = ol.sparse_linear_f64x(w_bits, x)
+    assert got.shape == (3, 6)
+    for t in range(3):
+        for n in range(6):
+            want = sum(_bf16_fraction(int(w_bits[n, c])) * Fraction(int(round(x[t, c] * 8)), 8) for c in range(10))
+            assert Fraction(float(got[t, n])) == want
+    # the mask argument prunes: brute force over the kept columns only
+    mask = rng.random((6, 10)) < 0.5
+    got_m = ol.sparse_linear_f64x(w_bits, x, mask)
+    for t in range(3):
+        for n in range(6):
+            want = sum(_bf16_fraction(int(w_bits[n, c])) * Fraction(int(round(x[t, c] * 8)), 8) for c in range(10) if mask[n, c])
+            assert Fraction(float(got_m[t, n])) == want
+    # bf16-exact activations: identical to the variant that takes bits
+    x_bits = _bits_of_ints(rng.integers(-20, 21, size=(4, 10)))
+    assert np.array_equal(ol.sparse_linear_f64x(w_bits, bits_to_f64(x_bits)), ol.sparse_linear(w_bits, x_bits))

@@ -113,3 +113,40 @@ def test_stack_step_by_step_recomputation():
     g, u = gu[:, :SHAPE.inter], gu[:, SHAPE.inter:]
     m = round_to_bf16(np.array([[float(gv) / (1 + math.exp(-float(gv))) * float(uv) for gv, uv in zip(gr, ur)] for gr, ur in zip(g, u)]))
     assert np.mean(trace[3][2] != m) < 1e-3  # identical up to rare last-bit differences of exp
+
+
+def test_mlp_block_against_scalar_loops_and_a_swapped_gate():
+    """The stand-alone MLP block down(bf16(silu(gate x) * (up x))), recomputed entry by entry with math.exp and
+    Python sums on small integer-valued weights; swapping gate and up (a plausible slip: silu then lands on the
+    wrong branch) must change the result."""
+    rng = np.random.default_rng(17)
+    k_in, inter, k_tok = 6, 5, 3
+    def ints(shape, lo, hi, p_zero):
+        a = rng.integers(lo, hi + 1, size=shape)
+        a[rng.random(shape) < p_zero] = 0
+        return a
+    wg_i, wu_i, wd_i = ints((inter, k_in), -3, 3, 0.4), ints((inter, k_in), -3, 3, 0.4), ints((k_in, inter), -3, 3, 0.4)
+    x_i = rng.integers(-2, 3, size=(k_tok, k_in))
+    bits = lambda a: wl.f32_to_bf16_bits(np.asarray(a, dtype=np.float32))
+    y, m = os_.mlp_block(bits(wg_i), bits(wu_i), bits(wd_i), bits(x_i))
+    assert y.shape == (k_tok, k_in) and m.shape == (k_tok, inter)
+    for t in range(k_tok):
+        m_row = []
+        for j in range(inter):
+            g = sum(int(wg_i[j, c]) * int(x_i[t, c]) for c in range(k_in))
+            u = sum(int(wu_i[j, c]) * int(x_i[t, c]) for c in range(k_in))
+            val = g / (1.0 + math.exp(-g)) * u
+            m_row.append(float(bits_to_f64(wl.f32_to_bf16_bits(np.array([val], dtype=np.float32)))[0]))   # the workload's own rounding routine
+            assert m[t, j] == pytest.approx(m_row[-1], rel=0, abs=abs(m_row[-1]) * 2.0 ** -8)  # same value or its bf16 neighbour
+        for n in range(k_in):
+            want = sum(int(wd_i[n, j]) * m[t, j] for j in range(inter))
+            assert y[t, n] == pytest.approx(want, rel=1e-12, abs=1e-12)
+    y_swapped, _ = os_.mlp_block(bits(wu_i), bits(wg_i), bits(wd_i), bits(x_i))
+    assert np.abs(y_swapped - y).max() > 1e-3
+    # a down projection applied to the unrounded product differs as well (the rounding point is part of the definition)
+    x = bits_to_f64(bits(x_i))
+    g = x @ wg_i.T.astype(np.float64)
+    u = x @ wu_i.T.astype(np.float64)
+    unrounded = (g / (1.0 + np.exp(-g)) * u) @ wd_i.T.astype(np.float64)
+    assert np.abs(unrounded - y).max() > 0
+    assert np.abs(unrounded - y).max() <= np.abs(wd_i).sum(axis=1).max() * np.abs(m).max() * 2.0 ** -8
