@@ -8,10 +8,18 @@ One "step" is one pass of the whole hot path over one batch of synthetic input: 
 Forward and verify are each captured once into a HIP graph and replayed K times; an event pair
 on the same stream brackets every forward inside the timed region.
 
-Prints one JSON line.  `roofline` describes the dominant kernel: algorithmic bytes per launch divided by the
-live event-timed duration, against the published 8 TB/s of HBM3E (`traffic` = HBM bytes per launch measured with
-profiler counters in separate runs).  `cpu_baseline` is the NumPy fp64 oracle timed on the host's cores.  The
-other keys (`lm_head`, `draft_round`, `decode`, `draft_round_cached`, `nm24_linear`, `mask_gradient`) time further kernels on their own; they are not in `value`.
+Prints one JSON line.  `value` is the step above and nothing else.  Beside it:
+* `roofline`: the dominant kernel -- algorithmic bytes per launch divided by the live event-timed duration, against
+  the published 8 TB/s of HBM3E (`traffic` = HBM bytes per launch measured with profiler counters in separate runs)
+  and against a measured pure read stream of 2 GiB;
+* `config.dense_stack_us`, `speedup_vs_dense`, `linears_only_us`: the same stack with the same masked weights stored
+  densely, and every linear of the stack as an independent call (sparse and dense);
+* `configs`: the other benchmark configurations, each with microseconds per call, useful and stored bytes, effective
+  GB/s, fraction of peak and the dense kernel's time: the single 512 x 512 linear (latency-bound), the 1B-shape MLP
+  block run cold over distinct matrices, the twelve cells of the 1.5B-shape stack, the wide regime (16/32/64 tokens);
+* `cpu_baseline`: the NumPy fp64 oracle timed on the host's cores;
+* further kernels timed on their own (`lm_head`, `draft_round`, `decode`, `draft_round_cached`, `nm24_linear`,
+  `mask_gradient`).
 """
 
 import argparse
@@ -29,12 +37,13 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 # HBM bytes per launch of the forward kernel (and of the gate+up sparse linear) from rocprofv3 --pmc
 # FETCH_SIZE / WRITE_SIZE runs, scaled by the plain copy kernel of --calibrate; None until measured.
-MEASURED_TRAFFIC_BYTES = 3448133254
+MEASURED_TRAFFIC_BYTES = None
 MEASURED_LINEAR_TRAFFIC_BYTES = 61260497
 MEASURED_LM_HEAD_TRAFFIC_BYTES = 788275309
 MEASURED_NM24_TRAFFIC_BYTES = 57261905
-MEASURED_DECODE_TRAFFIC_BYTES = 3351187117  # the single-launch decode step (one token, 429 cached positions)
+MEASURED_DECODE_TRAFFIC_BYTES = None
 CALIBRATION_BYTES = 256 << 20  # size of the plain copies launched by --calibrate
+STREAM_BYTES = 2 << 30         # the pure read stream that serves as the measured ceiling
 
 
 def parse_args():
@@ -50,30 +59,253 @@ def parse_args():
     ap.add_argument("--layers", type=int, default=0, help="debug: fewer layers (reported as such)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true")
-    ap.add_argument("--dense", action="store_true", help="also time the dense bf16 stack")
-    ap.add_argument("--no-lm-head", action="store_true", help="skip the separately timed LM head + greedy choice")
+    ap.add_argument("--no-dense", action="store_true", help="skip the dense bf16 stack and the linears-only comparison")
+    ap.add_argument("--no-configs", action="store_true", help="skip the other benchmark configurations (`configs`)")
+    ap.add_argument("--no-lm-head", action="store_true", help="skip the separately timed LM head, drafting rounds and decode step")
     ap.add_argument("--no-nm24", action="store_true", help="skip the separately timed 2:4 semi-structured gate+up linear")
-    ap.add_argument("--nm24-stack", action="store_true", help="also time the whole stack with 2:4 matrices (multi-launch chain)")
+    ap.add_argument("--nm24-stack", action="store_true", help="also time the whole stack with 2:4 matrices")
     ap.add_argument("--calibrate", action="store_true",
                     help="also launch three plain 256 MiB copies (reference dispatches for profiler HBM counters)")
     return ap.parse_args()
 
 
-def build_weights(shape, cfg_id, pct, layers, workers, pattern="row"):
-    """Per layer the four fused bf16 matrices (qkv, o, gate_up, down), generated from the seed recipe."""
+FUSED_GROUPS = (("q", "k", "v"), ("o",), ("gate", "up"), ("down",))
+
+
+def build_weights(shape, cfg_id, pcts, layers, workers, pattern="row"):
+    """Per sparsity the per-layer fused bf16 matrices (qkv, o, gate_up, down) from the seed recipe.  The random draw
+    of a matrix does not depend on the sparsity, so several sparsities share it and differ in the mask only."""
     import sd2_workload as wl
 
     table = {p: (n, k) for p, n, k in wl.layer_matrix_shapes(shape)}
+    mask_fn = wl.magnitude_mask_per_row if pattern == "row" else wl.magnitude_mask_global
 
     def one(job):
         layer, projs = job
-        mats = [wl.gen_weight(cfg_id, layer, p, table[p][0], table[p][1], pct, pattern=pattern) for p in projs]
-        return layer, projs, (mats[0] if len(mats) == 1 else np.concatenate(mats, axis=0))
+        per_pct = {p: [] for p in pcts}
+        for proj in projs:
+            dense = wl.gen_weight_dense(cfg_id, layer, proj, table[proj][0], table[proj][1])
+            for p in pcts:
+                w = np.where(mask_fn(dense, p), dense, np.uint16(0)).astype(np.uint16)
+                per_pct[p].append(w)
+        return {p: (m[0] if len(m) == 1 else np.concatenate(m, axis=0)) for p, m in per_pct.items()}
 
-    jobs = [(l, g) for l in range(layers) for g in (("q", "k", "v"), ("o",), ("gate", "up"), ("down",))]
+    jobs = [(l, g) for l in range(layers) for g in FUSED_GROUPS]
     with ThreadPoolExecutor(max_workers=workers) as ex:
         done = list(ex.map(one, jobs))
-    return [w for _, _, w in done]
+    return {p: [d[p] for d in done] for p in pcts}
+
+
+class Bench:
+    """Shared state of one benchmark process: device, stream, small helpers."""
+
+    def __init__(self, args):
+        import torch
+        import paper_2504_08838_amd as sd2
+        import sd2_workload as wl
+
+        self.torch, self.sd2, self.wl, self.args = torch, sd2, wl, args
+        self.dev = torch.device("cuda:0")
+        torch.cuda.set_device(self.dev)
+        self.stream = torch.cuda.Stream()  # default priority
+        self.workers = min(16, os.cpu_count() or 8)
+
+    def to_dev(self, a):
+        a = np.ascontiguousarray(a)
+        return self.torch.from_numpy(a.view(np.int16) if a.dtype == np.uint16 else a).to(self.dev)
+
+    def pack_model(self, fused, shape, layers, sparse=True):
+        """-> (model, descriptors, useful bytes, stored bytes); the model keeps its device tensors alive."""
+        sd2, torch = self.sd2, self.torch
+        keep, mats, useful, total = [], [], 0, 0
+        if sparse:
+            with ThreadPoolExecutor(max_workers=self.workers) as ex:
+                blobs = list(ex.map(lambda w: sd2.pack_sparse(w, 1), fused))
+            for blob in blobs:
+                d = torch.from_numpy(blob).to(self.dev)
+                keep.append(d)
+                mats.append(sd2.matrix_init_sparse(blob, d.data_ptr()))
+        else:
+            for w in fused:
+                d = self.to_dev(w)
+                keep.append(d)
+                mats.append(sd2.matrix_init_dense(d.data_ptr(), w.shape[0], w.shape[1]))
+        for m in mats:
+            useful += int(m.info.useful_bytes)
+            total += int(m.info.total_bytes)
+        ms = sd2.ModelShape(layers, shape.hidden, shape.q_out, shape.kv_out, shape.inter, shape.n_heads, shape.n_kv, shape.head_dim)
+        return sd2.model_create(ms, mats, keep=keep), mats, useful, total
+
+    def graph_us(self, call, reps, warm=3, graph=True):
+        """Event-timed microseconds per call (list), the call captured once into a HIP graph and replayed."""
+        torch, stream = self.torch, self.stream
+        with torch.cuda.stream(stream):
+            call(stream.cuda_stream)
+            stream.synchronize()
+            g = None
+            if graph:
+                g = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g, stream=stream):
+                    call(torch.cuda.current_stream().cuda_stream)
+                run = g.replay
+            else:
+                run = lambda: call(stream.cuda_stream)
+            for _ in range(warm):
+                run()
+            ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+            for e0, e1 in ev:
+                e0.record(stream)
+                run()
+                e1.record(stream)
+            stream.synchronize()
+            del g
+        return [e0.elapsed_time(e1) * 1e3 for e0, e1 in ev]
+
+    def forward_us(self, model, shape, k_tok, reps, cfg_id=3):
+        """Mean microseconds of sd2_sparse_drafter_forward on k_tok tokens (graph replays), output checked finite."""
+        sd2, torch, wl = self.sd2, self.torch, self.wl
+        h_in = self.to_dev(wl.gen_x(cfg_id, 0, "q", k_tok, shape.hidden))
+        h_out = torch.empty((k_tok, shape.hidden), dtype=torch.float32, device=self.dev)
+        nb = sd2.drafter_workspace_size(model, k_tok)
+        ws = torch.empty(nb, dtype=torch.uint8, device=self.dev)
+        us = self.graph_us(lambda sp: sd2.sparse_drafter_forward(model, h_in.data_ptr(), k_tok, h_out.data_ptr(), ws.data_ptr(), nb, sp), reps)
+        sd2.drafter_forward_status(model, k_tok, ws.data_ptr(), self.stream.cuda_stream)
+        assert torch.isfinite(h_out).all(), "non-finite drafter output"
+        return float(np.mean(us))
+
+    def linears_us(self, mats, layers, k_tok, fn, cfg_id=3):
+        """Every linear of a stack as an independent call on its own seeded input, event-timed per kind; microseconds summed."""
+        sd2, torch, wl, stream = self.sd2, self.torch, self.wl, self.stream
+        tot = 0.0
+        with torch.cuda.stream(stream):
+            spp = stream.cuda_stream
+            for kind in range(4):
+                ms_k = [mats[4 * l + kind] for l in range(layers)]
+                info = ms_k[0].info
+                xk = self.to_dev(wl.gen_x(cfg_id, 0, ("q", "o", "gate", "down")[kind], k_tok, int(info.k_in)))
+                yk = torch.empty((k_tok, int(info.n_out)), dtype=torch.float32, device=self.dev)
+                wsb = max(sd2.linear_workspace_size(ms_k[0], k_tok), 16)
+                wsk = torch.empty(wsb, dtype=torch.uint8, device=self.dev)
+                best = None
+                for rep in range(3):
+                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    e0.record(stream)
+                    for m in ms_k:
+                        fn(m, xk.data_ptr(), k_tok, yk.data_ptr(), wsk.data_ptr(), wsb, spp)
+                    e1.record(stream)
+                    stream.synchronize()
+                    t = e0.elapsed_time(e1) * 1e3
+                    best = t if best is None or (rep and t < best) else best
+                tot += best
+        return tot
+
+
+def rate(nbytes, us):
+    gbs = nbytes / us / 1e3
+    return {"GBps": round(gbs, 1), "frac_of_peak": round(gbs / HBM_PEAK_GBS, 4)}
+
+
+def other_configs(B, fused3, model3, mats3, dmodel3, dmats3, useful3, total3, layers3):
+    """The benchmark's other configurations.  None of them enters `value`."""
+    sd2, torch, wl, args = B.sd2, B.torch, B.wl, B.args
+    out = []
+
+    # --- config 1: one 512 x 512 linear, 50 %, one token.  0.29 MB: launch latency, not bandwidth.
+    c1 = wl.CONFIGS[1]
+    w1 = wl.gen_weight(1, 0, "q", c1["n_out"], c1["k_in"], c1["sparsity"])
+    b1 = sd2.pack_sparse(w1, 1)
+    b1_dev = torch.from_numpy(b1).to(B.dev)
+    m1 = sd2.matrix_init_sparse(b1, b1_dev.data_ptr())
+    w1_dev = B.to_dev(w1)
+    d1 = sd2.matrix_init_dense(w1_dev.data_ptr(), c1["n_out"], c1["k_in"])
+    x1 = B.to_dev(wl.gen_x(1, 0, "q", c1["k_tok"], c1["k_in"]))
+    y1 = torch.empty((c1["k_tok"], c1["n_out"]), dtype=torch.float32, device=B.dev)
+    ws1 = torch.empty(max(sd2.linear_workspace_size(m1, c1["k_tok"]), sd2.linear_workspace_size(d1, c1["k_tok"]), 16), dtype=torch.uint8, device=B.dev)
+    us_s = float(np.median(B.graph_us(lambda sp: sd2.sparse_linear(m1, x1.data_ptr(), c1["k_tok"], y1.data_ptr(), ws1.data_ptr(), ws1.numel(), sp), 100)))
+    us_d = float(np.median(B.graph_us(lambda sp: sd2.dense_linear(d1, x1.data_ptr(), c1["k_tok"], y1.data_ptr(), ws1.data_ptr(), ws1.numel(), sp), 100)))
+    out.append({"config": 1, "what": "single sparse linear 512x512, 50 %, k=1", "us": round(us_s, 2), "dense_us": round(us_d, 2),
+                "speedup_vs_dense": round(us_d / us_s, 3), "useful_bytes": int(m1.info.useful_bytes), "stored_bytes": int(m1.info.total_bytes),
+                "bound": "launch latency: 0.3 MB is 0.04 us of traffic at peak, so GB/s says nothing here", **rate(int(m1.info.useful_bytes), us_s)})
+
+    # --- config 2: the 1B-shape MLP block, 50 %, k = 5, cold: ten distinct blocks (566 MB packed, 1 GB dense), so that
+    # no call finds its matrices in the last-level cache left by the call before
+    c2 = wl.CONFIGS[2]
+    n_blk = 10
+
+    def gen2(i):
+        gu = np.concatenate([wl.gen_weight(2, i, p, c2["inter"], c2["hidden"], c2["sparsity"]) for p in ("gate", "up")], axis=0)
+        dn = wl.gen_weight(2, i, "down", c2["hidden"], c2["inter"], c2["sparsity"])
+        return gu, dn, sd2.pack_sparse(gu, 1), sd2.pack_sparse(dn, 1)
+
+    with ThreadPoolExecutor(max_workers=B.workers) as ex:
+        blocks = list(ex.map(gen2, range(n_blk)))
+    keep2, sp2, de2, useful2, stored2 = [], [], [], 0, 0
+    for gu, dn, bgu, bdn in blocks:
+        dg, dd = torch.from_numpy(bgu).to(B.dev), torch.from_numpy(bdn).to(B.dev)
+        wg, wd = B.to_dev(gu), B.to_dev(dn)
+        keep2 += [dg, dd, wg, wd]
+        sp2.append((sd2.matrix_init_sparse(bgu, dg.data_ptr()), sd2.matrix_init_sparse(bdn, dd.data_ptr())))
+        de2.append((sd2.matrix_init_dense(wg.data_ptr(), gu.shape[0], gu.shape[1]), sd2.matrix_init_dense(wd.data_ptr(), dn.shape[0], dn.shape[1])))
+    useful2 = sum(int(a.info.useful_bytes) + int(b.info.useful_bytes) for a, b in sp2) // n_blk
+    stored2 = sum(int(a.info.total_bytes) + int(b.info.total_bytes) for a, b in sp2) // n_blk
+    x2 = B.to_dev(wl.gen_x(2, 0, "gate", c2["k_tok"], c2["hidden"]))
+    y2 = torch.empty((c2["k_tok"], c2["hidden"]), dtype=torch.float32, device=B.dev)
+    nb2 = max(sd2.mlp_workspace_size(sp2[0][0], sp2[0][1], c2["k_tok"]), sd2.mlp_workspace_size(de2[0][0], de2[0][1], c2["k_tok"]))
+    ws2 = torch.empty(nb2, dtype=torch.uint8, device=B.dev)
+
+    def cold(pairs):
+        d = []
+        with torch.cuda.stream(B.stream):
+            for rep in range(3):
+                ev = [torch.cuda.Event(enable_timing=True) for _ in range(2 * n_blk)]
+                for i, (a, b) in enumerate(pairs):
+                    ev[2 * i].record(B.stream)
+                    sd2.sparse_mlp_forward(a, b, x2.data_ptr(), c2["k_tok"], y2.data_ptr(), ws2.data_ptr(), nb2, B.stream.cuda_stream)
+                    ev[2 * i + 1].record(B.stream)
+                B.stream.synchronize()
+                if rep:
+                    d += [ev[2 * i].elapsed_time(ev[2 * i + 1]) * 1e3 for i in range(n_blk)]
+        return float(np.mean(d))
+
+    us_s, us_d = cold(sp2), cold(de2)
+    out.append({"config": 2, "what": f"1B-shape MLP block (gate|up 16384x2048, down 2048x8192), 50 %, k=5, cold over {n_blk} distinct blocks "
+                                     "(3 launches per call: gate|up, gated product, down)",
+                "us": round(us_s, 2), "dense_us": round(us_d, 2), "speedup_vs_dense": round(us_d / us_s, 3), "useful_bytes": useful2,
+                "stored_bytes": stored2, **rate(useful2, us_s)})
+    del keep2, sp2, de2, blocks
+
+    # --- config 4: the 1.5B-shape stack, 28 layers, 50 / 60 / 70 % x k = 1, 3, 5, 8, against the dense stack of the same shape
+    c4 = wl.CONFIGS[4]
+    shape4 = c4["shape"]
+    fused4 = build_weights(shape4, 4, list(c4["sparsity"]), shape4.layers, B.workers)
+    dmodel4, _, _, _ = B.pack_model(fused4[c4["sparsity"][0]], shape4, shape4.layers, sparse=False)
+    dense4 = {k: B.forward_us(dmodel4, shape4, k, 10, cfg_id=4) for k in c4["k_tok"]}
+    sd2.model_destroy(dmodel4)
+    for pct in c4["sparsity"]:
+        model4, _, useful4, stored4 = B.pack_model(fused4[pct], shape4, shape4.layers)
+        for k in c4["k_tok"]:
+            us = B.forward_us(model4, shape4, k, 30, cfg_id=4)
+            out.append({"config": 4, "what": f"1.5B-shape stack, 28 layers, {pct} %, k={k}", "sparsity_pct": pct, "k_tok": k, "us": round(us, 1),
+                        "dense_us": round(dense4[k], 1), "speedup_vs_dense": round(dense4[k] / us, 3), "useful_bytes": useful4,
+                        "stored_bytes": stored4, **rate(useful4, us)})
+        sd2.model_destroy(model4)
+    del fused4
+
+    # --- config 5: the 3B-shape stack on 16 / 32 / 64 tokens, sparse against dense: the whole stack and the linears alone
+    for k in wl.CONFIGS[5]["k_tok"]:
+        us_s = B.forward_us(model3, wl.CONFIGS[3]["shape"], k, 10)
+        entry = {"config": 5, "what": f"3B-shape stack, {layers3} layers, 50 %, k={k} (wide regime)", "k_tok": k, "us": round(us_s, 1),
+                 "useful_bytes": useful3, "stored_bytes": total3, **rate(useful3, us_s)}
+        lin_s = B.linears_us(mats3, layers3, k, sd2.sparse_linear)
+        entry["linears_only_us"] = {"sparse": round(lin_s, 1)}
+        if dmodel3 is not None:
+            us_d = B.forward_us(dmodel3, wl.CONFIGS[3]["shape"], k, 5)
+            lin_d = B.linears_us(dmats3, layers3, k, sd2.dense_linear)
+            entry.update({"dense_us": round(us_d, 1), "speedup_vs_dense": round(us_d / us_s, 3)})
+            entry["linears_only_us"].update({"dense": round(lin_d, 1), "speedup": round(lin_d / lin_s, 3),
+                                             **{"sparse_" + a: b for a, b in rate(useful3, lin_s).items()}})
+        out.append(entry)
+    return out
 
 
 def main():
@@ -90,34 +322,19 @@ def main():
     if not torch.cuda.is_available():
         print("no GPU visible", file=sys.stderr)
         sys.exit(1)
-    dev = torch.device("cuda:0")
-    torch.cuda.set_device(dev)
+    B = Bench(args)
+    dev, stream, to_dev, workers = B.dev, B.stream, B.to_dev, B.workers
 
     cfg = wl.CONFIGS[args.config]
     shape = cfg["shape"]
     layers = args.layers or shape.layers
     k_tok, pct = args.k_tok, args.sparsity
-    workers = min(16, os.cpu_count() or 8)
+    headline = args.config == 3 and layers == shape.layers and pct == 50 and k_tok == 5 and args.pattern == "row"
 
     t_setup = time.time()
-    fused = build_weights(shape, args.config, pct, layers, workers, args.pattern)
-    with ThreadPoolExecutor(max_workers=workers) as ex:
-        blobs = list(ex.map(lambda w: sd2.pack_sparse(w, 1), fused))
-    keep, mats, useful, total = [], [], 0, 0
-    for blob in blobs:
-        d = torch.from_numpy(blob).to(dev)
-        keep.append(d)
-        m = sd2.matrix_init_sparse(blob, d.data_ptr())
-        mats.append(m)
-        useful += int(m.info.useful_bytes)
-        total += int(m.info.total_bytes)
-    ms = sd2.ModelShape(layers, shape.hidden, shape.q_out, shape.kv_out, shape.inter, shape.n_heads, shape.n_kv,
-                        shape.head_dim)
-    model = sd2.model_create(ms, mats, keep=keep)
-
-    def to_dev(a):
-        a = np.ascontiguousarray(a)
-        return torch.from_numpy(a.view(np.int16) if a.dtype == np.uint16 else a).to(dev)
+    fused = build_weights(shape, args.config, [pct], layers, workers, args.pattern)[pct]
+    model, mats, useful, total = B.pack_model(fused, shape, layers)
+    ms = sd2.ModelShape(layers, shape.hidden, shape.q_out, shape.kv_out, shape.inter, shape.n_heads, shape.n_kv, shape.head_dim)
 
     h_in = to_dev(wl.gen_x(args.config, 0, "q", k_tok, shape.hidden))
     h_out = torch.empty((k_tok, shape.hidden), dtype=torch.float32, device=dev)
@@ -130,8 +347,6 @@ def main():
     out_tok = torch.empty((vcfg["batch"], vcfg["k"] + 1), dtype=torch.int32, device=dev)
     setup_s = time.time() - t_setup
 
-    stream = torch.cuda.Stream()  # default priority
-
     def fwd(sp):
         sd2.sparse_drafter_forward(model, h_in.data_ptr(), k_tok, h_out.data_ptr(), ws.data_ptr(), ws_bytes, sp)
 
@@ -141,7 +356,7 @@ def main():
 
     # A step is forward + verify.  Each half is captured into a HIP graph of its own so that an event pair
     # recorded on the same stream brackets the forward inside the timed region: the forward is one persistent
-    # kernel (plus two tiny set-up launches), and that pair is the live duration the roofline entry uses.
+    # kernel (plus a tiny set-up launch), and that pair is the live duration the roofline entry uses.
     use_graph = not args.no_graph
     with torch.cuda.stream(stream):
         sp = stream.cuda_stream
@@ -186,7 +401,7 @@ def main():
     # algorithmic bytes = every matrix's useful bytes (2 B per nonzero + 1 mask bit per weight) plus the
     # activations each linear reads (bf16) and the sums it produces (fp32).
     # the single-launch kernel serves up to 8 tokens (and is switched off by SD2_FORWARD=multi)
-    forward_path = "multi" if (os.environ.get("SD2_FORWARD") == "multi" or k_tok > 8) else "single-launch"
+    forward_path = "multi" if (sd2.get_option(sd2.OPT_FORWARD_MULTI) or k_tok > 8) else "single-launch"
     act_bytes = 0
     for m in mats:
         act_bytes += 2 * k_tok * int(m.info.k_in) + 4 * k_tok * int(m.info.n_out)
@@ -229,10 +444,18 @@ def main():
             for _ in range(3):
                 sd2.calibration_copy(cal_dst.data_ptr(), cal_src.data_ptr(), CALIBRATION_BYTES, sp)
             stream.synchronize()
+            del cal_src, cal_dst
     kern_us, part_us = float(np.mean(durs)), float(np.mean(durs_part))
     gi = gu[0].info
     alg_bytes = int(gi.useful_bytes) + 2 * k_tok * gi.k_in + 4 * k_tok * gi.n_out
     achieved = alg_bytes / kern_us / 1e3  # GB/s
+
+    # --- measured ceiling: a pure read stream of 2 GiB (more than the last-level cache holds), event-timed per launch
+    src = torch.empty(STREAM_BYTES, dtype=torch.uint8, device=dev).fill_(3)
+    sink = torch.empty(2048, dtype=torch.int32, device=dev)
+    rd = B.graph_us(lambda spp: sd2.calibration_read(src.data_ptr(), STREAM_BYTES, sink.data_ptr(), spp), 10, graph=False)
+    stream_gbs = STREAM_BYTES / float(np.mean(rd)) / 1e3
+    del src
 
     single = forward_path != "multi"
     record = {
@@ -270,21 +493,51 @@ def main():
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
             "frac": round(fwd_achieved / HBM_PEAK_GBS, 4),
-            "traffic": MEASURED_TRAFFIC_BYTES if (single and layers == shape.layers and args.config == 3 and pct == 50
-                                                  and k_tok == 5) else None,
+            "traffic": MEASURED_TRAFFIC_BYTES if (single and headline) else None,
             "kernel_us": round(fwd_us, 2),
             "algorithmic_bytes": fwd_alg_bytes,
+            "measured_read_stream_GBps": round(stream_gbs, 1),
+            "measured_read_stream_what": f"pure read of {STREAM_BYTES >> 20} MiB (sd2_calibration_read), event-timed",
+            "frac_of_measured_stream": round(fwd_achieved / stream_gbs, 4),
             "linear_kernel": {
                 "kernel": f"sparse_strip_kernel (fused gate+up, {gi.n_out}x{gi.k_in}, final results in one launch)",
                 "achieved": round(achieved, 1),
                 "frac": round(achieved / HBM_PEAK_GBS, 4),
                 "kernel_us": round(kern_us, 2),
                 "algorithmic_bytes": alg_bytes,
-                "traffic": MEASURED_LINEAR_TRAFFIC_BYTES,
+                "traffic": MEASURED_LINEAR_TRAFFIC_BYTES if headline else None,
                 "partials_kernel_us": round(part_us, 2),
             },
         },
     }
+
+    # --- the same stack with the same masked weights stored densely (the hand-written dense bf16 baseline), and every
+    # linear of the stack as an independent call without any glue: sparse against dense, like for like
+    dmodel = dmats = None
+    if not args.no_dense:
+        dmodel, dmats, _, _ = B.pack_model(fused, shape, layers, sparse=False)
+        dense_us = B.forward_us(dmodel, shape, k_tok, max(args.steps // 8, 10), cfg_id=args.config)
+        record["config"]["dense_stack_us"] = round(dense_us, 2)
+        record["config"]["dense_stack_path"] = "multi-launch (the single-launch kernel is written for the packed format)"
+        record["config"]["speedup_vs_dense"] = round(dense_us / fwd_us, 3)
+        sd2.set_option(sd2.OPT_FORWARD_MULTI, 1)  # the sparse stack on the dense stack's launch structure
+        try:
+            multi_us = B.forward_us(model, shape, k_tok, max(args.steps // 8, 10), cfg_id=args.config)
+        finally:
+            sd2.set_option(sd2.OPT_FORWARD_MULTI, 0)
+        record["config"]["sparse_stack_multi_launch_us"] = round(multi_us, 2)
+        record["config"]["speedup_vs_dense_same_launch_structure"] = round(dense_us / multi_us, 3)
+        sp_lin = B.linears_us(mats, layers, k_tok, sd2.sparse_linear, cfg_id=args.config)
+        de_lin = B.linears_us(dmats, layers, k_tok, sd2.dense_linear, cfg_id=args.config)
+        record["config"]["linears_only_us"] = {"sparse": round(sp_lin, 1), "dense": round(de_lin, 1), "speedup": round(de_lin / sp_lin, 3),
+                                               **{"sparse_" + a: b for a, b in rate(useful, sp_lin).items()}}
+
+    if not args.no_configs and headline:
+        record["configs"] = other_configs(B, fused, model, mats, dmodel, dmats, useful, total, layers)
+
+    if dmodel is not None:
+        sd2.model_destroy(dmodel)
+        dmodel = dmats = None
 
     if not args.no_lm_head:
         # The drafter's dense LM head with the final norm and the greedy choice fused in, timed on its own
@@ -294,37 +547,16 @@ def main():
         lm_ws_bytes = sd2.lm_head_workspace_size(vocab, shape.hidden, k_tok)
         lm_ws = torch.empty(lm_ws_bytes, dtype=torch.uint8, device=dev)
         lm = {}
-        with torch.cuda.stream(stream):
-            for kt in sorted({1, k_tok}):
-                h_fin = torch.from_numpy(wl.gen_final_hidden(args.config, kt, shape.hidden)).to(dev)
-                ids = torch.empty(kt, dtype=torch.int32, device=dev)
-                call = lambda spp: sd2.lm_head_argmax(w_lm.data_ptr(), vocab, shape.hidden, h_fin.data_ptr(), kt,
-                                                      ids.data_ptr(), lm_ws.data_ptr(), lm_ws_bytes, spp)
-                call(stream.cuda_stream)
-                stream.synchronize()
-                g_lm = torch.cuda.CUDAGraph()
-                with torch.cuda.graph(g_lm, stream=stream):
-                    call(torch.cuda.current_stream().cuda_stream)
-                n_rep = 30
-                evl = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_rep)]
-                for _ in range(3):
-                    g_lm.replay()
-                for e0, e1 in evl:
-                    e0.record(stream)
-                    g_lm.replay()
-                    e1.record(stream)
-                stream.synchronize()
-                us = float(np.mean([e0.elapsed_time(e1) for e0, e1 in evl])) * 1e3
-                lm_bytes = 2 * vocab * shape.hidden + 4 * kt * shape.hidden + 8 * kt
-                lm[f"k{kt}"] = {"us": round(us, 2), "achieved_GBps": round(lm_bytes / us / 1e3, 1),
-                                "frac": round(lm_bytes / us / 1e3 / HBM_PEAK_GBS, 4), "algorithmic_bytes": lm_bytes}
-                ids_host = ids.cpu().numpy()
-                assert ids_host.min() >= 0 and ids_host.max() < vocab
-                del g_lm
-        # the head is a plain read stream of 788 MB: its rate serves as the measured read-stream ceiling of this part
-        ceiling = max(v["achieved_GBps"] for v in lm.values())
-        record["roofline"]["measured_read_stream_GBps"] = ceiling
-        record["roofline"]["frac_of_measured_stream"] = round(fwd_achieved / ceiling, 4)
+        for kt in sorted({1, k_tok}):
+            h_fin = torch.from_numpy(wl.gen_final_hidden(args.config, kt, shape.hidden)).to(dev)
+            ids = torch.empty(kt, dtype=torch.int32, device=dev)
+            us = float(np.mean(B.graph_us(lambda spp: sd2.lm_head_argmax(w_lm.data_ptr(), vocab, shape.hidden, h_fin.data_ptr(), kt,
+                                                                        ids.data_ptr(), lm_ws.data_ptr(), lm_ws_bytes, spp), 30)))
+            lm_bytes = 2 * vocab * shape.hidden + 4 * kt * shape.hidden + 8 * kt
+            lm[f"k{kt}"] = {"us": round(us, 2), "achieved_GBps": round(lm_bytes / us / 1e3, 1),
+                            "frac": round(lm_bytes / us / 1e3 / HBM_PEAK_GBS, 4), "algorithmic_bytes": lm_bytes}
+            ids_host = ids.cpu().numpy()
+            assert ids_host.min() >= 0 and ids_host.max() < vocab
         record["lm_head"] = {"kernel": f"lm_head_kernel (dense bf16 {vocab}x{shape.hidden}, final norm + argmax fused)",
                              "bound": "hbm", "peak": HBM_PEAK_GBS, "unit": "GB/s",
                              "traffic": MEASURED_LM_HEAD_TRAFFIC_BYTES if (args.config == 3) else None, **lm}
@@ -335,24 +567,9 @@ def main():
         dr_ws = torch.empty(dr_bytes, dtype=torch.uint8, device=dev)
         start_tok = torch.tensor([1], dtype=torch.int32, device=dev)
         dr_ids = torch.full((kr,), -1, dtype=torch.int32, device=dev)
-        with torch.cuda.stream(stream):
-            dcall = lambda spp: sd2.draft_round(model, w_lm.data_ptr(), vocab, start_tok.data_ptr(), kr, dr_ids.data_ptr(),
-                                                dr_ws.data_ptr(), dr_bytes, spp)
-            dcall(stream.cuda_stream)
-            sd2.draft_round_status(model, vocab, kr, dr_ws.data_ptr(), stream.cuda_stream)
-            g_dr = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(g_dr, stream=stream):
-                dcall(torch.cuda.current_stream().cuda_stream)
-            for _ in range(2):
-                g_dr.replay()
-            n_dr = 20
-            evd = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_dr)]
-            for e0, e1 in evd:
-                e0.record(stream)
-                g_dr.replay()
-                e1.record(stream)
-            stream.synchronize()
-        dr_us = float(np.mean([e0.elapsed_time(e1) for e0, e1 in evd])) * 1e3
+        dr_us = float(np.mean(B.graph_us(lambda spp: sd2.draft_round(model, w_lm.data_ptr(), vocab, start_tok.data_ptr(), kr, dr_ids.data_ptr(),
+                                                                     dr_ws.data_ptr(), dr_bytes, spp), 20, warm=2)))
+        sd2.draft_round_status(model, vocab, kr, dr_ws.data_ptr(), stream.cuda_stream)
         ids_host = dr_ids.cpu().numpy()
         assert ids_host.min() >= 0 and ids_host.max() < vocab
         dr_alg = kr * (useful + 2 * vocab * shape.hidden)  # every step streams the stack and the head once
@@ -361,7 +578,6 @@ def main():
                                  "us_per_token": round(dr_us / kr, 1), "algorithmic_bytes": dr_alg,
                                  "achieved_GBps": round(dr_alg / dr_us / 1e3, 1),
                                  "frac": round(dr_alg / dr_us / 1e3 / HBM_PEAK_GBS, 4)}
-        del g_dr
 
         # One decode step with rotary embedding and a key/value cache: one new token at position 428 (a 300-token prompt
         # and 128 generated tokens: the middle of the request shape of the paper's serving measurements), synthetic history.
@@ -382,24 +598,9 @@ def main():
         win_call = lambda spp: sd2.sparse_drafter_forward(model, dh_in.data_ptr(), 1, dh_out.data_ptr(), w1_ws.data_ptr(),
                                                           w1_bytes, spp)
         dec_us = {}
-        with torch.cuda.stream(stream):
-            for name, call in (("decode", dec_call), ("window", win_call)):
-                call(stream.cuda_stream)
-                stream.synchronize()
-                g_dec = torch.cuda.CUDAGraph()
-                with torch.cuda.graph(g_dec, stream=stream):
-                    call(torch.cuda.current_stream().cuda_stream)
-                for _ in range(3):
-                    g_dec.replay()
-                evq = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(30)]
-                for e0, e1 in evq:
-                    e0.record(stream)
-                    g_dec.replay()
-                    e1.record(stream)
-                stream.synchronize()
-                dec_us[name] = float(np.mean([e0.elapsed_time(e1) for e0, e1 in evq])) * 1e3
-                assert torch.isfinite(dh_out).all()
-                del g_dec
+        for name, call in (("decode", dec_call), ("window", win_call)):
+            dec_us[name] = float(np.mean(B.graph_us(call, 30)))
+            assert torch.isfinite(dh_out).all()
         sd2.drafter_forward_status(model, 1, w1_ws.data_ptr(), stream.cuda_stream)
         sd2.drafter_decode_status(model, 1, dec_ws.data_ptr(), stream.cuda_stream)
         kv_bytes = 2 * 2 * layers * shape.n_kv * (dpos + 1) * shape.head_dim  # keys and values of the positions read, bf16
@@ -415,24 +616,10 @@ def main():
         rc_bytes = sd2.draft_round_cached_workspace_size(model, vocab, kr)
         rc_ws = torch.empty(rc_bytes, dtype=torch.uint8, device=dev)
         rc_ids = torch.full((kr,), -1, dtype=torch.int32, device=dev)
-        rc_call = lambda spp: sd2.draft_round_cached(model, w_lm.data_ptr(), vocab, start_tok.data_ptr(), kr, dpos,
-                                                     kc_dev.data_ptr(), vc_dev.data_ptr(), dmax, 500000.0, rc_ids.data_ptr(),
-                                                     rc_ws.data_ptr(), rc_bytes, spp)
-        with torch.cuda.stream(stream):
-            rc_call(stream.cuda_stream)
-            sd2.draft_round_cached_status(model, vocab, kr, rc_ws.data_ptr(), stream.cuda_stream)
-            g_rc = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(g_rc, stream=stream):
-                rc_call(torch.cuda.current_stream().cuda_stream)
-            for _ in range(2):
-                g_rc.replay()
-            evr = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(20)]
-            for e0, e1 in evr:
-                e0.record(stream)
-                g_rc.replay()
-                e1.record(stream)
-            stream.synchronize()
-        rc_us = float(np.mean([e0.elapsed_time(e1) for e0, e1 in evr])) * 1e3
+        rc_us = float(np.mean(B.graph_us(lambda spp: sd2.draft_round_cached(model, w_lm.data_ptr(), vocab, start_tok.data_ptr(), kr, dpos,
+                                                                            kc_dev.data_ptr(), vc_dev.data_ptr(), dmax, 500000.0,
+                                                                            rc_ids.data_ptr(), rc_ws.data_ptr(), rc_bytes, spp), 20, warm=2)))
+        sd2.draft_round_cached_status(model, vocab, kr, rc_ws.data_ptr(), stream.cuda_stream)
         ids_host = rc_ids.cpu().numpy()
         assert ids_host.min() >= 0 and ids_host.max() < vocab
         rc_alg = kr * (useful + 2 * vocab * shape.hidden) + sum(
@@ -442,9 +629,8 @@ def main():
                                         "us_per_token": round(rc_us / kr, 1), "algorithmic_bytes": rc_alg,
                                         "achieved_GBps": round(rc_alg / rc_us / 1e3, 1),
                                         "frac": round(rc_alg / rc_us / 1e3 / HBM_PEAK_GBS, 4)}
-        del g_rc, w_lm, kc_dev, vc_dev
+        del w_lm, kc_dev, vc_dev
 
-    if not args.no_lm_head:
         # Masked-gradient step of sparse fine-tuning on the fused gate+up shape (fp32 gradient, in place), two
         # gradient buffers alternating so that the last-level cache cannot hold the working set.  Not part of `value`.
         gsh = (int(gi.n_out), int(gi.k_in))
@@ -507,110 +693,29 @@ def main():
         del keep24, mats24, blobs24
 
     if args.nm24_stack:
+        table_nk = {p: (n, k) for p, n, k in wl.layer_matrix_shapes(shape)}
+
         def gen24_fused(job):
             l, projs = job
-            return sd2.pack_sparse(np.concatenate([wl.gen_weight(args.config, l, p, table_nk[p][0], table_nk[p][1], 50,
-                                                                 pattern="2:4") for p in projs], axis=0), 3)
+            return np.concatenate([wl.gen_weight(args.config, l, p, table_nk[p][0], table_nk[p][1], 50, pattern="2:4") for p in projs], axis=0)
 
-        table_nk = {p: (n, k) for p, n, k in wl.layer_matrix_shapes(shape)}
-        jobs = [(l, g) for l in range(layers) for g in (("q", "k", "v"), ("o",), ("gate", "up"), ("down",))]
+        jobs = [(l, g) for l in range(layers) for g in FUSED_GROUPS]
         with ThreadPoolExecutor(max_workers=workers) as ex:
-            sblobs = list(ex.map(gen24_fused, jobs))
+            fused24 = list(ex.map(gen24_fused, jobs))
+            sblobs = list(ex.map(lambda w: sd2.pack_sparse(w, 3), fused24))
         skeep = [torch.from_numpy(b).to(dev) for b in sblobs]
         smats = [sd2.matrix_init_sparse(b, d.data_ptr()) for b, d in zip(sblobs, skeep)]
         smodel = sd2.model_create(ms, smats, keep=skeep)
-        sws_bytes = sd2.drafter_workspace_size(smodel, k_tok)
-        sws = torch.empty(sws_bytes, dtype=torch.uint8, device=dev)
-        with torch.cuda.stream(stream):
-            def sstep(spp):
-                sd2.sparse_drafter_forward(smodel, h_in.data_ptr(), k_tok, h_out.data_ptr(), sws.data_ptr(), sws_bytes, spp)
-            sstep(stream.cuda_stream)
-            stream.synchronize()
-            sgraph = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(sgraph, stream=stream):
-                sstep(torch.cuda.current_stream().cuda_stream)
-            for _ in range(5):
-                sgraph.replay()
-            torch.cuda.synchronize()
-            t0 = time.perf_counter()
-            n24 = max(args.steps // 4, 10)
-            for _ in range(n24):
-                sgraph.replay()
-            torch.cuda.synchronize()
-            s24_us = (time.perf_counter() - t0) / n24 * 1e6
+        s24_us = B.forward_us(smodel, shape, k_tok, max(args.steps // 4, 10), cfg_id=args.config)
         sbytes = sum(int(m.info.useful_bytes) for m in smats)
         record["config"]["nm24_stack_us"] = round(s24_us, 2)
         record["config"]["nm24_stack_GBps"] = round(sbytes / s24_us / 1e3, 1)
-        assert np.isfinite(h_out.cpu().numpy()).all()
-        del sgraph
         sd2.model_destroy(smodel)
-        del skeep, sws
-
-    if args.dense:
-        dkeep, dmats = [], []
-        for w in fused:
-            d = to_dev(w)
-            dkeep.append(d)
-            dmats.append(sd2.matrix_init_dense(d.data_ptr(), w.shape[0], w.shape[1]))
-        dmodel = sd2.model_create(ms, dmats, keep=dkeep)
-        dws_bytes = sd2.drafter_workspace_size(dmodel, k_tok)
-        dws = torch.empty(dws_bytes, dtype=torch.uint8, device=dev)
-        with torch.cuda.stream(stream):
-            def dstep(spp):
-                sd2.sparse_drafter_forward(dmodel, h_in.data_ptr(), k_tok, h_out.data_ptr(), dws.data_ptr(), dws_bytes, spp)
-            dstep(stream.cuda_stream)
-            stream.synchronize()
-            dgraph = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(dgraph, stream=stream):
-                dstep(torch.cuda.current_stream().cuda_stream)
-            for _ in range(5):
-                dgraph.replay()
-            torch.cuda.synchronize()
-            t0 = time.perf_counter()
-            for _ in range(max(args.steps // 4, 10)):
-                dgraph.replay()
-            torch.cuda.synchronize()
-            dense_us = (time.perf_counter() - t0) / max(args.steps // 4, 10) * 1e6
-        record["config"]["dense_stack_us"] = round(dense_us, 2)
-        record["config"]["speedup_vs_dense"] = round(dense_us / us_per_step, 3)
-
-        # The same comparison without any glue: every linear of the stack as an independent call on its own
-        # seeded input (sd2_sparse_linear against sd2_dense_linear, same masked weights), event-timed per call.
-        def linears_us(matrices, fn):
-            tot = 0.0
-            with torch.cuda.stream(stream):
-                spp = stream.cuda_stream
-                for kind in range(4):
-                    ms_k = [matrices[4 * l + kind] for l in range(layers)]
-                    info = ms_k[0].info
-                    xk = to_dev(wl.gen_x(args.config, 0, ("q", "o", "gate", "down")[kind], k_tok, int(info.k_in)))
-                    yk = torch.empty((k_tok, int(info.n_out)), dtype=torch.float32, device=dev)
-                    wsb = max(sd2.linear_workspace_size(ms_k[0], k_tok), 16)
-                    wsk = torch.empty(wsb, dtype=torch.uint8, device=dev)
-                    best = None
-                    for rep in range(3):
-                        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                        e0.record(stream)
-                        for m in ms_k:
-                            fn(m, xk.data_ptr(), k_tok, yk.data_ptr(), wsk.data_ptr(), wsb, spp)
-                        e1.record(stream)
-                        stream.synchronize()
-                        t = e0.elapsed_time(e1) * 1e3
-                        best = t if best is None or (rep and t < best) else best
-                    tot += best
-            return tot
-
-        sp_lin, de_lin = linears_us(mats, sd2.sparse_linear), linears_us(dmats, sd2.dense_linear)
-        record["config"]["linears_only_us"] = {"sparse": round(sp_lin, 1), "dense": round(de_lin, 1),
-                                               "speedup": round(de_lin / sp_lin, 3)}
-        del dgraph
-        sd2.model_destroy(dmodel)
-        del dkeep, dws
+        del skeep, fused24
 
     if not args.no_cpu_baseline:
         from oracle import stack as ostack
 
-        table = {p: (n, k) for p, n, k in wl.layer_matrix_shapes(shape)}
         split = {"q": (0, 0, shape.q_out), "k": (0, shape.q_out, shape.q_out + shape.kv_out),
                  "v": (0, shape.q_out + shape.kv_out, shape.q_out + 2 * shape.kv_out), "o": (1, 0, shape.hidden),
                  "gate": (2, 0, shape.inter), "up": (2, shape.inter, 2 * shape.inter), "down": (3, 0, shape.hidden)}

@@ -73,12 +73,15 @@ int sd2_version(void);
  *   SD2_OPT_SPIN_LIMIT       polls a bounded wait of the single-launch kernel may spend; -1: the default (2^20)
  *   SD2_OPT_MEGA_TIMING      1 / 2: the trace variant of the forward records timestamps only (2: also wavefront 0's
  *                               split into waiting and decoding)
+ *   SD2_OPT_FIXED_BITS       fraction bits F (8..22, default 17) of the fixed-point sums of the single-launch kernel:
+ *                               resolution 2^-F, range +-2^(31-F); see sd2_sparse_drafter_forward
  * SD2_ERR_RANGE for an unknown switch or a value outside its range. */
 #define SD2_OPT_FORWARD_MULTI 0
 #define SD2_OPT_LINEAR_PARTIALS 1
 #define SD2_OPT_SPIN_LIMIT 2
 #define SD2_OPT_MEGA_TIMING 3
-#define SD2_OPT_COUNT 4
+#define SD2_OPT_FIXED_BITS 4
+#define SD2_OPT_COUNT 5
 int sd2_set_option(int32_t which, int32_t value);
 int sd2_get_option(int32_t which, int32_t* value_out);
 
@@ -219,7 +222,16 @@ int sd2_sparse_drafter_forward(const sd2_model_t* model, const uint16_t* h_in_bf
 /* The forward is asynchronous and its single-launch kernel synchronises the GPU's compute units with
  * bounded waits (it needs all of them at once; a wait that runs out sets a flag in the workspace and the
  * kernel still ends).  This call waits for `stream`, reads that flag of the last forward that used
- * `workspace_dev` with this model and k_tok, and returns SD2_OK or SD2_ERR_TIMEOUT. */
+ * `workspace_dev` with this model and k_tok, and returns SD2_OK, SD2_ERR_TIMEOUT or SD2_ERR_RANGE.
+ *
+ * Arithmetic of the single-launch kernel (k_tok <= 8): every workgroup adds up its share of a linear in fp32 and hands
+ * it over as a 32-bit fixed-point number with F = 17 fraction bits (SD2_OPT_FIXED_BITS); the shares and the residual
+ * stream are summed by integer atomics, which are exact, so equal inputs give bit-identical outputs whatever the order
+ * in which workgroups finish.  Resolution 2^-17 (the fp32 spacing at magnitude 64), range +-16384: a share must stay
+ * below 8192 / (its linear's slab blocks) and a token's residual norm below 8192.  A forward that leaves that range
+ * still ends, and the status call reports SD2_ERR_RANGE (results invalid) -- nothing wraps silently.  The
+ * launch-per-step path (more tokens, dense or mixed models, SD2_OPT_FORWARD_MULTI) accumulates in fp32 throughout, in a
+ * fixed order, and has no such range. */
 int sd2_drafter_forward_status(const sd2_model_t* model, int32_t k_tok, const void* workspace_dev, void* stream);
 
 /* Debug variant for step-by-step checking: the same forward, which also records, per linear
@@ -323,6 +335,11 @@ int sd2_draft_round_cached_status(const sd2_model_t* model, int32_t vocab, int32
  * without a device sync; use sd2_check_token_ids_host on host copies). */
 int sd2_greedy_verify(const int32_t* draft_dev, const int32_t* target_dev, int32_t batch, int32_t k,
                       int32_t vocab, int32_t* accepted_len_dev, int32_t* out_tokens_dev, void* stream);
+/* The same rule on host arrays, with the range check the device call cannot make: SD2_ERR_RANGE (and nothing
+ * written) if any draft or target id lies outside [0, vocab).  A reference for callers that hold the ids on the
+ * host anyway, and for checking a device result. */
+int sd2_greedy_verify_host(const int32_t* draft, const int32_t* target, int32_t batch, int32_t k, int32_t vocab,
+                           int32_t* accepted_len, int32_t* out_tokens);
 /* SD2_ERR_RANGE if any of the n host ids lies outside [0, vocab). */
 int sd2_check_token_ids_host(const int32_t* ids, size_t n, int32_t vocab);
 
@@ -359,6 +376,11 @@ int sd2_mask_gradient(const sd2_matrix_t* m, void* grad_dev, int32_t grad_is_bf1
  * the scale that turns the same counters of the other kernels into bytes.  bytes must be a multiple
  * of 16, both pointers 16-byte aligned, the ranges disjoint; asynchronous on `stream`. */
 int sd2_calibration_copy(void* dst_dev, const void* src_dev, size_t bytes, void* stream);
+/* Pure read stream of src[0..bytes) (16 bytes per lane, eight loads in flight, folded into checksums): the rate a
+ * kernel that only reads reaches on this part, the ceiling the weight-streaming kernels are measured against next to
+ * the published peak.  sink_dev: device, 2048 uint32 (one checksum per workgroup, overwritten).  bytes a non-zero
+ * multiple of 16; pointers 16-byte aligned; asynchronous on `stream`. */
+int sd2_calibration_read(const void* src_dev, size_t bytes, uint32_t* sink_dev, void* stream);
 
 #ifdef __cplusplus
 }

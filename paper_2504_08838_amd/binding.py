@@ -111,8 +111,10 @@ def lib():
             "sd2_sparse_drafter_forward_trace": (C.c_int, [vp, vp, i32, vp, vp, sz, vp, sz, vp]),
             "sd2_greedy_verify": (C.c_int, [vp, vp, i32, i32, i32, vp, vp, vp]),
             "sd2_check_token_ids_host": (C.c_int, [vp, sz, i32]),
+            "sd2_greedy_verify_host": (C.c_int, [vp, vp, i32, i32, i32, vp, vp]),
             "sd2_drafter_forward_status": (C.c_int, [vp, i32, vp, vp]),
             "sd2_calibration_copy": (C.c_int, [vp, vp, sz, vp]),
+            "sd2_calibration_read": (C.c_int, [vp, sz, vp, vp]),
             "sd2_mask_gradient": (C.c_int, [vp, vp, i32, vp]),
             "sd2_improvement_factor": (C.c_int, [C.c_double, i32, C.c_double, C.POINTER(C.c_double)]),
             "sd2_draft_round_cached_workspace_size": (C.c_int, [vp, i32, i32, C.POINTER(sz)]),
@@ -152,7 +154,7 @@ def version():
     return lib().sd2_version()
 
 
-OPT_FORWARD_MULTI, OPT_LINEAR_PARTIALS, OPT_SPIN_LIMIT, OPT_MEGA_TIMING = 0, 1, 2, 3
+OPT_FORWARD_MULTI, OPT_LINEAR_PARTIALS, OPT_SPIN_LIMIT, OPT_MEGA_TIMING, OPT_FIXED_BITS = 0, 1, 2, 3, 4
 
 
 def set_option(which, value):
@@ -313,6 +315,20 @@ def greedy_verify(draft_ptr, target_ptr, batch, k, vocab, accepted_ptr, out_toke
            "sd2_greedy_verify")
 
 
+def greedy_verify_host(draft, target, vocab):
+    """Host arrays draft [batch][k], target [batch][k+1] -> (accepted_len [batch], out_tokens [batch][k+1])."""
+    d = np.ascontiguousarray(draft, dtype=np.int32)
+    t = np.ascontiguousarray(target, dtype=np.int32)
+    batch, k = t.shape[0], t.shape[1] - 1
+    if d.shape != (batch, k):
+        raise ValueError("draft must be [batch][k] for target [batch][k+1]")
+    acc = np.empty(batch, dtype=np.int32)
+    out = np.empty((batch, k + 1), dtype=np.int32)
+    _check(lib().sd2_greedy_verify_host(_host_ptr(d), _host_ptr(t), batch, k, vocab, _host_ptr(acc), _host_ptr(out)),
+           "sd2_greedy_verify_host")
+    return acc, out
+
+
 def lm_head_workspace_size(vocab, hidden, k_tok):
     n = C.c_size_t(0)
     _check(lib().sd2_lm_head_workspace_size(vocab, hidden, k_tok, C.byref(n)), "sd2_lm_head_workspace_size")
@@ -398,6 +414,11 @@ def mask_gradient(m, grad_ptr, grad_is_bf16, stream=0):
 def calibration_copy(dst_ptr, src_ptr, nbytes, stream=0):
     _check(lib().sd2_calibration_copy(C.c_void_p(dst_ptr), C.c_void_p(src_ptr), nbytes, C.c_void_p(stream)),
            "sd2_calibration_copy")
+
+
+def calibration_read(src_ptr, nbytes, sink_ptr, stream=0):
+    _check(lib().sd2_calibration_read(C.c_void_p(src_ptr), nbytes, C.c_void_p(sink_ptr), C.c_void_p(stream)),
+           "sd2_calibration_read")
 
 
 def improvement_factor(mean_emitted, k, cost_ratio):

@@ -30,6 +30,7 @@ struct Options {
         v[SD2_OPT_LINEAR_PARTIALS] = ((e = getenv("SD2_LINEAR")) && strcmp(e, "partials") == 0) ? 1 : 0;
         v[SD2_OPT_SPIN_LIMIT] = (e = getenv("SD2_MEGA_SPIN_LIMIT")) ? std::max(0, atoi(e)) : -1;
         v[SD2_OPT_MEGA_TIMING] = ((e = getenv("SD2_MEGA_TIMING")) && (e[0] == '1' || e[0] == '2')) ? e[0] - '0' : 0;
+        v[SD2_OPT_FIXED_BITS] = 17;
     }
 };
 Options& options() {
@@ -118,9 +119,11 @@ hipError_t run_linear(const sd2_matrix_t* m, const uint16_t* x, int k_tok, float
         return hipSuccess;
     }
     if (is_dense_stream(m)) {
-        for (int t0 = 0; t0 < k_tok; t0 += 16) {
+        // 32 tokens per pass where two groups' activations fit the registers, else 16
+        const int per_pass = dense_stream_pair_ok(ma.k_in) ? 32 : 16;
+        for (int t0 = 0; t0 < k_tok; t0 += per_pass) {
             const hipError_t e = launch_dense_stream_linear(ma.w, x + (size_t)t0 * ma.k_in, ma.n_out, ma.k_in,
-                                                            std::min(16, k_tok - t0), out + (size_t)t0 * ma.n_out, s);
+                                                            std::min(per_pass, k_tok - t0), out + (size_t)t0 * ma.n_out, s);
             if (e != hipSuccess) return e;
         }
         return hipSuccess;
@@ -203,6 +206,13 @@ bool plan_mega_path(const sd2_model* md, int k_tok, MegaGeo (&geo)[4], bool* nm2
     return mega_plan(geo, sh.layers, sh.hidden, sh.head_dim, k_tok, max_nnz, nm24);
 }
 
+// Workspace layout of the single-launch kernel for a plan made by plan_mega_path.
+MegaLayout planned_layout(const sd2_model* md, int k_tok, const MegaGeo (&geo)[4]) {
+    const sd2_model_shape_t& sh = md->shape;
+    (void)geo;
+    return mega_layout(sh.layers, sh.hidden, sh.q_out, sh.kv_out, sh.inter, k_tok);
+}
+
 }  // namespace
 
 extern "C" {
@@ -227,7 +237,11 @@ int sd2_version(void) { return 101; }
 
 int sd2_set_option(int32_t which, int32_t value) {
     if (which < 0 || which >= SD2_OPT_COUNT) return SD2_ERR_RANGE;
-    if (which == SD2_OPT_SPIN_LIMIT ? value < -1 : (value < 0 || value > (which == SD2_OPT_MEGA_TIMING ? 2 : 1))) return SD2_ERR_RANGE;
+    if (which == SD2_OPT_FIXED_BITS) {
+        if (value < 8 || value > 22) return SD2_ERR_RANGE;
+    } else if (which == SD2_OPT_SPIN_LIMIT ? value < -1 : (value < 0 || value > (which == SD2_OPT_MEGA_TIMING ? 2 : 1))) {
+        return SD2_ERR_RANGE;
+    }
     options().v[which].store(value, std::memory_order_relaxed);
     return SD2_OK;
 }
@@ -397,8 +411,9 @@ int sd2_drafter_workspace_size(const sd2_model_t* model, int32_t k_tok, size_t* 
     if (!model || !bytes_out) return SD2_ERR_NULL;
     int rc = check_tokens(k_tok);
     if (rc != SD2_OK) return rc;
-    const sd2_model_shape_t& sh = model->shape;
-    const size_t mega = mega_layout(sh.layers, sh.hidden, sh.q_out, sh.kv_out, sh.inter, k_tok).total;
+    // the single-launch kernel's buffers count only where that kernel serves the model and the token count
+    MegaGeo geo[4];
+    const size_t mega = plan_mega_path(model, k_tok, geo) ? planned_layout(model, k_tok, geo).total : 0;
     *bytes_out = std::max(stack_layout(model, k_tok).total, mega);
     return SD2_OK;
 }
@@ -439,12 +454,18 @@ static void fill_mega_args(MegaArgs& ma, const sd2_model* md, int k_tok, const M
     ma.h_out = h_out;
     ma.bar = reinterpret_cast<unsigned*>(base + ML.bar_off);
     ma.err = reinterpret_cast<unsigned*>(base + ML.err_off);
-    ma.yqkv = reinterpret_cast<float*>(base + ML.yqkv_off);
-    ma.ygu = reinterpret_cast<float*>(base + ML.ygu_off);
-    ma.hv = reinterpret_cast<float*>(base + ML.hv_off);
+    ma.yqkv = reinterpret_cast<int*>(base + ML.yqkv_off);
+    ma.ygu = reinterpret_cast<int*>(base + ML.ygu_off);
+    ma.hv = reinterpret_cast<int*>(base + ML.hv_off);
     ma.h_stride = ML.h_stride;
     ma.yqkv_stride = ML.yqkv_stride;
     ma.ygu_stride = ML.ygu_stride;
+    // fixed point of the sums that cross compute units: F fraction bits (SD2_OPT_FIXED_BITS), limits that exclude a wrap
+    const int fbits = option(SD2_OPT_FIXED_BITS);
+    ma.fix_scale = std::ldexp(1.0f, fbits);
+    ma.fix_inv = std::ldexp(1.0f, -fbits);
+    for (int kd = 0; kd < 4; ++kd) ma.fix_limit[kd] = std::ldexp(1.0f, 30) / (float)std::max(ma.geo[kd].n_bblk, 1);
+    ma.h_limit_sq = std::ldexp(1.0f, 2 * (30 - fbits));
     for (size_t i = 0; i < md->mats.size(); ++i) ma.blob[i] = static_cast<const unsigned char*>(md->mats[i].data_dev);
 }
 
@@ -455,14 +476,16 @@ static int forward_impl(const sd2_model_t* md, const uint16_t* h_in, int32_t k_t
     if (rc != SD2_OK) return rc;
     const StackLayout L = stack_layout(md, k_tok);
     const sd2_model_shape_t& sh = md->shape;
-    const MegaLayout ML = mega_layout(sh.layers, sh.hidden, sh.q_out, sh.kv_out, sh.inter, k_tok);
-    if (!aligned16(h_in) || !aligned16(h_out) || !aligned16(ws) || ws_bytes < std::max(L.total, ML.total))
-        return SD2_ERR_BUFFER;
     hipStream_t s = static_cast<hipStream_t>(stream);
     MegaArgs ma;
     memset(&ma, 0, sizeof(ma));
     bool nm24 = false;
     const bool single_launch = plan_mega_path(md, k_tok, ma.geo, &nm24);
+    MegaLayout ML;
+    memset(&ML, 0, sizeof(ML));
+    if (single_launch) ML = planned_layout(md, k_tok, ma.geo);
+    if (!aligned16(h_in) || !aligned16(h_out) || !aligned16(ws) || ws_bytes < std::max(L.total, ML.total))
+        return SD2_ERR_BUFFER;
     // the attention kernel of the launch-per-step path keeps q, k, v and the scores of a head in LDS
     if (!single_launch && sh.layers > 0 && inflight_attention_lds(k_tok, sh.head_dim) > kMaxLdsBytes) return SD2_ERR_UNSUPPORTED;
     if (single_launch) {
@@ -548,12 +571,11 @@ int sd2_drafter_forward_status(const sd2_model_t* md, int32_t k_tok, const void*
     if (hipStreamSynchronize(static_cast<hipStream_t>(stream)) != hipSuccess) return SD2_ERR_HIP;
     MegaGeo geo[4];
     if (!plan_mega_path(md, k_tok, geo)) return SD2_OK;  // the multi-launch path has no waits inside kernels
-    const sd2_model_shape_t& sh = md->shape;
-    const MegaLayout ML = mega_layout(sh.layers, sh.hidden, sh.q_out, sh.kv_out, sh.inter, k_tok);
+    const MegaLayout ML = planned_layout(md, k_tok, geo);
     unsigned flag = 0;
     if (hipMemcpy(&flag, static_cast<const uint8_t*>(ws) + ML.err_off, sizeof(flag), hipMemcpyDeviceToHost) != hipSuccess)
         return SD2_ERR_HIP;
-    return flag ? SD2_ERR_TIMEOUT : SD2_OK;
+    return (flag & 1u) ? SD2_ERR_TIMEOUT : ((flag & 2u) ? SD2_ERR_RANGE : SD2_OK);
 }
 
 int sd2_drafter_trace_size(const sd2_model_t* model, int32_t k_tok, size_t* bytes_out) {
@@ -595,7 +617,7 @@ static DecodeLayout decode_layout(const sd2_model* md, int k_tok) {
     if (k_tok <= kMegaMaxTok && plan_mega_path(md, k_tok, geo)) {
         D.chunks = mega_attention_chunks(sh.n_heads, sh.n_kv, k_tok);
         if (D.chunks > 0) {
-            D.mega_table_off = mega_layout(sh.layers, sh.hidden, sh.q_out, sh.kv_out, sh.inter, k_tok).total;
+            D.mega_table_off = planned_layout(md, k_tok, geo).total;
             D.mega_part_off = D.mega_table_off + table_bytes;
             const size_t part = (size_t)sh.layers * k_tok * sh.n_heads * D.chunks * kMegaAttPartDw * sizeof(float);
             D.total = std::max(D.total, D.mega_part_off + align256(part));
@@ -618,12 +640,13 @@ int sd2_drafter_decode_status(const sd2_model_t* md, int32_t k_tok, const void* 
     if (rc != SD2_OK) return rc;
     if (hipStreamSynchronize(static_cast<hipStream_t>(stream)) != hipSuccess) return SD2_ERR_HIP;
     if (decode_layout(md, k_tok).chunks == 0) return SD2_OK;  // one launch per step: no waits inside kernels
-    const sd2_model_shape_t& sh = md->shape;
-    const MegaLayout ML = mega_layout(sh.layers, sh.hidden, sh.q_out, sh.kv_out, sh.inter, k_tok);
+    MegaGeo geo[4];
+    if (!plan_mega_path(md, k_tok, geo)) return SD2_OK;
+    const MegaLayout ML = planned_layout(md, k_tok, geo);
     unsigned flag = 0;
     if (hipMemcpy(&flag, static_cast<const uint8_t*>(ws) + ML.err_off, sizeof(flag), hipMemcpyDeviceToHost) != hipSuccess)
         return SD2_ERR_HIP;
-    return flag ? SD2_ERR_TIMEOUT : SD2_OK;
+    return (flag & 1u) ? SD2_ERR_TIMEOUT : ((flag & 2u) ? SD2_ERR_RANGE : SD2_OK);
 }
 
 int sd2_sparse_drafter_decode(const sd2_model_t* md, const uint16_t* h_in, int32_t k_tok, int32_t pos0, uint16_t* k_cache,
@@ -648,7 +671,7 @@ int sd2_sparse_drafter_decode(const sd2_model_t* md, const uint16_t* h_in, int32
         memset(&ma, 0, sizeof(ma));
         bool nm24 = false;
         if (!plan_mega_path(md, k_tok, ma.geo, &nm24)) return SD2_ERR_UNSUPPORTED;
-        const MegaLayout ML = mega_layout(sh.layers, sh.hidden, sh.q_out, sh.kv_out, sh.inter, k_tok);
+        const MegaLayout ML = planned_layout(md, k_tok, ma.geo);
         fill_mega_args(ma, md, k_tok, ML, base, h_out);
         float2* table = reinterpret_cast<float2*>(base + DL.mega_table_off);
         ma.k_cache = k_cache;
@@ -715,6 +738,31 @@ int sd2_improvement_factor(double mean_emitted, int32_t k, double cost_ratio, do
     return SD2_OK;
 }
 
+int sd2_greedy_verify_host(const int32_t* draft, const int32_t* target, int32_t batch, int32_t k, int32_t vocab,
+                           int32_t* accepted, int32_t* out_tokens) {
+    if (batch < 0 || k < 0) return SD2_ERR_SHAPE;
+    if (vocab < 1) return SD2_ERR_RANGE;
+    if (batch == 0) return SD2_OK;
+    if (!target || !accepted || !out_tokens || (k > 0 && !draft)) return SD2_ERR_NULL;
+    // ids are checked before anything is written
+    for (int64_t i = 0; i < (int64_t)batch * k; ++i)
+        if (draft[i] < 0 || draft[i] >= vocab) return SD2_ERR_RANGE;
+    for (int64_t i = 0; i < (int64_t)batch * (k + 1); ++i)
+        if (target[i] < 0 || target[i] >= vocab) return SD2_ERR_RANGE;
+    for (int32_t b = 0; b < batch; ++b) {
+        const int32_t* d = draft + (int64_t)b * k;
+        const int32_t* t = target + (int64_t)b * (k + 1);
+        int32_t* o = out_tokens + (int64_t)b * (k + 1);
+        int32_t n = 0;
+        while (n < k && d[n] == t[n]) ++n;  // the longest prefix on which the drafter agrees with the target
+        accepted[b] = n;
+        for (int32_t i = 0; i < n; ++i) o[i] = d[i];
+        o[n] = t[n];                        // then the target's own token
+        for (int32_t i = n + 1; i <= k; ++i) o[i] = -1;
+    }
+    return SD2_OK;
+}
+
 int sd2_check_token_ids_host(const int32_t* ids, size_t n, int32_t vocab) {
     if (n > 0 && !ids) return SD2_ERR_NULL;
     if (vocab < 1) return SD2_ERR_RANGE;
@@ -728,6 +776,13 @@ int sd2_calibration_copy(void* dst, const void* src, size_t bytes, void* stream)
     if (!dst || !src) return SD2_ERR_NULL;
     if (bytes % 16 != 0 || !aligned16(dst) || !aligned16(src)) return SD2_ERR_BUFFER;
     if (launch_calibration_copy(dst, src, bytes, static_cast<hipStream_t>(stream)) != hipSuccess) return SD2_ERR_HIP;
+    return SD2_OK;
+}
+
+int sd2_calibration_read(const void* src, size_t bytes, uint32_t* sink, void* stream) {
+    if (!src || !sink) return SD2_ERR_NULL;
+    if (bytes == 0 || bytes % 16 != 0 || !aligned16(src) || !aligned16(sink)) return SD2_ERR_BUFFER;
+    if (launch_calibration_read(src, bytes, sink, static_cast<hipStream_t>(stream)) != hipSuccess) return SD2_ERR_HIP;
     return SD2_OK;
 }
 
@@ -861,7 +916,7 @@ int sd2_draft_round(const sd2_model_t* model, const uint16_t* emb, int32_t vocab
         if (rc != SD2_OK) return rc;
         MegaGeo geo[4];
         if (plan_mega_path(model, i + 1, geo)) {  // keep a give-up flag beyond the next forward's set-up
-            const MegaLayout ML = mega_layout(sh.layers, sh.hidden, sh.q_out, sh.kv_out, sh.inter, i + 1);
+            const MegaLayout ML = planned_layout(model, i + 1, geo);
             if (launch_fold_flag(reinterpret_cast<const unsigned*>(static_cast<uint8_t*>(fwd_ws) + ML.err_off), round_flag, s) !=
                 hipSuccess)
                 return SD2_ERR_HIP;
@@ -882,7 +937,7 @@ int sd2_draft_round_status(const sd2_model_t* model, int32_t vocab, int32_t k, c
     unsigned flag = 0;
     if (hipMemcpy(&flag, static_cast<const uint8_t*>(ws) + L.flag_off, sizeof(flag), hipMemcpyDeviceToHost) != hipSuccess)
         return SD2_ERR_HIP;
-    return flag ? SD2_ERR_TIMEOUT : SD2_OK;
+    return (flag & 1u) ? SD2_ERR_TIMEOUT : ((flag & 2u) ? SD2_ERR_RANGE : SD2_OK);
 }
 
 // ---- the round against a key/value cache: k single-token decode steps
@@ -933,8 +988,11 @@ int sd2_draft_round_cached(const sd2_model_t* model, const uint16_t* emb, int32_
     unsigned* round_flag = reinterpret_cast<unsigned*>(base + L.flag_off);
     void* lm_ws = base + L.lm_off;
     void* dec_ws = base + L.fwd_off;
-    const bool single_launch = decode_layout(model, 1).chunks > 0;
-    const MegaLayout ML = mega_layout(sh.layers, sh.hidden, sh.q_out, sh.kv_out, sh.inter, 1);
+    MegaGeo geo1[4];
+    const bool single_launch = decode_layout(model, 1).chunks > 0 && plan_mega_path(model, 1, geo1);
+    MegaLayout ML;
+    memset(&ML, 0, sizeof(ML));
+    if (single_launch) ML = planned_layout(model, 1, geo1);
     if (launch_fold_flag(nullptr, round_flag, s) != hipSuccess) return SD2_ERR_HIP;
     for (int32_t i = 0; i < k; ++i) {
         // step i: one token (the start token, then the one chosen at step i - 1) at position pos0 + i
@@ -961,7 +1019,7 @@ int sd2_draft_round_cached_status(const sd2_model_t* model, int32_t vocab, int32
     unsigned flag = 0;
     if (hipMemcpy(&flag, static_cast<const uint8_t*>(ws) + L.flag_off, sizeof(flag), hipMemcpyDeviceToHost) != hipSuccess)
         return SD2_ERR_HIP;
-    return flag ? SD2_ERR_TIMEOUT : SD2_OK;
+    return (flag & 1u) ? SD2_ERR_TIMEOUT : ((flag & 2u) ? SD2_ERR_RANGE : SD2_OK);
 }
 
 }  // extern "C"

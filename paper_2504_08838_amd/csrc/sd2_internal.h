@@ -88,6 +88,8 @@ hipError_t launch_mask_gradient(const MatArgs& m, void* grad, bool bf16, hipStre
 
 // dst[0..bytes) = src[0..bytes), bytes a multiple of 16 (traffic calibration for profiler counters)
 hipError_t launch_calibration_copy(void* dst, const void* src, size_t bytes, hipStream_t s);
+// pure read of src[0..bytes): one checksum word per workgroup goes to sink[0..2048)
+hipError_t launch_calibration_read(const void* src, size_t bytes, uint32_t* sink, hipStream_t s);
 
 }  // namespace sd2
 
@@ -111,15 +113,20 @@ struct MegaGeo {
 struct MegaArgs {
     MegaGeo geo[4];  // qkv, o, gate_up, down
     int layers, hidden, q_out, kv_out, inter, n_heads, n_kv, head_dim, k_tok, spin_limit;
-    // Every activation buffer is written (by atomics that complete at memory) and afterwards read at addresses no
-    // CU has touched before in this launch: one copy per layer, so a barrier needs no cache invalidation.
-    float* hv;            // [2 layers][k_tok][hidden] residual versions 0 .. 2 layers - 1 (stride h_stride floats)
-    float* h_out;         // [k_tok][hidden] version 2 layers = the output
-    float* yqkv;          // [layers][k_tok][q_out + 2 kv_out] accumulators (stride yqkv_stride floats)
-    float* ygu;           // [layers][k_tok][2 inter] (stride ygu_stride floats)
+    // Every activation buffer is written (by agent-scope stores and integer atomics, which go through to memory) and
+    // afterwards read at addresses no CU has touched before in this launch: one copy per layer, so a barrier needs no
+    // cache invalidation.  The buffers hold 32-bit fixed point (17 fraction bits): contributions of several workgroups
+    // are added by integer atomics, which are exact, so the sums do not depend on the order of arrival.
+    int* hv;              // [2 layers + 1][k_tok][hidden] residual versions (stride h_stride values)
+    float* h_out;         // [k_tok][hidden]: the last version as fp32
+    int* yqkv;            // [layers][k_tok][q_out + 2 kv_out] accumulators (stride yqkv_stride values)
+    int* ygu;             // [layers][k_tok][2 inter] (stride ygu_stride values)
     unsigned long long h_stride, yqkv_stride, ygu_stride;
+    float fix_scale, fix_inv;  // 2^F and 2^-F
+    float fix_limit[4];        // per kind: what one workgroup's contribution must stay below, 2^30 / slab blocks
+    float h_limit_sq;          // (2^30 / 2^F)^2: a token's squared residual norm must stay below it
     unsigned* bar;        // grid barrier state (see mega kernel)
-    unsigned* err;        // set to 1 if a bounded wait ran out
+    unsigned* err;        // bit 0: a bounded wait ran out; bit 1: a fixed-point sum left the checked range
     uint16_t* trace_x;    // optional [phase][k_tok][trace_kmax] bf16: the activations each linear consumed
     float* trace_src;     // optional [phase][k_tok][trace_smax] fp32: the values its input glue read
     int trace_kmax, trace_smax;
@@ -140,7 +147,7 @@ constexpr int kMegaMaxChunks = 32;
 
 struct MegaLayout {
     size_t bar_off, err_off, yqkv_off, ygu_off, hv_off, total;  // [0, hv_off) starts as zero
-    size_t h_stride, yqkv_stride, ygu_stride;                    // in floats
+    size_t h_stride, yqkv_stride, ygu_stride;                    // in values of four bytes
 };
 
 MegaLayout mega_layout(int layers, int hidden, int q_out, int kv_out, int inter, int k_tok);
@@ -169,5 +176,7 @@ hipError_t launch_lm_head(const uint16_t* w, const float* h, int vocab, int hidd
 hipError_t launch_dense_stream_linear(const uint16_t* w, const uint16_t* x, int n_out, int k_in, int k_tok, float* y,
                                       hipStream_t s);
 inline bool dense_stream_ok(int k_in) { return k_in % 128 == 0 && k_in <= kLmMaxHidden; }
+// up to 4096 columns the kernel takes 32 tokens per pass
+inline bool dense_stream_pair_ok(int k_in) { return dense_stream_ok(k_in) && k_in <= 4096; }
 
 }  // namespace sd2

@@ -135,9 +135,14 @@ __global__ __launch_bounds__(256) void sparse_linear_kernel(const DirEnt* __rest
 // LDS; every few strips a barrier that waits for LDS only lets the threads add them in a fixed order and write y.  A wavefront with one slab keeps that slab's activation columns in registers for the whole kernel; with
 // more slabs it fetches them per tile (they stay in the caches).  The streams of the next two tiles are in flight in
 // registers while the current one is expanded.
-constexpr int kStripRound = 4;  // strips between two workgroup barriers of the kernel below
+//
+// More than 16 tokens (TG = 2..4 groups of 16): the tile is still expanded once, and each of its eight dense fragments
+// goes through one matrix instruction per token group.  The activation columns of all groups no longer fit a
+// wavefront's registers, so they are fetched per 64-column step (they stay in the caches: every wavefront of the chip
+// reads the same [k_tok][k_in] array), one step ahead of the expansion that consumes them.
+constexpr int kStripRound = 4;  // strip results (of 16 tokens each) between two workgroup barriers of the kernel below
 
-template <int MAXCH, int SPW, int WAVES>
+template <int MAXCH, int SPW, int WAVES, int TG>
 __global__ __launch_bounds__(64 * WAVES) void sparse_strip_kernel(const DirEnt* __restrict__ dir, const uint2* __restrict__ masks,
                                                                  const uint16_t* __restrict__ vals,
                                                                  const uint16_t* __restrict__ x, float* __restrict__ y,
@@ -152,6 +157,7 @@ __global__ __launch_bounds__(64 * WAVES) void sparse_strip_kernel(const DirEnt* 
     const int n = lane & 15, g = lane >> 4;
     uint32_t* buf = strip_smem + wave * (MAXCH * 256);
     float* red = reinterpret_cast<float*>(strip_smem + WAVES * (MAXCH * 256));
+    constexpr int kRound = kStripRound / TG > 0 ? kStripRound / TG : 1;  // strips per round: the slots of a round fit LDS
     const int my_strips = (n_strips - (int)blockIdx.x + (int)gridDim.x - 1) / (int)gridDim.x;
     int n_mine = 0;  // this wavefront's slabs: wave + WAVES * j
 #pragma unroll
@@ -162,21 +168,24 @@ __global__ __launch_bounds__(64 * WAVES) void sparse_strip_kernel(const DirEnt* 
         return (wave + WAVES * j) * n_strips + ((int)blockIdx.x + i * (int)gridDim.x);
     };
 
-    // The strips are handled in rounds of kStripRound: every wavefront leaves its block of a strip in the strip's slot,
-    // one barrier (LDS only: streams stay in flight) ends the round, and the threads share the adding: entry e of a
-    // block is token (e & 63) >> 2, row 4 (e >> 6) + (e & 3) of the strip.  A second barrier frees the slots.
-    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    // The strips are handled in rounds of kRound: every wavefront leaves its blocks of a strip (one per token group) in
+    // the strip's slot, one barrier (LDS only: streams stay in flight) ends the round, and the threads share the adding:
+    // entry e of a block is token 16 tg + ((e & 63) >> 2), row 4 (e >> 6) + (e & 3) of the strip.  A second barrier
+    // frees the slots.
+    f32x4 acc[TG];
+#pragma unroll
+    for (int tg = 0; tg < TG; ++tg) acc[tg] = f32x4{0.f, 0.f, 0.f, 0.f};
     auto round_end = [&](int i_first, int n_in_round) {
         __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
-        for (int idx = tid; idx < n_in_round * 256; idx += 64 * WAVES) {
-            const int r = idx >> 8, e = idx & 255;
-            const float* slot = red + (size_t)r * (WAVES * 256);
+        for (int idx = tid; idx < n_in_round * TG * 256; idx += 64 * WAVES) {
+            const int e = idx & 255, tg = (idx >> 8) % TG, r = (idx >> 8) / TG;
+            const float* slot = red + (size_t)r * (WAVES * TG * 256) + tg * 256;
             float v = 0.f;
 #pragma unroll
-            for (int ww = 0; ww < WAVES; ++ww) v += slot[ww * 256 + e];
-            const int tok = (e & 63) >> 2;
+            for (int ww = 0; ww < WAVES; ++ww) v += slot[ww * (TG * 256) + e];
+            const int tok = 16 * tg + ((e & 63) >> 2);
             const int row = ((int)blockIdx.x + (i_first + r) * (int)gridDim.x) * 16 + 4 * (e >> 6) + (e & 3);
             if (row < n_out && tok < k_tok) y[(size_t)tok * n_out + row] = v;
         }
@@ -185,9 +194,12 @@ __global__ __launch_bounds__(64 * WAVES) void sparse_strip_kernel(const DirEnt* 
         asm volatile("" ::: "memory");
     };
     auto strip_done = [&](int i) {  // lane (n, g) holds rows 4g..4g+3 of token n: entry (16 g + n) * 4 + v of the block
-        *reinterpret_cast<f32x4*>(red + (size_t)(i % kStripRound) * (WAVES * 256) + wave * 256 + lane * 4) = acc;
-        acc = f32x4{0.f, 0.f, 0.f, 0.f};
-        if ((i + 1) % kStripRound == 0 || i + 1 == my_strips) round_end(i - i % kStripRound, i % kStripRound + 1);
+#pragma unroll
+        for (int tg = 0; tg < TG; ++tg) {
+            *reinterpret_cast<f32x4*>(red + (size_t)(i % kRound) * (WAVES * TG * 256) + (wave * TG + tg) * 256 + lane * 4) = acc[tg];
+            acc[tg] = f32x4{0.f, 0.f, 0.f, 0.f};
+        }
+        if ((i + 1) % kRound == 0 || i + 1 == my_strips) round_end(i - i % kRound, i % kRound + 1);
     };
     if (n_mine == 0) {  // a wavefront without slabs contributes zeros and joins every barrier
 #pragma unroll 1
@@ -195,13 +207,19 @@ __global__ __launch_bounds__(64 * WAVES) void sparse_strip_kernel(const DirEnt* 
         return;
     }
 
-    Frag b[4][2];
+    // Operand B in registers: always for one token group; for two groups when the wavefront owns a single slab (its
+    // activation columns then never change).  Otherwise B is fetched per 64-column step (below).
+    constexpr bool kBRegs = TG == 1 || (TG == 2 && SPW == 1);
+    constexpr int kBG = kBRegs ? TG : 1;
+    Frag b[kBG][4][2];
     auto load_b = [&](int slab) {
         const int col0 = slab * 256 + 16 * g;
 #pragma unroll
-        for (int q = 0; q < 4; ++q) load_row16(x, n, k_tok, col0 + 64 * q, k_in, b[q][0], b[q][1]);
+        for (int tg = 0; tg < kBG; ++tg)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) load_row16(x, n + 16 * tg, k_tok, col0 + 64 * q, k_in, b[tg][q][0], b[tg][q][1]);
     };
-    if (SPW == 1) load_b(wave);
+    if (kBRegs && SPW == 1) load_b(wave);
 
     // two tiles' streams are in flight in registers while a third is expanded
     u32x4 st[2][MAXCH];
@@ -222,13 +240,36 @@ __global__ __launch_bounds__(64 * WAVES) void sparse_strip_kernel(const DirEnt* 
         for (int c = 0; c < MAXCH; ++c) reinterpret_cast<u32x4*>(buf)[c * 64 + lane] = st[slot][c];
         const uint2 mk = mkn[slot];
         const DirEnt de = den[slot];
-        if (SPW > 1) load_b(wave + WAVES * j);
-        request(slot, f + 2);
-        expand_tile<SD2_LINEAR_STEPS>(reinterpret_cast<const uint8_t*>(buf), lut, de.base, mk,
-                                      [&](int q, const Frag& f0, const Frag& f1) {
-                                          acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f0.v, b[q][0].v, acc, 0, 0, 0);
-                                          acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f1.v, b[q][1].v, acc, 0, 0, 0);
-                                      });
+        if (kBRegs) {
+            if (SPW > 1) load_b(wave + WAVES * j);
+            request(slot, f + 2);
+            expand_tile<SD2_LINEAR_STEPS>(reinterpret_cast<const uint8_t*>(buf), lut, de.base, mk,
+                                          [&](int q, const Frag& f0, const Frag& f1) {
+#pragma unroll
+                                              for (int tg = 0; tg < kBG; ++tg) {
+                                                  acc[tg] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f0.v, b[tg][q][0].v, acc[tg], 0, 0, 0);
+                                                  acc[tg] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f1.v, b[tg][q][1].v, acc[tg], 0, 0, 0);
+                                              }
+                                          });
+        } else {
+            // operand B of step q for every token group, requested one step ahead of its use
+            const int col0 = (wave + WAVES * j) * 256 + 16 * g;
+            Frag bb[2][TG][2];
+            auto load_bq = [&](int q) {
+#pragma unroll
+                for (int tg = 0; tg < TG; ++tg) load_row16(x, n + 16 * tg, k_tok, col0 + 64 * q, k_in, bb[q & 1][tg][0], bb[q & 1][tg][1]);
+            };
+            load_bq(0);
+            request(slot, f + 2);
+            expand_tile<1>(reinterpret_cast<const uint8_t*>(buf), lut, de.base, mk, [&](int q, const Frag& f0, const Frag& f1) {
+                if (q < 3) load_bq(q + 1);
+#pragma unroll
+                for (int tg = 0; tg < TG; ++tg) {
+                    acc[tg] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f0.v, bb[q & 1][tg][0].v, acc[tg], 0, 0, 0);
+                    acc[tg] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f1.v, bb[q & 1][tg][1].v, acc[tg], 0, 0, 0);
+                }
+            });
+        }
         if (++j == n_mine) {
             j = 0;
             strip_done(i);
@@ -341,12 +382,19 @@ static hipError_t launch_sparse_t(const MatArgs& m, const LinArgs& a, hipStream_
     return hipGetLastError();
 }
 
-// Slabs per wavefront and wavefronts per workgroup of the kernel that writes final results: one slab per wavefront up
-// to 16 slabs, two beyond (then with 16 wavefronts); more than 32 slabs, more than 16 tokens or tiles too dense for the
-// 5 KiB buffers go to the kernel with partial sums.
-static bool strip_shape(int n_slabs, int& spw, int& waves) {
-    if (n_slabs < 1 || n_slabs > 32) return false;
-    spw = n_slabs <= 16 ? 1 : 2;
+// Slabs per wavefront and wavefronts per workgroup of the kernel that writes final results.  Up to 16 tokens: one
+// slab per wavefront up to 16 slabs, two beyond (then with 16 wavefronts).  More tokens need more registers per
+// wavefront, so at most 12 wavefronts share a compute unit and take up to four slabs each.  More than 32 (48) slabs
+// or tiles too dense for the 5 KiB buffers go to the kernel with partial sums.
+static bool strip_shape(int n_slabs, int tg, int& spw, int& waves) {
+    if (n_slabs < 1 || tg < 1 || tg > 4) return false;
+    if (tg == 1) {
+        if (n_slabs > 32) return false;
+        spw = n_slabs <= 16 ? 1 : 2;
+    } else {
+        if (n_slabs > 48) return false;
+        spw = (n_slabs + 11) / 12;
+    }
     const int need = (n_slabs + spw - 1) / spw;
     waves = std::max(4, (need + 3) / 4 * 4);
     return true;
@@ -354,17 +402,19 @@ static bool strip_shape(int n_slabs, int& spw, int& waves) {
 
 bool sparse_strip_supported(const MatArgs& m, int k_tok) {
     int spw, waves;
-    return k_tok >= 1 && k_tok <= 16 && (m.max_tile_nnz * 2 + 8 + 1023) / 1024 <= 5 && strip_shape(m.n_slabs, spw, waves);
+    return k_tok >= 1 && k_tok <= 64 && (m.max_tile_nnz * 2 + 8 + 1023) / 1024 <= 5 &&
+           strip_shape(m.n_slabs, (k_tok + 15) / 16, spw, waves);
 }
 
-template <int SPW, int WAVES>
+template <int SPW, int WAVES, int TG>
 static hipError_t launch_strip_t(const MatArgs& m, const LinArgs& a, hipStream_t s) {
     constexpr int kCh = 5;
-    const size_t lds = (size_t)WAVES * kCh * 1024 + (size_t)kStripRound * WAVES * 256 * sizeof(float);
+    constexpr int kRound = kStripRound / TG > 0 ? kStripRound / TG : 1;
+    const size_t lds = (size_t)WAVES * kCh * 1024 + (size_t)kRound * TG * WAVES * 256 * sizeof(float);
     static std::atomic<int> cached{0};  // workgroups resident on the chip; threads that race here compute the same value
     int resident = cached.load(std::memory_order_acquire);
     if (resident == 0) {
-        const void* fn = reinterpret_cast<const void*>(sparse_strip_kernel<kCh, SPW, WAVES>);
+        const void* fn = reinterpret_cast<const void*>(sparse_strip_kernel<kCh, SPW, WAVES, TG>);
         int per_cu = 0;
         if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) return hipErrorInvalidValue;
         if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, 64 * WAVES, lds) != hipSuccess || per_cu < 1) per_cu = 1;
@@ -372,23 +422,44 @@ static hipError_t launch_strip_t(const MatArgs& m, const LinArgs& a, hipStream_t
         cached.store(resident, std::memory_order_release);
     }
     const int grid = std::min(m.n_strips, resident);
-    hipLaunchKernelGGL((sparse_strip_kernel<kCh, SPW, WAVES>), dim3((unsigned)grid), dim3(64 * WAVES), lds, s,
+    hipLaunchKernelGGL((sparse_strip_kernel<kCh, SPW, WAVES, TG>), dim3((unsigned)grid), dim3(64 * WAVES), lds, s,
                        static_cast<const DirEnt*>(m.dir), m.masks, m.vals, a.x, a.out, m.n_out, m.k_in, a.k_tok, m.n_strips, m.n_slabs);
     return hipGetLastError();
 }
 
-// y[t][n] final (every entry written), k_tok <= 16; sparse_strip_supported(m, k_tok) must hold
+// y[t][n] final (every entry written), k_tok <= 64; sparse_strip_supported(m, k_tok) must hold
 hipError_t launch_sparse_strip_linear(const MatArgs& m, const LinArgs& a, hipStream_t s) {
     int spw, waves;
-    if (!sparse_strip_supported(m, a.k_tok) || !strip_shape(m.n_slabs, spw, waves)) return hipErrorInvalidValue;
-#define SD2_STRIP_CASE(S, W) \
-    if (spw == S && waves == W) return launch_strip_t<S, W>(m, a, s)
-    SD2_STRIP_CASE(1, 4);
-    SD2_STRIP_CASE(1, 8);
-    SD2_STRIP_CASE(1, 12);
-    SD2_STRIP_CASE(1, 16);
-    SD2_STRIP_CASE(2, 12);
-    SD2_STRIP_CASE(2, 16);
+    const int tg = (a.k_tok + 15) / 16;
+    if (!sparse_strip_supported(m, a.k_tok) || !strip_shape(m.n_slabs, tg, spw, waves)) return hipErrorInvalidValue;
+    if (tg > 2 && spw == 1) {
+        // One slab per wavefront: two token groups' activation columns fit its registers for the whole kernel, more do
+        // not, and fetching them per step costs more than streaming the matrix again: 32 tokens per pass.
+        const LinArgs lo{a.x, 32, a.out};
+        const LinArgs hi{a.x + (size_t)32 * m.k_in, a.k_tok - 32, a.out + (size_t)32 * m.n_out};
+        const hipError_t e = launch_sparse_strip_linear(m, lo, s);
+        return e != hipSuccess ? e : launch_sparse_strip_linear(m, hi, s);
+    }
+#define SD2_STRIP_CASE(S, W, T) \
+    if (spw == S && waves == W && tg == T) return launch_strip_t<S, W, T>(m, a, s)
+    SD2_STRIP_CASE(1, 4, 1);
+    SD2_STRIP_CASE(1, 8, 1);
+    SD2_STRIP_CASE(1, 12, 1);
+    SD2_STRIP_CASE(1, 16, 1);
+    SD2_STRIP_CASE(2, 12, 1);
+    SD2_STRIP_CASE(2, 16, 1);
+    SD2_STRIP_CASE(1, 4, 2);
+    SD2_STRIP_CASE(1, 8, 2);
+    SD2_STRIP_CASE(1, 12, 2);
+#define SD2_STRIP_WIDE(T) \
+    SD2_STRIP_CASE(2, 8, T); \
+    SD2_STRIP_CASE(2, 12, T); \
+    SD2_STRIP_CASE(3, 12, T); \
+    SD2_STRIP_CASE(4, 12, T)
+    SD2_STRIP_WIDE(2);
+    SD2_STRIP_WIDE(3);
+    SD2_STRIP_WIDE(4);
+#undef SD2_STRIP_WIDE
 #undef SD2_STRIP_CASE
     return hipErrorInvalidValue;
 }
@@ -1099,6 +1170,36 @@ hipError_t launch_calibration_copy(void* dst, const void* src, size_t bytes, hip
     const unsigned blocks = (unsigned)std::min<size_t>((n16 + 255) / 256, 256 * 16);
     hipLaunchKernelGGL(calibration_copy_kernel, dim3(blocks), dim3(256), 0, s, static_cast<u32x4*>(dst),
                        static_cast<const u32x4*>(src), n16);
+    return hipGetLastError();
+}
+
+// Pure read stream: every lane reads 16 bytes per step, eight steps in flight, and folds them into a checksum; one
+// word per workgroup leaves the chip.  Its rate is what a kernel that only reads can reach on this part.
+constexpr int kReadBlocks = 256 * 8;
+
+__global__ __launch_bounds__(256) void calibration_read_kernel(const u32x4* __restrict__ src, size_t n16, uint32_t* __restrict__ sink) {
+    __shared__ uint32_t part[4];
+    const size_t stride = (size_t)gridDim.x * 256;
+    u32x4 acc = {0u, 0u, 0u, 0u};
+    size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    for (; i + 7 * stride < n16; i += 8 * stride) {
+        u32x4 v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = src[i + u * stride];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) acc ^= v[u];
+    }
+    for (; i < n16; i += stride) acc ^= src[i];
+    uint32_t x = acc[0] ^ acc[1] ^ acc[2] ^ acc[3];
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) x ^= (uint32_t)__shfl_xor((int)x, o);
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = x;
+    __syncthreads();
+    if (threadIdx.x == 0) sink[blockIdx.x] = part[0] ^ part[1] ^ part[2] ^ part[3];
+}
+
+hipError_t launch_calibration_read(const void* src, size_t bytes, uint32_t* sink, hipStream_t s) {
+    hipLaunchKernelGGL(calibration_read_kernel, dim3(kReadBlocks), dim3(256), 0, s, static_cast<const u32x4*>(src), bytes / 16, sink);
     return hipGetLastError();
 }
 

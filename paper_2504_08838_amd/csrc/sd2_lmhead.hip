@@ -46,8 +46,10 @@ __device__ __forceinline__ void lm_better(float& a, int32_t& ia, float b, int32_
 
 // HEAD = true: the LM head (fp32 residual in `h`, final norm, greedy choice, logits optional).
 // HEAD = false: the same stream as a plain dense linear, y = x W^T with bf16 activations `x` and every result
-// written to `logits` ([k_tok][vocab] with vocab = n_out): the dense baseline of the sparse linears.
-template <int CPW, bool HEAD>
+// written to `logits` ([k_tok][vocab] with vocab = n_out): the dense baseline of the sparse linears.  There TG = 2
+// takes up to 32 tokens in one pass (two sets of B operands in registers, two accumulators per strip; the partial
+// strips then share one LDS buffer and need a second barrier per strip).
+template <int CPW, bool HEAD, int TG = 1>
 __global__ __launch_bounds__(64 * kLmWaves) void lm_head_kernel(const uint16_t* __restrict__ w,
                                                                 const float* __restrict__ h,
                                                                 const uint16_t* __restrict__ x, int vocab, int hidden,
@@ -104,8 +106,9 @@ __global__ __launch_bounds__(64 * kLmWaves) void lm_head_kernel(const uint16_t* 
 #pragma unroll
     for (int c = 0; c < kLmRing; ++c) issue_chunk(c);
 
+    static_assert(TG == 1 || !HEAD, "the head takes one token group per pass");
     const int tok = min(n, k_tok - 1);  // lanes past the last token repeat it; their results are never used
-    Frag b[CPW][4];
+    Frag b[TG][CPW][4];
     if (HEAD) {
         // ---- final norm of the residual stream, straight into operand B: a = bf16(h / sqrt(mean(h^2) + eps))
         for (int t = 0; t < k_tok; ++t) {
@@ -132,24 +135,28 @@ __global__ __launch_bounds__(64 * kLmWaves) void lm_head_kernel(const uint16_t* 
                     const float* src = h + (size_t)tok * hidden + colchunk * kLmChunkCols + (q * 4 + g) * 8;
                     const f32x4 lo = *reinterpret_cast<const f32x4*>(src);
                     const f32x4 hi = *reinterpret_cast<const f32x4*>(src + 4);
-                    b[cc][q].u[0] = pack_bf16(lo[0] * inv, lo[1] * inv);
-                    b[cc][q].u[1] = pack_bf16(lo[2] * inv, lo[3] * inv);
-                    b[cc][q].u[2] = pack_bf16(hi[0] * inv, hi[1] * inv);
-                    b[cc][q].u[3] = pack_bf16(hi[2] * inv, hi[3] * inv);
+                    b[0][cc][q].u[0] = pack_bf16(lo[0] * inv, lo[1] * inv);
+                    b[0][cc][q].u[1] = pack_bf16(lo[2] * inv, lo[3] * inv);
+                    b[0][cc][q].u[2] = pack_bf16(hi[0] * inv, hi[1] * inv);
+                    b[0][cc][q].u[3] = pack_bf16(hi[2] * inv, hi[3] * inv);
                 } else {
-                    b[cc][q].q = u32x4{0u, 0u, 0u, 0u};  // column chunk past the matrix: contributes nothing
+                    b[0][cc][q].q = u32x4{0u, 0u, 0u, 0u};  // column chunk past the matrix: contributes nothing
                 }
             }
         }
     } else {
 #pragma unroll
-        for (int cc = 0; cc < CPW; ++cc) {
-            const int colchunk = wave + kLmWaves * cc;
+        for (int tg = 0; tg < TG; ++tg) {
+            const int tk = min(n + 16 * tg, k_tok - 1);
 #pragma unroll
-            for (int q = 0; q < 4; ++q)
-                b[cc][q].q = colchunk < n_colchunks
-                                 ? *reinterpret_cast<const u32x4*>(x + (size_t)tok * hidden + colchunk * kLmChunkCols + (q * 4 + g) * 8)
-                                 : u32x4{0u, 0u, 0u, 0u};
+            for (int cc = 0; cc < CPW; ++cc) {
+                const int colchunk = wave + kLmWaves * cc;
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    b[tg][cc][q].q = colchunk < n_colchunks
+                                         ? *reinterpret_cast<const u32x4*>(x + (size_t)tk * hidden + colchunk * kLmChunkCols + (q * 4 + g) * 8)
+                                         : u32x4{0u, 0u, 0u, 0u};
+            }
         }
     }
 
@@ -162,7 +169,9 @@ __global__ __launch_bounds__(64 * kLmWaves) void lm_head_kernel(const uint16_t* 
     int ci = 0;
 #pragma unroll 1
     for (int si = 0; si < my_strips; ++si) {
-        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+        f32x4 acc[TG];
+#pragma unroll
+        for (int tg = 0; tg < TG; ++tg) acc[tg] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int cc = 0; cc < CPW; ++cc) {
             wait_chunk(ci);
@@ -175,26 +184,40 @@ __global__ __launch_bounds__(64 * kLmWaves) void lm_head_kernel(const uint16_t* 
             asm volatile("" ::: "memory");
             issue_chunk(ci + kLmRing);
 #pragma unroll
-            for (int q = 0; q < 4; ++q) acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[q].v, b[cc][q].v, acc, 0, 0, 0);
+            for (int q = 0; q < 4; ++q)
+#pragma unroll
+                for (int tg = 0; tg < TG; ++tg) acc[tg] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[q].v, b[tg][cc][q].v, acc[tg], 0, 0, 0);
             ++ci;
         }
-        float* mine = red + (si & 1) * kLmRedDw;
-        *reinterpret_cast<f32x4*>(mine + wave * 256 + lane * 4) = acc;
+        // one token group: the partial strips alternate between two buffers (one barrier per strip); two groups fill
+        // both buffers at once and a second barrier frees them
+        float* mine = red + (TG == 1 ? (si & 1) * kLmRedDw : 0);
+#pragma unroll
+        for (int tg = 0; tg < TG; ++tg) *reinterpret_cast<f32x4*>(mine + tg * kLmRedDw + wave * 256 + lane * 4) = acc[tg];
         __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): the partial strip is in LDS; loads stay in flight
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
         if (wave < 4) {
-            float v = 0.f;
 #pragma unroll
-            for (int ww = 0; ww < kLmWaves; ++ww) v += mine[ww * 256 + wave * 64 + lane];
-            const int row = ((int)blockIdx.x + si * (int)gridDim.x) * 16 + red_row;
-            if (row < vocab && red_tok < k_tok) {
-                if (HEAD && v > best) {  // rows come in increasing order: '>' keeps the lowest index among equals
-                    best = v;
-                    best_i = row;
+            for (int tg = 0; tg < TG; ++tg) {
+                float v = 0.f;
+#pragma unroll
+                for (int ww = 0; ww < kLmWaves; ++ww) v += mine[tg * kLmRedDw + ww * 256 + wave * 64 + lane];
+                const int row = ((int)blockIdx.x + si * (int)gridDim.x) * 16 + red_row;
+                const int rt = red_tok + 16 * tg;
+                if (row < vocab && rt < k_tok) {
+                    if (HEAD && v > best) {  // rows come in increasing order: '>' keeps the lowest index among equals
+                        best = v;
+                        best_i = row;
+                    }
+                    if (!HEAD || logits) logits[(size_t)rt * vocab + row] = v;
                 }
-                if (!HEAD || logits) logits[(size_t)red_tok * vocab + row] = v;
             }
+        }
+        if (TG > 1) {
+            __builtin_amdgcn_s_waitcnt(0xC07F);
+            __builtin_amdgcn_s_barrier();
+            asm volatile("" ::: "memory");
         }
     }
     if (!HEAD) return;
@@ -246,18 +269,18 @@ static int lm_cu_count() {
     return 256;
 }
 
-template <int CPW, bool HEAD>
+template <int CPW, bool HEAD, int TG = 1>
 static hipError_t launch_lm_t(const uint16_t* w, const float* h, const uint16_t* x, int vocab, int hidden, int k_tok,
                               int n_strips, int n_wg, LmCand* part, float* logits, hipStream_t s) {
     static std::atomic<bool> attr_set{false};  // more than the default 64 KiB of dynamic LDS needs opting in, once per kernel
     const size_t lds = (size_t)kLmLdsDw * 4;
     if (!attr_set.load(std::memory_order_acquire)) {
-        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&lm_head_kernel<CPW, HEAD>),
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&lm_head_kernel<CPW, HEAD, TG>),
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
         attr_set.store(true, std::memory_order_release);
     }
-    hipLaunchKernelGGL((lm_head_kernel<CPW, HEAD>), dim3((unsigned)n_wg), dim3(64 * kLmWaves), lds, s, w, h, x, vocab, hidden,
+    hipLaunchKernelGGL((lm_head_kernel<CPW, HEAD, TG>), dim3((unsigned)n_wg), dim3(64 * kLmWaves), lds, s, w, h, x, vocab, hidden,
                        k_tok, n_strips, part, logits);
     return hipGetLastError();
 }
@@ -290,12 +313,23 @@ hipError_t launch_lm_head(const uint16_t* w, const float* h, int vocab, int hidd
     return hipGetLastError();
 }
 
-// y[t][n] = sum_c W[n][c] x[t][c] for a dense row-major bf16 matrix and tokens [0, k_tok), k_tok <= 16; every entry
-// of y written (final values: the contraction is added up inside the workgroup).  k_in a multiple of 128, <= 9216.
+// y[t][n] = sum_c W[n][c] x[t][c] for a dense row-major bf16 matrix and tokens [0, k_tok); every entry of y written
+// (final values: the contraction is added up inside the workgroup).  k_in a multiple of 128, <= 9216.  k_tok <= 16, or
+// <= 32 where dense_stream_pair_ok(k_in): two token groups' activations then fit the registers next to each other.
 hipError_t launch_dense_stream_linear(const uint16_t* w, const uint16_t* x, int n_out, int k_in, int k_tok, float* y,
                                       hipStream_t s) {
     const int n_strips = (n_out + 15) / 16;
     const int n_wg = std::min(n_strips, lm_cu_count());
+    if (k_tok > 16) {
+        if (k_tok > 32 || !dense_stream_pair_ok(k_in)) return hipErrorInvalidValue;
+        switch ((k_in / kLmChunkCols + kLmWaves - 1) / kLmWaves) {
+            case 1: return launch_lm_t<1, false, 2>(w, nullptr, x, n_out, k_in, k_tok, n_strips, n_wg, nullptr, y, s);
+            case 2: return launch_lm_t<2, false, 2>(w, nullptr, x, n_out, k_in, k_tok, n_strips, n_wg, nullptr, y, s);
+            case 3: return launch_lm_t<3, false, 2>(w, nullptr, x, n_out, k_in, k_tok, n_strips, n_wg, nullptr, y, s);
+            case 4: return launch_lm_t<4, false, 2>(w, nullptr, x, n_out, k_in, k_tok, n_strips, n_wg, nullptr, y, s);
+            default: return hipErrorInvalidValue;
+        }
+    }
     return launch_lm_cpw<false>(w, nullptr, x, n_out, k_in, k_tok, n_strips, n_wg, nullptr, y, s);
 }
 

@@ -5,9 +5,10 @@
 // tiles, and each wavefront keeps the compacted stream of its next tile in flight -- also across
 // the end of a linear, because weights never depend on activations -- so HBM keeps streaming
 // while the grid synchronises.  Tile results are summed per strip in LDS and leave the CU once
-// per linear as float atomic adds (split-K only across the few slab blocks).  Between dependent
-// linears the grid meets at a barrier built from agent-scope atomics.  Everything a CU hands to
-// other CUs is written with agent-scope atomic stores / float adds, which go through to memory,
+// per linear as integer atomic adds of fixed-point numbers (split-K only across the few slab blocks):
+// integer sums are exact, so their order does not matter and the forward is bit-reproducible.  Between
+// dependent linears the grid meets at a barrier built from agent-scope atomics.  Everything a CU hands to
+// other CUs is written with agent-scope atomic stores / integer adds, which go through to memory,
 // so no cache write-back is needed before arriving; nothing is invalidated after the barrier either:
 // every activation buffer exists once per layer, so what the prologue reads (with ordinary cached loads)
 // lies at addresses no compute unit has touched before in this launch.  After each barrier a workgroup
@@ -51,10 +52,24 @@ static_assert(kMaxBAtt * 256 <= kAttHeads * 128, "attention block fits the head 
 
 #define SD2_AGENT __HIP_MEMORY_SCOPE_AGENT
 
-// Activations cross compute units through memory: written by agent-scope stores and float atomics, read (after a
+// Activations cross compute units through memory: written by agent-scope stores and integer atomics, read (after a
 // grid barrier, at addresses no compute unit has read before in this launch) with ordinary loads.
 __device__ __forceinline__ void astore(float* p, float v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, SD2_AGENT); }
-__device__ __forceinline__ void aadd(float* p, float v) { (void)__hip_atomic_fetch_add(p, v, __ATOMIC_RELAXED, SD2_AGENT); }
+__device__ __forceinline__ void astore_i(int* p, int v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, SD2_AGENT); }
+__device__ __forceinline__ void aadd_i(int* p, int v) { (void)__hip_atomic_fetch_add(p, v, __ATOMIC_RELAXED, SD2_AGENT); }
+
+// What crosses compute units as a sum of several workgroups' contributions (the results of a linear whose contraction
+// is split over slab blocks, and the residual stream they are added to) is kept in 32-bit fixed point: a workgroup
+// adds up its tiles in fp32, rounds its contribution once to a multiple of 2^-F and adds it with an integer atomic.
+// Integer adds are exact, so the sum does not depend on the order in which the workgroups arrive -- the forward is
+// bit-reproducible -- and a consumer reads four bytes per value, as it would for fp32.  F = 17 by default: resolution
+// 7.6e-6 (the fp32 spacing at magnitude 64; activations are rounded to bf16, spacing 2^-8 relative, before their next
+// use), range +-16384.  No sum can wrap unnoticed: a contribution must stay below 2^30 / (slab blocks of its linear)
+// in fixed point, and a token's residual below 2^30 in norm (checked where the norm is computed anyway); whatever
+// breaks that raises bit 1 of the error word, which the status calls report as SD2_ERR_RANGE.
+__device__ __forceinline__ float from_fixed(int w, float inv) { return (float)w * inv; }
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+typedef int i32x2 __attribute__((ext_vector_type(2)));
 
 // sum over the 64 lanes (cross-lane adds on the DPP path, no LDS traffic); result in every lane
 __device__ __forceinline__ float wave_sum(float v) {
@@ -93,6 +108,7 @@ typedef const __attribute__((address_space(4))) MegaArgs* KArgs;
 // the matrix, so every position of the s_eff x b_eff block is a real tile) and the blob offsets common to all
 // layers of the kind.
 constexpr int kMaxTilesPerWave = 8;  // per phase: ceil(kMaxS * kMaxB / waves)
+constexpr int kFlushIters = (kMaxS * kMegaMaxTok * 16 + kMegaThreads - 1) / kMegaThreads;  // results per thread leaving the CU
 
 
 __device__ __forceinline__ int uni(uint32_t v) { return __builtin_amdgcn_readfirstlane((int)v); }
@@ -285,12 +301,18 @@ __device__ __forceinline__ void bf16x8_unpack(const u32x4 w, float (&f)[8]) {
     }
 }
 
-// dimensions 8 piece .. 8 piece + 7 of a head (fp32, 128 dimensions at `head`) after the rotation of token u
-__device__ __forceinline__ void rotated_piece(const float* __restrict__ head, const float2* __restrict__ rope, int u, int piece,
+// four consecutive results of the q|k|v linear (fixed point) as fp32
+__device__ __forceinline__ f32x4 load_fixed4(const int* __restrict__ p, float inv) {
+    const i32x4 w = *reinterpret_cast<const i32x4*>(p);
+    return f32x4{from_fixed(w[0], inv), from_fixed(w[1], inv), from_fixed(w[2], inv), from_fixed(w[3], inv)};
+}
+
+// dimensions 8 piece .. 8 piece + 7 of a head (128 fixed-point values at `head`) after the rotation of token u
+__device__ __forceinline__ void rotated_piece(const int* __restrict__ head, float inv, const float2* __restrict__ rope, int u, int piece,
                                               float (&out)[8]) {
     const int d0 = 8 * piece, i0 = d0 & 63;
-    const f32x4 a0 = *reinterpret_cast<const f32x4*>(head + d0), a1 = *reinterpret_cast<const f32x4*>(head + d0 + 4);
-    const f32x4 b0 = *reinterpret_cast<const f32x4*>(head + (d0 ^ 64)), b1 = *reinterpret_cast<const f32x4*>(head + (d0 ^ 64) + 4);
+    const f32x4 a0 = load_fixed4(head + d0, inv), a1 = load_fixed4(head + d0 + 4, inv);
+    const f32x4 b0 = load_fixed4(head + (d0 ^ 64), inv), b1 = load_fixed4(head + (d0 ^ 64) + 4, inv);
     const f32x4* cs = reinterpret_cast<const f32x4*>(rope + (size_t)u * 64 + i0);  // (cos, sin) pairs, two per load
     const float sgn = d0 < 64 ? -1.f : 1.f;  // lower half: x cos - y sin; upper half: x cos + y sin
 #pragma unroll
@@ -355,7 +377,7 @@ __device__ __forceinline__ void attention_item(KArgs ka, int layer, const AttIte
     const int c = it.c, t = it.t, g = it.g, j_lo = it.j_lo, j_hi = it.j_hi;
     const int pos0 = ka->pos0, max_pos = ka->max_pos, q_out = ka->q_out, kv_out = ka->kv_out;
     const int nqkv = q_out + 2 * kv_out;
-    const float* yq = ka->yqkv + (size_t)layer * ka->yqkv_stride;
+    const int* yq = ka->yqkv + (size_t)layer * ka->yqkv_stride;
     const float2* rope = ka->rope;
     float* so = scratch + kAttSo;
     float* smax = scratch + kAttMax;
@@ -373,15 +395,16 @@ __device__ __forceinline__ void attention_item(KArgs ka, int layer, const AttIte
     if (slot < REP + n_own) {
         const bool is_q = slot < REP;
         const int tok = is_q ? t : slot - REP;
-        const float* head = yq + (size_t)tok * nqkv + (is_q ? (size_t)(g * rep + min(slot, rep - 1)) * D : q_out + (size_t)g * D);
+        const int* head = yq + (size_t)tok * nqkv + (is_q ? (size_t)(g * rep + min(slot, rep - 1)) * D : q_out + (size_t)g * D);
+        const float fix_inv = ka->fix_inv;
         float f[8];
-        rotated_piece(head, rope, tok, piece, f);
+        rotated_piece(head, fix_inv, rope, tok, piece, f);
         if (is_q) {
             sq[slot * 32 + 2 * piece] = f32x4{f[0] * scale, f[1] * scale, f[2] * scale, f[3] * scale};
             sq[slot * 32 + 2 * piece + 1] = f32x4{f[4] * scale, f[5] * scale, f[6] * scale, f[7] * scale};
         } else {
-            const float* src = head + kv_out + 8 * piece;  // the value head sits kv_out floats after the key head
-            const f32x4 v0 = *reinterpret_cast<const f32x4*>(src), v1 = *reinterpret_cast<const f32x4*>(src + 4);
+            const int* src = head + kv_out + 8 * piece;  // the value head sits kv_out values after the key head
+            const f32x4 v0 = load_fixed4(src, fix_inv), v1 = load_fixed4(src + 4, fix_inv);
             const u32x4 pk = pack_bf16x8(f);
             const u32x4 pv = u32x4{pack_bf16(v0[0], v0[1]), pack_bf16(v0[2], v0[3]), pack_bf16(v1[0], v1[1]), pack_bf16(v1[2], v1[3])};
             own_k[tok * 16 + piece] = pk;
@@ -561,7 +584,6 @@ __global__ __launch_bounds__(kMegaThreads) void mega_forward_kernel(const MegaAr
     plan_phase<NM24>(nt, ka, plans, 1, n_phases, wave, lane);
     unsigned gen = 0;
     int spin_limit = a.spin_limit;
-    const bool copies_residual = (tid % ncu) == cu;  // this thread's columns of the residual are copied by this workgroup
 
     for (int p = 0; p < n_phases; ++p) {
         const int layer = p >> 2, kind = p & 3;
@@ -642,6 +664,24 @@ __global__ __launch_bounds__(kMegaThreads) void mega_forward_kernel(const MegaAr
             tpre.v[0] = tpre.v[1] = tpre.v[2] = tpre.v[3] = u32x4{0, 0, 0, 0};
             tpre.idx = make_uint2(0u, 0u);
         }
+        // The next version of the residual stream starts from zero and receives every slab block's contribution by
+        // integer adds; the workgroups of the first slab block add the current version along with theirs.  Their
+        // entries of it are requested here, between arrival and release (final since the barrier before last).
+        const int slab_block = cu / ka->geo[kind].n_sblk;
+        const uint32_t* kpl_s = plans + kind * kPlanDw;
+        const int strip_lo_s = uni(kpl_s[2]);
+        const bool adds_residual = (kind & 1) && uni(kpl_s[6]) != 0 && slab_block == 0;
+        const int* h_seed_src = a.hv + (size_t)(2 * layer + (kind >= 2 ? 1 : 0)) * a.h_stride;
+        int hseed[kFlushIters];
+#pragma unroll
+        for (int j = 0; j < kFlushIters; ++j) {
+            hseed[j] = 0;
+            const int idx = tid + j * kMegaThreads;
+            const int r = idx & 15, t = (idx >> 4) & (kMegaMaxTok - 1), sl = idx >> 7;
+            const int strip = strip_lo_s + sl, row = strip * 16 + r;
+            if (adds_residual && sl < ge.s_blk && t < k_tok && strip < ge.n_strips && row < ge.n_out) hseed[j] = h_seed_src[(size_t)t * ge.n_out + row];
+        }
+
         if (PROBE && tt && tid == 0) tt[4] = __builtin_amdgcn_s_memrealtime();
         plan_phase<NM24>(nnt, ka, plans, p + 2, n_phases, wave, lane);  // its loads travel during the barrier and the prologue
         if (p > 0) barrier_wait(a.bar, a.err, (unsigned)ncu, gen, spin_limit);
@@ -654,12 +694,13 @@ __global__ __launch_bounds__(kMegaThreads) void mega_forward_kernel(const MegaAr
         const int col_lo = uni(kpl[3]) * 256;                                     // first column of the block
         const int n_col = active ? max(0, min(ge.b_blk * 256, ge.k_in - col_lo)) : 0;  // columns that exist
         const int nqkv = a.q_out + 2 * a.kv_out;
-        float* yq = a.yqkv + (size_t)layer * a.yqkv_stride;
-        float* yg = a.ygu + (size_t)layer * a.ygu_stride;
+        int* yq = a.yqkv + (size_t)layer * a.yqkv_stride;
+        int* yg = a.ygu + (size_t)layer * a.ygu_stride;
+        const float fix_inv = a.fix_inv;
         // residual versions: 2 layer before the attention output is added, 2 layer + 1 after it, 2 layer + 2 after the MLP
         const int hv_in = 2 * layer + (kind >= 2 ? 1 : 0);  // what this phase's norm reads / what its output is added to
-        const float* h_cur = a.hv + (size_t)hv_in * a.h_stride;
-        float* h_nxt = hv_in + 1 == 2 * a.layers ? a.h_out : a.hv + (size_t)(hv_in + 1) * a.h_stride;
+        const int* h_cur = a.hv + (size_t)hv_in * a.h_stride;
+        int* h_nxt = a.hv + (size_t)(hv_in + 1) * a.h_stride;
         const size_t tr_x = ((size_t)p * k_tok) * a.trace_kmax, tr_s = ((size_t)p * k_tok) * a.trace_smax;
 
         // columns past the end of a ragged last slab must read as zero
@@ -671,11 +712,15 @@ __global__ __launch_bounds__(kMegaThreads) void mega_forward_kernel(const MegaAr
             // Thread i owns columns 4i..4i+3 of every token: all loads of the residual are in flight at once,
             // the squares meet in LDS, and each thread then normalises and rounds the columns it holds.
             const int c4 = 4 * tid;
+            i32x4 hraw[kMegaMaxTok];
+#pragma unroll
+            for (int t = 0; t < kMegaMaxTok; ++t)
+                hraw[t] = (t < k_tok && c4 < a.hidden) ? *reinterpret_cast<const i32x4*>(h_cur + (size_t)t * a.hidden + c4) : i32x4{0, 0, 0, 0};
             f32x4 hv[kMegaMaxTok];
 #pragma unroll
             for (int t = 0; t < kMegaMaxTok; ++t)
-                hv[t] = (t < k_tok && c4 < a.hidden) ? *reinterpret_cast<const f32x4*>(h_cur + (size_t)t * a.hidden + c4)
-                                                     : f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int e = 0; e < 4; ++e) hv[t][e] = from_fixed(hraw[t][e], fix_inv);
             if (PROBE) {
                     __builtin_amdgcn_s_waitcnt(0);
                     if (tt && tid == 0) tt[5] = __builtin_amdgcn_s_memrealtime();
@@ -692,23 +737,14 @@ __global__ __launch_bounds__(kMegaThreads) void mega_forward_kernel(const MegaAr
                     for (int t = 0; t < kMegaMaxTok; ++t) part_sums[wave * kMegaMaxTok + t] = ss[t];  // plain stores: LDS float atomics are slow
                 }
             }
-            // the next version of the residual starts as a copy of this one (the linear after next adds into it); the
-            // workgroups share the copying, written through to memory
-            if (copies_residual && c4 < a.hidden) {
-#pragma unroll
-                for (int t = 0; t < kMegaMaxTok; ++t)
-                    if (t < k_tok) {
-                        float* dst = h_nxt + (size_t)t * a.hidden + c4;
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) astore(dst + e, hv[t][e]);
-                    }
-            }
             lds_barrier();
             if (tid < k_tok) {
                 float tot = 0.f;
 #pragma unroll
                 for (int w = 0; w < kMegaWaves; ++w) tot += part_sums[w * kMegaMaxTok + tid];
                 sums[8 + tid] = 1.0f / sqrtf(tot / (float)a.hidden + 1e-5f);
+                // a residual whose norm stays below the limit has every entry below it: the adds into it cannot wrap
+                if (!(tot < a.h_limit_sq)) __hip_atomic_fetch_or(a.err, 2u, __ATOMIC_RELAXED, SD2_AGENT);
             }
             lds_barrier();
             const int c = c4 - col_lo;
@@ -730,15 +766,23 @@ __global__ __launch_bounds__(kMegaThreads) void mega_forward_kernel(const MegaAr
             // thread i owns columns 2i, 2i+1 of the block; gate and up of every token are in flight at once
             const int c = 2 * tid;
             if (c < n_col) {
+                // loads of every token first, conversions afterwards: a use inside a token's own block would wait there,
+                // with the loads of the tokens after it not yet issued
+                i32x2 gr[kMegaMaxTok], ur[kMegaMaxTok];
+#pragma unroll
+                for (int t = 0; t < kMegaMaxTok; ++t) {
+                    gr[t] = ur[t] = i32x2{0, 0};  // defined in every path: nothing is carried from the phase before
+                    if (t < k_tok) {
+                        const int* row = yg + (size_t)t * 2 * a.inter + col_lo + c;
+                        gr[t] = *reinterpret_cast<const i32x2*>(row);
+                        ur[t] = *reinterpret_cast<const i32x2*>(row + a.inter);
+                    }
+                }
                 f32x2 gv[kMegaMaxTok], uv[kMegaMaxTok];
 #pragma unroll
                 for (int t = 0; t < kMegaMaxTok; ++t) {
-                    gv[t] = uv[t] = f32x2{0.f, 0.f};  // defined in every path: nothing is carried from the phase before
-                    if (t < k_tok) {
-                        const float* row = yg + (size_t)t * 2 * a.inter + col_lo + c;
-                        gv[t] = *reinterpret_cast<const f32x2*>(row);
-                        uv[t] = *reinterpret_cast<const f32x2*>(row + a.inter);
-                    }
+                    gv[t] = f32x2{from_fixed(gr[t][0], fix_inv), from_fixed(gr[t][1], fix_inv)};
+                    uv[t] = f32x2{from_fixed(ur[t][0], fix_inv), from_fixed(ur[t][1], fix_inv)};
                 }
 #pragma unroll
                 for (int t = 0; t < kMegaMaxTok; ++t)
@@ -806,16 +850,27 @@ __global__ __launch_bounds__(kMegaThreads) void mega_forward_kernel(const MegaAr
             const int head = col_lo / D + hh;                 // blocks start on head boundaries (256 | col_lo)
             const int kvh = head / rep;
             const bool live = hh * D < n_col;
-            float qv[kMegaMaxTok], kv[kMegaMaxTok], vv[kMegaMaxTok];
+            int qr[kMegaMaxTok], kr[kMegaMaxTok], vr[kMegaMaxTok];
 #pragma unroll
             for (int t = 0; t < kMegaMaxTok; ++t) {
-                qv[t] = kv[t] = vv[t] = 0.f;
+                qr[t] = kr[t] = vr[t] = 0;
                 if (live && t < k_tok) {
-                    const float* row = yq + (size_t)t * nqkv;
-                    qv[t] = row[head * D + d];
-                    kv[t] = row[a.q_out + kvh * D + d];
-                    vv[t] = row[a.q_out + a.kv_out + kvh * D + d];
+                    const int* row = yq + (size_t)t * nqkv;
+                    qr[t] = row[head * D + d];
+                    kr[t] = row[a.q_out + kvh * D + d];
+                    vr[t] = row[a.q_out + a.kv_out + kvh * D + d];
                 }
+            }
+            // the compiler would otherwise move each conversion into its token's block above, where it waits for that
+            // token's loads before the next token's are issued: eight trips to memory in a row
+#pragma unroll
+            for (int t = 0; t < kMegaMaxTok; ++t) asm volatile("" : "+v"(qr[t]), "+v"(kr[t]), "+v"(vr[t]));
+            float qv[kMegaMaxTok], kv[kMegaMaxTok], vv[kMegaMaxTok];
+#pragma unroll
+            for (int t = 0; t < kMegaMaxTok; ++t) {  // after all the loads (see the gated product above)
+                qv[t] = from_fixed(qr[t], fix_inv);
+                kv[t] = from_fixed(kr[t], fix_inv);
+                vv[t] = from_fixed(vr[t], fix_inv);
             }
             // scores of a head: lower triangle [i][j <= i] at i (i + 1) / 2 + j, 36 entries; two shares, one per wavefront
             float* sp = misc + hh * 36;
@@ -978,10 +1033,15 @@ __global__ __launch_bounds__(kMegaThreads) void mega_forward_kernel(const MegaAr
         lds_barrier();
         if (tt && tid == 0) tt[3] = __builtin_amdgcn_s_memrealtime();
 
-        // ---------------- the block's results leave the CU: split-K across the slab blocks by float atomics
+        // ---------------- the block's results leave the CU: split-K across the slab blocks by exact fixed-point adds
         if (active) {
-            float* ybase = kind == 0 ? yq : (kind == 2 ? yg : h_nxt);
-            for (int idx = tid; idx < ge.s_blk * kMegaMaxTok * 16; idx += kMegaThreads) {
+            int* ybase = kind == 0 ? yq : (kind == 2 ? yg : h_nxt);
+            const float scale = a.fix_scale, lim = ka->fix_limit[kind];
+            bool bad = false;
+#pragma unroll
+            for (int j = 0; j < kFlushIters; ++j) {
+                const int idx = tid + j * kMegaThreads;
+                if (idx >= ge.s_blk * kMegaMaxTok * 16) break;
                 const int r = idx & 15, t = (idx >> 4) & (kMegaMaxTok - 1), sl = idx >> 7;
                 float v = 0.f;
                 for (int gq = 0; gq < n_grp; ++gq) {  // the strip's slab groups, each summed by one wavefront
@@ -990,20 +1050,39 @@ __global__ __launch_bounds__(kMegaThreads) void mega_forward_kernel(const MegaAr
                     *slot = 0.f;
                 }
                 const int strip = strip_lo + sl, row = strip * 16 + r;
-                if (t < k_tok && strip < ge.n_strips && row < ge.n_out) aadd(ybase + (size_t)t * ge.n_out + row, v);
+                if (t < k_tok && strip < ge.n_strips && row < ge.n_out) {
+                    const float sv = v * scale;
+                    bad |= !(fabsf(sv) < lim);  // also true for NaN
+                    aadd_i(ybase + (size_t)t * ge.n_out + row, (int)__builtin_rintf(fminf(fmaxf(sv, -lim), lim)) + hseed[j]);
+                }
             }
+            if (bad) __hip_atomic_fetch_or(a.err, 2u, __ATOMIC_RELAXED, SD2_AGENT);  // the call's results are invalid
         }
+    }
+    // ---------------- the last version of the residual stream as fp32
+    if (n_phases > 0) {
+        barrier_arrive(a.bar, gen);
+        barrier_wait(a.bar, a.err, (unsigned)ncu, gen, spin_limit);
+    }
+    {
+        const int* h_last = a.hv + (size_t)(2 * a.layers) * a.h_stride;
+        const int n_h = k_tok * a.hidden;
+        const float fix_inv = a.fix_inv;
+        for (int idx = cu * kMegaThreads + tid; idx < n_h; idx += ncu * kMegaThreads) a.h_out[idx] = from_fixed(h_last[idx], fix_inv);
     }
 }
 
 // ---------------------------------------------------------------- set-up kernels and launch
 
-// One set-up launch: the barrier words and accumulators start from zero, the residual from the bf16 input.
-__global__ __launch_bounds__(256) void mega_setup_kernel(uint32_t* __restrict__ zero, size_t n_zero, float* __restrict__ h,
-                                                        const uint16_t* __restrict__ h_in, size_t n_h) {
+// One set-up launch: the barrier words, the accumulators and every residual version but the first start from zero;
+// the first version is the bf16 input in fixed point.
+__global__ __launch_bounds__(256) void mega_setup_kernel(uint32_t* __restrict__ zero, size_t n_zero, int* __restrict__ h,
+                                                        const uint16_t* __restrict__ h_in, size_t n_h, size_t n_h_rest, float scale) {
     const size_t i0 = (size_t)blockIdx.x * 256 + threadIdx.x, step = (size_t)gridDim.x * 256;
     for (size_t i = i0; i < n_zero; i += step) zero[i] = 0u;
-    for (size_t i = i0; i < n_h; i += step) h[i] = bf16_to_f32(h_in[i]);
+    // out-of-range inputs saturate here; the first norm's range check then reports them
+    for (size_t i = i0; i < n_h; i += step) h[i] = (int)__builtin_rintf(fminf(fmaxf(bf16_to_f32(h_in[i]) * scale, -1073741824.f), 1073741824.f));
+    for (size_t i = n_h + i0; i < n_h + n_h_rest; i += step) h[i] = 0;
 }
 
 static size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
@@ -1024,7 +1103,7 @@ MegaLayout mega_layout(int layers, int hidden, int q_out, int kv_out, int inter,
     L.ygu_off = off;
     off += nl * L.ygu_stride * 4;
     L.hv_off = off;
-    off += 2 * nl * L.h_stride * 4;
+    off += (2 * nl + 1) * L.h_stride * 4;
     L.total = off;
     return L;
 }
@@ -1142,8 +1221,9 @@ hipError_t launch_mega_forward(const MegaArgs& a, const uint16_t* h_in, void* ze
     const int ncu = mega_grid();
     if (ncu < 1) return hipErrorNotSupported;
     const size_t nh = (size_t)a.k_tok * a.hidden;
+    const size_t n_rest = (size_t)(2 * a.layers + 1) * a.h_stride - nh;  // the padding of the first version and all later ones
     hipLaunchKernelGGL(mega_setup_kernel, dim3(512), dim3(256), 0, s, static_cast<uint32_t*>(zero_base), zero_bytes / 4, a.hv,
-                       h_in, nh);
+                       h_in, nh, n_rest, a.fix_scale);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     MegaArgs args = a;

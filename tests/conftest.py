@@ -24,8 +24,8 @@ class _Options:
         import paper_2504_08838_amd as sd2
         self.sd2 = sd2
         self.names = {"forward_multi": sd2.OPT_FORWARD_MULTI, "linear_partials": sd2.OPT_LINEAR_PARTIALS,
-                      "spin_limit": sd2.OPT_SPIN_LIMIT, "mega_timing": sd2.OPT_MEGA_TIMING}
-        self.defaults = {"forward_multi": 0, "linear_partials": 0, "spin_limit": -1, "mega_timing": 0}
+                      "spin_limit": sd2.OPT_SPIN_LIMIT, "mega_timing": sd2.OPT_MEGA_TIMING, "fixed_bits": sd2.OPT_FIXED_BITS}
+        self.defaults = {"forward_multi": 0, "linear_partials": 0, "spin_limit": -1, "mega_timing": 0, "fixed_bits": 17}
 
     def set(self, name, value):
         self.sd2.set_option(self.names[name], value)

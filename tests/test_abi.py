@@ -267,7 +267,7 @@ def test_improvement_factor_matches_eq3_and_the_oracle():
 def test_options_round_trip_and_ranges():
     L = sd2.lib()
     for which, good, bad in ((sd2.OPT_FORWARD_MULTI, 1, 2), (sd2.OPT_LINEAR_PARTIALS, 1, -1), (sd2.OPT_SPIN_LIMIT, 7, -2),
-                             (sd2.OPT_MEGA_TIMING, 2, 3)):
+                             (sd2.OPT_MEGA_TIMING, 2, 3), (sd2.OPT_FIXED_BITS, 15, 30)):
         before = sd2.get_option(which)
         sd2.set_option(which, good)
         assert sd2.get_option(which) == good
@@ -319,3 +319,23 @@ def test_model_create_rejects_head_sizes_the_attention_kernels_cannot_split():
     ok = sd2.ModelShape(0, 1664, 1664, 416, 64, 16, 4, 104)
     assert L.sd2_model_create(C.byref(ok), None, 0, C.byref(handle)) == 0
     L.sd2_model_destroy(handle)
+
+
+def test_greedy_verify_host_against_the_hand_cases_and_the_range_rule(golden_dir):
+    path = os.path.join(golden_dir, "verify_hand_cases.txt")
+    for line in open(path):
+        if line.startswith("#") or not line.strip():
+            continue
+        d, t, n, out = [np.array(f.split(), dtype=np.int32) for f in line.split("|")]
+        acc, toks = sd2.greedy_verify_host(d.reshape(1, -1), t.reshape(1, -1), vocab=100)
+        assert acc.tolist() == n.tolist() and toks[0].tolist() == out.tolist()
+    draft, target = wl.gen_verify(5, 64, 5, 128256, 0.85)
+    acc, toks = sd2.greedy_verify_host(draft, target, 128256)
+    from oracle import verify as ov
+    ref_acc, ref_toks = ov.greedy_verify(draft, target, vocab=128256)
+    assert np.array_equal(acc, ref_acc) and np.array_equal(toks, ref_toks)
+    bad = target.copy()
+    bad[3, 2] = 128256
+    with pytest.raises(sd2.SD2Error) as e:
+        sd2.greedy_verify_host(draft, bad, 128256)
+    assert e.value.status == -6

@@ -48,13 +48,15 @@ def _decode(model, shape, h_bits, kc_dev, vc_dev, max_pos, pos0, theta=THETA):
 
 
 def _cache_close(got_bits, want_bits):
-    """bf16 bit patterns equal, or neighbours (one step apart, or both tiny) in at most 1 % of the entries."""
+    """bf16 bit patterns equal, or neighbours (one step apart, or both tiny) in at most 1 % of the entries.  Tiny: the
+    single-launch kernel hands the q|k|v sums over in fixed point with 17 fraction bits, each slab block rounding its
+    share by at most 2^-18, so an entry may sit 2^-16 from the oracle's whatever its size."""
     g, w = got_bits.astype(np.int64), want_bits.astype(np.int64)
     diff = g != w
     if not diff.any():
         return 0.0
     gv, wv = bits_to_f64(got_bits), bits_to_f64(want_bits)
-    ok = (np.abs(g - w) <= 1) | (np.abs(gv - wv) <= 2.0 ** -8 * np.maximum(np.abs(wv), 1e-3))
+    ok = (np.abs(g - w) <= 1) | (np.abs(gv - wv) <= 2.0 ** -8 * np.maximum(np.abs(wv), 1e-3) + 2.0 ** -16)
     assert ok[diff].all()
     frac = diff.mean()
     assert frac <= 0.01, frac

@@ -66,17 +66,19 @@ def test_cfg3_graph_replays_as_timed_by_the_benchmark(cfg3):
         with torch.cuda.graph(graph, stream=stream):
             sd2.sparse_drafter_forward(model, h_in.data_ptr(), k_tok, h_out.data_ptr(), ws.data_ptr(), ws_bytes,
                                        torch.cuda.current_stream().cuda_stream)
-        for _ in range(3):
+        for _ in range(20):
             h_out.fill_(float("nan"))
             graph.replay()
             torch.cuda.synchronize()
             outs.append(h_out.cpu().numpy().copy())
-    for o in outs:
-        assert np.isfinite(o).all()
-        assert ol.rel_l2(o, ref) <= FULL_E2E_TOL
-    # replays agree with the eager call up to the order of the float atomics (and the rounding flips that can follow)
-    for o in outs[1:]:
-        assert ol.rel_l2(o, outs[0]) <= FULL_E2E_TOL
+    assert np.isfinite(outs[0]).all()
+    err = ol.rel_l2(outs[0], ref)
+    print(f"28-layer end-to-end rel-L2 against the fp64 oracle: {err:.3e}")
+    assert err <= FULL_E2E_TOL
+    # nothing in the forward depends on the order in which workgroups finish: every replay reproduces the eager
+    # call bit for bit (partial results are added in a fixed order, the residual stream by exact integer adds)
+    for i, o in enumerate(outs[1:]):
+        assert np.array_equal(o.view(np.uint32), outs[0].view(np.uint32)), f"replay {i} differs from the eager call"
 
 
 # ---- the decode step at full size (the configuration bench.py times: one token at position 428 of a 1024-slot cache)
@@ -159,5 +161,7 @@ def test_cfg3_decode_28_layers_as_timed_by_the_benchmark(cfg3):
     for o in outs:
         assert np.isfinite(o).all()
         assert ol.rel_l2(o, want) <= FULL_E2E_TOL
+    # The forward itself is order-independent, but a replay starts from the cache the call before it left: the step's
+    # own key/value rows are rewritten with the same bits, so the replays agree bit for bit as well.
     for o in outs[1:]:
-        assert ol.rel_l2(o, outs[0]) <= FULL_E2E_TOL
+        assert np.array_equal(o.view(np.uint32), outs[0].view(np.uint32))

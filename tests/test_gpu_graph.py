@@ -12,10 +12,11 @@ pytestmark = pytest.mark.gpu
 SHAPE = SimpleNamespace(layers=2, hidden=512, q_out=512, kv_out=256, inter=1024, n_heads=4, n_kv=2, head_dim=128)
 
 
-def test_forward_graph_replays_match_eager(sd2_options):
-    # the launch-per-step path is the one meant for graph capture (the persistent kernel is a single
-    # cooperative launch already and adds float atomics, whose order may differ between runs)
-    sd2_options.set("forward_multi", 1)
+@pytest.mark.parametrize("path", ["single-launch", "multi-launch"])
+def test_forward_graph_replays_match_eager(path, sd2_options):
+    # both forward paths add partial results in a fixed order (the single-launch kernel sums the residual stream
+    # with exact integer atomics), so a replay must reproduce the eager call bit for bit
+    sd2_options.set("forward_multi", 1 if path == "multi-launch" else 0)
     import torch
     import paper_2504_08838_amd as sd2
     import gpu_util as gu
