@@ -99,6 +99,11 @@ inline bool sparse_final_ok(const sd2_matrix_t* m, int k_tok) {
     return sparse_strip_supported(mat_args(m), k_tok);
 }
 
+// The gate|up linear and the gated product in one launch (the bitmask kernel that adds the slabs up inside the workgroup).
+inline bool gated_ok(const sd2_matrix_t* m, int k_tok) {
+    return sparse_final_ok(m, k_tok) && sparse_strip_gated_supported(mat_args(m), k_tok);
+}
+
 // Partial results run_linear leaves in `out` for this token count (1: final values).  Never more than n_partials(m),
 // which sizes the buffers.
 inline int n_splits(const sd2_matrix_t* m, int k_tok) { return sparse_final_ok(m, k_tok) ? 1 : n_partials(m); }
@@ -155,7 +160,7 @@ int linear_entry(const sd2_matrix_t* m, int kind, const uint16_t* x, int32_t k_t
 }
 
 struct StackLayout {
-    size_t act_off, part_off, ssq_off, total;
+    size_t act_off, act2_off, part_off, ssq_off, total;  // two activation buffers: a fused kernel reads one and writes the other
 };
 
 StackLayout stack_layout(const sd2_model* md, int k_tok) {
@@ -165,7 +170,8 @@ StackLayout stack_layout(const sd2_model* md, int k_tok) {
     L.act_off = 0;
     size_t part = 0;
     for (const sd2_matrix_t& m : md->mats) part = std::max(part, partial_bytes(&m, k_tok));
-    L.part_off = align256((size_t)k_tok * widest * sizeof(uint16_t));
+    L.act2_off = align256((size_t)k_tok * widest * sizeof(uint16_t));
+    L.part_off = 2 * L.act2_off;
     L.ssq_off = L.part_off + align256(part);
     L.total = L.ssq_off + align256((size_t)k_tok * ((sh.hidden + 255) / 256) * sizeof(float));
     return L;
@@ -363,8 +369,12 @@ int sd2_sparse_mlp_forward(const sd2_matrix_t* gu, const sd2_matrix_t* dn, const
     const int inter = dn->info.k_in;
     uint16_t* act = static_cast<uint16_t*>(ws);
     float* part = reinterpret_cast<float*>(static_cast<uint8_t*>(ws) + align256((size_t)k_tok * inter * sizeof(uint16_t)));
-    if (run_linear(gu, x, k_tok, part, s) != hipSuccess) return SD2_ERR_HIP;
-    if (launch_silu_mul(part, n_splits(gu, k_tok), k_tok, inter, act, s) != hipSuccess) return SD2_ERR_HIP;
+    if (gated_ok(gu, k_tok)) {
+        if (launch_sparse_strip_gated(mat_args(gu), x, k_tok, act, s) != hipSuccess) return SD2_ERR_HIP;
+    } else {
+        if (run_linear(gu, x, k_tok, part, s) != hipSuccess) return SD2_ERR_HIP;
+        if (launch_silu_mul(part, n_splits(gu, k_tok), k_tok, inter, act, s) != hipSuccess) return SD2_ERR_HIP;
+    }
     if (n_splits(dn, k_tok) == 1) return run_linear(dn, act, k_tok, y, s) == hipSuccess ? SD2_OK : SD2_ERR_HIP;
     if (run_linear(dn, act, k_tok, part, s) != hipSuccess) return SD2_ERR_HIP;
     if (launch_reduce_partials(part, n_splits(dn, k_tok), (size_t)k_tok * dn->info.n_out, y, s) != hipSuccess)
@@ -486,8 +496,6 @@ static int forward_impl(const sd2_model_t* md, const uint16_t* h_in, int32_t k_t
     if (single_launch) ML = planned_layout(md, k_tok, ma.geo);
     if (!aligned16(h_in) || !aligned16(h_out) || !aligned16(ws) || ws_bytes < std::max(L.total, ML.total))
         return SD2_ERR_BUFFER;
-    // the attention kernel of the launch-per-step path keeps q, k, v and the scores of a head in LDS
-    if (!single_launch && sh.layers > 0 && inflight_attention_lds(k_tok, sh.head_dim) > kMaxLdsBytes) return SD2_ERR_UNSUPPORTED;
     if (single_launch) {
         uint8_t* base = static_cast<uint8_t*>(ws);
         fill_mega_args(ma, md, k_tok, ML, base, h_out);
@@ -508,6 +516,7 @@ static int forward_impl(const sd2_model_t* md, const uint16_t* h_in, int32_t k_t
         return launch_mega_forward(ma, h_in, base, ML.hv_off, probe, nm24, s) == hipSuccess ? SD2_OK : SD2_ERR_HIP;
     }
     uint16_t* act = reinterpret_cast<uint16_t*>(static_cast<uint8_t*>(ws) + L.act_off);
+    uint16_t* act2 = reinterpret_cast<uint16_t*>(static_cast<uint8_t*>(ws) + L.act2_off);
     float* part = reinterpret_cast<float*>(static_cast<uint8_t*>(ws) + L.part_off);
     float* ssq = reinterpret_cast<float*>(static_cast<uint8_t*>(ws) + L.ssq_off);
     float* h = h_out;  // the residual stream lives in the output buffer
@@ -548,8 +557,15 @@ static int forward_impl(const sd2_model_t* md, const uint16_t* h_in, int32_t k_t
         SD2_TRY(run_linear(o, act, k_tok, part, s));
         SD2_TRY(launch_residual_rmsnorm(h, nullptr, part, n_splits(o, k_tok), k_tok, sh.hidden, act, ssq, s));
         SD2_TRY(record(4 * l + 2, h, nullptr, 0, sh.hidden, sh.hidden));
-        SD2_TRY(run_linear(gu, act, k_tok, part, s));
-        SD2_TRY(launch_silu_mul(part, n_splits(gu, k_tok), k_tok, sh.inter, act, s));
+        if (!trace && gated_ok(gu, k_tok)) {
+            // one launch: the gated product is written by the linear's own epilogue (act is read and written: the
+            // kernel has taken its input columns into registers before the first result leaves)
+            SD2_TRY(launch_sparse_strip_gated(mat_args(gu), act, k_tok, act2, s));
+            std::swap(act, act2);
+        } else {
+            SD2_TRY(run_linear(gu, act, k_tok, part, s));
+            SD2_TRY(launch_silu_mul(part, n_splits(gu, k_tok), k_tok, sh.inter, act, s));
+        }
         SD2_TRY(record(4 * l + 3, nullptr, part, n_splits(gu, k_tok), 2 * sh.inter, sh.inter));
         SD2_TRY(run_linear(dn, act, k_tok, part, s));
         SD2_TRY(launch_residual_rmsnorm(h, nullptr, part, n_splits(dn, k_tok), k_tok, sh.hidden,
@@ -686,6 +702,7 @@ int sd2_sparse_drafter_decode(const sd2_model_t* md, const uint16_t* h_in, int32
         return launch_mega_forward(ma, h_in, base, ML.hv_off, false, nm24, s) == hipSuccess ? SD2_OK : SD2_ERR_HIP;
     }
     uint16_t* act = reinterpret_cast<uint16_t*>(base + L.act_off);
+    uint16_t* act2 = reinterpret_cast<uint16_t*>(base + L.act2_off);
     float* part = reinterpret_cast<float*>(base + L.part_off);
     float* ssq = reinterpret_cast<float*>(base + L.ssq_off);
     float* q_rot = reinterpret_cast<float*>(base + DL.q_off);
@@ -709,8 +726,13 @@ int sd2_sparse_drafter_decode(const sd2_model_t* md, const uint16_t* h_in, int32
         SD2_TRY(launch_cached_attention(q_rot, kc, vc, max_pos, pos0, k_tok, sh.q_out, sh.n_heads, sh.n_kv, sh.head_dim, act, s));
         SD2_TRY(run_linear(o, act, k_tok, part, s));
         SD2_TRY(launch_residual_rmsnorm(h, nullptr, part, n_splits(o, k_tok), k_tok, sh.hidden, act, ssq, s));
-        SD2_TRY(run_linear(gu, act, k_tok, part, s));
-        SD2_TRY(launch_silu_mul(part, n_splits(gu, k_tok), k_tok, sh.inter, act, s));
+        if (gated_ok(gu, k_tok)) {
+            SD2_TRY(launch_sparse_strip_gated(mat_args(gu), act, k_tok, act2, s));
+            std::swap(act, act2);
+        } else {
+            SD2_TRY(run_linear(gu, act, k_tok, part, s));
+            SD2_TRY(launch_silu_mul(part, n_splits(gu, k_tok), k_tok, sh.inter, act, s));
+        }
         SD2_TRY(run_linear(dn, act, k_tok, part, s));
         SD2_TRY(launch_residual_rmsnorm(h, nullptr, part, n_splits(dn, k_tok), k_tok, sh.hidden,
                                         l + 1 < sh.layers ? act : nullptr, ssq, s));

@@ -29,6 +29,9 @@ hipError_t launch_dense_linear(const MatArgs& m, const LinArgs& a, hipStream_t s
 // the sparse linear with final results in one launch (no partial sums): a.out is y [k_tok][n_out]
 bool sparse_strip_supported(const MatArgs& m, int k_tok);
 hipError_t launch_sparse_strip_linear(const MatArgs& m, const LinArgs& a, hipStream_t s);
+// the fused [gate; up] product with the gating in its epilogue: m_out [k_tok][n_out / 2] = bf16(silu(gate x) * (up x))
+bool sparse_strip_gated_supported(const MatArgs& m, int k_tok);
+hipError_t launch_sparse_strip_gated(const MatArgs& m, const uint16_t* x, int k_tok, uint16_t* m_out, hipStream_t s);
 
 // Device address, on the current device, of the library's static scratch array (kStaticScratchBytes bytes, 256-byte
 // aligned): looked up once per device, no allocation.  Calls that use it on one GPU share it.
@@ -48,12 +51,8 @@ hipError_t launch_reduce_partials_strided(const float* part, int n_splits, size_
 hipError_t launch_residual_rmsnorm(float* h, const uint16_t* h_in, const float* part, int n_splits,
                                    int k_tok, int hidden, uint16_t* a, float* ssq, hipStream_t s);
 
-// LDS a workgroup may use on gfx950, and what the kernel below needs: checked on the host before the first launch.
-constexpr size_t kMaxLdsBytes = 160 * 1024;
-inline size_t inflight_attention_lds(int k_tok, int head_dim) {
-    return ((size_t)3 * k_tok * head_dim + (size_t)k_tok * k_tok) * sizeof(float);
-}
-// Causal softmax attention among the k_tok in-flight tokens; qkv partials [n_splits][k_tok][q_out+2*kv_out].
+// Causal softmax attention among the k_tok <= 64 in-flight tokens (head_dim a multiple of 8, <= 256); qkv partials
+// [n_splits][k_tok][q_out+2*kv_out].
 hipError_t launch_inflight_attention(const float* part, int n_splits, int k_tok, int q_out, int kv_out,
                                      int n_heads, int n_kv, int head_dim, uint16_t* ctx, hipStream_t s);
 

@@ -141,8 +141,17 @@ __global__ __launch_bounds__(256) void sparse_linear_kernel(const DirEnt* __rest
 // wavefront's registers, so they are fetched per 64-column step (they stay in the caches: every wavefront of the chip
 // reads the same [k_tok][k_in] array), one step ahead of the expansion that consumes them.
 constexpr int kStripRound = 4;  // strip results (of 16 tokens each) between two workgroup barriers of the kernel below
+// strips per round for TG token groups; the gated variant needs whole pairs in a round
+constexpr int strip_round(int tg, bool gated) {
+    const int r = kStripRound / tg > 0 ? kStripRound / tg : 1;
+    return gated && (r & 1) ? r + 1 : r;
+}
 
-template <int MAXCH, int SPW, int WAVES, int TG>
+//
+// GATED: the matrix is [gate; up] (two halves of n_out / 2 rows that share the input) and what leaves the kernel is the
+// gated product bf16(silu(gate x) * (up x)), [k_tok][n_out / 2], written to y (as uint16): a workgroup then owns pairs
+// of strips, strip p of the gate half and strip p of the up half, which sit side by side in a round's slots.
+template <int MAXCH, int SPW, int WAVES, int TG, bool GATED = false>
 __global__ __launch_bounds__(64 * WAVES) void sparse_strip_kernel(const DirEnt* __restrict__ dir, const uint2* __restrict__ masks,
                                                                  const uint16_t* __restrict__ vals,
                                                                  const uint16_t* __restrict__ x, float* __restrict__ y,
@@ -157,15 +166,21 @@ __global__ __launch_bounds__(64 * WAVES) void sparse_strip_kernel(const DirEnt* 
     const int n = lane & 15, g = lane >> 4;
     uint32_t* buf = strip_smem + wave * (MAXCH * 256);
     float* red = reinterpret_cast<float*>(strip_smem + WAVES * (MAXCH * 256));
-    constexpr int kRound = kStripRound / TG > 0 ? kStripRound / TG : 1;  // strips per round: the slots of a round fit LDS
-    const int my_strips = (n_strips - (int)blockIdx.x + (int)gridDim.x - 1) / (int)gridDim.x;
+    constexpr int kRound = strip_round(TG, GATED);  // strips per round: the slots of a round fit LDS
+    // the strips this workgroup walks, in order: b, b + G, ... -- or, gated, the pairs (b, b + half), (b + G, b + G + half), ...
+    const int n_units = GATED ? n_strips / 2 : n_strips;
+    const int my_units = (n_units - (int)blockIdx.x + (int)gridDim.x - 1) / (int)gridDim.x;
+    const int my_strips = GATED ? 2 * my_units : my_units;
+    auto strip_of = [&](int ord) {
+        return GATED ? (int)blockIdx.x + (ord >> 1) * (int)gridDim.x + (ord & 1) * n_units : (int)blockIdx.x + ord * (int)gridDim.x;
+    };
     int n_mine = 0;  // this wavefront's slabs: wave + WAVES * j
 #pragma unroll
     for (int j = 0; j < SPW; ++j) n_mine += (wave + WAVES * j < n_slabs) ? 1 : 0;
     const int n_flat = my_strips * n_mine;  // its tiles, strip by strip
     auto tile_of = [&](int f) {
         const int i = f / max(n_mine, 1), j = f - i * max(n_mine, 1);
-        return (wave + WAVES * j) * n_strips + ((int)blockIdx.x + i * (int)gridDim.x);
+        return (wave + WAVES * j) * n_strips + strip_of(i);
     };
 
     // The strips are handled in rounds of kRound: every wavefront leaves its blocks of a strip (one per token group) in
@@ -179,15 +194,34 @@ __global__ __launch_bounds__(64 * WAVES) void sparse_strip_kernel(const DirEnt* 
         __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
-        for (int idx = tid; idx < n_in_round * TG * 256; idx += 64 * WAVES) {
-            const int e = idx & 255, tg = (idx >> 8) % TG, r = (idx >> 8) / TG;
-            const float* slot = red + (size_t)r * (WAVES * TG * 256) + tg * 256;
-            float v = 0.f;
+        if (GATED) {
+            // a round holds whole pairs: slot 2 r is the gate strip, slot 2 r + 1 the up strip of pair r
+            const int half_rows = n_out / 2;
+            uint16_t* m_out = reinterpret_cast<uint16_t*>(y);
+            for (int idx = tid; idx < (n_in_round / 2) * TG * 256; idx += 64 * WAVES) {
+                const int e = idx & 255, tg = (idx >> 8) % TG, r = (idx >> 8) / TG;
+                const float* slot = red + (size_t)(2 * r) * (WAVES * TG * 256) + tg * 256;
+                float gv = 0.f, uv = 0.f;
 #pragma unroll
-            for (int ww = 0; ww < WAVES; ++ww) v += slot[ww * (TG * 256) + e];
-            const int tok = 16 * tg + ((e & 63) >> 2);
-            const int row = ((int)blockIdx.x + (i_first + r) * (int)gridDim.x) * 16 + 4 * (e >> 6) + (e & 3);
-            if (row < n_out && tok < k_tok) y[(size_t)tok * n_out + row] = v;
+                for (int ww = 0; ww < WAVES; ++ww) {
+                    gv += slot[ww * (TG * 256) + e];
+                    uv += slot[WAVES * TG * 256 + ww * (TG * 256) + e];
+                }
+                const int tok = 16 * tg + ((e & 63) >> 2);
+                const int row = strip_of(i_first + 2 * r) * 16 + 4 * (e >> 6) + (e & 3);
+                if (row < half_rows && tok < k_tok) m_out[(size_t)tok * half_rows + row] = f32_to_bf16(gv / (1.0f + expf(-gv)) * uv);
+            }
+        } else {
+            for (int idx = tid; idx < n_in_round * TG * 256; idx += 64 * WAVES) {
+                const int e = idx & 255, tg = (idx >> 8) % TG, r = (idx >> 8) / TG;
+                const float* slot = red + (size_t)r * (WAVES * TG * 256) + tg * 256;
+                float v = 0.f;
+#pragma unroll
+                for (int ww = 0; ww < WAVES; ++ww) v += slot[ww * (TG * 256) + e];
+                const int tok = 16 * tg + ((e & 63) >> 2);
+                const int row = strip_of(i_first + r) * 16 + 4 * (e >> 6) + (e & 3);
+                if (row < n_out && tok < k_tok) y[(size_t)tok * n_out + row] = v;
+            }
         }
         __builtin_amdgcn_s_waitcnt(0xC07F);
         __builtin_amdgcn_s_barrier();
@@ -406,23 +440,23 @@ bool sparse_strip_supported(const MatArgs& m, int k_tok) {
            strip_shape(m.n_slabs, (k_tok + 15) / 16, spw, waves);
 }
 
-template <int SPW, int WAVES, int TG>
+template <int SPW, int WAVES, int TG, bool GATED = false>
 static hipError_t launch_strip_t(const MatArgs& m, const LinArgs& a, hipStream_t s) {
     constexpr int kCh = 5;
-    constexpr int kRound = kStripRound / TG > 0 ? kStripRound / TG : 1;
+    constexpr int kRound = strip_round(TG, GATED);
     const size_t lds = (size_t)WAVES * kCh * 1024 + (size_t)kRound * TG * WAVES * 256 * sizeof(float);
     static std::atomic<int> cached{0};  // workgroups resident on the chip; threads that race here compute the same value
     int resident = cached.load(std::memory_order_acquire);
     if (resident == 0) {
-        const void* fn = reinterpret_cast<const void*>(sparse_strip_kernel<kCh, SPW, WAVES, TG>);
+        const void* fn = reinterpret_cast<const void*>(sparse_strip_kernel<kCh, SPW, WAVES, TG, GATED>);
         int per_cu = 0;
         if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) return hipErrorInvalidValue;
         if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, 64 * WAVES, lds) != hipSuccess || per_cu < 1) per_cu = 1;
         resident = device_cu_count() * per_cu;
         cached.store(resident, std::memory_order_release);
     }
-    const int grid = std::min(m.n_strips, resident);
-    hipLaunchKernelGGL((sparse_strip_kernel<kCh, SPW, WAVES, TG>), dim3((unsigned)grid), dim3(64 * WAVES), lds, s,
+    const int grid = std::min(GATED ? m.n_strips / 2 : m.n_strips, resident);
+    hipLaunchKernelGGL((sparse_strip_kernel<kCh, SPW, WAVES, TG, GATED>), dim3((unsigned)grid), dim3(64 * WAVES), lds, s,
                        static_cast<const DirEnt*>(m.dir), m.masks, m.vals, a.x, a.out, m.n_out, m.k_in, a.k_tok, m.n_strips, m.n_slabs);
     return hipGetLastError();
 }
@@ -461,6 +495,37 @@ hipError_t launch_sparse_strip_linear(const MatArgs& m, const LinArgs& a, hipStr
     SD2_STRIP_WIDE(4);
 #undef SD2_STRIP_WIDE
 #undef SD2_STRIP_CASE
+    return hipErrorInvalidValue;
+}
+
+// The gated product of a fused [gate; up] matrix in one launch: m_out [k_tok][n_out / 2] bf16 = bf16(silu(gate x) * (up x)).
+// One slab per wavefront (k_in <= 3072 for more than 16 tokens, <= 4096 else), whole strips per half.
+bool sparse_strip_gated_supported(const MatArgs& m, int k_tok) {
+    int spw, waves;
+    return sparse_strip_supported(m, k_tok) && strip_shape(m.n_slabs, std::min((k_tok + 15) / 16, 2), spw, waves) && spw == 1 &&
+           m.n_out % 32 == 0;
+}
+
+hipError_t launch_sparse_strip_gated(const MatArgs& m, const uint16_t* x, int k_tok, uint16_t* m_out, hipStream_t s) {
+    if (!sparse_strip_gated_supported(m, k_tok)) return hipErrorInvalidValue;
+    if (k_tok > 32) {  // 32 tokens per pass, as for the plain product
+        const hipError_t e = launch_sparse_strip_gated(m, x, 32, m_out, s);
+        return e != hipSuccess ? e : launch_sparse_strip_gated(m, x + (size_t)32 * m.k_in, k_tok - 32, m_out + (size_t)32 * (m.n_out / 2), s);
+    }
+    int spw, waves;
+    const int tg = (k_tok + 15) / 16;
+    strip_shape(m.n_slabs, tg, spw, waves);
+    const LinArgs a{x, k_tok, reinterpret_cast<float*>(m_out)};
+#define SD2_GATED_CASE(W, T) \
+    if (waves == W && tg == T) return launch_strip_t<1, W, T, true>(m, a, s)
+    SD2_GATED_CASE(4, 1);
+    SD2_GATED_CASE(8, 1);
+    SD2_GATED_CASE(12, 1);
+    SD2_GATED_CASE(16, 1);
+    SD2_GATED_CASE(4, 2);
+    SD2_GATED_CASE(8, 2);
+    SD2_GATED_CASE(12, 2);
+#undef SD2_GATED_CASE
     return hipErrorInvalidValue;
 }
 
@@ -792,79 +857,119 @@ __global__ __launch_bounds__(256) void rmsnorm_apply_kernel(const float* __restr
     if (i < hidden) a[(size_t)t * hidden + i] = f32_to_bf16(h[(size_t)t * hidden + i] * inv);
 }
 
+// Both steps in one launch for hidden <= 16384: one workgroup of 1024 threads per token keeps its columns in registers
+// between the residual update, the sum of squares (cross-lane sums, then the 16 wavefronts' totals in a fixed order)
+// and the normalisation.
+constexpr int kRnThreads = 1024, kRnCols = 16;
+
+__global__ __launch_bounds__(kRnThreads) void residual_norm_kernel(float* __restrict__ h, const uint16_t* __restrict__ h_in,
+                                                                  const float* __restrict__ part, int n_splits, int k_tok,
+                                                                  int hidden, uint16_t* __restrict__ a) {
+    __shared__ float wave_tot[kRnThreads / 64];
+    const int t = blockIdx.x, tid = threadIdx.x;
+    float v[kRnCols];
+    float ss = 0.f;
+#pragma unroll
+    for (int j = 0; j < kRnCols; ++j) {
+        const int i = tid + j * kRnThreads;
+        v[j] = 0.f;
+        if (i < hidden) {
+            const size_t at = (size_t)t * hidden + i;
+            v[j] = h_in ? bf16_to_f32(h_in[at]) : h[at] + sum_splits(part + at, n_splits, (size_t)k_tok * hidden);
+            h[at] = v[j];
+            ss += v[j] * v[j];
+        }
+    }
+    if (!a) return;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) ss += __shfl_xor(ss, o);
+    if ((tid & 63) == 0) wave_tot[tid >> 6] = ss;
+    __syncthreads();
+    float tot = 0.f;
+#pragma unroll
+    for (int w = 0; w < kRnThreads / 64; ++w) tot += wave_tot[w];
+    const float inv = 1.0f / sqrtf(tot / (float)hidden + 1e-5f);
+#pragma unroll
+    for (int j = 0; j < kRnCols; ++j) {
+        const int i = tid + j * kRnThreads;
+        if (i < hidden) a[(size_t)t * hidden + i] = f32_to_bf16(v[j] * inv);
+    }
+}
+
 hipError_t launch_residual_rmsnorm(float* h, const uint16_t* h_in, const float* part, int n_splits, int k_tok,
                                    int hidden, uint16_t* a, float* ssq, hipStream_t s) {
+    if (hidden <= kRnThreads * kRnCols) {
+        hipLaunchKernelGGL(residual_norm_kernel, dim3((unsigned)k_tok), dim3(kRnThreads), 0, s, h, h_in, part, n_splits, k_tok, hidden, a);
+        return hipGetLastError();
+    }
     const dim3 grid((unsigned)((hidden + 255) / 256), (unsigned)k_tok);
     hipLaunchKernelGGL(residual_update_kernel, grid, dim3(256), 0, s, h, h_in, part, n_splits, k_tok, hidden, ssq);
     if (a) hipLaunchKernelGGL(rmsnorm_apply_kernel, grid, dim3(256), 0, s, h, ssq, hidden, a);
     return hipGetLastError();
 }
 
-__global__ __launch_bounds__(256) void inflight_attention_kernel(const float* __restrict__ part, int n_splits, int k_tok,
+// Causal softmax attention among the k_tok <= 64 in-flight tokens: one workgroup of two wavefronts per (head, query
+// token i).  Scores: lane j of each wavefront owns key j <= i and half of the head's dimensions (its key row is
+// contiguous in memory: 16-byte loads), the halves meet in LDS; softmax over the 64 lanes of one wavefront by
+// cross-lane maxima and sums; output: thread d owns dimension d and walks the values of tokens 0..i (coalesced).
+__global__ __launch_bounds__(128) void inflight_attention_kernel(const float* __restrict__ part, int n_splits, int k_tok,
                                                                 int q_out, int kv_out, int n_heads, int n_kv, int D,
                                                                 uint16_t* __restrict__ ctx) {
-    extern __shared__ float smem[];
-    float* sq = smem;
-    float* sk = sq + k_tok * D;
-    float* sv = sk + k_tok * D;
-    float* sp = sv + k_tok * D;  // [k_tok][k_tok]
-    const int head = blockIdx.x;
+    __shared__ __attribute__((aligned(16))) float sq[256];  // the query (head_dim <= 256)
+    __shared__ float sc[2][64];                             // each wavefront's share of the scores
+    __shared__ float sp[64];                                // probabilities
+    const int head = blockIdx.x, i = blockIdx.y;
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int grp = head / (n_heads / n_kv);
     const int n_out = q_out + 2 * kv_out;
     const size_t stride = (size_t)k_tok * n_out;
-    for (int idx = threadIdx.x; idx < k_tok * D; idx += 256) {
-        const int t = idx / D, d = idx % D;
-        const float* p = part + (size_t)t * n_out;
-        sq[idx] = sum_splits(p + head * D + d, n_splits, stride);
-        sk[idx] = sum_splits(p + q_out + grp * D + d, n_splits, stride);
-        sv[idx] = sum_splits(p + q_out + kv_out + grp * D + d, n_splits, stride);
-    }
+    for (int d = tid; d < D; d += 128) sq[d] = sum_splits(part + (size_t)i * n_out + head * D + d, n_splits, stride);
     __syncthreads();
-    // scores: eight threads per (i, j) pair, each over an eighth of the head dimension
-    const float scale = 1.0f / sqrtf((float)D);
-    const int r = threadIdx.x & 7, seg = D / 8;
-    for (int pair = threadIdx.x >> 3; pair < k_tok * k_tok; pair += 32) {
-        const int i = pair / k_tok, j = pair % k_tok;
-        float dot = 0.f;
-        if (j <= i)
-            for (int d = r * seg; d < (r + 1) * seg; ++d) dot += sq[i * D + d] * sk[j * D + d];
-        dot += __shfl_xor(dot, 1);
-        dot += __shfl_xor(dot, 2);
-        dot += __shfl_xor(dot, 4);
-        if (r == 0) sp[pair] = dot * scale;
-    }
-    __syncthreads();
-    for (int i = threadIdx.x; i < k_tok; i += 256) {
-        float mx = sp[i * k_tok];
-        for (int j = 1; j <= i; ++j) mx = fmaxf(mx, sp[i * k_tok + j]);
-        float sum = 0.f;
-        for (int j = 0; j <= i; ++j) {
-            const float e = expf(sp[i * k_tok + j] - mx);
-            sp[i * k_tok + j] = e;
-            sum += e;
+    const int half = D / 2;  // a multiple of 4 (head_dim is a multiple of 8)
+    float dot = 0.f;
+    if (lane <= i) {
+        const float* kr = part + (size_t)lane * n_out + q_out + grp * D + w * half;
+        const float* qh = sq + w * half;
+        for (int d = 0; d < half; d += 4) {
+            float4 kk = *reinterpret_cast<const float4*>(kr + d);
+            for (int sp_i = 1; sp_i < n_splits; ++sp_i) {
+                const float4 more = *reinterpret_cast<const float4*>(kr + (size_t)sp_i * stride + d);
+                kk.x += more.x;
+                kk.y += more.y;
+                kk.z += more.z;
+                kk.w += more.w;
+            }
+            const float4 qq = *reinterpret_cast<const float4*>(qh + d);
+            dot += qq.x * kk.x + qq.y * kk.y + qq.z * kk.z + qq.w * kk.w;
         }
-        const float inv = 1.0f / sum;
-        for (int j = 0; j <= i; ++j) sp[i * k_tok + j] *= inv;
+    }
+    sc[w][lane] = dot;
+    __syncthreads();
+    if (w == 0) {
+        const bool on = lane <= i;
+        const float s = on ? (sc[0][lane] + sc[1][lane]) * (1.0f / sqrtf((float)D)) : -INFINITY;
+        float mx = s;
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
+        const float e = on ? expf(s - mx) : 0.f;
+        float sum = e;
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o);
+        sp[lane] = e / sum;
     }
     __syncthreads();
-    for (int idx = threadIdx.x; idx < k_tok * D; idx += 256) {
-        const int i = idx / D, d = idx % D;
+    for (int d = tid; d < D; d += 128) {
+        const float* vr = part + q_out + kv_out + grp * D + d;
         float o = 0.f;
-        for (int j = 0; j <= i; ++j) o += sp[i * k_tok + j] * sv[j * D + d];
+        for (int j = 0; j <= i; ++j) o += sp[j] * sum_splits(vr + (size_t)j * n_out, n_splits, stride);
         ctx[(size_t)i * q_out + head * D + d] = f32_to_bf16(o);
     }
 }
 
 hipError_t launch_inflight_attention(const float* part, int n_splits, int k_tok, int q_out, int kv_out, int n_heads,
                                      int n_kv, int head_dim, uint16_t* ctx, hipStream_t s) {
-    const size_t lds = inflight_attention_lds(k_tok, head_dim);
-    if (lds > kMaxLdsBytes) return hipErrorInvalidValue;
-    if (lds > 64 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(inflight_attention_kernel),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-    }
-    hipLaunchKernelGGL(inflight_attention_kernel, dim3((unsigned)n_heads), dim3(256), lds, s, part, n_splits, k_tok,
+    if (k_tok < 1 || k_tok > 64 || head_dim < 8 || head_dim > 256 || head_dim % 8) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(inflight_attention_kernel, dim3((unsigned)n_heads, (unsigned)k_tok), dim3(128), 0, s, part, n_splits, k_tok,
                        q_out, kv_out, n_heads, n_kv, head_dim, ctx);
     return hipGetLastError();
 }

@@ -86,3 +86,44 @@ def test_wide_token_counts_on_both_kernels(k_tok, sd2_options):
     for partials in (0, 1):
         sd2_options.set("linear_partials", partials)
         _check(gu.run_linear(mat, x), w, x, f"k={k_tok} partials={partials}")
+
+
+@pytest.mark.parametrize("k_tok", [16, 40, 64])
+def test_wide_mlp_block_with_the_gated_epilogue(k_tok):
+    """gate|up with the gated product in the linear's own epilogue, then down: the 1B-shape block on 16 to 64 tokens."""
+    import torch
+    import paper_2504_08838_amd as sd2
+    from oracle import stack as os_
+    gu = _gu()
+    hidden, inter = 2048, 8192
+    wg, wu, wd = (wl.gen_weight(2, 1, p, *sh, 50) for p, sh in (("gate", (inter, hidden)), ("up", (inter, hidden)), ("down", (hidden, inter))))
+    x_bits = wl.gen_x(2, 1, "gate", k_tok, hidden)
+    ref, _ = os_.mlp_block(wg, wu, wd, x_bits)
+    g_u, dn = gu.SparseMat(np.concatenate([wg, wu], axis=0)), gu.SparseMat(wd)
+    x = gu.dev(x_bits)
+    y = torch.full((k_tok, hidden), float("nan"), dtype=torch.float32, device="cuda")
+    nb = sd2.mlp_workspace_size(g_u.m, dn.m, k_tok)
+    ws = torch.empty(nb, dtype=torch.uint8, device="cuda")
+    sd2.sparse_mlp_forward(g_u.m, dn.m, x.data_ptr(), k_tok, y.data_ptr(), ws.data_ptr(), nb, gu.stream_ptr())
+    torch.cuda.synchronize()
+    # end to end through one bf16 rounding point: a few products within fp32 error of a rounding boundary may round the other way
+    assert ol.rel_l2(y.cpu().numpy(), ref) <= 2e-3
+
+
+@pytest.mark.parametrize("k_tok", [16, 64])
+def test_wide_two_layers_at_3b_width_link_by_link(k_tok):
+    """Two layers of the 3B shape on 16 and 64 tokens: every linear and every glue step against the oracle on the GPU's
+    own recorded inputs (the wide regime runs as one launch per linear and glue step)."""
+    from types import SimpleNamespace
+    from test_gpu_stack import _verify_steps, _weights
+    from oracle import stack as os_
+    gu = _gu()
+    shape = SimpleNamespace(**{**wl.CONFIGS[3]["shape"].__dict__, "layers": 2})
+    get = _weights(shape, 3)
+    h_in = wl.gen_x(3, 0, "q", k_tok, shape.hidden)
+    model = gu.build_model(shape, get)
+    h_out, x, src = gu.run_forward_trace(model, h_in, shape)
+    _verify_steps(shape, get, h_in, h_out, x, src)
+    plain = gu.run_forward(model, h_in, shape.hidden)      # the non-recording entry point (fused epilogues) agrees
+    assert ol.rel_l2(plain, h_out) <= 5e-3
+    assert ol.rel_l2(plain, os_.drafter_forward(shape, get, h_in)) <= 5e-3
