@@ -37,11 +37,11 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 # HBM bytes per launch of the forward kernel (and of the gate+up sparse linear) from rocprofv3 --pmc
 # FETCH_SIZE / WRITE_SIZE runs, scaled by the plain copy kernel of --calibrate; None until measured.
-MEASURED_TRAFFIC_BYTES = None
-MEASURED_LINEAR_TRAFFIC_BYTES = 61260497
-MEASURED_LM_HEAD_TRAFFIC_BYTES = 788275309
-MEASURED_NM24_TRAFFIC_BYTES = 57261905
-MEASURED_DECODE_TRAFFIC_BYTES = None
+MEASURED_TRAFFIC_BYTES = 3421587955
+MEASURED_LINEAR_TRAFFIC_BYTES = 61251766
+MEASURED_LM_HEAD_TRAFFIC_BYTES = 788241409
+MEASURED_NM24_TRAFFIC_BYTES = 57259750
+MEASURED_DECODE_TRAFFIC_BYTES = 3349557141
 CALIBRATION_BYTES = 256 << 20  # size of the plain copies launched by --calibrate
 STREAM_BYTES = 2 << 30         # the pure read stream that serves as the measured ceiling
 
@@ -459,7 +459,7 @@ def main():
 
     single = forward_path != "multi"
     record = {
-        "metric": "us per sparse drafter forward (k=5) and effective HBM GB/s vs peak",
+        "metric": f"us per sparse drafter forward (k={args.k_tok}) and effective HBM GB/s vs peak",
         "value": round(us_per_step, 2),
         "unit": "us",
         "n_gpus": 1,
