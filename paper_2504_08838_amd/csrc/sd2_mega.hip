@@ -17,6 +17,7 @@
 // in-flight tokens for the heads of its slabs, or the SiLU-gated product.
 #include <algorithm>
 #include <atomic>
+#include <type_traits>
 
 #include "sd2_device.h"
 #include "sd2_internal.h"
@@ -530,6 +531,10 @@ __global__ __launch_bounds__(kMegaThreads) void mega_forward_kernel(const MegaAr
     const int n = lane & 15, g = lane >> 4;
     const int n_phases = 4 * a.layers;
     const int k_tok = a.k_tok;
+    // Results leave the CU as (strip, token, row) triples dealt to the threads: entry q = idx / 16 is strip q / k_tok, token
+    // q % k_tok; for q < 128 and k_tok <= 8 the quotient is (q * ceil(1024 / k_tok)) >> 10.
+    const uint32_t tok_mul = (1024u + (uint32_t)k_tok - 1u) / (uint32_t)k_tok;
+    static_assert(kMaxS * kMegaMaxTok <= 128 && kMegaMaxTok <= 8, "range in which the multiply-shift division is exact");
     KArgs ka = (KArgs)__builtin_amdgcn_kernarg_segment_ptr();
 
     uint32_t* bufs = mega_lds + wave * (2 * kTileDw);           // this wave's two tile buffers
@@ -537,8 +542,8 @@ __global__ __launch_bounds__(kMegaThreads) void mega_forward_kernel(const MegaAr
     uint16_t* xlds = reinterpret_cast<uint16_t*>(mega_lds + kAreaDw);
     float* red = reinterpret_cast<float*>(mega_lds + kAreaDw + kXldsDw);
     float* misc = red + kRedDw;                                 // [0,432) attention scores / probabilities
-    float* sums = misc + 432;                                   // [8,16) inverse root mean squares of the tokens
-    float* part_sums = misc + 448;                              // [wave][token] sums of squares of a wavefront's columns
+    float* part_sums = misc + 448;                              // [token][wave] sums of squares of a wavefront's columns
+    static_assert(448 + kMegaMaxTok * kMegaWaves <= kMiscDw && (kAreaDw + kXldsDw + kRedDw + 448) % 4 == 0, "partial sums fit, 16-byte aligned");
     if (tid < 16) lut[tid] = make_expand_selector((uint32_t)tid);
     for (int i = tid; i < kRedDw + kMiscDw; i += kMegaThreads) red[i] = 0.f;  // accumulators, scores, sums
     for (int i = tid; i < kXldsDw; i += kMegaThreads) (mega_lds + kAreaDw)[i] = 0u;  // rows of unused token slots stay zero
@@ -677,9 +682,9 @@ __global__ __launch_bounds__(kMegaThreads) void mega_forward_kernel(const MegaAr
         for (int j = 0; j < kFlushIters; ++j) {
             hseed[j] = 0;
             const int idx = tid + j * kMegaThreads;
-            const int r = idx & 15, t = (idx >> 4) & (kMegaMaxTok - 1), sl = idx >> 7;
+            const int r = idx & 15, sl = (int)(((uint32_t)(idx >> 4) * tok_mul) >> 10), t = (idx >> 4) - sl * k_tok;
             const int strip = strip_lo_s + sl, row = strip * 16 + r;
-            if (adds_residual && sl < ge.s_blk && t < k_tok && strip < ge.n_strips && row < ge.n_out) hseed[j] = h_seed_src[(size_t)t * ge.n_out + row];
+            if (adds_residual && sl < ge.s_blk && strip < ge.n_strips && row < ge.n_out) hseed[j] = h_seed_src[(size_t)t * ge.n_out + row];
         }
 
         if (PROBE && tt && tid == 0) tt[4] = __builtin_amdgcn_s_memrealtime();
@@ -716,48 +721,67 @@ __global__ __launch_bounds__(kMegaThreads) void mega_forward_kernel(const MegaAr
 #pragma unroll
             for (int t = 0; t < kMegaMaxTok; ++t)
                 hraw[t] = (t < k_tok && c4 < a.hidden) ? *reinterpret_cast<const i32x4*>(h_cur + (size_t)t * a.hidden + c4) : i32x4{0, 0, 0, 0};
-            f32x4 hv[kMegaMaxTok];
-#pragma unroll
-            for (int t = 0; t < kMegaMaxTok; ++t)
-#pragma unroll
-                for (int e = 0; e < 4; ++e) hv[t][e] = from_fixed(hraw[t][e], fix_inv);
             if (PROBE) {
                     __builtin_amdgcn_s_waitcnt(0);
                     if (tt && tid == 0) tt[5] = __builtin_amdgcn_s_memrealtime();
             }
             {
-                // sums of squares of all token slots at once (unused slots hold zeros); lane 63 ends up with the totals
-                float ss[kMegaMaxTok];
+                // Sums of squares of all token slots at once (unused slots hold zeros), on the fixed-point numbers as they
+                // are: the scale is a power of two, so it can be applied to the totals without changing a bit.  Lane 63
+                // ends up with the wavefront's totals.
+                auto sums_of = [&](auto n_tag) {
+                    constexpr int N = decltype(n_tag)::value;
+                    float ss[N];
 #pragma unroll
-                for (int t = 0; t < kMegaMaxTok; ++t)
-                    ss[t] = hv[t][0] * hv[t][0] + hv[t][1] * hv[t][1] + hv[t][2] * hv[t][2] + hv[t][3] * hv[t][3];
-                wave_sums_lane63(ss);
-                if (lane == 63) {
+                    for (int t = 0; t < N; ++t) {
+                        const float f0 = (float)hraw[t][0], f1 = (float)hraw[t][1], f2 = (float)hraw[t][2], f3 = (float)hraw[t][3];
+                        ss[t] = f0 * f0 + f1 * f1 + f2 * f2 + f3 * f3;
+                    }
+                    wave_sums_lane63(ss);
+                    if (lane == 63) {
 #pragma unroll
-                    for (int t = 0; t < kMegaMaxTok; ++t) part_sums[wave * kMegaMaxTok + t] = ss[t];  // plain stores: LDS float atomics are slow
-                }
+                        for (int t = 0; t < N; ++t) part_sums[t * kMegaWaves + wave] = ss[t];  // plain stores: LDS float atomics are slow
+                    }
+                };
+                // the usual draft lengths skip the work of the unused slots (their partial sums stay zero)
+                if (k_tok <= 5)
+                    sums_of(std::integral_constant<int, 5>{});
+                else
+                    sums_of(std::integral_constant<int, kMegaMaxTok>{});
             }
             lds_barrier();
-            if (tid < k_tok) {
+            // Every wavefront adds the twelve partial sums itself (lane t: token t, always in the same order), so the
+            // scale factors reach its lanes through scalar registers: no second trip through LDS, no second barrier.
+            float inv_t[kMegaMaxTok];
+            {
                 float tot = 0.f;
-#pragma unroll
-                for (int w = 0; w < kMegaWaves; ++w) tot += part_sums[w * kMegaMaxTok + tid];
-                sums[8 + tid] = 1.0f / sqrtf(tot / (float)a.hidden + 1e-5f);
+                if (lane < kMegaMaxTok) {
+                    const f32x4* ps = reinterpret_cast<const f32x4*>(part_sums + lane * kMegaWaves);
+                    static_assert(kMegaWaves == 12, "three 16-byte reads hold a token's partial sums");
+                    const f32x4 p0 = ps[0], p1 = ps[1], p2 = ps[2];
+                    tot = ((((((((((p0[0] + p0[1]) + p0[2]) + p0[3]) + p1[0]) + p1[1]) + p1[2]) + p1[3]) + p2[0]) + p2[1]) + p2[2]) + p2[3];
+                }
+                tot *= fix_inv * fix_inv;
+                const float r = 1.0f / sqrtf(tot / (float)a.hidden + 1e-5f);
                 // a residual whose norm stays below the limit has every entry below it: the adds into it cannot wrap
-                if (!(tot < a.h_limit_sq)) __hip_atomic_fetch_or(a.err, 2u, __ATOMIC_RELAXED, SD2_AGENT);
+                if (wave == 0 && lane < k_tok && !(tot < a.h_limit_sq)) __hip_atomic_fetch_or(a.err, 2u, __ATOMIC_RELAXED, SD2_AGENT);
+                const float scaled = r * fix_inv;
+#pragma unroll
+                for (int t = 0; t < kMegaMaxTok; ++t) inv_t[t] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(scaled), t));
             }
-            lds_barrier();
             const int c = c4 - col_lo;
             if (c >= 0 && c < n_col) {
 #pragma unroll
                 for (int t = 0; t < kMegaMaxTok; ++t)
                     if (t < k_tok) {
-                        const float inv = sums[8 + t];
-                        const uint32_t lo = pack_bf16(hv[t][0] * inv, hv[t][1] * inv);
-                        const uint32_t hi = pack_bf16(hv[t][2] * inv, hv[t][3] * inv);
+                        const float inv = inv_t[t];
+                        const uint32_t lo = pack_bf16((float)hraw[t][0] * inv, (float)hraw[t][1] * inv);
+                        const uint32_t hi = pack_bf16((float)hraw[t][2] * inv, (float)hraw[t][3] * inv);
                         *reinterpret_cast<uint2*>(xlds + ((c >> 8) * kMegaMaxTok + t) * kXRow + (c & 255)) = make_uint2(lo, hi);
                         if (TRACE) {
-                            *reinterpret_cast<f32x4*>(a.trace_src + tr_s + (size_t)t * a.trace_smax + c4) = hv[t];
+                            *reinterpret_cast<f32x4*>(a.trace_src + tr_s + (size_t)t * a.trace_smax + c4) =
+                                f32x4{from_fixed(hraw[t][0], fix_inv), from_fixed(hraw[t][1], fix_inv), from_fixed(hraw[t][2], fix_inv),
+                                      from_fixed(hraw[t][3], fix_inv)};
                             *reinterpret_cast<uint2*>(a.trace_x + tr_x + (size_t)t * a.trace_kmax + c4) = make_uint2(lo, hi);
                         }
                     }
@@ -1041,8 +1065,8 @@ __global__ __launch_bounds__(kMegaThreads) void mega_forward_kernel(const MegaAr
 #pragma unroll
             for (int j = 0; j < kFlushIters; ++j) {
                 const int idx = tid + j * kMegaThreads;
-                if (idx >= ge.s_blk * kMegaMaxTok * 16) break;
-                const int r = idx & 15, t = (idx >> 4) & (kMegaMaxTok - 1), sl = idx >> 7;
+                if (idx >= ge.s_blk * k_tok * 16) break;
+                const int r = idx & 15, sl = (int)(((uint32_t)(idx >> 4) * tok_mul) >> 10), t = (idx >> 4) - sl * k_tok;
                 float v = 0.f;
                 for (int gq = 0; gq < n_grp; ++gq) {  // the strip's slab groups, each summed by one wavefront
                     float* slot = red + (((sl * n_grp + gq) * kMegaMaxTok + t) << 4) + r;
@@ -1050,7 +1074,7 @@ __global__ __launch_bounds__(kMegaThreads) void mega_forward_kernel(const MegaAr
                     *slot = 0.f;
                 }
                 const int strip = strip_lo + sl, row = strip * 16 + r;
-                if (t < k_tok && strip < ge.n_strips && row < ge.n_out) {
+                if (strip < ge.n_strips && row < ge.n_out) {
                     const float sv = v * scale;
                     bad |= !(fabsf(sv) < lim);  // also true for NaN
                     aadd_i(ybase + (size_t)t * ge.n_out + row, (int)__builtin_rintf(fminf(fmaxf(sv, -lim), lim)) + hseed[j]);
