@@ -437,6 +437,20 @@ def main():
             stream.synchronize()
             if rep:
                 durs_part += [evl[2 * l].elapsed_time(evl[2 * l + 1]) * 1e3 for l in range(layers)]
+        # the same per-slab kernel with the multiply on the vector ALU (packed bf16 dot products) instead of the matrix cores
+        durs_valu = []
+        sd2.set_option(sd2.OPT_LINEAR_PARTIALS, 2)
+        if k_tok <= 8:
+            for rep in range(3):
+                evl = [torch.cuda.Event(enable_timing=True) for _ in range(2 * layers)]
+                for l in range(layers):
+                    evl[2 * l].record(stream)
+                    sd2.sparse_linear_partials(gu[l], x_act.data_ptr(), k_tok, part.data_ptr(), part.numel(), sp)
+                    evl[2 * l + 1].record(stream)
+                stream.synchronize()
+                if rep:
+                    durs_valu += [evl[2 * l].elapsed_time(evl[2 * l + 1]) * 1e3 for l in range(layers)]
+        sd2.set_option(sd2.OPT_LINEAR_PARTIALS, 0)
         if args.calibrate:
             # plain copies of known size: the scale for the profiler's HBM counters
             cal_src = torch.empty(CALIBRATION_BYTES, dtype=torch.uint8, device=dev).fill_(1)
@@ -507,6 +521,7 @@ def main():
                 "algorithmic_bytes": alg_bytes,
                 "traffic": MEASURED_LINEAR_TRAFFIC_BYTES if headline else None,
                 "partials_kernel_us": round(part_us, 2),
+                "partials_kernel_vector_alu_us": round(float(np.mean(durs_valu)), 2) if durs_valu else None,
             },
         },
     }

@@ -69,7 +69,9 @@ int sd2_version(void);
  *   SD2_OPT_FORWARD_MULTI    1: the stack runs as one launch per linear and glue step even where the single-launch
  *                               kernel could serve it
  *   SD2_OPT_LINEAR_PARTIALS  1: sparse linears keep one partial result per slab and add them in a second launch even
- *                               where the kernel that writes final results could serve them
+ *                               where the kernel that writes final results could serve them; 2: as 1, and for up to 8
+ *                               tokens that kernel multiplies on the vector ALU (packed bf16 dot products) instead of
+ *                               the matrix cores: a measurement variant, same results within the same bound
  *   SD2_OPT_SPIN_LIMIT       polls a bounded wait of the single-launch kernel may spend; -1: the default (2^20)
  *   SD2_OPT_MEGA_TIMING      1 / 2: the trace variant of the forward records timestamps only (2: also wavefront 0's
  *                               split into waiting and decoding)

@@ -134,6 +134,8 @@ hipError_t run_linear(const sd2_matrix_t* m, const uint16_t* x, int k_tok, float
         return hipSuccess;
     }
     LinArgs la{x, k_tok, out};
+    if (m->kind == SD2_KIND_SPARSE && option(SD2_OPT_LINEAR_PARTIALS) == 2 && sparse_linear_valu_supported(ma, k_tok))
+        return launch_sparse_linear_valu(ma, la, s);  // the measurement variant without matrix instructions
     return m->kind == SD2_KIND_SPARSE ? launch_sparse_linear(ma, la, s) : launch_dense_linear(ma, la, s);
 }
 
@@ -245,7 +247,7 @@ int sd2_set_option(int32_t which, int32_t value) {
     if (which < 0 || which >= SD2_OPT_COUNT) return SD2_ERR_RANGE;
     if (which == SD2_OPT_FIXED_BITS) {
         if (value < 8 || value > 22) return SD2_ERR_RANGE;
-    } else if (which == SD2_OPT_SPIN_LIMIT ? value < -1 : (value < 0 || value > (which == SD2_OPT_MEGA_TIMING ? 2 : 1))) {
+    } else if (which == SD2_OPT_SPIN_LIMIT ? value < -1 : (value < 0 || value > ((which == SD2_OPT_MEGA_TIMING || which == SD2_OPT_LINEAR_PARTIALS) ? 2 : 1))) {
         return SD2_ERR_RANGE;
     }
     options().v[which].store(value, std::memory_order_relaxed);

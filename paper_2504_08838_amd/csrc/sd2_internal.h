@@ -28,6 +28,9 @@ hipError_t launch_sparse_linear(const MatArgs& m, const LinArgs& a, hipStream_t 
 hipError_t launch_dense_linear(const MatArgs& m, const LinArgs& a, hipStream_t s);
 // the sparse linear with final results in one launch (no partial sums): a.out is y [k_tok][n_out]
 bool sparse_strip_supported(const MatArgs& m, int k_tok);
+// the per-slab kernel with the multiply on the vector ALU (up to 8 tokens): a measurement variant
+bool sparse_linear_valu_supported(const MatArgs& m, int k_tok);
+hipError_t launch_sparse_linear_valu(const MatArgs& m, const LinArgs& a, hipStream_t s);
 hipError_t launch_sparse_strip_linear(const MatArgs& m, const LinArgs& a, hipStream_t s);
 // the fused [gate; up] product with the gating in its epilogue: m_out [k_tok][n_out / 2] = bf16(silu(gate x) * (up x))
 bool sparse_strip_gated_supported(const MatArgs& m, int k_tok);

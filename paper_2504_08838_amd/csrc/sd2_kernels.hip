@@ -93,6 +93,106 @@ __device__ __forceinline__ void sparse_tile(u32x4 (&st)[MAXCH], uint2& mk_next, 
     store_tile<TG>(acc, out, n_out, k_tok, strip, slab, lane);
 }
 
+// The same tile with the multiply on the vector ALU instead of the matrix cores (k_tok <= 8): the lane that owns 16
+// columns of a row in a super-step reads the matching 16 activations of every token from the wavefront's copy of the
+// slab's activation columns in LDS (the four lanes groups read four addresses: broadcasts) and adds the products with
+// the packed bf16 dot-product instruction, fp32 sums; at the end of the tile the four column groups of a row are
+// added across lanes.  It exists to put a number on the alternative to the matrix instruction; nothing selects it
+// unless the caller asks for it.
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+constexpr int kValuTok = 8;
+
+template <int MAXCH, bool PREFETCH>
+__device__ __forceinline__ void sparse_tile_valu(u32x4 (&st)[MAXCH], uint2& mk_next, DirEnt& de_cur, DirEnt& de_next,
+                                                 int& cur_slab, uint32_t* __restrict__ buf, uint32_t* __restrict__ xs,
+                                                 const uint2* __restrict__ lut, const DirEnt* __restrict__ dir,
+                                                 const uint2* __restrict__ masks, const uint16_t* __restrict__ vals,
+                                                 const uint16_t* __restrict__ x, float* __restrict__ out, int n_out, int k_in,
+                                                 int k_tok, int n_strips, int n_tiles, int t, int lane) {
+    const int n = lane & 15, g = lane >> 4;
+#pragma unroll
+    for (int c = 0; c < MAXCH; ++c) reinterpret_cast<u32x4*>(buf)[c * 64 + lane] = st[c];
+    const uint2 mk = mk_next;
+    const int strip = t % n_strips, slab = t / n_strips;
+    if (slab != cur_slab) {  // this wavefront's copy of the slab's activation columns: [token][256] bf16
+        cur_slab = slab;
+#pragma unroll
+        for (int it = 0; it < kValuTok / 2; ++it) {
+            const int tok = 2 * it + (lane >> 5), piece = lane & 31, col = slab * 256 + 8 * piece;
+            u32x4 v = u32x4{0, 0, 0, 0};
+            if (tok < k_tok && col < k_in) v = *reinterpret_cast<const u32x4*>(x + (size_t)tok * k_in + col);
+            reinterpret_cast<u32x4*>(xs)[tok * 32 + piece] = v;
+        }
+    }
+    if (PREFETCH) issue_tile<MAXCH>(st, mk_next, vals, masks, de_next.val_start, de_next.nnz, t + 1, lane);
+    const DirEnt de = de_cur;
+    de_cur = de_next;
+    de_next = dir[min(t + 2, n_tiles - 1)];
+
+    float acc[kValuTok];
+#pragma unroll
+    for (int tok = 0; tok < kValuTok; ++tok) acc[tok] = 0.f;
+    expand_tile<SD2_LINEAR_STEPS>(reinterpret_cast<const uint8_t*>(buf), lut, de.base, mk, [&](int q, const Frag& f0, const Frag& f1) {
+#pragma unroll
+        for (int tok = 0; tok < kValuTok; ++tok) {
+            if (tok < k_tok) {
+                Frag x0, x1;
+                const u32x4* xr = reinterpret_cast<const u32x4*>(xs) + tok * 32 + 8 * q + 2 * g;
+                x0.q = xr[0];
+                x1.q = xr[1];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    acc[tok] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, f0.u[e]), __builtin_bit_cast(bf16x2_t, x0.u[e]), acc[tok], false);
+                    acc[tok] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, f1.u[e]), __builtin_bit_cast(bf16x2_t, x1.u[e]), acc[tok], false);
+                }
+            }
+        }
+    });
+    float* base = out + (size_t)slab * k_tok * n_out;
+    const int row = strip * 16 + n;
+#pragma unroll
+    for (int tok = 0; tok < kValuTok; ++tok) {
+        if (tok < k_tok) {
+            float v = acc[tok];
+            v += __shfl_xor(v, 16);
+            v += __shfl_xor(v, 32);
+            if (g == (tok & 3) && row < n_out) base[(size_t)tok * n_out + row] = v;
+        }
+    }
+}
+
+template <int MAXCH>
+__global__ __launch_bounds__(256) void sparse_linear_valu_kernel(const DirEnt* __restrict__ dir, const uint2* __restrict__ masks,
+                                                                const uint16_t* __restrict__ vals,
+                                                                const uint16_t* __restrict__ x, float* __restrict__ out,
+                                                                int n_out, int k_in, int k_tok, int n_strips, int n_tiles,
+                                                                int tiles_per_wave) {
+    extern __shared__ uint32_t tile_smem[];  // per wavefront: the tile buffer, then [kValuTok][256] bf16 activations
+    __shared__ uint2 lut[16];
+    const int tid = threadIdx.x;
+    if (tid < 16) lut[tid] = make_expand_selector((uint32_t)tid);
+    __syncthreads();
+    const int lane = tid & 63, wave = tid >> 6;
+    const int gw = __builtin_amdgcn_readfirstlane((int)blockIdx.x * kWavesPerBlock + wave);
+    const int t0 = gw * tiles_per_wave;
+    const int t1 = min(t0 + tiles_per_wave, n_tiles);
+    if (t0 >= t1) return;
+    uint32_t* buf = tile_smem + wave * (MAXCH * 256 + kValuTok * 128);
+    uint32_t* xs = buf + MAXCH * 256;
+    u32x4 st[MAXCH];
+    uint2 mk_next;
+    DirEnt de_cur = dir[t0];
+    DirEnt de_next = dir[min(t0 + 1, n_tiles - 1)];
+    issue_tile<MAXCH>(st, mk_next, vals, masks, de_cur.val_start, de_cur.nnz, t0, lane);
+    int cur_slab = -1;
+#pragma unroll 1
+    for (int t = t0; t < t1 - 1; ++t)
+        sparse_tile_valu<MAXCH, true>(st, mk_next, de_cur, de_next, cur_slab, buf, xs, lut, dir, masks, vals, x, out, n_out, k_in,
+                                      k_tok, n_strips, n_tiles, t, lane);
+    sparse_tile_valu<MAXCH, false>(st, mk_next, de_cur, de_next, cur_slab, buf, xs, lut, dir, masks, vals, x, out, n_out, k_in,
+                                   k_tok, n_strips, n_tiles, t1 - 1, lane);
+}
+
 template <int MAXCH, int TG>
 __global__ __launch_bounds__(256) void sparse_linear_kernel(const DirEnt* __restrict__ dir, const uint2* __restrict__ masks,
                                                            const uint16_t* __restrict__ vals,
@@ -414,6 +514,26 @@ static hipError_t launch_sparse_t(const MatArgs& m, const LinArgs& a, hipStream_
     hipLaunchKernelGGL((sparse_linear_kernel<MAXCH, TG>), grid, block, lds, s, static_cast<const DirEnt*>(m.dir), m.masks,
                        m.vals, a.x, a.out, m.n_out, m.k_in, a.k_tok, m.n_strips, m.n_tiles, tpw);
     return hipGetLastError();
+}
+
+template <int MAXCH>
+static hipError_t launch_sparse_valu_t(const MatArgs& m, const LinArgs& a, hipStream_t s) {
+    const int tpw = tiles_per_wave_for(m.n_tiles, 16);
+    const int waves = (m.n_tiles + tpw - 1) / tpw;
+    const dim3 grid((unsigned)((waves + kWavesPerBlock - 1) / kWavesPerBlock)), block(64 * kWavesPerBlock);
+    const size_t lds = (size_t)kWavesPerBlock * (MAXCH * 1024 + kValuTok * 512);
+    hipLaunchKernelGGL((sparse_linear_valu_kernel<MAXCH>), grid, block, lds, s, static_cast<const DirEnt*>(m.dir), m.masks,
+                       m.vals, a.x, a.out, m.n_out, m.k_in, a.k_tok, m.n_strips, m.n_tiles, tpw);
+    return hipGetLastError();
+}
+
+bool sparse_linear_valu_supported(const MatArgs& m, int k_tok) {
+    return k_tok >= 1 && k_tok <= kValuTok && (m.k_in & 7) == 0 && m.max_tile_nnz * 2 + 8 <= 5 * 1024;
+}
+
+hipError_t launch_sparse_linear_valu(const MatArgs& m, const LinArgs& a, hipStream_t s) {
+    if (!sparse_linear_valu_supported(m, a.k_tok)) return hipErrorInvalidValue;
+    return launch_sparse_valu_t<5>(m, a, s);
 }
 
 // Slabs per wavefront and wavefronts per workgroup of the kernel that writes final results.  Up to 16 tokens: one

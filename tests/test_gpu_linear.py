@@ -13,14 +13,12 @@ pytestmark = pytest.mark.gpu
 TOL = 1e-3
 
 
-@pytest.fixture(autouse=True, params=["final", "partials"])
+@pytest.fixture(autouse=True, params=["final", "partials", "partials-vector-alu"])
 def linear_kernel(request, sd2_options):
-    """Every case runs on both sparse kernels: the one that adds the slabs up inside the workgroup (up to 16 tokens)
-    and the one that leaves a partial result per slab for a second launch."""
-    if request.param == "partials":
-        sd2_options.set("linear_partials", 1)
-    else:
-        sd2_options.set("linear_partials", 0)
+    """Every case runs on the sparse kernels: the one that adds the slabs up inside the workgroup (up to 16 tokens), the
+    one that leaves a partial result per slab for a second launch, and the latter's measurement variant that multiplies
+    on the vector ALU instead of the matrix cores (up to 8 tokens; wider cases fall back to the matrix cores)."""
+    sd2_options.set("linear_partials", {"final": 0, "partials": 1, "partials-vector-alu": 2}[request.param])
     return request.param
 
 
