@@ -179,6 +179,13 @@ __device__ __forceinline__ uint32_t lane_word(uint32_t v, int l) { return (uint3
 
 // Requests the value stream (straight into LDS) and the masks of tile j of a phase.  A 2:4 tile is 4608 bytes in
 // the layout of the structured-sparse matrix instruction: four KiB of values, then 512 bytes of column indices.
+//
+// Invariant for every direct-to-LDS request of this kernel: the buffer it fills is one whose previous contents are
+// dead -- the request before it into that buffer was drained by a full wait (vmcnt(0): nothing here is decided by
+// counting outstanding loads, so no assumption about their completion order is made), and the expansion that read
+// those contents has ended, i.e. its LDS reads have returned (their results were consumed before this point in
+// program order).  A wavefront never has two requests for one buffer in flight.  Lanes past a tile's last 16-byte
+// piece repeat that piece's source address, each into a destination of its own that no window reads.
 template <bool NM24>
 __device__ __forceinline__ void issue_phase_tile(const PhaseTiles& pt, int j, uint32_t* lds_buf, uint2& mk, int lane) {
     if (lane_word(pt.key, 8 * j) & kKeyEmpty) {  // nothing stored for it: all-zero masks expand to zeros
