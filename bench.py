@@ -37,11 +37,11 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 # HBM bytes per launch of the forward kernel (and of the gate+up sparse linear) from rocprofv3 --pmc
 # FETCH_SIZE / WRITE_SIZE runs, scaled by the plain copy kernel of --calibrate; None until measured.
-MEASURED_TRAFFIC_BYTES = 3421587955
-MEASURED_LINEAR_TRAFFIC_BYTES = 61251766
-MEASURED_LM_HEAD_TRAFFIC_BYTES = 788241409
-MEASURED_NM24_TRAFFIC_BYTES = 57259750
-MEASURED_DECODE_TRAFFIC_BYTES = 3349557141
+MEASURED_TRAFFIC_BYTES = 3425351415
+MEASURED_LINEAR_TRAFFIC_BYTES = 61258973
+MEASURED_LM_HEAD_TRAFFIC_BYTES = 788238775
+MEASURED_NM24_TRAFFIC_BYTES = 57259560
+MEASURED_DECODE_TRAFFIC_BYTES = 3359744520
 CALIBRATION_BYTES = 256 << 20  # size of the plain copies launched by --calibrate
 STREAM_BYTES = 2 << 30         # the pure read stream that serves as the measured ceiling
 
