@@ -1050,35 +1050,35 @@ __global__ __launch_bounds__(128) void inflight_attention_kernel(const float* __
     if (lane <= i) {
         const float* kr = part + (size_t)lane * n_out + q_out + grp * D + w * half;
         const float* qh = sq + w * half;
-        // sixteen 16-byte loads of the key row in flight at a time: a loop that uses each load before it issues the next
-        // pays the latency of the caches sixteen times over
-        for (int d0 = 0; d0 < half; d0 += 64) {
-            float4 kk[16];
-#pragma unroll
-            for (int u = 0; u < 16; ++u) {
-                const int d = d0 + 4 * u;
-                kk[u] = d < half ? *reinterpret_cast<const float4*>(kr + d) : make_float4(0.f, 0.f, 0.f, 0.f);
-            }
-            for (int sp_i = 1; sp_i < n_splits; ++sp_i) {
+        if (n_splits == 1) {
+            // final values: sixteen 16-byte loads of the key row in flight at a time -- a loop that uses each load before it
+            // issues the next pays the latency of the caches sixteen times over
+            for (int d0 = 0; d0 < half; d0 += 64) {
+                float4 kk[16];
 #pragma unroll
                 for (int u = 0; u < 16; ++u) {
                     const int d = d0 + 4 * u;
-                    if (d < half) {
-                        const float4 more = *reinterpret_cast<const float4*>(kr + (size_t)sp_i * stride + d);
-                        kk[u].x += more.x;
-                        kk[u].y += more.y;
-                        kk[u].z += more.z;
-                        kk[u].w += more.w;
-                    }
+                    kk[u] = d < half ? *reinterpret_cast<const float4*>(kr + d) : make_float4(0.f, 0.f, 0.f, 0.f);
                 }
-            }
 #pragma unroll
-            for (int u = 0; u < 16; ++u) {
-                const int d = d0 + 4 * u;
-                if (d < half) {
+                for (int u = 0; u < 16; ++u) {
+                    const int d = min(d0 + 4 * u, half - 4);  // (a clamped index multiplies zeros)
                     const float4 qq = *reinterpret_cast<const float4*>(qh + d);
                     dot += qq.x * kk[u].x + qq.y * kk[u].y + qq.z * kk[u].z + qq.w * kk[u].w;
                 }
+            }
+        } else {  // partial sums of a split contraction
+            for (int d = 0; d < half; d += 4) {
+                float4 kk = *reinterpret_cast<const float4*>(kr + d);
+                for (int sp_i = 1; sp_i < n_splits; ++sp_i) {
+                    const float4 more = *reinterpret_cast<const float4*>(kr + (size_t)sp_i * stride + d);
+                    kk.x += more.x;
+                    kk.y += more.y;
+                    kk.z += more.z;
+                    kk.w += more.w;
+                }
+                const float4 qq = *reinterpret_cast<const float4*>(qh + d);
+                dot += qq.x * kk.x + qq.y * kk.y + qq.z * kk.z + qq.w * kk.w;
             }
         }
     }
@@ -1099,15 +1099,17 @@ __global__ __launch_bounds__(128) void inflight_attention_kernel(const float* __
     __syncthreads();
     for (int d = tid; d < D; d += 128) {
         const float* vr = part + q_out + kv_out + grp * D + d;
-        // eight values in flight at a time (the loop over the tokens would otherwise wait for each load in turn); the
-        // products are added in token order, so the result does not depend on the grouping
         float o = 0.f;
-        for (int j0 = 0; j0 <= i; j0 += 8) {
-            float v[8];
+        if (n_splits == 1) {  // final values: plain loads, sixteen in flight; the products are added in token order
+            for (int j0 = 0; j0 <= i; j0 += 16) {
+                float v[16];
 #pragma unroll
-            for (int u = 0; u < 8; ++u) v[u] = j0 + u <= i ? sum_splits(vr + (size_t)(j0 + u) * n_out, n_splits, stride) : 0.f;
+                for (int u = 0; u < 16; ++u) v[u] = j0 + u <= i ? vr[(size_t)(j0 + u) * n_out] : 0.f;
 #pragma unroll
-            for (int u = 0; u < 8; ++u) o += sp[min(j0 + u, 63)] * v[u];
+                for (int u = 0; u < 16; ++u) o += sp[min(j0 + u, 63)] * v[u];
+            }
+        } else {
+            for (int j = 0; j <= i; ++j) o += sp[j] * sum_splits(vr + (size_t)j * n_out, n_splits, stride);
         }
         ctx[(size_t)i * q_out + head * D + d] = f32_to_bf16(o);
     }
