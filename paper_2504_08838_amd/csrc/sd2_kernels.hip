@@ -586,7 +586,9 @@ hipError_t launch_sparse_strip_linear(const MatArgs& m, const LinArgs& a, hipStr
     int spw, waves;
     const int tg = (a.k_tok + 15) / 16;
     if (!sparse_strip_supported(m, a.k_tok) || !strip_shape(m.n_slabs, tg, spw, waves)) return hipErrorInvalidValue;
-    if (tg > 2 && spw == 1) {
+    // (a matrix with at most one strip per compute unit is timed by its start-up, not by its stream: one pass then)
+    const bool few_strips = m.n_strips <= device_cu_count();
+    if (tg > 2 && spw == 1 && !few_strips) {
         // One slab per wavefront: two token groups' activation columns fit its registers for the whole kernel, more do
         // not, and fetching them per step costs more than streaming the matrix again: 32 tokens per pass.
         const LinArgs lo{a.x, 32, a.out};
@@ -605,6 +607,12 @@ hipError_t launch_sparse_strip_linear(const MatArgs& m, const LinArgs& a, hipStr
     SD2_STRIP_CASE(1, 4, 2);
     SD2_STRIP_CASE(1, 8, 2);
     SD2_STRIP_CASE(1, 12, 2);
+    SD2_STRIP_CASE(1, 4, 3);
+    SD2_STRIP_CASE(1, 8, 3);
+    SD2_STRIP_CASE(1, 12, 3);
+    SD2_STRIP_CASE(1, 4, 4);
+    SD2_STRIP_CASE(1, 8, 4);
+    SD2_STRIP_CASE(1, 12, 4);
 #define SD2_STRIP_WIDE(T) \
     SD2_STRIP_CASE(2, 8, T); \
     SD2_STRIP_CASE(2, 12, T); \
