@@ -269,7 +269,7 @@ def other_configs(B, fused3, model3, mats3, dmodel3, dmats3, useful3, total3, la
 
     us_s, us_d = cold(sp2), cold(de2)
     out.append({"config": 2, "what": f"1B-shape MLP block (gate|up 16384x2048, down 2048x8192), 50 %, k=5, cold over {n_blk} distinct blocks "
-                                     "(3 launches per call: gate|up, gated product, down)",
+                                     "(sparse: 2 launches per call, gate|up with the gated product in its epilogue, then down; dense: 3)",
                 "us": round(us_s, 2), "dense_us": round(us_d, 2), "speedup_vs_dense": round(us_d / us_s, 3), "useful_bytes": useful2,
                 "stored_bytes": stored2, **rate(useful2, us_s)})
     del keep2, sp2, de2, blocks
