@@ -254,9 +254,16 @@ constexpr int strip_round(int tg, bool gated) {
 template <int MAXCH, int SPW, int WAVES, int TG, bool GATED = false>
 __global__ __launch_bounds__(64 * WAVES) void sparse_strip_kernel(const DirEnt* __restrict__ dir, const uint2* __restrict__ masks,
                                                                  const uint16_t* __restrict__ vals,
-                                                                 const uint16_t* __restrict__ x, float* __restrict__ y,
-                                                                 int n_out, int k_in, int k_tok, int n_strips, int n_slabs) {
+                                                                 const uint16_t* __restrict__ x_all, float* __restrict__ y_all,
+                                                                 int n_out, int k_in, int k_tok_all, int n_strips, int n_slabs) {
     extern __shared__ uint32_t strip_smem[];  // [WAVES][MAXCH * 256] tile buffers, then [kStripRound][WAVES][256] floats
+    // More tokens than one pass takes: the grid's second dimension numbers the passes of 16 TG tokens each (the matrix is
+    // streamed once per pass; a pass is this kernel on its own slice of the activations and of the results).
+    const int pass = (int)blockIdx.y;
+    const uint16_t* __restrict__ x = x_all + (size_t)pass * (16 * TG) * k_in;
+    float* __restrict__ y = GATED ? reinterpret_cast<float*>(reinterpret_cast<uint16_t*>(y_all) + (size_t)pass * (16 * TG) * (n_out / 2))
+                                  : y_all + (size_t)pass * (16 * TG) * n_out;
+    const int k_tok = min(16 * TG, k_tok_all - pass * (16 * TG));
     __shared__ uint2 lut[16];
     const int tid = threadIdx.x;
     if (tid < 16) lut[tid] = make_expand_selector((uint32_t)tid);
@@ -561,7 +568,7 @@ bool sparse_strip_supported(const MatArgs& m, int k_tok) {
 }
 
 template <int SPW, int WAVES, int TG, bool GATED = false>
-static hipError_t launch_strip_t(const MatArgs& m, const LinArgs& a, hipStream_t s) {
+static hipError_t launch_strip_t(const MatArgs& m, const LinArgs& a, hipStream_t s, int passes = 1) {
     constexpr int kCh = 5;
     constexpr int kRound = strip_round(TG, GATED);
     const size_t lds = (size_t)WAVES * kCh * 1024 + (size_t)kRound * TG * WAVES * 256 * sizeof(float);
@@ -576,7 +583,7 @@ static hipError_t launch_strip_t(const MatArgs& m, const LinArgs& a, hipStream_t
         cached.store(resident, std::memory_order_release);
     }
     const int grid = std::min(GATED ? m.n_strips / 2 : m.n_strips, resident);
-    hipLaunchKernelGGL((sparse_strip_kernel<kCh, SPW, WAVES, TG, GATED>), dim3((unsigned)grid), dim3(64 * WAVES), lds, s,
+    hipLaunchKernelGGL((sparse_strip_kernel<kCh, SPW, WAVES, TG, GATED>), dim3((unsigned)grid, (unsigned)passes), dim3(64 * WAVES), lds, s,
                        static_cast<const DirEnt*>(m.dir), m.masks, m.vals, a.x, a.out, m.n_out, m.k_in, a.k_tok, m.n_strips, m.n_slabs);
     return hipGetLastError();
 }
@@ -591,10 +598,11 @@ hipError_t launch_sparse_strip_linear(const MatArgs& m, const LinArgs& a, hipStr
     if (tg > 2 && spw == 1 && !few_strips) {
         // One slab per wavefront: two token groups' activation columns fit its registers for the whole kernel, more do
         // not, and fetching them per step costs more than streaming the matrix again: 32 tokens per pass.
-        const LinArgs lo{a.x, 32, a.out};
-        const LinArgs hi{a.x + (size_t)32 * m.k_in, a.k_tok - 32, a.out + (size_t)32 * m.n_out};
-        const hipError_t e = launch_sparse_strip_linear(m, lo, s);
-        return e != hipSuccess ? e : launch_sparse_strip_linear(m, hi, s);
+        // (both passes in one launch: the grid's second dimension)
+        if (waves == 4) return launch_strip_t<1, 4, 2>(m, a, s, 2);
+        if (waves == 8) return launch_strip_t<1, 8, 2>(m, a, s, 2);
+        if (waves == 12) return launch_strip_t<1, 12, 2>(m, a, s, 2);
+        return hipErrorInvalidValue;
     }
 #define SD2_STRIP_CASE(S, W, T) \
     if (spw == S && waves == W && tg == T) return launch_strip_t<S, W, T>(m, a, s)
@@ -636,14 +644,16 @@ bool sparse_strip_gated_supported(const MatArgs& m, int k_tok) {
 
 hipError_t launch_sparse_strip_gated(const MatArgs& m, const uint16_t* x, int k_tok, uint16_t* m_out, hipStream_t s) {
     if (!sparse_strip_gated_supported(m, k_tok)) return hipErrorInvalidValue;
-    if (k_tok > 32) {  // 32 tokens per pass, as for the plain product
-        const hipError_t e = launch_sparse_strip_gated(m, x, 32, m_out, s);
-        return e != hipSuccess ? e : launch_sparse_strip_gated(m, x + (size_t)32 * m.k_in, k_tok - 32, m_out + (size_t)32 * (m.n_out / 2), s);
-    }
     int spw, waves;
-    const int tg = (k_tok + 15) / 16;
+    const int tg = std::min((k_tok + 15) / 16, 2);
     strip_shape(m.n_slabs, tg, spw, waves);
     const LinArgs a{x, k_tok, reinterpret_cast<float*>(m_out)};
+    if (k_tok > 32) {  // 32 tokens per pass, as for the plain product; both passes in one launch
+        if (waves == 4) return launch_strip_t<1, 4, 2, true>(m, a, s, 2);
+        if (waves == 8) return launch_strip_t<1, 8, 2, true>(m, a, s, 2);
+        if (waves == 12) return launch_strip_t<1, 12, 2, true>(m, a, s, 2);
+        return hipErrorInvalidValue;
+    }
 #define SD2_GATED_CASE(W, T) \
     if (waves == W && tg == T) return launch_strip_t<1, W, T, true>(m, a, s)
     SD2_GATED_CASE(4, 1);
