@@ -123,16 +123,8 @@ hipError_t run_linear(const sd2_matrix_t* m, const uint16_t* x, int k_tok, float
         }
         return hipSuccess;
     }
-    if (is_dense_stream(m)) {
-        // 32 tokens per pass where two groups' activations fit the registers, else 16
-        const int per_pass = dense_stream_pair_ok(ma.k_in) ? 32 : 16;
-        for (int t0 = 0; t0 < k_tok; t0 += per_pass) {
-            const hipError_t e = launch_dense_stream_linear(ma.w, x + (size_t)t0 * ma.k_in, ma.n_out, ma.k_in,
-                                                            std::min(per_pass, k_tok - t0), out + (size_t)t0 * ma.n_out, s);
-            if (e != hipSuccess) return e;
-        }
-        return hipSuccess;
-    }
+    if (is_dense_stream(m))  // one launch; 32 tokens per pass where two groups' activations fit the registers, else 16
+        return launch_dense_stream_linear(ma.w, x, ma.n_out, ma.k_in, k_tok, out, s);
     LinArgs la{x, k_tok, out};
     if (m->kind == SD2_KIND_SPARSE && option(SD2_OPT_LINEAR_PARTIALS) == 2 && sparse_linear_valu_supported(ma, k_tok))
         return launch_sparse_linear_valu(ma, la, s);  // the measurement variant without matrix instructions

@@ -52,10 +52,16 @@ __device__ __forceinline__ void lm_better(float& a, int32_t& ia, float b, int32_
 template <int CPW, bool HEAD, int TG = 1>
 __global__ __launch_bounds__(64 * kLmWaves) void lm_head_kernel(const uint16_t* __restrict__ w,
                                                                 const float* __restrict__ h,
-                                                                const uint16_t* __restrict__ x, int vocab, int hidden,
-                                                                int k_tok, int n_strips, LmCand* __restrict__ part,
-                                                                float* __restrict__ logits) {
+                                                                const uint16_t* __restrict__ x_all, int vocab, int hidden,
+                                                                int k_tok_all, int n_strips, LmCand* __restrict__ part,
+                                                                float* __restrict__ logits_all) {
     extern __shared__ __attribute__((aligned(16))) uint32_t lm_smem[];
+    // As a plain linear with more tokens than one pass takes, the grid's second dimension numbers the passes of 16 TG
+    // tokens (the matrix is streamed once per pass); the head itself is launched with one pass.
+    const int pass = HEAD ? 0 : (int)blockIdx.y;
+    const uint16_t* __restrict__ x = HEAD ? x_all : x_all + (size_t)pass * (16 * TG) * hidden;
+    float* __restrict__ logits = (HEAD || !logits_all) ? logits_all : logits_all + (size_t)pass * (16 * TG) * vocab;
+    const int k_tok = HEAD ? k_tok_all : min(16 * TG, k_tok_all - pass * (16 * TG));
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -271,7 +277,7 @@ static int lm_cu_count() {
 
 template <int CPW, bool HEAD, int TG = 1>
 static hipError_t launch_lm_t(const uint16_t* w, const float* h, const uint16_t* x, int vocab, int hidden, int k_tok,
-                              int n_strips, int n_wg, LmCand* part, float* logits, hipStream_t s) {
+                              int n_strips, int n_wg, LmCand* part, float* logits, hipStream_t s, int passes = 1) {
     static std::atomic<bool> attr_set{false};  // more than the default 64 KiB of dynamic LDS needs opting in, once per kernel
     const size_t lds = (size_t)kLmLdsDw * 4;
     if (!attr_set.load(std::memory_order_acquire)) {
@@ -280,23 +286,23 @@ static hipError_t launch_lm_t(const uint16_t* w, const float* h, const uint16_t*
         if (e != hipSuccess) return e;
         attr_set.store(true, std::memory_order_release);
     }
-    hipLaunchKernelGGL((lm_head_kernel<CPW, HEAD, TG>), dim3((unsigned)n_wg), dim3(64 * kLmWaves), lds, s, w, h, x, vocab, hidden,
+    hipLaunchKernelGGL((lm_head_kernel<CPW, HEAD, TG>), dim3((unsigned)n_wg, (unsigned)passes), dim3(64 * kLmWaves), lds, s, w, h, x, vocab, hidden,
                        k_tok, n_strips, part, logits);
     return hipGetLastError();
 }
 
 template <bool HEAD>
 static hipError_t launch_lm_cpw(const uint16_t* w, const float* h, const uint16_t* x, int vocab, int hidden, int k_tok,
-                                int n_strips, int n_wg, LmCand* part, float* logits, hipStream_t s) {
+                                int n_strips, int n_wg, LmCand* part, float* logits, hipStream_t s, int passes = 1) {
     const int cpw = (hidden / kLmChunkCols + kLmWaves - 1) / kLmWaves;
     switch (cpw) {
-        case 1: return launch_lm_t<1, HEAD>(w, h, x, vocab, hidden, k_tok, n_strips, n_wg, part, logits, s);
-        case 2: return launch_lm_t<2, HEAD>(w, h, x, vocab, hidden, k_tok, n_strips, n_wg, part, logits, s);
-        case 3: return launch_lm_t<3, HEAD>(w, h, x, vocab, hidden, k_tok, n_strips, n_wg, part, logits, s);
-        case 4: return launch_lm_t<4, HEAD>(w, h, x, vocab, hidden, k_tok, n_strips, n_wg, part, logits, s);
-        case 5: case 6: return launch_lm_t<6, HEAD>(w, h, x, vocab, hidden, k_tok, n_strips, n_wg, part, logits, s);
-        case 7: case 8: return launch_lm_t<8, HEAD>(w, h, x, vocab, hidden, k_tok, n_strips, n_wg, part, logits, s);
-        case 9: return launch_lm_t<9, HEAD>(w, h, x, vocab, hidden, k_tok, n_strips, n_wg, part, logits, s);
+        case 1: return launch_lm_t<1, HEAD>(w, h, x, vocab, hidden, k_tok, n_strips, n_wg, part, logits, s, passes);
+        case 2: return launch_lm_t<2, HEAD>(w, h, x, vocab, hidden, k_tok, n_strips, n_wg, part, logits, s, passes);
+        case 3: return launch_lm_t<3, HEAD>(w, h, x, vocab, hidden, k_tok, n_strips, n_wg, part, logits, s, passes);
+        case 4: return launch_lm_t<4, HEAD>(w, h, x, vocab, hidden, k_tok, n_strips, n_wg, part, logits, s, passes);
+        case 5: case 6: return launch_lm_t<6, HEAD>(w, h, x, vocab, hidden, k_tok, n_strips, n_wg, part, logits, s, passes);
+        case 7: case 8: return launch_lm_t<8, HEAD>(w, h, x, vocab, hidden, k_tok, n_strips, n_wg, part, logits, s, passes);
+        case 9: return launch_lm_t<9, HEAD>(w, h, x, vocab, hidden, k_tok, n_strips, n_wg, part, logits, s, passes);
         default: return hipErrorInvalidValue;
     }
 }
@@ -314,23 +320,25 @@ hipError_t launch_lm_head(const uint16_t* w, const float* h, int vocab, int hidd
 }
 
 // y[t][n] = sum_c W[n][c] x[t][c] for a dense row-major bf16 matrix and tokens [0, k_tok); every entry of y written
-// (final values: the contraction is added up inside the workgroup).  k_in a multiple of 128, <= 9216.  k_tok <= 16, or
-// <= 32 where dense_stream_pair_ok(k_in): two token groups' activations then fit the registers next to each other.
+// (final values: the contraction is added up inside the workgroup).  k_in a multiple of 128, <= 9216.  A pass takes 16
+// tokens, or 32 where dense_stream_pair_ok(k_in) (two token groups' activations then fit the registers next to each
+// other); more tokens are further passes of the same launch (the grid's second dimension).
 hipError_t launch_dense_stream_linear(const uint16_t* w, const uint16_t* x, int n_out, int k_in, int k_tok, float* y,
                                       hipStream_t s) {
     const int n_strips = (n_out + 15) / 16;
     const int n_wg = std::min(n_strips, lm_cu_count());
-    if (k_tok > 16) {
-        if (k_tok > 32 || !dense_stream_pair_ok(k_in)) return hipErrorInvalidValue;
+    if (k_tok < 1 || k_tok > 64) return hipErrorInvalidValue;
+    if (k_tok > 16 && dense_stream_pair_ok(k_in)) {
+        const int passes = (k_tok + 31) / 32;
         switch ((k_in / kLmChunkCols + kLmWaves - 1) / kLmWaves) {
-            case 1: return launch_lm_t<1, false, 2>(w, nullptr, x, n_out, k_in, k_tok, n_strips, n_wg, nullptr, y, s);
-            case 2: return launch_lm_t<2, false, 2>(w, nullptr, x, n_out, k_in, k_tok, n_strips, n_wg, nullptr, y, s);
-            case 3: return launch_lm_t<3, false, 2>(w, nullptr, x, n_out, k_in, k_tok, n_strips, n_wg, nullptr, y, s);
-            case 4: return launch_lm_t<4, false, 2>(w, nullptr, x, n_out, k_in, k_tok, n_strips, n_wg, nullptr, y, s);
+            case 1: return launch_lm_t<1, false, 2>(w, nullptr, x, n_out, k_in, k_tok, n_strips, n_wg, nullptr, y, s, passes);
+            case 2: return launch_lm_t<2, false, 2>(w, nullptr, x, n_out, k_in, k_tok, n_strips, n_wg, nullptr, y, s, passes);
+            case 3: return launch_lm_t<3, false, 2>(w, nullptr, x, n_out, k_in, k_tok, n_strips, n_wg, nullptr, y, s, passes);
+            case 4: return launch_lm_t<4, false, 2>(w, nullptr, x, n_out, k_in, k_tok, n_strips, n_wg, nullptr, y, s, passes);
             default: return hipErrorInvalidValue;
         }
     }
-    return launch_lm_cpw<false>(w, nullptr, x, n_out, k_in, k_tok, n_strips, n_wg, nullptr, y, s);
+    return launch_lm_cpw<false>(w, nullptr, x, n_out, k_in, k_tok, n_strips, n_wg, nullptr, y, s, (k_tok + 15) / 16);
 }
 
 }  // namespace sd2
