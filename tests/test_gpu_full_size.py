@@ -17,7 +17,8 @@ pytestmark = pytest.mark.gpu
 
 # After 28 layers (112 bf16 re-rounding points) a handful of activations that sit within fp32 error of a rounding
 # boundary round the other way than in the fp64 oracle; each such flip moves the output by ~1e-4 of its norm and
-# they add up like a random walk.  The link-by-link part below is the contract; this bound only catches a broken run.
+# they add up like a random walk.  Observed at 28 layers: 8.0e-3 (printed by the test below); the bound is 2.5 times
+# that.  The link-by-link part below is the contract; this bound only catches a broken run.
 FULL_E2E_TOL = 2e-2
 
 
